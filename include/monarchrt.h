@@ -1,0 +1,120 @@
+/*
+ * monarchrt.h -- C ABI of the MonarchRT attention forward operator for AMD MI355X (gfx950).
+ *
+ * The library computes, for every (batch, head) independently, the MonarchAttention
+ * output of App. A of the MonarchRT paper (arXiv 2602.12271):
+ *
+ *   regular Monarch (App. A.1, Alg. 1): factors L[j,k,l] (b2 blocks of b1 x b1) and
+ *   R[k,j,i] (b1 blocks of b2 x b2) of  M[(l*b2+j),(k*b2+i)] = L[j,l,k] R[k,j,i]  (Sec. 4.2)
+ *   are refined for T alternating iterations (R: softmax over i of beta_R / c_R;
+ *   L: softmax over k of beta_L - c_L), then O = L (R V);
+ *
+ *   tiled Monarch (Sec. 4.2, App. A.2, Alg. 2): the same per pair of (query tile m,
+ *   key tile n) with tile-local block sizes (b1, b2), the softmax of L taken jointly
+ *   over all visible key tiles and key rows (n, k).
+ *
+ * Token order is row-major (frame, height, width) (App. B.1).  Blocks are the aligned
+ * choice of Sec. 4.1: grid rows (frame, height) go to the b1 side, width to the b2 side.
+ * A tile is b1 consecutive grid rows by b2 consecutive columns (Alg. 2, the
+ * "(a l b j)" split); token = ((a*b1 + l)*c2 + b)*b2 + j with c2 = w / b2.
+ *
+ * All data pointers are DEVICE pointers owned by the caller.  The library allocates
+ * nothing, enqueues its kernels on the given HIP stream and returns without
+ * synchronising.  Entry points return a status code; nothing is thrown across the ABI.
+ * All argument checks happen on the host before the first launch.
+ */
+#ifndef MONARCHRT_H
+#define MONARCHRT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MRT_OK = 0,
+  MRT_ERR_NULL = 1,        /* a required pointer is NULL                               */
+  MRT_ERR_SHAPE = 2,       /* batch/heads/head_dim/grid/stride values out of range      */
+  MRT_ERR_BLOCK = 3,       /* (b1,b2) do not tile the grids as required                 */
+  MRT_ERR_UNSUPPORTED = 4, /* valid in the paper, not built here (see each entry point) */
+  MRT_ERR_WORKSPACE = 5,   /* workspace smaller than monarch_attn_workspace_min_bytes   */
+  MRT_ERR_HIP = 6          /* a HIP call or kernel launch reported an error             */
+} mrt_status;
+
+typedef enum { MRT_F32 = 0, MRT_BF16 = 1 } mrt_dtype;
+
+/* Arithmetic used inside the kernels.
+ *   MRT_COMPUTE_DEFAULT : f32 storage -> fp32 arithmetic throughout;
+ *                         bf16 storage -> bf16 MFMA operands, fp32 accumulation and softmax.
+ *   MRT_COMPUTE_F32     : fp32 arithmetic and fp32 intermediates whatever the storage type
+ *                         (slow; a device-side cross-check). */
+typedef enum { MRT_COMPUTE_DEFAULT = 0, MRT_COMPUTE_F32 = 1 } mrt_compute;
+
+/* Element strides of one [batch, heads, tokens, head_dim] tensor; head_dim is contiguous. */
+typedef struct {
+  long long batch, head, token;
+} mrt_strides;
+
+typedef struct {
+  int batch, heads;
+  int head_dim;        /* multiple of 32, 32..128                                          */
+  int f_q, f_kv;       /* frames of the query grid and of the key/value grid               */
+  int h, w;            /* height and width of both grids; N_q = f_q*h*w, N_kv = f_kv*h*w    */
+  int q_frame_offset;  /* absolute frame of query frame 0 inside the kv grid (mask only)    */
+  mrt_strides q, k, v, o;
+  mrt_dtype dtype;     /* storage type of Q, K, V and O                                     */
+  mrt_compute compute;
+  float scale;         /* multiplies both logit contractions (beta_R and beta_L);
+                          1.0 is the paper's softmax(Q K^T) (Sec. 2.2)                      */
+} mrt_problem;
+
+/* Checks a MonarchRT call without touching the GPU (same rules monarch_attn_fwd applies).
+ *   tile = 0  regular Monarch: needs f_q == f_kv, b1 == f*h, b2 == w, causal_chunk == 0.
+ *   tile = 1  tiled: (b1,b2) are tile-local; needs b1 % h == 0, (f_q*h) % b1 == 0,
+ *             (f_kv*h) % b1 == 0, w % b2 == 0.
+ *   iters >= 1 (R is undefined before the first update, App. A.1).
+ *   causal_chunk = 0: no mask.  > 0: frames per autoregressive chunk; a key tile is visible
+ *             to a query tile iff its chunk is not later than the query tile's chunk, hidden
+ *             tile pairs take no part at all.  Needs (b1/h) to divide causal_chunk and
+ *             q_frame_offset, and tile = 1.
+ *   Limits of this build: b1 <= 1024, b2 <= 128. */
+mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, int iters,
+                              int causal_chunk);
+
+/* Smallest workspace (bytes) monarch_attn_fwd accepts: room for the alpha_L, c_L, Y and
+ * alpha_R intermediates of ONE (batch, head) (App. A; Sec. 4.3 explains why these, unlike
+ * L and R, have to live in device memory).  Returns 0 if the arguments are invalid. */
+size_t monarch_attn_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
+
+/* Recommended workspace: enough (batch, head) slabs per pass to fill the GPU while the
+ * intermediates of a pass still fit the last-level cache.  Any size between the minimum and
+ * batch*heads slabs is accepted; the library processes as many heads per pass as fit. */
+size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
+
+/* MonarchRT attention forward (Alg. 1 for tile = 0, Alg. 2 for tile = 1).
+ *   Q [batch, heads, N_q, head_dim], K, V [batch, heads, N_kv, head_dim], O like Q; device
+ *   memory, element strides in p.  O is fully overwritten.  workspace: device memory, 256-byte
+ *   aligned, contents undefined on entry and exit.  hip_stream: a hipStream_t (NULL = the
+ *   default stream).  Calls sharing a workspace must be ordered on one stream. */
+mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
+                            const mrt_problem* p, int b1, int b2, int tile, int iters,
+                            int causal_chunk, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+
+/* Dense baseline  O = softmax(scale * Q K^T + mask) V  (Sec. 2.2), flash-style, no workspace.
+ * causal_chunk > 0 masks, per token, keys whose frame's chunk is later than the query frame's
+ * chunk (query frames offset by q_frame_offset). */
+mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk);
+mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
+                          const mrt_problem* p, int causal_chunk, void* hip_stream);
+
+const char* mrt_status_string(mrt_status s);
+
+/* Text of the last error detail recorded on the calling thread ("" if none). */
+const char* mrt_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONARCHRT_H */

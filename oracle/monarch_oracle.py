@@ -1,0 +1,312 @@
+"""fp64 CPU oracle for MonarchRT attention.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain statement of what the operator computes.  It is
+imported by tests, by the smoke check and by the benchmark's cpu_baseline leg,
+and by nothing on the product path.  It shares no code with the HIP kernels and
+never imports them.
+
+Every function works on ONE head: Q is [N_q, d], K and V are [N_kv, d], tokens
+in row-major (frame, height, width) order (App. B.1, the ordering called phi).
+All arithmetic is float64 (torch CPU tensors); inputs of any float dtype are
+widened first.
+
+Notation follows App. A (Alg. 1 / Alg. 2 and the two pseudocode figures):
+  l  query row inside a tile      j  column inside a tile (queries and keys)
+  k  key row inside a tile        i  key column inside a tile
+  m  query tile                   n  key tile              v  feature
+  L[m,n,j,k,l], R[m,n,k,j,i]      (regular Monarch: one tile, m = n = 0)
+
+Readings taken where the paper is silent or garbled (each is listed in the
+design document as well):
+  * an explicit `scale` multiplies both logit contractions (beta_R, beta_L);
+    scale = 1 is the paper's softmax(Q K^T).
+  * c_L sums R log R over i (the text's summation index is a typo; the
+    pseudocode's einsum is over i), with 0 log 0 = 0.
+  * the tiled pseudocode's second rearrange assigns K.
+  * rectangular N_q != N_kv: query tiles m and key tiles n are counted
+    separately, the initial L is the identity in (k,l) for every pair (m,n).
+  * chunk-causal mask: applied per tile pair.  A key tile is visible to a query
+    tile iff the chunk of the key tile's frames is not later than the chunk of
+    the query tile's frames; hidden pairs take no part at all (no R, not in the
+    joint softmax of L).  A tile never straddles a chunk boundary.
+  * beta_R / c_R with c_R == 0 exactly: that row of Z_R is set to 0 (uniform R).
+
+Parity status: every function here is pinned by tests/test_oracle_pins.py
+(degenerate block sizes == dense softmax attention; separable logits == dense
+for every T; materialised M @ V == factored product; row-stochasticity;
+parameter tying; an independent index-loop transcription of the update
+equations; monotone KL along the iterations; constant V).
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+F64 = torch.float64
+
+
+# --------------------------------------------------------------------------
+# geometry (index arithmetic only)
+# --------------------------------------------------------------------------
+@dataclass(frozen=True)
+class TileGeometry:
+    """Tile-local block sizes (b1, b2) laid over row-major (f*h, w) token grids.
+
+    Rows of the grid are (frame, height) pairs, columns are width (Sec. 4.1,
+    the aligned choice (fh, w)); a tile is b1 consecutive rows by b2 consecutive
+    columns (Alg. 2 pseudocode, the "(a l b j)" split).  c1q / c1k count row
+    tiles of the query / key grid, c2 counts column tiles of both.
+    """
+
+    b1: int
+    b2: int
+    c1q: int
+    c1k: int
+    c2: int
+
+    @property
+    def ntq(self) -> int:
+        return self.c1q * self.c2
+
+    @property
+    def ntk(self) -> int:
+        return self.c1k * self.c2
+
+
+def to_tiles(X: torch.Tensor, c1: int, b1: int, c2: int, b2: int) -> torch.Tensor:
+    """[(a l b j), v] -> [(a b), l, j, v]   (Alg. 2 pseudocode, the rearranges)."""
+    N, d = X.shape
+    assert N == c1 * b1 * c2 * b2
+    X = X.reshape(c1, b1, c2, b2, d)            # a l b j v
+    X = X.permute(0, 2, 1, 3, 4)                # a b l j v
+    return X.reshape(c1 * c2, b1, b2, d).contiguous()
+
+
+def from_tiles(Z: torch.Tensor, c1: int, b1: int, c2: int, b2: int) -> torch.Tensor:
+    """[(a b), l, j, v] -> [(a l b j), v]   (inverse of to_tiles)."""
+    d = Z.shape[-1]
+    Z = Z.reshape(c1, c2, b1, b2, d).permute(0, 2, 1, 3, 4)
+    return Z.reshape(c1 * b1 * c2 * b2, d).contiguous()
+
+
+def chunk_causal_visibility(geom: TileGeometry, h: int, causal_chunk: int,
+                            q_frame_offset: int) -> torch.Tensor:
+    """visible[m, n] for the tile-level chunk-causal reading (see module header).
+
+    Frames per tile row = b1 / h.  Query tile row a covers absolute frames
+    q_frame_offset + a*fb ... ; key tile row a' covers frames a'*fb ... .
+    causal_chunk == 0 means no mask.
+    """
+    vis = torch.ones(geom.ntq, geom.ntk, dtype=torch.bool)
+    if causal_chunk == 0:
+        return vis
+    assert geom.b1 % h == 0
+    fb = geom.b1 // h
+    assert causal_chunk % fb == 0 and q_frame_offset % fb == 0
+    for m in range(geom.ntq):
+        qa = m // geom.c2
+        q_chunk = (q_frame_offset + qa * fb) // causal_chunk
+        for n in range(geom.ntk):
+            ka = n // geom.c2
+            k_chunk = (ka * fb) // causal_chunk
+            vis[m, n] = k_chunk <= q_chunk
+    return vis
+
+
+# --------------------------------------------------------------------------
+# dense attention (Sec. 2.2: Attn(Q,K,V) = softmax(Q K^T) V, row-wise softmax)
+# --------------------------------------------------------------------------
+def dense_attention(Q, K, V, scale: float = 1.0,
+                    mask: Optional[torch.Tensor] = None) -> torch.Tensor:
+    Q, K, V = Q.to(F64), K.to(F64), V.to(F64)
+    S = scale * (Q @ K.T)
+    if mask is not None:
+        S = S.masked_fill(~mask, -math.inf)
+    return torch.softmax(S, dim=1) @ V
+
+
+def token_chunk_causal_mask(f_q: int, f_kv: int, h: int, w: int, causal_chunk: int,
+                            q_frame_offset: int) -> Optional[torch.Tensor]:
+    """Token-level chunk-causal mask [N_q, N_kv]: a key is visible iff its frame's
+    chunk is not later than the query frame's chunk.  None when causal_chunk == 0."""
+    if causal_chunk == 0:
+        return None
+    qf = (torch.arange(f_q * h * w) // (h * w) + q_frame_offset) // causal_chunk
+    kf = (torch.arange(f_kv * h * w) // (h * w)) // causal_chunk
+    return kf[None, :] <= qf[:, None]
+
+
+# --------------------------------------------------------------------------
+# Alg. 1: regular MonarchAttention (App. A.1)
+# --------------------------------------------------------------------------
+def _xlogx_sum(R: torch.Tensor, dim: int) -> torch.Tensor:
+    """sum R log R along dim with 0 log 0 = 0."""
+    return torch.where(R > 0, R * torch.log(torch.where(R > 0, R, torch.ones_like(R))),
+                       torch.zeros_like(R)).sum(dim)
+
+
+def _safe_rows_div(bR: torch.Tensor, cR: torch.Tensor) -> torch.Tensor:
+    """beta_R / c_R along the last axis; rows with c_R == 0 become all-zero logits."""
+    c = cR.unsqueeze(-1)
+    return torch.where(c != 0, bR / torch.where(c != 0, c, torch.ones_like(c)),
+                       torch.zeros_like(bR))
+
+
+def monarch_attention_regular(Q, K, V, T: int, b1: int, b2: int, scale: float = 1.0,
+                              return_factors: bool = False):
+    """App. A.1 update equations / pseudocode (a).  N = b1*b2, Q,K,V viewed as
+    [b1, b2, d].  Returns O [N, d] (and L[j,k,l], R[k,j,i] on request)."""
+    assert T >= 1
+    N, d = Q.shape
+    assert N == b1 * b2 and K.shape == (N, d) and V.shape[0] == N
+    Qv = Q.to(F64).reshape(b1, b2, d)            # l j v
+    Kv = K.to(F64).reshape(b1, b2, d)            # k i v
+    Vv = V.to(F64).reshape(b1, b2, V.shape[1])   # k i v
+    L = torch.eye(b1, dtype=F64).expand(b2, b1, b1).clone()      # j k l
+    R = None
+    for _ in range(T):
+        aR = torch.einsum("jkl,ljv->kjv", L, Qv)
+        bR = scale * torch.einsum("kjv,kiv->kji", aR, Kv)
+        cR = torch.einsum("jkl->kj", L)
+        R = torch.softmax(_safe_rows_div(bR, cR), dim=2)         # over i
+
+        aL = torch.einsum("kji,kiv->jkv", R, Kv)
+        bL = scale * torch.einsum("jkv,ljv->jkl", aL, Qv)
+        cL = _xlogx_sum(R, 2).transpose(0, 1)                    # kj -> jk
+        L = torch.softmax(bL - cL[:, :, None], dim=1)            # over k
+    Y = torch.einsum("kji,kiv->jkv", R, Vv)
+    Z = torch.einsum("jkl,jkv->ljv", L, Y)
+    O = Z.reshape(N, -1)
+    if return_factors:
+        return O, L, R
+    return O
+
+
+def materialise_regular(L: torch.Tensor, R: torch.Tensor) -> torch.Tensor:
+    """Sec. 4.2: M[(l*b2 + j), (k*b2 + i)] = L[j,l,k] * R[k,j,i], with L stored
+    as [j,k,l] like the pseudocode does."""
+    b2, b1, _ = L.shape
+    M4 = torch.einsum("jkl,kji->ljki", L, R)
+    return M4.reshape(b1 * b2, b1 * b2)
+
+
+# --------------------------------------------------------------------------
+# Alg. 2: tiled MonarchAttention (App. A.2), rectangular + tile mask
+# --------------------------------------------------------------------------
+def _tiled_one_query_tile(Qm, Kt, Vt, T, scale):
+    """Alg. 2 for one query tile against the list of its visible key tiles.
+
+    Qm [b1,b2,d] (l j v); Kt,Vt [nv,b1,b2,d] (n k i v).  Returns Z [b1,b2,dv],
+    L [nv,b2,b1,b1] (n j k l), R [nv,b1,b2,b2] (n k j i).
+    """
+    nv, b1, b2, _ = Kt.shape
+    L = torch.eye(b1, dtype=F64).expand(nv, b2, b1, b1).clone()  # n j k l
+    R = None
+    for _ in range(T):
+        aR = torch.einsum("njkl,ljv->nkjv", L, Qm)
+        bR = scale * torch.einsum("nkjv,nkiv->nkji", aR, Kt)
+        cR = torch.einsum("njkl->nkj", L)
+        R = torch.softmax(_safe_rows_div(bR, cR), dim=3)         # over i
+
+        aL = torch.einsum("nkji,nkiv->njkv", R, Kt)
+        bL = scale * torch.einsum("njkv,ljv->njkl", aL, Qm)
+        cL = _xlogx_sum(R, 3).permute(0, 2, 1)                   # nkj -> njk
+        ZL = bL - cL[..., None]                                  # n j k l
+        # joint softmax over (n, k) for every (j, l)
+        Zf = ZL.permute(1, 3, 0, 2).reshape(b2, b1, nv * b1)     # j l (n k)
+        Lf = torch.softmax(Zf, dim=2)
+        L = Lf.reshape(b2, b1, nv, b1).permute(2, 0, 3, 1).contiguous()  # n j k l
+    Y = torch.einsum("nkji,nkiv->njkv", R, Vt)
+    Z = torch.einsum("njkl,njkv->ljv", L, Y)
+    return Z, L, R
+
+
+def monarch_attention_tiled(Q, K, V, T: int, geom: TileGeometry, scale: float = 1.0,
+                            visible: Optional[torch.Tensor] = None,
+                            return_factors: bool = False):
+    """App. A.2 update equations / pseudocode (b), generalised to N_q != N_kv and
+    to a tile-pair visibility table.  Query tiles are independent of each other
+    (the joint softmax of L runs over key tiles only), so the loop over m below
+    is the algorithm itself, not a blocking of it.
+
+    Returns O [N_q, dv]; with return_factors also lists (per m) of the visible
+    key-tile ids, L[n,j,k,l] and R[n,k,j,i].
+    """
+    assert T >= 1
+    g = geom
+    Qt = to_tiles(Q.to(F64), g.c1q, g.b1, g.c2, g.b2)            # m l j v
+    Kt = to_tiles(K.to(F64), g.c1k, g.b1, g.c2, g.b2)            # n k i v
+    Vt = to_tiles(V.to(F64), g.c1k, g.b1, g.c2, g.b2)
+    if visible is None:
+        visible = torch.ones(g.ntq, g.ntk, dtype=torch.bool)
+    Z = torch.zeros(g.ntq, g.b1, g.b2, V.shape[1], dtype=F64)
+    vis_ids: List[torch.Tensor] = []
+    Ls, Rs = [], []
+    for m in range(g.ntq):
+        ids = torch.nonzero(visible[m]).flatten()
+        assert ids.numel() > 0, "a query tile with no visible key tile has no softmax"
+        Zm, Lm, Rm = _tiled_one_query_tile(Qt[m], Kt[ids], Vt[ids], T, scale)
+        Z[m] = Zm
+        if return_factors:
+            vis_ids.append(ids); Ls.append(Lm); Rs.append(Rm)
+    O = from_tiles(Z, g.c1q, g.b1, g.c2, g.b2)
+    if return_factors:
+        return O, vis_ids, Ls, Rs
+    return O
+
+
+def materialise_tiled(geom: TileGeometry, vis_ids: Sequence[torch.Tensor],
+                      Ls: Sequence[torch.Tensor], Rs: Sequence[torch.Tensor]) -> torch.Tensor:
+    """M[(m,l,j),(n,k,i)] = L[m,n,j,k,l] * R[m,n,k,j,i] in token order
+    (Sec. 4.2, tiled factors); hidden tile pairs are zero."""
+    g = geom
+    nq = g.ntq * g.b1 * g.b2
+    nk = g.ntk * g.b1 * g.b2
+    # token index of (tile, row, col)
+    def tok(c2, tile, r, c):
+        a, b = tile // c2, tile % c2
+        return ((a * g.b1 + r) * c2 + b) * g.b2 + c
+    M = torch.zeros(nq, nk, dtype=F64)
+    rows = torch.arange(g.b1)
+    cols = torch.arange(g.b2)
+    for m in range(g.ntq):
+        qtok = tok(g.c2, m, rows[:, None], cols[None, :])        # l j
+        for s, n in enumerate(vis_ids[m].tolist()):
+            ktok = tok(g.c2, n, rows[:, None], cols[None, :])    # k i
+            blk = torch.einsum("jkl,kji->ljki", Ls[m][s], Rs[m][s])
+            M[qtok[:, :, None, None], ktok[None, None, :, :]] = blk
+    return M
+
+
+# --------------------------------------------------------------------------
+# whole-operator front end (same argument meaning as the C ABI, one head)
+# --------------------------------------------------------------------------
+def geometry_from_grid(f_q: int, f_kv: int, h: int, w: int, b1: int, b2: int,
+                       tile: int) -> TileGeometry:
+    if tile == 0:
+        assert f_q == f_kv and b1 == f_q * h and b2 == w
+        return TileGeometry(b1, b2, 1, 1, 1)
+    assert (f_q * h) % b1 == 0 and (f_kv * h) % b1 == 0 and w % b2 == 0
+    return TileGeometry(b1, b2, (f_q * h) // b1, (f_kv * h) // b1, w // b2)
+
+
+def monarch_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, b1: int, b2: int,
+                 tile: int, iters: int, causal_chunk: int = 0, q_frame_offset: int = 0,
+                 scale: float = 1.0) -> torch.Tensor:
+    """One head of the operator the library exports: regular (tile=0, Alg. 1) or
+    tiled (tile=1, Alg. 2) MonarchAttention on (f,h,w) grids."""
+    g = geometry_from_grid(f_q, f_kv, h, w, b1, b2, tile)
+    if tile == 0:
+        assert causal_chunk == 0
+        return monarch_attention_regular(Q, K, V, iters, b1, b2, scale)
+    vis = chunk_causal_visibility(g, h, causal_chunk, q_frame_offset)
+    return monarch_attention_tiled(Q, K, V, iters, g, scale, vis)
+
+
+def dense_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, causal_chunk: int = 0,
+               q_frame_offset: int = 0, scale: float = 1.0) -> torch.Tensor:
+    mask = token_chunk_causal_mask(f_q, f_kv, h, w, causal_chunk, q_frame_offset)
+    return dense_attention(Q, K, V, scale, mask)

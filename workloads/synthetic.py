@@ -1,0 +1,186 @@
+"""Seeded synthetic inputs and the named workload shapes.
+
+This module serves both the CPU oracle's tests and the GPU path's tests and
+benchmark.  It holds NO arithmetic of the attention method: only shapes, random
+draws, rotary position encoding of the inputs, and rounding to the storage
+dtype.  Everything is numpy on the host; callers move the arrays where they
+need them.
+
+The shapes stand in for Self-Forcing / Wan 2.1 activations (Sec. 5, kernel
+latency tables): 480p latent grid h=30, w=52 (1560 tokens per frame), 3-frame
+autoregressive chunks, 21 latent frames for an 81-frame video, 12 heads of 128;
+720p: h=45, w=80.  No model weights or datasets are used.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    batch: int
+    heads: int
+    head_dim: int
+    f_q: int
+    f_kv: int
+    h: int
+    w: int
+    b1: int
+    b2: int
+    tile: int            # 0 regular Monarch, 1 tiled (b1,b2 are tile-local block sizes)
+    iters: int           # T
+    causal_chunk: int    # frames per autoregressive chunk, 0 = no mask
+    q_frame_offset: int  # absolute frame of query frame 0 inside the kv grid
+    dtype: str           # "f32" | "bf16"
+    scale: float         # logits multiplier
+    rope: bool
+    sigma_qk: float = 1.0
+    sigma_v: float = 1.0
+    seed: int = 0
+
+    @property
+    def n_q(self) -> int:
+        return self.f_q * self.h * self.w
+
+    @property
+    def n_kv(self) -> int:
+        return self.f_kv * self.h * self.w
+
+    @property
+    def ntq(self) -> int:
+        return 1 if self.tile == 0 else (self.f_q * self.h // self.b1) * (self.w // self.b2)
+
+    @property
+    def ntk(self) -> int:
+        return 1 if self.tile == 0 else (self.f_kv * self.h // self.b1) * (self.w // self.b2)
+
+
+_INV_SQRT128 = 1.0 / np.sqrt(128.0)
+
+WORKLOADS: Dict[str, Workload] = {
+    # tiny regular Monarch, fp32; inputs already carry 1/sqrt(d)
+    "C0": Workload("C0", 1, 1, 64, 1, 1, 24, 24, 24, 24, 0, 1, 0, 0, "f32", 1.0, False,
+                   sigma_qk=1.0 / 8.0, sigma_v=1.0 / 8.0),
+    # Self-Forcing chunk shape, regular Monarch (f*h, w)
+    "C1": Workload("C1", 1, 12, 128, 3, 3, 30, 52, 90, 52, 0, 2, 0, 0, "bf16", _INV_SQRT128, True),
+    # same tensors, tiled Monarch with tiles (90, 26)
+    "C2": Workload("C2", 1, 12, 128, 3, 3, 30, 52, 90, 26, 1, 2, 0, 0, "bf16", _INV_SQRT128, True),
+    # KV-cache step: last 3-frame chunk against a 21-frame cache
+    "C3": Workload("C3", 1, 12, 128, 3, 21, 30, 52, 90, 26, 1, 2, 3, 18, "bf16", _INV_SQRT128, True),
+    # 720p stress
+    "C4": Workload("C4", 1, 40, 128, 3, 21, 45, 80, 135, 40, 1, 3, 3, 18, "bf16", _INV_SQRT128, True),
+}
+
+
+def variant(name: str, **kw) -> Workload:
+    return replace(WORKLOADS[name], **kw)
+
+
+# --------------------------------------------------------------------------
+# storage rounding
+# --------------------------------------------------------------------------
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest-even bfloat16, returned as fp32 holding exactly those values."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 values that are exactly representable in bf16 -> uint16 bit patterns."""
+    return (np.ascontiguousarray(x, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+# --------------------------------------------------------------------------
+# 3-D rotary position encoding of the inputs (input generation only)
+# --------------------------------------------------------------------------
+def rope_pairs_split(head_dim: int) -> Tuple[int, int, int]:
+    """Rotary pairs assigned to (frame, height, width); 64 pairs -> (22, 21, 21)."""
+    pairs = head_dim // 2
+    ph = pw = pairs // 3
+    return pairs - ph - pw, ph, pw
+
+
+def rope_angles(frames: np.ndarray, h: int, w: int, head_dim: int,
+                theta: float = 10000.0) -> np.ndarray:
+    """angles[token, pair] for tokens in row-major (frame, height, width) order;
+    `frames` holds the absolute frame index of each frame of the grid."""
+    pf, ph, pw = rope_pairs_split(head_dim)
+    fr = np.repeat(np.asarray(frames, dtype=np.float64), h * w)
+    hh = np.tile(np.repeat(np.arange(h, dtype=np.float64), w), len(frames))
+    ww = np.tile(np.arange(w, dtype=np.float64), len(frames) * h)
+    def freqs(n):
+        return theta ** (-np.arange(n, dtype=np.float64) / n)
+    return np.concatenate([fr[:, None] * freqs(pf)[None], hh[:, None] * freqs(ph)[None],
+                           ww[:, None] * freqs(pw)[None]], axis=1)
+
+
+def apply_rope(x: np.ndarray, ang: np.ndarray) -> np.ndarray:
+    """Rotate adjacent element pairs (2p, 2p+1) of x[..., token, d] by ang[token, p]."""
+    c, s = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+    xe, xo = x[..., 0::2], x[..., 1::2]
+    out = np.empty_like(x)
+    out[..., 0::2] = xe * c - xo * s
+    out[..., 1::2] = xe * s + xo * c
+    return out
+
+
+# --------------------------------------------------------------------------
+# generators
+# --------------------------------------------------------------------------
+def _draw(wl: Workload, tensor_id: int, b: int, hd: int, n: int, sigma: float) -> np.ndarray:
+    rng = np.random.default_rng((wl.seed, tensor_id, b, hd))
+    return (sigma * rng.standard_normal((n, wl.head_dim), dtype=np.float32)).astype(np.float32)
+
+
+def make_head(wl: Workload, b: int, hd: int):
+    """Q [n_q,d], K,V [n_kv,d] of one (batch, head) as fp32 arrays whose values are
+    exactly representable in the workload's storage dtype.  Heads are drawn from
+    independent streams keyed by (seed, tensor, batch, head), so any head can be
+    regenerated alone."""
+    Q = _draw(wl, 0, b, hd, wl.n_q, wl.sigma_qk)
+    K = _draw(wl, 1, b, hd, wl.n_kv, wl.sigma_qk)
+    V = _draw(wl, 2, b, hd, wl.n_kv, wl.sigma_v)
+    if wl.rope:
+        Q = apply_rope(Q, rope_angles(wl.q_frame_offset + np.arange(wl.f_q), wl.h, wl.w, wl.head_dim))
+        K = apply_rope(K, rope_angles(np.arange(wl.f_kv), wl.h, wl.w, wl.head_dim))
+    if wl.dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    return Q, K, V
+
+
+def make_inputs(wl: Workload):
+    """All heads: Q [batch, heads, n_q, d], K, V [batch, heads, n_kv, d] (fp32 arrays
+    holding storage-dtype-exact values)."""
+    Q = np.empty((wl.batch, wl.heads, wl.n_q, wl.head_dim), np.float32)
+    K = np.empty((wl.batch, wl.heads, wl.n_kv, wl.head_dim), np.float32)
+    V = np.empty_like(K)
+    for b in range(wl.batch):
+        for hd in range(wl.heads):
+            Q[b, hd], K[b, hd], V[b, hd] = make_head(wl, b, hd)
+    return Q, K, V
+
+
+def make_separable_head(wl: Workload, b: int, hd: int):
+    """Position-only inputs: one constant content vector per tensor, rotated by the
+    3-D rotary encoding.  The logit between two tokens is then a sum of a
+    (frame,height) term and a width term, which an aligned (f*h, w) Monarch
+    structure represents exactly (Sec. 4.1), so MonarchRT must equal dense
+    attention on them.  Values are NOT rounded to bf16 exactly separable any more
+    after storage rounding, so callers compare with a tolerance."""
+    rng = np.random.default_rng((wl.seed, 7, b, hd))
+    q0 = rng.standard_normal(wl.head_dim).astype(np.float32)
+    k0 = rng.standard_normal(wl.head_dim).astype(np.float32)
+    Q = np.broadcast_to(q0, (wl.n_q, wl.head_dim)).copy()
+    K = np.broadcast_to(k0, (wl.n_kv, wl.head_dim)).copy()
+    V = _draw(wl, 2, b, hd, wl.n_kv, 1.0)
+    Q = apply_rope(Q, rope_angles(wl.q_frame_offset + np.arange(wl.f_q), wl.h, wl.w, wl.head_dim))
+    K = apply_rope(K, rope_angles(np.arange(wl.f_kv), wl.h, wl.w, wl.head_dim))
+    if wl.dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    return Q, K, V
