@@ -78,7 +78,7 @@ typedef struct {
  *             to a query tile iff its chunk is not later than the query tile's chunk, hidden
  *             tile pairs take no part at all.  Needs (b1/h) to divide causal_chunk and
  *             q_frame_offset, and tile = 1.
- *   Limits of this build: b1 <= 1024, b2 <= 128. */
+ *   Limits of this build: b1 <= 192, b2 <= 96 (else MRT_ERR_UNSUPPORTED). */
 mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, int iters,
                               int causal_chunk);
 

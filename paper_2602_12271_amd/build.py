@@ -1,0 +1,46 @@
+"""Compile the HIP sources into paper_2602_12271_amd/libmonarchrt.so for gfx950.
+
+    python -m paper_2602_12271_amd.build
+
+hipcc cross-compiles without a GPU.  The library is built in-tree so that it travels
+with the source tree to the machine that runs it.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+SOURCES = ["mrt_api.cpp", "mrt_f32.hip", "mrt_bf16.hip"]
+OUT = os.path.join(HERE, "libmonarchrt.so")
+
+FLAGS = [
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
+    # packed fp32 instructions are kept out of the generated code on this target
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wno-unused-command-line-argument",
+]
+
+
+def build(verbose: bool = True) -> str:
+    cmd = ["hipcc"] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", OUT + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in r.stderr.splitlines()
+                    if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
+    if r.returncode != 0:
+        sys.stderr.write(r.stdout + r.stderr)
+        raise RuntimeError("hipcc failed")
+    if verbose and err.strip():
+        print(err)
+    os.replace(OUT + ".tmp", OUT)
+    return OUT
+
+
+if __name__ == "__main__":
+    build()

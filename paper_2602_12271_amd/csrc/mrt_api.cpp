@@ -1,0 +1,264 @@
+// Host side of the C ABI: argument checks, workspace carving, pass scheduling.
+// No arithmetic of the method happens here; every step runs in the kernels.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "mrt_internal.hpp"
+
+namespace mrt {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+static size_t round256(size_t x) { return (x + 255) & ~size_t(255); }
+
+static mrt_status check_common(const mrt_problem* p) {
+  if (!p) { set_error("problem is NULL"); return MRT_ERR_NULL; }
+  if (p->batch < 1 || p->heads < 1 || p->f_q < 1 || p->f_kv < 1 || p->h < 1 || p->w < 1) {
+    set_error("batch/heads/f_q/f_kv/h/w must be >= 1");
+    return MRT_ERR_SHAPE;
+  }
+  if ((long long)p->batch * p->heads > 65535) {
+    set_error("batch*heads = %lld exceeds 65535", (long long)p->batch * p->heads);
+    return MRT_ERR_SHAPE;
+  }
+  if (p->dtype != MRT_F32 && p->dtype != MRT_BF16) { set_error("unknown dtype"); return MRT_ERR_SHAPE; }
+  if (p->compute != MRT_COMPUTE_DEFAULT && p->compute != MRT_COMPUTE_F32) {
+    set_error("unknown compute mode");
+    return MRT_ERR_SHAPE;
+  }
+  const bool f32 = p->dtype == MRT_F32 || p->compute == MRT_COMPUTE_F32;
+  if (f32) {
+    if (p->head_dim < 1 || p->head_dim > 128) { set_error("head_dim must be 1..128"); return MRT_ERR_SHAPE; }
+  } else if (p->head_dim != 64 && p->head_dim != 128) {
+    set_error("bf16 path needs head_dim 64 or 128, got %d", p->head_dim);
+    return MRT_ERR_SHAPE;
+  }
+  long long nq = (long long)p->f_q * p->h * p->w, nkv = (long long)p->f_kv * p->h * p->w;
+  if (nq > (1 << 24) || nkv > (1 << 24)) { set_error("more than 2^24 tokens per head"); return MRT_ERR_SHAPE; }
+  const mrt_strides* st[4] = {&p->q, &p->k, &p->v, &p->o};
+  for (int t = 0; t < 4; ++t) {
+    if (st[t]->token < p->head_dim || st[t]->head < 1 || st[t]->batch < 1) {
+      set_error("stride set %d: token stride must be >= head_dim, head/batch strides >= 1", t);
+      return MRT_ERR_SHAPE;
+    }
+    // 16-byte vector accesses on the bf16 path need rows aligned to 8 elements
+    if (!f32 && (st[t]->token % 8 || st[t]->head % 8 || st[t]->batch % 8)) {
+      set_error("stride set %d: bf16 path needs strides that are multiples of 8 elements", t);
+      return MRT_ERR_SHAPE;
+    }
+  }
+  if (p->q_frame_offset < 0) { set_error("q_frame_offset < 0"); return MRT_ERR_SHAPE; }
+  if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) { set_error("scale must be positive and finite"); return MRT_ERR_SHAPE; }
+  return MRT_OK;
+}
+
+static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int iters,
+                            int causal_chunk, Plan* out) {
+  mrt_status st = check_common(p);
+  if (st != MRT_OK) return st;
+  if (tile != 0 && tile != 1) { set_error("tile must be 0 or 1"); return MRT_ERR_SHAPE; }
+  if (iters < 1) { set_error("iters must be >= 1"); return MRT_ERR_SHAPE; }
+  if (iters > 64) { set_error("iters > 64"); return MRT_ERR_SHAPE; }
+  if (causal_chunk < 0) { set_error("causal_chunk < 0"); return MRT_ERR_SHAPE; }
+  if (b1 < 1 || b2 < 1) { set_error("block sizes must be >= 1"); return MRT_ERR_BLOCK; }
+  if (b1 > 192 || b2 > 96) {
+    set_error("this build supports b1 <= 192 and b2 <= 96 (got %d, %d)", b1, b2);
+    return MRT_ERR_UNSUPPORTED;
+  }
+  Plan pl;
+  memset(&pl, 0, sizeof(pl));
+  KParams& k = pl.kp;
+  if (tile == 0) {
+    if (p->f_q != p->f_kv) {
+      set_error("regular Monarch needs f_q == f_kv (use tile=1 for a KV cache)");
+      return MRT_ERR_UNSUPPORTED;
+    }
+    if (causal_chunk != 0) { set_error("regular Monarch with a causal mask is not built"); return MRT_ERR_UNSUPPORTED; }
+    if (b1 != p->f_q * p->h || b2 != p->w) {
+      set_error("regular Monarch needs (b1,b2) = (f*h, w) = (%d,%d), got (%d,%d)", p->f_q * p->h, p->w, b1, b2);
+      return MRT_ERR_BLOCK;
+    }
+    k.c2 = 1; k.ntq = 1; k.ntk = 1; k.c1k = 1;
+  } else {
+    if (b1 % p->h != 0) {
+      set_error("tiled Monarch needs b1 to be a whole number of frames (b1 %% h == 0)");
+      return (p->h % b1 == 0 || b1 < p->h) ? MRT_ERR_UNSUPPORTED : MRT_ERR_BLOCK;
+    }
+    if ((p->f_q * p->h) % b1 || (p->f_kv * p->h) % b1 || p->w % b2) {
+      set_error("tile blocks (%d,%d) do not divide the grids (%d|%d rows, %d cols)", b1, b2,
+                p->f_q * p->h, p->f_kv * p->h, p->w);
+      return MRT_ERR_BLOCK;
+    }
+    k.c2 = p->w / b2;
+    k.c1k = (p->f_kv * p->h) / b1;
+    k.ntq = ((p->f_q * p->h) / b1) * k.c2;
+    k.ntk = k.c1k * k.c2;
+  }
+  if (causal_chunk > 0) {
+    int fb = b1 / p->h;
+    if (causal_chunk % fb || p->q_frame_offset % fb) {
+      set_error("a tile (%d frames) must not straddle a causal chunk (%d frames, offset %d)", fb,
+                causal_chunk, p->q_frame_offset);
+      return MRT_ERR_BLOCK;
+    }
+    k.fb = fb; k.cc = causal_chunk; k.qoff = p->q_frame_offset;
+  }
+  k.qs = p->q; k.ks = p->k; k.vs = p->v; k.os = p->o;
+  k.H = p->heads; k.d = p->head_dim; k.b1 = b1; k.b2 = b2; k.w = p->w;
+  k.Nq = p->f_q * p->h * p->w; k.Nkv = p->f_kv * p->h * p->w; k.hw = p->h * p->w;
+  k.scale = p->scale;
+  pl.B = p->batch; pl.T = iters; pl.Nq = k.Nq; pl.Nkv = k.Nkv;
+  pl.dtype = p->dtype; pl.compute = p->compute;
+  const size_t es = pl.f32_path() ? 4 : 2;
+  const size_t rows = (size_t)k.Nq * k.ntk;          // (m, j, nk) triples
+  pl.slab_aL = round256(rows * k.d * es);
+  pl.slab_Y = pl.slab_aL;
+  pl.slab_aR = iters >= 2 ? pl.slab_aL : 0;
+  pl.slab_cL = round256(rows * sizeof(float));
+  *out = pl;
+  return MRT_OK;
+}
+
+// heads per pass the recommended workspace is sized for
+static int recommended_heads_per_pass(const Plan& pl) {
+  const size_t cache_budget = size_t(160) << 20;      // stay inside the 256 MB last-level cache
+  const int BH = pl.B * pl.kp.H;
+  size_t g = cache_budget / pl.slab_bytes();
+  if (g < 1) g = 1;
+  if (g > (size_t)BH) g = BH;
+  return (int)g;
+}
+
+static mrt_status hip_fail(hipError_t e, const char* what) {
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return MRT_ERR_HIP;
+}
+
+}  // namespace mrt
+
+using namespace mrt;
+
+extern "C" {
+
+const char* mrt_status_string(mrt_status s) {
+  switch (s) {
+    case MRT_OK: return "ok";
+    case MRT_ERR_NULL: return "null pointer";
+    case MRT_ERR_SHAPE: return "bad shape or stride";
+    case MRT_ERR_BLOCK: return "block sizes do not fit the grid";
+    case MRT_ERR_UNSUPPORTED: return "not supported by this build";
+    case MRT_ERR_WORKSPACE: return "workspace too small";
+    case MRT_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+const char* mrt_last_error(void) { return g_err; }
+
+mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, int iters,
+                              int causal_chunk) {
+  Plan pl;
+  return make_plan(p, b1, b2, tile, iters, causal_chunk, &pl);
+}
+
+size_t monarch_attn_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
+  Plan pl;
+  if (make_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
+  return pl.slab_bytes();
+}
+
+size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
+  Plan pl;
+  if (make_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
+  return pl.slab_bytes() * recommended_heads_per_pass(pl);
+}
+
+mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
+                            const mrt_problem* p, int b1, int b2, int tile, int iters,
+                            int causal_chunk, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  Plan pl;
+  mrt_status st = make_plan(p, b1, b2, tile, iters, causal_chunk, &pl);
+  if (st != MRT_OK) return st;
+  if (!Q || !K || !V || !O || !workspace) { set_error("Q, K, V, O and workspace must be non-NULL"); return MRT_ERR_NULL; }
+  if ((uintptr_t)workspace % 256) { set_error("workspace must be 256-byte aligned"); return MRT_ERR_WORKSPACE; }
+  if (!pl.f32_path()) {
+    const void* ptrs[4] = {Q, K, V, O};
+    for (const void* q : ptrs)
+      if ((uintptr_t)q % 16) { set_error("bf16 path needs 16-byte aligned tensors"); return MRT_ERR_SHAPE; }
+  }
+  const size_t slab = pl.slab_bytes();
+  if (workspace_bytes < slab) {
+    set_error("workspace has %zu bytes, one (batch,head) needs %zu", workspace_bytes, slab);
+    return MRT_ERR_WORKSPACE;
+  }
+  const int BH = pl.B * pl.kp.H;
+  int G = (int)(workspace_bytes / slab < (size_t)BH ? workspace_bytes / slab : (size_t)BH);
+  hipStream_t s = (hipStream_t)hip_stream;
+
+  KParams kp = pl.kp;
+  kp.Q = Q; kp.K = K; kp.V = V; kp.O = O;
+  char* base = (char*)workspace;
+  kp.aL = base;
+  kp.Y = base + pl.slab_aL * G;
+  kp.aR = base + (pl.slab_aL + pl.slab_Y) * G;
+  kp.cL = (float*)(base + (pl.slab_aL + pl.slab_Y + pl.slab_aR) * G);
+
+  for (int bh0 = 0; bh0 < BH; bh0 += G) {
+    const int nbh = BH - bh0 < G ? BH - bh0 : G;
+    kp.bh0 = bh0;
+    for (int t = 1; t <= pl.T; ++t) {
+      const bool first = t == 1, last = t == pl.T;
+      hipError_t e;
+      if (pl.f32_path()) e = launch_f32_stage_r(kp, pl.dtype, nbh, first, last, s);
+      else e = launch_bf16_stage_r(kp, nbh, first, last, s);
+      if (e != hipSuccess) return hip_fail(e, "stage R launch");
+      if (pl.f32_path()) e = launch_f32_stage_l(kp, pl.dtype, nbh, last, s);
+      else e = launch_bf16_stage_l(kp, nbh, last, s);
+      if (e != hipSuccess) return hip_fail(e, "stage L launch");
+    }
+  }
+  return MRT_OK;
+}
+
+mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk) {
+  mrt_status st = check_common(p);
+  if (st != MRT_OK) return st;
+  if (causal_chunk < 0) { set_error("causal_chunk < 0"); return MRT_ERR_SHAPE; }
+  return MRT_OK;
+}
+
+mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
+                          const mrt_problem* p, int causal_chunk, void* hip_stream) {
+  mrt_status st = dense_attn_check(p, causal_chunk);
+  if (st != MRT_OK) return st;
+  if (!Q || !K || !V || !O) { set_error("Q, K, V and O must be non-NULL"); return MRT_ERR_NULL; }
+  const bool f32 = p->dtype == MRT_F32 || p->compute == MRT_COMPUTE_F32;
+  if (!f32) {
+    const void* ptrs[4] = {Q, K, V, O};
+    for (const void* q : ptrs)
+      if ((uintptr_t)q % 16) { set_error("bf16 path needs 16-byte aligned tensors"); return MRT_ERR_SHAPE; }
+  }
+  KParams kp;
+  memset(&kp, 0, sizeof(kp));
+  kp.Q = Q; kp.K = K; kp.V = V; kp.O = O;
+  kp.qs = p->q; kp.ks = p->k; kp.vs = p->v; kp.os = p->o;
+  kp.H = p->heads; kp.d = p->head_dim; kp.w = p->w;
+  kp.Nq = p->f_q * p->h * p->w; kp.Nkv = p->f_kv * p->h * p->w; kp.hw = p->h * p->w;
+  kp.cc = causal_chunk; kp.qoff = p->q_frame_offset; kp.scale = p->scale;
+  const int BH = p->batch * p->heads;
+  hipError_t e = f32 ? launch_f32_dense(kp, p->dtype, BH, (hipStream_t)hip_stream)
+                     : launch_bf16_dense(kp, BH, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return hip_fail(e, "dense launch");
+  return MRT_OK;
+}
+
+}  // extern "C"
