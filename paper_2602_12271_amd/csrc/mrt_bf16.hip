@@ -1,7 +1,571 @@
-// bf16 MFMA path (placeholder until the kernels land)
+// bf16 MFMA path for gfx950: bf16 operands, fp32 accumulation, fp32 softmax arithmetic.
+//
+// Every contraction runs on v_mfma_f32_16x16x32_bf16.  One wave owns 16 "query" rows and keeps
+// them as the B operand (N side) of the logit product, so that a logit column -- everything
+// the softmax of one query needs -- lives in one lane column (lane & 15) of the accumulators:
+//
+//   S^T[i, q] = sum_v Key[i, v] Qry[q, v]        A = Key rows from LDS, B = Qry rows in registers
+//   lane (g = lane>>4, c = lane&15), register r of tile t holds S^T[16t + 4g + r, c]
+//
+// Row max / row sum are then in-lane reductions plus two cross-lane steps (xor 16, xor 32).
+// The probabilities stay in registers: a lane's 8 values of two adjacent tiles are exactly the
+// B operand of the second product once the contraction slots of group g are read as
+// key = 32s + 16(e/4) + 4g + (e%4), e = 0..7:
+//
+//   Out^T[v, q] = sum_i Val^T[v, i] P^T[i, q]    A = Val read transposed from row-major LDS
+//
+// The A operand of that product needs, per lane, 8 different LDS rows of one column; gfx950's
+// ds_read_b64_tr_b16 delivers exactly that from row-major tiles (lane c of a 16-lane group
+// receives column c of the 4 rows addressed by the group), so no transposed copy is staged.
+// Output rows of the second product are permuted (phi below) so that each lane ends up with 8
+// consecutive features and stores 16 bytes.
+//
+// Stages (App. A.1 / A.2 update equations):
+//   stage R      one workgroup per (m, n, k): Z_R, R = softmax_i, c_L, alpha_L = R K, Y = R V
+//   stage L out  one workgroup per (m, j): flash loop over nk: L = softmax(Z_L), O = L Y
+//   stage L ref  one workgroup per (m, j): log-sum-exp pass over nk, then alpha_R / c_R
 #include "mrt_internal.hpp"
+
 namespace mrt {
-hipError_t launch_bf16_stage_r(const KParams&, int, bool, bool, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_bf16_stage_l(const KParams&, int, bool, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_bf16_dense(const KParams&, int, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef unsigned short u16;
+
+constexpr int kPad = 16;   // bf16 elements of padding per LDS row: row stride = 8 banks mod 64
+
+__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ inline bf16x8 ld_global_16B(const u16* p) { return as_bf16x8(*(const uint4*)p); }
+
+__device__ inline bf16x8 ld_lds_16B(const u16* p) { return as_bf16x8(*(const uint4*)p); }
+
+// transposed LDS read: the 16 lanes of a group address 4 rows x 16 columns (lane s -> row s/4,
+// columns 4(s%4)..+3); lane c receives column c of those 4 rows.
+__device__ inline s16x4 ld_lds_tr(const u16* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
 }
+
+__device__ inline u16 f2bf(float x) { return __builtin_bit_cast(u16, (__bf16)x); }
+
+__device__ inline bf16x8 pack8(f32x4 a, f32x4 b) {
+  bf16x8 r;
+  r[0] = (__bf16)a[0]; r[1] = (__bf16)a[1]; r[2] = (__bf16)a[2]; r[3] = (__bf16)a[3];
+  r[4] = (__bf16)b[0]; r[5] = (__bf16)b[1]; r[6] = (__bf16)b[2]; r[7] = (__bf16)b[3];
+  return r;
+}
+
+__device__ inline f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ inline float xmax(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ inline float xsum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+
+// Second product for one 32-key step: acc[vt] += Val^T[phi(vt, .), keys] * P.
+// vals points at LDS row `32*step` of a row-major [rows][D + kPad] tile; output feature of
+// accumulator row (4g + r) of tile vt is phi = 32(vt/2) + 8g + 4(vt%2) + r.
+template <int D>
+__device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane) {
+  constexpr int LD = D + kPad;
+  const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
+  const u16* base = vals + (4 * g + e) * LD + 8 * q;
+#pragma unroll
+  for (int vt = 0; vt < D / 16; ++vt) {
+    const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+    s16x4 lo = ld_lds_tr(p0);
+    s16x4 hi = ld_lds_tr(p0 + 16 * LD);
+    s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    acc[vt] = mfma(__builtin_bit_cast(bf16x8, a), pb, acc[vt]);
+  }
+}
+
+// Store a lane's D/16 accumulator tiles (scaled) as bf16: 16 bytes per pair of tiles at
+// feature 32q + 8g.
+template <int D>
+__device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) {
+#pragma unroll
+  for (int q = 0; q < D / 32; ++q) {
+    bf16x8 o = pack8(acc[2 * q] * mul, acc[2 * q + 1] * mul);
+    *(uint4*)(row + 32 * q + 8 * g) = __builtin_bit_cast(uint4, o);
+  }
+}
+
+// Cooperative copy of `rows` rows of D bf16 (row r at src + r*stride) into a row-major LDS tile,
+// zero-filling rows >= valid.
+template <int D>
+__device__ inline void stage_rows(u16* dst, const u16* src, long long stride, int rows, int valid,
+                                  int tid, int nthr) {
+  constexpr int CPR = D / 8, LD = D + kPad;
+  for (int idx = tid; idx < rows * CPR; idx += nthr) {
+    const int r = idx / CPR, c = idx - r * CPR;
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (r < valid) v = *(const uint4*)(src + (long long)r * stride + 8 * c);
+    *(uint4*)(dst + r * LD + 8 * c) = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// stage R
+// ---------------------------------------------------------------------------------------
+template <int NT, int D, bool FIRST, bool LAST>
+__global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
+  constexpr int LD = D + kPad, KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
+  constexpr int NTHR = 64 * NT;
+  __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];
+  __shared__ __attribute__((aligned(16))) u16 Vs[LAST ? ROWS * LD : 8];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int nk = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int n = nk / b1, k = nk - n * b1;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int an = n / p.c2, bn = n - an * p.c2;
+  if (an >= visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff)) return;
+  const int b = bh / p.H, hd = bh - b * p.H;
+
+  const long long qtok0 = (long long)(a * b1 + k) * p.w + bq * b2;
+  const long long ktok0 = (long long)(an * b1 + k) * p.w + bn * b2;
+  const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + ktok0 * p.ks.token;
+  const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + ktok0 * p.vs.token;
+  const size_t NKtot = (size_t)p.ntk * b1;
+
+  stage_rows<D>(Ks, Kp, p.ks.token, ROWS, b2, tid, NTHR);
+  if (LAST) stage_rows<D>(Vs, Vp, p.vs.token, ROWS, b2, tid, NTHR);
+
+  // query-side rows of this wave (row j = 16*wave + c), straight to registers
+  const int j = 16 * wave + c;
+  const int jc = j < b2 ? j : b2 - 1;
+  const u16* arow;
+  if (FIRST) {
+    arow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + (qtok0 + jc) * p.qs.token;
+  } else {
+    arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + m) * NKtot + nk) * b2 + jc) * D;
+  }
+  bf16x8 qv[KS1];
+#pragma unroll
+  for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(arow + 32 * ks + 8 * g);
+  __syncthreads();
+
+  // Z_R^T tiles
+  f32x4 s[NT];
+#pragma unroll
+  for (int it = 0; it < NT; ++it) {
+    s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks)
+      s[it] = mfma(ld_lds_16B(Ks + (16 * it + c) * LD + 32 * ks + 8 * g), qv[ks], s[it]);
+  }
+  // softmax over i (rows of the tiles) for column j, and sum_i R log R
+  float mx = -INFINITY;
+#pragma unroll
+  for (int it = 0; it < NT; ++it)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const bool ok = 16 * it + 4 * g + r < b2;
+      const float z = ok ? s[it][r] * p.scale : -INFINITY;
+      s[it][r] = z;
+      mx = fmaxf(mx, z);
+    }
+  mx = xmax(mx);
+  float sum = 0.f, ent = 0.f;
+#pragma unroll
+  for (int it = 0; it < NT; ++it)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const bool ok = 16 * it + 4 * g + r < b2;
+      const float z = ok ? s[it][r] - mx : 0.f;
+      const float e = ok ? __expf(z) : 0.f;
+      sum += e;
+      ent = fmaf(e, z, ent);
+      s[it][r] = e;
+    }
+  sum = xsum(sum);
+  ent = xsum(ent);
+  const float inv = 1.0f / sum;
+  if (g == 0 && j < b2)
+    p.cL[(((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk] = ent * inv - __logf(sum);
+
+  // alpha_L = R K (and Y = R V)
+  f32x4 oK[NVT], oV[LAST ? NVT : 1];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) {
+    oK[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if constexpr (LAST) oV[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int st = 0; st < KS2; ++st) {
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f32x4 lo = s[2 * st] * inv;
+    const f32x4 hi = (2 * st + 1 < NT) ? s[(2 * st + 1 < NT) ? 2 * st + 1 : 0] * inv : zero;
+    const bf16x8 pb = pack8(lo, hi);
+    pv_step<D>(Ks + 32 * st * LD, pb, oK, lane);
+    if constexpr (LAST) pv_step<D>(Vs + 32 * st * LD, pb, oV, lane);
+  }
+  if (j < b2) {
+    const size_t row = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk;
+    store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
+    if constexpr (LAST) store_rows<D>((u16*)p.Y + row * D, oV, 1.0f, g);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// flash loop shared by stage L (out), stage L (refine, pass 1) and the dense baseline
+// ---------------------------------------------------------------------------------------
+constexpr int kCK = 64;   // keys per LDS chunk (two 32-key steps)
+
+struct FlashState {
+  float mrun, lrun;   // running max (reduced over the column) and this lane's partial sum
+};
+
+// One 64-key chunk: logits against the wave's 16 queries, online softmax update; when
+// WITH_V also rescales and accumulates the output tiles.
+// bias[i] is added to the scaled logit of key i (-inf for keys beyond the end); kchunk[i] >
+// qchunk hides key i from this lane's query.
+template <int D, bool WITH_V>
+__device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bias,
+                                   const int* kchunk, int qchunk, const bf16x8* qv, float scale,
+                                   FlashState& st, f32x4* o, int lane) {
+  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+  const int g = lane >> 4, c = lane & 15;
+  f32x4 s[4];
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks)
+      s[it] = mfma(ld_lds_16B(Kc + (16 * it + c) * LD + 32 * ks + 8 * g), qv[ks], s[it]);
+  }
+  float cm = -INFINITY;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const f32x4 bi = *(const f32x4*)(bias + 16 * it + 4 * g);
+    const int4 kc = *(const int4*)(kchunk + 16 * it + 4 * g);
+    const int kcs[4] = {kc.x, kc.y, kc.z, kc.w};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float z = fmaf(s[it][r], scale, bi[r]);
+      if (kcs[r] > qchunk) z = -INFINITY;
+      s[it][r] = z;
+      cm = fmaxf(cm, z);
+    }
+  }
+  cm = xmax(cm);
+  const float mnew = fmaxf(st.mrun, cm);
+  // mnew == -inf only if every key so far is hidden from this query: keep the state empty
+  const float msafe = mnew == -INFINITY ? 0.f : mnew;
+  const float alpha = __expf(st.mrun - msafe);   // mrun = -inf -> 0
+  float ps = 0.f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float e = __expf(s[it][r] - msafe);
+      s[it][r] = e;
+      ps += e;
+    }
+  st.lrun = fmaf(st.lrun, alpha, ps);
+  st.mrun = mnew;
+  if (WITH_V) {
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[vt] = o[vt] * alpha;
+    pv_step<D>(Vc, pack8(s[0], s[1]), o, lane);
+    pv_step<D>(Vc + 32 * LD, pack8(s[2], s[3]), o, lane);
+  }
+}
+
+// stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
+template <int D>
+__global__ __launch_bounds__(768) void k_bf16_stage_l_out(KParams p) {
+  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+  __shared__ __attribute__((aligned(16))) u16 Kc[kCK * LD];
+  __shared__ __attribute__((aligned(16))) u16 Vc[kCK * LD];
+  __shared__ __attribute__((aligned(16))) float bias[kCK];
+  __shared__ __attribute__((aligned(16))) int kch[kCK];
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int j = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+
+  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const int l = 16 * wave + c;
+  const int lc = l < b1 ? l : b1 - 1;
+  const u16* qrow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head +
+                    (qtok0 + (long long)lc * p.w) * p.qs.token;
+  bf16x8 qv[KS1];
+#pragma unroll
+  for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
+
+  const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const u16* Yp = (const u16*)p.Y + row0 * D;
+  const float* cLp = p.cL + row0;
+
+  FlashState st{-INFINITY, 0.f};
+  f32x4 o[NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (tid < kCK) kch[tid] = 0;
+  for (int c0 = 0; c0 < NK; c0 += kCK) {
+    const int valid = NK - c0 < kCK ? NK - c0 : kCK;
+    __syncthreads();
+    stage_rows<D>(Kc, aLp + (size_t)c0 * D, D, kCK, valid, tid, nthr);
+    stage_rows<D>(Vc, Yp + (size_t)c0 * D, D, kCK, valid, tid, nthr);
+    if (tid < kCK) bias[tid] = tid < valid ? -cLp[c0 + tid] : -INFINITY;
+    __syncthreads();
+    flash_chunk<D, true>(Kc, Vc, bias, kch, 0, qv, p.scale, st, o, lane);
+  }
+  const float lsum = xsum(st.lrun);
+  if (l < b1) {
+    u16* orow = (u16*)p.O + b * p.os.batch + hd * p.os.head +
+                (qtok0 + (long long)l * p.w) * p.os.token;
+    store_rows<D>(orow, o, 1.0f / lsum, g);
+  }
+}
+
+// stage L, earlier iterations:
+//   alpha_R[m, nk, j, :] / c_R[m, nk, j] = sum_l L[l, nk] Q[m, l, j, :] / sum_l L[l, nk]
+// with L = softmax_nk(Z_L).  Pass 1 finds the log-sum-exp of every row l (flash loop without
+// values); pass 2 recomputes Z_L one 16-wide nk tile per wave with l on the M side, forms
+// softmax over l of log L[l, nk] (the same ratio, safe against underflow) and contracts with Q
+// read transposed from LDS.
+constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
+
+template <int D>
+__global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrows) {
+  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u16* Qs = (u16*)smem;                          // [qrows][LD], rows >= b1 zero
+  u16* Kc = Qs + (size_t)qrows * LD;             // [kCK][LD]
+  float* bias = (float*)(Kc + kCK * LD);         // [kCK]
+  int* kch = (int*)(bias + kCK);                 // [kCK]
+  float* lse = (float*)(kch + kCK);              // [16 * kMaxLT]
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int nlt = (b1 + 15) >> 4;
+  const int j = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+
+  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
+  if (tid < kCK) kch[tid] = 0;
+
+  const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const float* cLp = p.cL + row0;
+
+  // ---- pass 1: wave w owns l tile w
+  {
+    const int l = 16 * wave + c;
+    const int lc = l < b1 ? l : b1 - 1;
+    const u16* qrow = Qp + (long long)lc * p.w * p.qs.token;
+    bf16x8 qv[KS1];
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
+    FlashState st{-INFINITY, 0.f};
+    for (int c0 = 0; c0 < NK; c0 += kCK) {
+      const int valid = NK - c0 < kCK ? NK - c0 : kCK;
+      __syncthreads();
+      stage_rows<D>(Kc, aLp + (size_t)c0 * D, D, kCK, valid, tid, nthr);
+      if (tid < kCK) bias[tid] = tid < valid ? -cLp[c0 + tid] : -INFINITY;
+      __syncthreads();
+      if (wave < nlt) flash_chunk<D, false>(Kc, nullptr, bias, kch, 0, qv, p.scale, st, nullptr, lane);
+    }
+    const float lsum = xsum(st.lrun);
+    if (wave < nlt && g == 0) lse[l] = st.mrun + __logf(lsum);
+  }
+  __syncthreads();
+
+  // ---- pass 2: waves stride over nk tiles
+  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + m) * NKtot * b2 * D;
+  const int ntiles = (NK + 15) >> 4;
+  for (int t = wave; t < ntiles; t += nwaves) {
+    const int nk = 16 * t + c;
+    const int nkc = nk < NK ? nk : NK - 1;
+    bf16x8 kb[KS1];
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) kb[ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
+    const float cl = cLp[nkc];
+    f32x4 z[kMaxLT];
+    float cmax = -INFINITY;
+#pragma unroll
+    for (int lt = 0; lt < kMaxLT; ++lt) {
+      if (lt < nlt) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks)
+          acc = mfma(ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g), kb[ks], acc);
+        const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool ok = 16 * lt + 4 * g + r < b1;
+          const float w = ok ? fmaf(acc[r], p.scale, -cl) - ls[r] : -INFINITY;   // log L[l, nk]
+          acc[r] = w;
+          cmax = fmaxf(cmax, w);
+        }
+        z[lt] = acc;
+      }
+    }
+    cmax = xmax(cmax);
+    float csum = 0.f;
+#pragma unroll
+    for (int lt = 0; lt < kMaxLT; ++lt) {
+      if (lt < nlt) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float e = __expf(z[lt][r] - cmax);
+          z[lt][r] = e;
+          csum += e;
+        }
+      }
+    }
+    csum = xsum(csum);
+    f32x4 o[NVT];
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st2 = 0; st2 < kMaxLT / 2; ++st2) {
+      if (2 * st2 < nlt) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        const f32x4 hi = (2 * st2 + 1 < nlt) ? z[2 * st2 + 1] : zero;
+        pv_step<D>(Qs + 32 * st2 * LD, pack8(z[2 * st2], hi), o, lane);
+      }
+    }
+    if (nk < NK) store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o, 1.0f / csum, g);
+  }
+}
+
+// dense baseline: 64 queries per workgroup (16 per wave), flash loop over all visible keys
+template <int D>
+__global__ __launch_bounds__(256) void k_bf16_dense(KParams p) {
+  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+  __shared__ __attribute__((aligned(16))) u16 Kc[kCK * LD];
+  __shared__ __attribute__((aligned(16))) u16 Vc[kCK * LD];
+  __shared__ __attribute__((aligned(16))) float bias[kCK];
+  __shared__ __attribute__((aligned(16))) int kch[kCK];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int q0 = blockIdx.x * 64, bh = blockIdx.y;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const int qi = q0 + 16 * wave + c;
+  const int qc = qi < p.Nq ? qi : p.Nq - 1;
+  const u16* qrow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + (long long)qc * p.qs.token;
+  bf16x8 qv[KS1];
+#pragma unroll
+  for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
+  const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head;
+  const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head;
+  int qchunk = 0x7fffffff, nkeys = p.Nkv;
+  if (p.cc > 0) {
+    qchunk = (p.qoff + qc / p.hw) / p.cc;
+    const int qlast = (q0 + 63 < p.Nq ? q0 + 63 : p.Nq - 1);
+    const long long lim = (long long)((p.qoff + qlast / p.hw) / p.cc + 1) * p.cc * p.hw;
+    if (lim < nkeys) nkeys = (int)lim;
+  }
+  FlashState st{-INFINITY, 0.f};
+  f32x4 o[NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < nkeys; c0 += kCK) {
+    const int valid = nkeys - c0 < kCK ? nkeys - c0 : kCK;
+    __syncthreads();
+    stage_rows<D>(Kc, Kp + (long long)c0 * p.ks.token, p.ks.token, kCK, valid, tid, 256);
+    stage_rows<D>(Vc, Vp + (long long)c0 * p.vs.token, p.vs.token, kCK, valid, tid, 256);
+    if (tid < kCK) {
+      bias[tid] = tid < valid ? 0.f : -INFINITY;
+      kch[tid] = p.cc > 0 ? ((c0 + tid) / p.hw) / p.cc : 0;
+    }
+    __syncthreads();
+    flash_chunk<D, true>(Kc, Vc, bias, kch, qchunk, qv, p.scale, st, o, lane);
+  }
+  const float lsum = xsum(st.lrun);
+  if (qi < p.Nq) {
+    u16* orow = (u16*)p.O + b * p.os.batch + hd * p.os.head + (long long)qi * p.os.token;
+    store_rows<D>(orow, o, lsum > 0.f ? 1.0f / lsum : 0.f, g);
+  }
+}
+
+template <int NT, int D>
+hipError_t launch_r(const KParams& kp, dim3 grid, bool first, bool last, hipStream_t s) {
+  if (first && last) k_bf16_stage_r<NT, D, true, true><<<grid, 64 * NT, 0, s>>>(kp);
+  else if (first) k_bf16_stage_r<NT, D, true, false><<<grid, 64 * NT, 0, s>>>(kp);
+  else if (last) k_bf16_stage_r<NT, D, false, true><<<grid, 64 * NT, 0, s>>>(kp);
+  else k_bf16_stage_r<NT, D, false, false><<<grid, 64 * NT, 0, s>>>(kp);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_r_d(const KParams& kp, dim3 grid, bool first, bool last, hipStream_t s) {
+  switch ((kp.b2 + 15) / 16) {
+    case 1: return launch_r<1, D>(kp, grid, first, last, s);
+    case 2: return launch_r<2, D>(kp, grid, first, last, s);
+    case 3: return launch_r<3, D>(kp, grid, first, last, s);
+    case 4: return launch_r<4, D>(kp, grid, first, last, s);
+    case 5: return launch_r<5, D>(kp, grid, first, last, s);
+    case 6: return launch_r<6, D>(kp, grid, first, last, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s) {
+  dim3 grid(kp.ntk * kp.b1, kp.ntq, nbh);
+  return kp.d == 128 ? launch_r_d<128>(kp, grid, first, last, s)
+                     : launch_r_d<64>(kp, grid, first, last, s);
+}
+
+hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_t s) {
+  dim3 grid(kp.b2, kp.ntq, nbh);
+  const int nlt = (kp.b1 + 15) / 16;
+  if (nlt > kMaxLT) return hipErrorInvalidValue;
+  if (last) {
+    if (kp.d == 128) k_bf16_stage_l_out<128><<<grid, 64 * nlt, 0, s>>>(kp);
+    else k_bf16_stage_l_out<64><<<grid, 64 * nlt, 0, s>>>(kp);
+    return hipGetLastError();
+  }
+  const int qrows = 32 * ((nlt + 1) / 2);
+  const int LD = kp.d + kPad;
+  const size_t lds = ((size_t)qrows * LD + (size_t)kCK * LD) * 2 + kCK * 8 + 16 * kMaxLT * 4;
+  hipError_t e;
+  if (kp.d == 128) {
+    if (lds > 64 * 1024 &&
+        (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<128>,
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+      return e;
+    k_bf16_stage_l_refine<128><<<grid, 64 * nlt, lds, s>>>(kp, qrows);
+  } else {
+    k_bf16_stage_l_refine<64><<<grid, 64 * nlt, lds, s>>>(kp, qrows);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_bf16_dense(const KParams& kp, int nbh, hipStream_t s) {
+  dim3 grid((kp.Nq + 63) / 64, nbh);
+  if (kp.d == 128) k_bf16_dense<128><<<grid, 256, 0, s>>>(kp);
+  else k_bf16_dense<64><<<grid, 256, 0, s>>>(kp);
+  return hipGetLastError();
+}
+
+}  // namespace mrt

@@ -1,0 +1,161 @@
+"""GPU parity of the bf16 MFMA path against the fp64 oracle, through the C ABI.
+
+Bar: max-abs <= 2e-2 on bf16 inputs with fp32 accumulation, for outputs of magnitude <= 1.
+bf16 rounding is relative (2^-9 per rounding of P, alpha_L, Y, alpha_R and O, compounding over
+the iterations), so for the stress cases whose outputs exceed 1 the bar scales with the oracle's
+largest output: tol = 2e-2 * max(1, max|O|).  Because the named workloads produce outputs of
+magnitude ~0.05 (their softmaxes average many N(0,1) values), the tests also require the error
+to stay below a fraction of the oracle's largest output, so a wrong result cannot hide under
+the absolute bar.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_12271_amd as pkg
+from workloads import synthetic as syn
+
+from gpu_harness import (compare_heads, oracle_dense_head, run_dense_gpu, run_monarch_gpu, to_device)
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+REL_BF16 = 4e-2        # of max |O_oracle|
+
+
+def small_bf16(**kw):
+    base = dict(name="small", batch=1, heads=2, head_dim=128, dtype="bf16", rope=False,
+                scale=128 ** -0.5, sigma_qk=1.0, sigma_v=1.0)
+    base.update(kw)
+    return syn.Workload(**base)
+
+
+SMALL = {
+    # one 16-tile per block, single chunk
+    "reg-16x16": small_bf16(f_q=1, f_kv=1, h=16, w=16, b1=16, b2=16, tile=0, iters=1,
+                            causal_chunk=0, q_frame_offset=0),
+    # ragged tiles on both sides, three iterations
+    "reg-ragged": small_bf16(batch=2, heads=3, f_q=2, f_kv=2, h=11, w=21, b1=22, b2=21, tile=0,
+                             iters=3, causal_chunk=0, q_frame_offset=0),
+    # head_dim 64
+    "reg-d64": small_bf16(head_dim=64, scale=0.125, f_q=2, f_kv=2, h=9, w=37, b1=18, b2=37,
+                          tile=0, iters=2, causal_chunk=0, q_frame_offset=0),
+    # tiled, rectangular, chunk-causal with hidden chunks; nk range spans several 64-key chunks
+    "tiled-rect-mask": small_bf16(f_q=2, f_kv=8, h=10, w=28, b1=20, b2=14, tile=1, iters=2,
+                                  causal_chunk=2, q_frame_offset=4),
+    # sharper logits (sigma ~ 3): near one-hot softmaxes, outputs of magnitude ~1
+    "tiled-sharp": small_bf16(f_q=2, f_kv=4, h=8, w=24, b1=16, b2=12, tile=1, iters=3,
+                              causal_chunk=0, q_frame_offset=0, sigma_qk=1.7),
+    # b2 = 1 and b1 = 1 degenerate blocks
+    "tiled-b2-1": small_bf16(f_q=2, f_kv=2, h=5, w=3, b1=5, b2=1, tile=1, iters=2,
+                             causal_chunk=0, q_frame_offset=0),
+    "tiled-b1-1": small_bf16(f_q=3, f_kv=3, h=1, w=40, b1=1, b2=20, tile=1, iters=2,
+                             causal_chunk=0, q_frame_offset=0),
+    # largest block sizes of this build
+    "max-blocks": small_bf16(heads=1, f_q=2, f_kv=2, h=96, w=96, b1=192, b2=96, tile=0, iters=2,
+                             causal_chunk=0, q_frame_offset=0),
+}
+
+
+def check(wl, arrays, O, heads=None, oracle=None, label=""):
+    kw = {} if oracle is None else {"oracle": oracle}
+    err, omax = compare_heads(wl, arrays, O, heads=heads, **kw)
+    print(f"  {label}: max|gpu-oracle| = {err:.3e}, max|O| = {omax:.3e}, ratio {err / omax:.3e}",
+          flush=True)
+    assert err <= TOL_BF16 * max(1.0, omax)
+    assert err <= REL_BF16 * omax + 1e-3
+    return err, omax
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_monarch_bf16_small(name):
+    wl = SMALL[name]
+    arrays = syn.make_inputs(wl)
+    print(f"case {name}", flush=True)
+    O = run_monarch_gpu(wl, *to_device(wl, arrays))
+    check(wl, arrays, O, label=name)
+
+
+@pytest.mark.parametrize("name", ["reg-ragged", "tiled-rect-mask", "tiled-sharp", "reg-d64"])
+def test_dense_bf16_small(name):
+    wl = SMALL[name]
+    arrays = syn.make_inputs(wl)
+    O = run_dense_gpu(wl, *to_device(wl, arrays))
+    check(wl, arrays, O, oracle=oracle_dense_head, label="dense " + name)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_monarch_bf16_named_configs_full(name):
+    """Full named configurations, every head, every output element, in the launch
+    configuration the benchmark times (default workspace)."""
+    wl = syn.WORKLOADS[name]
+    arrays = syn.make_inputs(wl)
+    print(f"config {name}", flush=True)
+    O = run_monarch_gpu(wl, *to_device(wl, arrays))
+    check(wl, arrays, O, label=name)
+
+
+def test_monarch_bf16_c3_hidden_chunks():
+    # the named KV-cache configuration has every chunk visible; move the query chunk back so
+    # that 3 of 7 chunks are hidden and the mask path is exercised at full size
+    wl = syn.variant("C3", q_frame_offset=9)
+    arrays = syn.make_inputs(wl)
+    O = run_monarch_gpu(wl, *to_device(wl, arrays))
+    check(wl, arrays, O, heads=[0, 5, 11], label="C3 offset 9")
+
+
+@pytest.mark.timeout(600)
+def test_monarch_bf16_c4_sampled_heads():
+    wl = syn.WORKLOADS["C4"]
+    arrays = syn.make_inputs(wl)
+    print("config C4 (40 heads on the GPU, 2 heads through the oracle)", flush=True)
+    O = run_monarch_gpu(wl, *to_device(wl, arrays))
+    assert torch.isfinite(O.float()).all()
+    check(wl, arrays, O, heads=[0, 39], label="C4")
+
+
+@pytest.mark.parametrize("name", ["C1", "C3"])
+def test_dense_bf16_named_configs_sampled(name):
+    wl = syn.WORKLOADS[name]
+    arrays = syn.make_inputs(wl)
+    O = run_dense_gpu(wl, *to_device(wl, arrays))
+    check(wl, arrays, O, heads=[0, wl.heads - 1], oracle=oracle_dense_head, label="dense " + name)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_separable_inputs_monarch_equals_dense(name):
+    """Position-only inputs (a constant vector under 3-D rotary encoding) have logits that split
+    into a (frame,height) term plus a width term, which the aligned structure represents exactly
+    (Sec. 4.1): the MonarchRT kernels and the dense kernel must agree, and both match the dense
+    oracle."""
+    wl = syn.variant(name, heads=2)
+    Q = np.empty((1, wl.heads, wl.n_q, wl.head_dim), np.float32)
+    K = np.empty((1, wl.heads, wl.n_kv, wl.head_dim), np.float32)
+    V = np.empty_like(K)
+    for hd in range(wl.heads):
+        Q[0, hd], K[0, hd], V[0, hd] = syn.make_separable_head(wl, 0, hd)
+    dev = to_device(wl, (Q, K, V))
+    Om = run_monarch_gpu(wl, *dev)
+    Od = run_dense_gpu(wl, *dev)
+    diff = (Om.float() - Od.float()).abs().max().item()
+    print(f"  separable {name}: max|monarch - dense| on GPU = {diff:.3e}", flush=True)
+    assert diff <= TOL_BF16
+    check(wl, (Q, K, V), Om, heads=[0], oracle=oracle_dense_head, label="separable vs dense oracle")
+
+
+def test_f32_compute_on_bf16_storage_matches_oracle_tighter():
+    # device-side cross-check mode: fp32 arithmetic on bf16 inputs; only the final store rounds
+    wl = SMALL["tiled-sharp"]
+    arrays = syn.make_inputs(wl)
+    O = run_monarch_gpu(wl, *to_device(wl, arrays), compute=pkg.MRT_COMPUTE_F32)
+    err, omax = compare_heads(wl, arrays, O)
+    print(f"  fp32 compute on bf16 storage: err {err:.3e} max|O| {omax:.3e}", flush=True)
+    assert err <= omax * 2 ** -8 + 1e-5
+
+
+def test_rerun_is_bit_identical():
+    wl = syn.variant("C2", heads=2)
+    dev = to_device(wl, syn.make_inputs(wl))
+    O1 = run_monarch_gpu(wl, *dev)
+    O2 = run_monarch_gpu(wl, *dev)
+    assert torch.equal(O1, O2)
