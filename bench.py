@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the MonarchRT attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C1]
+
+One "step" is one whole monarch_attn_fwd call (all 2T kernels of App. A's iteration plus the
+output product) on one batch of seeded synthetic inputs that are already resident in HBM.
+Prints ONE JSON line: the headline metric (ms per call at the 4680x4680, 12-head Self-Forcing
+chunk shape), the roofline of the dominant kernel (duration measured with HIP events recorded
+by the library around every launch), the in-library dense baseline, and the fp64 CPU oracle
+timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "MonarchRT attention ms/call + % MFMA/HBM roofline at 4680x4680, 12 heads"
+PEAK_MFMA_BF16 = 2.5e15      # FLOP/s, dense bf16 MFMA, MI355X published
+PEAK_HBM = 8.0e12            # B/s, MI355X published
+
+# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (summaries under profiles/); bytes.  None until measured for a workload.
+MEASURED_TRAFFIC = {}
+
+
+def visible_pairs(wl):
+    """sum over query tiles of their visible key tiles (tile-level chunk-causal reading)."""
+    if wl.tile == 0:
+        return 1
+    c2 = wl.w // wl.b2
+    c1q, c1k = wl.f_q * wl.h // wl.b1, wl.f_kv * wl.h // wl.b1
+    total = 0
+    for a in range(c1q):
+        rows = c1k
+        if wl.causal_chunk:
+            fb = wl.b1 // wl.h
+            q_chunk = (wl.q_frame_offset + a * fb) // wl.causal_chunk
+            rows = min(c1k, (q_chunk + 1) * wl.causal_chunk // fb)
+        total += c2 * rows * c2
+    return total
+
+
+def kernel_models(wl, es):
+    """Algorithmic FLOPs and bytes of every launch of one call, in launch order.
+
+    Per visible tile pair, with n_t = b1*b2 tokens per tile: the R-side products (beta_R,
+    alpha_L, Y) cost n_t*b2*d MACs each, the L-side products (beta_L, alpha_R or the output) cost
+    n_t*b1*d MACs each.  Bytes count every operand and result of the launch once: the alpha_L /
+    Y / alpha_R intermediates (n_t*d elements per pair), c_L (4 bytes per (pair, j, k)), and the
+    Q / K / V / O tensors touched."""
+    H = wl.batch * wl.heads
+    P = visible_pairs(wl)
+    nt, d = wl.b1 * wl.b2, wl.head_dim
+    inter = H * P * nt * d * es
+    cl = H * P * nt * 4
+    qb, ob = H * wl.n_q * d * es, H * wl.n_q * d * es
+    # visible key tokens (union over query tiles) -- all query tiles of the named workloads share it
+    kb = H * (P // max(1, wl.ntq)) * nt * d * es
+    out = []
+    for t in range(1, wl.iters + 1):
+        first, last = t == 1, t == wl.iters
+        fl = 2 * H * P * nt * wl.b2 * d * (3 if last else 2)
+        by = (qb if first else inter) + kb + inter + cl + ((kb + inter) if last else 0)
+        out.append(dict(name="stage_R" + ("_first" if first else "") + ("_last" if last else ""),
+                        kind=1 | (16 if first else 0) | (32 if last else 0), flops=fl, bytes=by))
+        fl = 2 * H * P * nt * wl.b1 * d * 2
+        by = inter + cl + qb + ((inter + ob) if last else inter)
+        out.append(dict(name="stage_L_out" if last else "stage_L_refine",
+                        kind=2 | (32 if last else 0), flops=fl, bytes=by))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(heads are independent and would shard without exchange, see DESIGN.md).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2602_12271_amd as pkg
+    from paper_2602_12271_amd import binding
+    from workloads import synthetic as syn
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    lib = pkg.load_library()          # raises if the HIP library is missing: no fallback
+    wl = syn.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    es = 4 if wl.dtype == "f32" else 2
+    Qh, Kh, Vh = syn.make_inputs(wl)
+    Q, K, V = (torch.from_numpy(x).to(dev).to(tdt) for x in (Qh, Kh, Vh))
+    O = torch.empty_like(Q)
+    prob = binding._torch_problem(Q, K, V, O, wl.f_q, wl.f_kv, wl.h, wl.w, wl.q_frame_offset,
+                                  wl.scale, pkg.MRT_COMPUTE_DEFAULT)
+    nws = pkg.monarch_attn_workspace_bytes(prob, wl.b1, wl.b2, wl.tile, wl.iters)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    pq, pk, pv, po, pw = Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), ws.data_ptr()
+    pref = ctypes.byref(prob)
+
+    def step():
+        st = lib.monarch_attn_fwd(pq, pk, pv, po, pref, wl.b1, wl.b2, wl.tile, wl.iters,
+                                  wl.causal_chunk, pw, nws, stream)
+        if st != 0:
+            raise RuntimeError(f"monarch_attn_fwd failed: {pkg.last_error()}")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per-kernel durations (HIP events recorded by the library around every launch)
+    pkg.binding.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    recs = pkg.binding.profile_read()
+    pkg.binding.profile_enable(False)
+    models = kernel_models(wl, es)
+    per_call = len(recs) // args.steps
+    passes = per_call // len(models)           # head groups per call
+    kernels = []
+    for i, mdl in enumerate(models):
+        # launch order inside a call: for each pass, the 2T kernels in order
+        tot = 0.0
+        for s in range(args.steps):
+            for g in range(passes):
+                ms, kind = recs[s * per_call + g * len(models) + i]
+                assert kind == mdl["kind"], (kind, mdl)
+                tot += ms
+        dur = tot / args.steps / 1e3           # seconds per call spent in this kernel (all passes)
+        kernels.append(dict(name=mdl["name"], launches_per_call=passes, ms_per_call=dur * 1e3,
+                            gflop=mdl["flops"] / 1e9, mbytes=mdl["bytes"] / 1e6,
+                            tflops=mdl["flops"] / dur / 1e12, gbps=mdl["bytes"] / dur / 1e9,
+                            frac_mfma=mdl["flops"] / dur / PEAK_MFMA_BF16,
+                            frac_hbm=mdl["bytes"] / dur / PEAK_HBM))
+    dom = max(kernels, key=lambda k: k["ms_per_call"])
+    dmodel = next(m for m in models if m["name"] == dom["name"])
+    hbm_bound = dmodel["bytes"] / PEAK_HBM >= dmodel["flops"] / PEAK_MFMA_BF16
+    launch_s = dom["ms_per_call"] / 1e3 / dom["launches_per_call"]
+    if hbm_bound:
+        ach = dmodel["bytes"] / dom["launches_per_call"] / launch_s / 1e9
+        roof = dict(bound="hbm", achieved=ach, peak=PEAK_HBM / 1e9, unit="GB/s", frac=ach / (PEAK_HBM / 1e9))
+    else:
+        ach = dmodel["flops"] / dom["launches_per_call"] / launch_s / 1e12
+        roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_BF16 / 1e12, unit="TFLOP/s",
+                    frac=ach / (PEAK_MFMA_BF16 / 1e12))
+    roof.update(kernel=dom["name"], launch_us=launch_s * 1e6,
+                traffic=MEASURED_TRAFFIC.get((wl.name, dom["name"])))
+    tot_flops = sum(m["flops"] for m in models)
+    compulsory = (wl.batch * wl.heads) * (2 * wl.n_q + 2 * wl.n_kv) * wl.head_dim * es
+
+    # ---- dense baseline in the same library, same inputs
+    dense_ms = None
+    if not args.no_dense:
+        Od = torch.empty_like(Q)
+        def dstep():
+            st = lib.dense_attn_fwd(pq, pk, pv, Od.data_ptr(), pref, wl.causal_chunk, stream)
+            if st != 0:
+                raise RuntimeError(f"dense_attn_fwd failed: {pkg.last_error()}")
+        nd = max(3, min(args.steps, 20))
+        for _ in range(2):
+            dstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(nd):
+            dstep()
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - t0) * 1e3 / nd
+
+    # ---- CPU oracle on the host cores (a reported baseline, not the target) + parity spot check
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import monarch_oracle as mo
+        def oracle_head(hd):
+            return mo.monarch_attn(torch.from_numpy(Qh[0, hd]), torch.from_numpy(Kh[0, hd]),
+                                   torch.from_numpy(Vh[0, hd]), f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h,
+                                   w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile, iters=wl.iters,
+                                   causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+                                   scale=wl.scale)
+        ref0 = oracle_head(0)                       # also warms the CPU libraries up
+        parity = (O[0, 0].float().cpu().double() - ref0).abs().max().item()
+        heads_run, t_acc, budget = 0, 0.0, 15.0
+        t0 = time.perf_counter()
+        while heads_run < wl.heads and (time.perf_counter() - t0) < budget:
+            oracle_head(heads_run)
+            heads_run += 1
+        t_acc = time.perf_counter() - t0
+        cpu = dict(value=t_acc / heads_run * wl.heads * 1e3, unit="ms/call",
+                   cores=torch.get_num_threads(), kind="oracle",
+                   sample=f"{heads_run} of {wl.heads} heads of {wl.name} in {t_acc:.1f} s, "
+                          f"scaled to all heads (heads are independent)")
+
+    out = {
+        "metric": METRIC, "value": ms_per_step, "unit": "ms/call", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.heads} heads x d{wl.head_dim}, grid ({wl.f_q}|{wl.f_kv},"
+                               f"{wl.h},{wl.w}), N_q={wl.n_q}, N_kv={wl.n_kv}, "
+                               f"{'tiled' if wl.tile else 'regular'} Monarch ({wl.b1},{wl.b2}), T={wl.iters}, "
+                               f"causal_chunk={wl.causal_chunk}",
+                   "scale": wl.scale, "workspace_mb": nws / 1e6, "heads_per_pass": (wl.batch * wl.heads + passes - 1) // passes},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "whole_call": {"algorithmic_gflop": tot_flops / 1e9, "tflops": tot_flops / (ms_per_step / 1e3) / 1e12,
+                       "frac_mfma": tot_flops / (ms_per_step / 1e3) / PEAK_MFMA_BF16,
+                       "compulsory_mbytes": compulsory / 1e6,
+                       "frac_hbm_compulsory": compulsory / (ms_per_step / 1e3) / PEAK_HBM,
+                       "sum_kernel_ms": sum(k["ms_per_call"] for k in kernels)},
+        "kernels": kernels,
+        "dense_baseline_ms": dense_ms,
+        "speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
+        "parity_max_abs_err_head0": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

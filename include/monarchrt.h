@@ -109,6 +109,18 @@ mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk);
 mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
                           const mrt_problem* p, int causal_chunk, void* hip_stream);
 
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the two entry points
+ * above is bracketed by a pair of HIP events recorded on the call's stream (this is the only
+ * mode in which the library creates HIP objects).  mrt_profile_read waits for the recorded
+ * events, writes up to `capacity` (elapsed milliseconds, kernel kind) pairs in launch order,
+ * forgets them and returns how many it wrote.  Kernel kind = one of MRT_KERNEL_STAGE_R /
+ * MRT_KERNEL_STAGE_L / MRT_KERNEL_DENSE, or-ed with MRT_KERNEL_FIRST (first iteration: alpha_R
+ * is Q itself) and MRT_KERNEL_LAST (last iteration: stage R also forms Y, stage L forms O). */
+enum { MRT_KERNEL_STAGE_R = 1, MRT_KERNEL_STAGE_L = 2, MRT_KERNEL_DENSE = 4,
+       MRT_KERNEL_FIRST = 16, MRT_KERNEL_LAST = 32 };
+void mrt_profile_enable(int on);
+int mrt_profile_read(float* ms, int* kind, int capacity);
+
 const char* mrt_status_string(mrt_status s);
 
 /* Text of the last error detail recorded on the calling thread ("" if none). */

@@ -4,6 +4,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "mrt_internal.hpp"
 
 namespace mrt {
@@ -137,6 +140,27 @@ static int recommended_heads_per_pass(const Plan& pl) {
   return (int)g;
 }
 
+// ---- optional per-kernel timing (benchmarks only) --------------------------------------
+struct ProfRecord { hipEvent_t a, b; int kind; };
+static bool g_prof_on = false;
+static std::vector<ProfRecord> g_prof;
+static std::mutex g_prof_mu;
+
+struct ProfScope {
+  hipStream_t s; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
+  ProfScope(hipStream_t s_, int kind_) : s(s_), kind(kind_), on(g_prof_on) {
+    if (!on) return;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(a, s);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(b, s);
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof.push_back({a, b, kind});
+  }
+};
+
 static mrt_status hip_fail(hipError_t e, const char* what) {
   set_error("%s: %s", what, hipGetErrorString(e));
   return MRT_ERR_HIP;
@@ -218,11 +242,17 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
     for (int t = 1; t <= pl.T; ++t) {
       const bool first = t == 1, last = t == pl.T;
       hipError_t e;
-      if (pl.f32_path()) e = launch_f32_stage_r(kp, pl.dtype, nbh, first, last, s);
-      else e = launch_bf16_stage_r(kp, nbh, first, last, s);
+      {
+        ProfScope ps(s, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0));
+        if (pl.f32_path()) e = launch_f32_stage_r(kp, pl.dtype, nbh, first, last, s);
+        else e = launch_bf16_stage_r(kp, nbh, first, last, s);
+      }
       if (e != hipSuccess) return hip_fail(e, "stage R launch");
-      if (pl.f32_path()) e = launch_f32_stage_l(kp, pl.dtype, nbh, last, s);
-      else e = launch_bf16_stage_l(kp, nbh, last, s);
+      {
+        ProfScope ps(s, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0));
+        if (pl.f32_path()) e = launch_f32_stage_l(kp, pl.dtype, nbh, last, s);
+        else e = launch_bf16_stage_l(kp, nbh, last, s);
+      }
       if (e != hipSuccess) return hip_fail(e, "stage L launch");
     }
   }
@@ -255,10 +285,33 @@ mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
   kp.Nq = p->f_q * p->h * p->w; kp.Nkv = p->f_kv * p->h * p->w; kp.hw = p->h * p->w;
   kp.cc = causal_chunk; kp.qoff = p->q_frame_offset; kp.scale = p->scale;
   const int BH = p->batch * p->heads;
-  hipError_t e = f32 ? launch_f32_dense(kp, p->dtype, BH, (hipStream_t)hip_stream)
-                     : launch_bf16_dense(kp, BH, (hipStream_t)hip_stream);
+  hipError_t e;
+  {
+    ProfScope ps((hipStream_t)hip_stream, MRT_KERNEL_DENSE);
+    e = f32 ? launch_f32_dense(kp, p->dtype, BH, (hipStream_t)hip_stream)
+            : launch_bf16_dense(kp, BH, (hipStream_t)hip_stream);
+  }
   if (e != hipSuccess) return hip_fail(e, "dense launch");
   return MRT_OK;
+}
+
+void mrt_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+}
+
+int mrt_profile_read(float* ms, int* kind, int capacity) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  int n = 0;
+  for (ProfRecord& r : g_prof) {
+    float t = -1.f;
+    if (hipEventSynchronize(r.b) == hipSuccess) (void)hipEventElapsedTime(&t, r.a, r.b);
+    if (n < capacity) { ms[n] = t; kind[n] = r.kind; ++n; }
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  g_prof.clear();
+  return n;
 }
 
 }  // extern "C"
