@@ -87,9 +87,9 @@ mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, in
  * L and R, have to live in device memory).  Returns 0 if the arguments are invalid. */
 size_t monarch_attn_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 
-/* Recommended workspace: enough (batch, head) slabs per pass to fill the GPU while the
- * intermediates of a pass still fit the last-level cache.  Any size between the minimum and
- * batch*heads slabs is accepted; the library processes as many heads per pass as fit. */
+/* Recommended workspace: one slab per (batch, head), capped at 8 GiB.  Any size from the
+ * minimum up is accepted; the library processes as many heads per pass as fit, and fewer heads
+ * per pass means fewer workgroups per launch. */
 size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 
 /* MonarchRT attention forward (Alg. 1 for tile = 0, Alg. 2 for tile = 1).

@@ -132,9 +132,12 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
 
 // heads per pass the recommended workspace is sized for
 static int recommended_heads_per_pass(const Plan& pl) {
-  const size_t cache_budget = size_t(160) << 20;      // stay inside the 256 MB last-level cache
+  // Measured on MI355X: more (batch, head) slabs per pass always won over keeping a pass inside
+  // the 256 MB last-level cache (stage L has only ntq*b2 workgroups per head), so the only cap
+  // is a bound on the workspace itself.
+  const size_t budget = size_t(8) << 30;
   const int BH = pl.B * pl.kp.H;
-  size_t g = cache_budget / pl.slab_bytes();
+  size_t g = budget / pl.slab_bytes();
   if (g < 1) g = 1;
   if (g > (size_t)BH) g = BH;
   return (int)g;

@@ -77,16 +77,24 @@ __device__ inline float xsum(float x) {
 // accumulator row (4g + r) of tile vt is phi = 32(vt/2) + 8g + 4(vt%2) + r.
 template <int D>
 __device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane) {
-  constexpr int LD = D + kPad;
+  constexpr int LD = D + kPad, NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
   const u16* base = vals + (4 * g + e) * LD + 8 * q;
 #pragma unroll
-  for (int vt = 0; vt < D / 16; ++vt) {
-    const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
-    s16x4 lo = ld_lds_tr(p0);
-    s16x4 hi = ld_lds_tr(p0 + 16 * LD);
-    s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    acc[vt] = mfma(__builtin_bit_cast(bf16x8, a), pb, acc[vt]);
+  for (int h = 0; h < 2; ++h) {
+    s16x4 lo[HALF], hi[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const int vt = h * HALF + i;
+      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+      lo[i] = ld_lds_tr(p0);
+      hi[i] = ld_lds_tr(p0 + 16 * LD);
+    }
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      s16x8 a = __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7);
+      acc[h * HALF + i] = mfma(__builtin_bit_cast(bf16x8, a), pb, acc[h * HALF + i]);
+    }
   }
 }
 
@@ -223,16 +231,49 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
 // flash loop shared by stage L (out), stage L (refine, pass 1) and the dense baseline
 // ---------------------------------------------------------------------------------------
 constexpr int kCK = 64;   // keys per LDS chunk (two 32-key steps)
+constexpr int kMinThreads = 256;   // the chunk copy below assumes at least this many threads
 
 struct FlashState {
   float mrun, lrun;   // running max (reduced over the column) and this lane's partial sum
 };
 
+// One 64-row chunk of D bf16 held in registers between its global load and its LDS commit, so
+// that the load of chunk c+1 is in flight while chunk c is being consumed.
+template <int D>
+struct ChunkRegs {
+  static constexpr int CPR = D / 8, TOTAL = kCK * CPR, N = (TOTAL + kMinThreads - 1) / kMinThreads;
+  uint4 v[N];
+  int valid;
+  // Loads are unconditional (rows beyond `nvalid` re-read the last valid row) so that nothing
+  // has to wait for them before the commit; the commit zero-fills the rows that do not exist.
+  __device__ inline void load(const u16* src, long long stride, int nvalid, int tid, int nthr) {
+    valid = nvalid;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      int idx = tid + i * nthr;
+      idx = idx < TOTAL ? idx : TOTAL - 1;
+      int r = idx / CPR;
+      const int c = idx - r * CPR;
+      r = r < nvalid ? r : nvalid - 1;
+      v[i] = *(const uint4*)(src + (long long)r * stride + 8 * c);
+    }
+  }
+  __device__ inline void commit(u16* dst, int tid, int nthr) const {
+    constexpr int LD = D + kPad;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int idx = tid + i * nthr;
+      const int r = idx / CPR, c = idx - r * CPR;
+      if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
+    }
+  }
+};
+
 // One 64-key chunk: logits against the wave's 16 queries, online softmax update; when
 // WITH_V also rescales and accumulates the output tiles.
-// bias[i] is added to the scaled logit of key i (-inf for keys beyond the end); kchunk[i] >
-// qchunk hides key i from this lane's query.
-template <int D, bool WITH_V>
+// bias[i] is added to the scaled logit of key i (-inf for keys beyond the end); when MASKED,
+// kchunk[i] > qchunk hides key i from this lane's query.
+template <int D, bool WITH_V, bool MASKED>
 __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bias,
                                    const int* kchunk, int qchunk, const bf16x8* qv, float scale,
                                    FlashState& st, f32x4* o, int lane) {
@@ -240,22 +281,35 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
   const int g = lane >> 4, c = lane & 15;
   f32x4 s[4];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < 4; ++it) s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // two key tiles at a time: all their operand reads are issued before the first MFMA, and
+  // consecutive MFMAs alternate between independent accumulators
+#pragma unroll
+  for (int ip = 0; ip < 2; ++ip) {
+    bf16x8 a[2][KS1];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks)
+        a[t][ks] = ld_lds_16B(Kc + (16 * (2 * ip + t) + c) * LD + 32 * ks + 8 * g);
 #pragma unroll
     for (int ks = 0; ks < KS1; ++ks)
-      s[it] = mfma(ld_lds_16B(Kc + (16 * it + c) * LD + 32 * ks + 8 * g), qv[ks], s[it]);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) s[2 * ip + t] = mfma(a[t][ks], qv[ks], s[2 * ip + t]);
   }
   float cm = -INFINITY;
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const f32x4 bi = *(const f32x4*)(bias + 16 * it + 4 * g);
-    const int4 kc = *(const int4*)(kchunk + 16 * it + 4 * g);
-    const int kcs[4] = {kc.x, kc.y, kc.z, kc.w};
+    int kcs[4] = {0, 0, 0, 0};
+    if (MASKED) {
+      const int4 kc = *(const int4*)(kchunk + 16 * it + 4 * g);
+      kcs[0] = kc.x; kcs[1] = kc.y; kcs[2] = kc.z; kcs[3] = kc.w;
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float z = fmaf(s[it][r], scale, bi[r]);
-      if (kcs[r] > qchunk) z = -INFINITY;
+      if (MASKED && kcs[r] > qchunk) z = -INFINITY;
       s[it][r] = z;
       cm = fmaxf(cm, z);
     }
@@ -263,7 +317,7 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
   cm = xmax(cm);
   const float mnew = fmaxf(st.mrun, cm);
   // mnew == -inf only if every key so far is hidden from this query: keep the state empty
-  const float msafe = mnew == -INFINITY ? 0.f : mnew;
+  const float msafe = (MASKED && mnew == -INFINITY) ? 0.f : mnew;
   const float alpha = __expf(st.mrun - msafe);   // mrun = -inf -> 0
   float ps = 0.f;
 #pragma unroll
@@ -284,14 +338,69 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
   }
 }
 
+// LDS layout of the double-buffered chunk pipeline
+template <int D, bool WITH_V>
+struct FlashLds {
+  static constexpr int LD = D + kPad;
+  static constexpr size_t kBytes = (size_t)2 * kCK * LD * 2 * (WITH_V ? 2 : 1) + 2 * kCK * 8;
+  u16* k0;
+  u16* v0;
+  float* b0;
+  int* c0;
+  __device__ inline explicit FlashLds(unsigned char* base) {
+    u16* p = (u16*)base;
+    k0 = p; p += 2 * kCK * LD;
+    v0 = p; if (WITH_V) p += 2 * kCK * LD;
+    b0 = (float*)p;
+    c0 = (int*)(b0 + 2 * kCK);
+  }
+  __device__ inline u16* K(int buf) const { return k0 + buf * (kCK * LD); }
+  __device__ inline u16* V(int buf) const { return v0 + buf * (kCK * LD); }
+  __device__ inline float* bias(int buf) const { return b0 + buf * kCK; }
+  __device__ inline int* kch(int buf) const { return c0 + buf * kCK; }
+};
+
+// The streaming loop: keys [0, nkeys) of a row-major key array (and value array), 64 at a time,
+// software-pipelined over two LDS buffers with one barrier per chunk.  meta(key) fetches the
+// value whose negative is the key's bias, and the chunk id of the key.  Waves with active == false only help copying.
+template <int D, bool WITH_V, bool MASKED, typename Meta>
+__device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
+                                  long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V>& lds,
+                                  const bf16x8* qv, float scale, int qchunk, bool active,
+                                  FlashState& st, f32x4* o, int tid, int nthr, int lane) {
+  ChunkRegs<D> rk, rv;
+  float rb = 0.f;    // raw per-key value fetched by meta(); turned into the bias at commit time
+  int rc = 0, rvalid = 0;
+  auto fetch = [&](int c0) {
+    const int valid = nkeys - c0 < kCK ? nkeys - c0 : kCK;
+    rk.load(kbase + (long long)c0 * kstride, kstride, valid, tid, nthr);
+    if (WITH_V) rv.load(vbase + (long long)c0 * vstride, vstride, valid, tid, nthr);
+    rvalid = valid;
+    if (tid < kCK) meta(c0 + (tid < valid ? tid : valid - 1), rb, rc);
+  };
+  fetch(0);
+  int buf = 0;
+  for (int c0 = 0; c0 < nkeys; c0 += kCK, buf ^= 1) {
+    rk.commit(lds.K(buf), tid, nthr);
+    if (WITH_V) rv.commit(lds.V(buf), tid, nthr);
+    if (tid < kCK) {
+      lds.bias(buf)[tid] = tid < rvalid ? -rb : -INFINITY;
+      if (MASKED) lds.kch(buf)[tid] = rc;
+    }
+    __syncthreads();
+    if (c0 + kCK < nkeys) fetch(c0 + kCK);
+    if (active)
+      flash_chunk<D, WITH_V, MASKED>(lds.K(buf), lds.V(buf), lds.bias(buf), lds.kch(buf), qchunk, qv,
+                                     scale, st, o, lane);
+  }
+}
+
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
 template <int D>
 __global__ __launch_bounds__(768) void k_bf16_stage_l_out(KParams p) {
-  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
-  __shared__ __attribute__((aligned(16))) u16 Kc[kCK * LD];
-  __shared__ __attribute__((aligned(16))) u16 Vc[kCK * LD];
-  __shared__ __attribute__((aligned(16))) float bias[kCK];
-  __shared__ __attribute__((aligned(16))) int kch[kCK];
+  constexpr int KS1 = D / 32, NVT = D / 16;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
+  FlashLds<D, true> lds(smem);
 
   const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
@@ -321,16 +430,9 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_out(KParams p) {
 #pragma unroll
   for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (tid < kCK) kch[tid] = 0;
-  for (int c0 = 0; c0 < NK; c0 += kCK) {
-    const int valid = NK - c0 < kCK ? NK - c0 : kCK;
-    __syncthreads();
-    stage_rows<D>(Kc, aLp + (size_t)c0 * D, D, kCK, valid, tid, nthr);
-    stage_rows<D>(Vc, Yp + (size_t)c0 * D, D, kCK, valid, tid, nthr);
-    if (tid < kCK) bias[tid] = tid < valid ? -cLp[c0 + tid] : -INFINITY;
-    __syncthreads();
-    flash_chunk<D, true>(Kc, Vc, bias, kch, 0, qv, p.scale, st, o, lane);
-  }
+  auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
+  flash_loop<D, true, false>(aLp, D, Yp, D, NK, meta, lds, qv, p.scale, 0, 16 * wave < b1, st, o, tid,
+                      nthr, lane);
   const float lsum = xsum(st.lrun);
   if (l < b1) {
     u16* orow = (u16*)p.O + b * p.os.batch + hd * p.os.head +
@@ -351,11 +453,9 @@ template <int D>
 __global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrows) {
   constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  u16* Qs = (u16*)smem;                          // [qrows][LD], rows >= b1 zero
-  u16* Kc = Qs + (size_t)qrows * LD;             // [kCK][LD]
-  float* bias = (float*)(Kc + kCK * LD);         // [kCK]
-  int* kch = (int*)(bias + kCK);                 // [kCK]
-  float* lse = (float*)(kch + kCK);              // [16 * kMaxLT]
+  FlashLds<D, false> lds(smem);
+  u16* Qs = (u16*)(smem + FlashLds<D, false>::kBytes);   // [qrows][LD], rows >= b1 zero
+  float* lse = (float*)(Qs + (size_t)qrows * LD);        // [16 * kMaxLT]
 
   const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
@@ -370,7 +470,6 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrow
   const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
-  if (tid < kCK) kch[tid] = 0;
 
   const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
@@ -385,29 +484,34 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrow
 #pragma unroll
     for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
     FlashState st{-INFINITY, 0.f};
-    for (int c0 = 0; c0 < NK; c0 += kCK) {
-      const int valid = NK - c0 < kCK ? NK - c0 : kCK;
-      __syncthreads();
-      stage_rows<D>(Kc, aLp + (size_t)c0 * D, D, kCK, valid, tid, nthr);
-      if (tid < kCK) bias[tid] = tid < valid ? -cLp[c0 + tid] : -INFINITY;
-      __syncthreads();
-      if (wave < nlt) flash_chunk<D, false>(Kc, nullptr, bias, kch, 0, qv, p.scale, st, nullptr, lane);
-    }
+    auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
+    flash_loop<D, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, p.scale, 0, wave < nlt, st, nullptr,
+                         tid, nthr, lane);
     const float lsum = xsum(st.lrun);
     if (wave < nlt && g == 0) lse[l] = st.mrun + __logf(lsum);
   }
   __syncthreads();
 
-  // ---- pass 2: waves stride over nk tiles
+  // ---- pass 2: waves stride over nk tiles; the next tile's operands are fetched while the
+  // current one is processed
   u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + m) * NKtot * b2 * D;
   const int ntiles = (NK + 15) >> 4;
-  for (int t = wave; t < ntiles; t += nwaves) {
+  bf16x8 kb[KS1], kbn[KS1];
+  float cl = 0.f, cln = 0.f;
+  auto fetch = [&](int t, bf16x8* dst, float& cdst) {
     const int nk = 16 * t + c;
     const int nkc = nk < NK ? nk : NK - 1;
-    bf16x8 kb[KS1];
 #pragma unroll
-    for (int ks = 0; ks < KS1; ++ks) kb[ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
-    const float cl = cLp[nkc];
+    for (int ks = 0; ks < KS1; ++ks) dst[ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
+    cdst = cLp[nkc];
+  };
+  if (wave < ntiles) fetch(wave, kbn, cln);
+  for (int t = wave; t < ntiles; t += nwaves) {
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) kb[ks] = kbn[ks];
+    cl = cln;
+    if (t + nwaves < ntiles) fetch(t + nwaves, kbn, cln);
+    const int nk = 16 * t + c;
     f32x4 z[kMaxLT];
     float cmax = -INFINITY;
 #pragma unroll
@@ -460,11 +564,9 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrow
 // dense baseline: 64 queries per workgroup (16 per wave), flash loop over all visible keys
 template <int D>
 __global__ __launch_bounds__(256) void k_bf16_dense(KParams p) {
-  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
-  __shared__ __attribute__((aligned(16))) u16 Kc[kCK * LD];
-  __shared__ __attribute__((aligned(16))) u16 Vc[kCK * LD];
-  __shared__ __attribute__((aligned(16))) float bias[kCK];
-  __shared__ __attribute__((aligned(16))) int kch[kCK];
+  constexpr int KS1 = D / 32, NVT = D / 16;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
+  FlashLds<D, true> lds(smem);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int q0 = blockIdx.x * 64, bh = blockIdx.y;
   const int b = bh / p.H, hd = bh - b * p.H;
@@ -487,18 +589,10 @@ __global__ __launch_bounds__(256) void k_bf16_dense(KParams p) {
   f32x4 o[NVT];
 #pragma unroll
   for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int c0 = 0; c0 < nkeys; c0 += kCK) {
-    const int valid = nkeys - c0 < kCK ? nkeys - c0 : kCK;
-    __syncthreads();
-    stage_rows<D>(Kc, Kp + (long long)c0 * p.ks.token, p.ks.token, kCK, valid, tid, 256);
-    stage_rows<D>(Vc, Vp + (long long)c0 * p.vs.token, p.vs.token, kCK, valid, tid, 256);
-    if (tid < kCK) {
-      bias[tid] = tid < valid ? 0.f : -INFINITY;
-      kch[tid] = p.cc > 0 ? ((c0 + tid) / p.hw) / p.cc : 0;
-    }
-    __syncthreads();
-    flash_chunk<D, true>(Kc, Vc, bias, kch, qchunk, qv, p.scale, st, o, lane);
-  }
+  const int cc = p.cc, hw = p.hw;
+  auto meta = [&](int key, float& raw, int& chunk) { raw = 0.f; chunk = cc > 0 ? (key / hw) / cc : 0; };
+  flash_loop<D, true, true>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, p.scale, qchunk, true,
+                      st, o, tid, 256, lane);
   const float lsum = xsum(st.lrun);
   if (qi < p.Nq) {
     u16* orow = (u16*)p.O + b * p.os.batch + hd * p.os.head + (long long)qi * p.os.token;
@@ -540,23 +634,25 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   dim3 grid(kp.b2, kp.ntq, nbh);
   const int nlt = (kp.b1 + 15) / 16;
   if (nlt > kMaxLT) return hipErrorInvalidValue;
+  const int nthr = 64 * (nlt < 4 ? 4 : nlt);   // the chunk copy needs >= 256 threads
+  hipError_t e;
   if (last) {
-    if (kp.d == 128) k_bf16_stage_l_out<128><<<grid, 64 * nlt, 0, s>>>(kp);
-    else k_bf16_stage_l_out<64><<<grid, 64 * nlt, 0, s>>>(kp);
+    if (kp.d == 128) k_bf16_stage_l_out<128><<<grid, nthr, 0, s>>>(kp);
+    else k_bf16_stage_l_out<64><<<grid, nthr, 0, s>>>(kp);
     return hipGetLastError();
   }
   const int qrows = 32 * ((nlt + 1) / 2);
   const int LD = kp.d + kPad;
-  const size_t lds = ((size_t)qrows * LD + (size_t)kCK * LD) * 2 + kCK * 8 + 16 * kMaxLT * 4;
-  hipError_t e;
+  const size_t lds = (kp.d == 128 ? FlashLds<128, false>::kBytes : FlashLds<64, false>::kBytes) +
+                     (size_t)qrows * LD * 2 + 16 * kMaxLT * 4;
   if (kp.d == 128) {
     if (lds > 64 * 1024 &&
         (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<128>,
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
       return e;
-    k_bf16_stage_l_refine<128><<<grid, 64 * nlt, lds, s>>>(kp, qrows);
+    k_bf16_stage_l_refine<128><<<grid, nthr, lds, s>>>(kp, qrows);
   } else {
-    k_bf16_stage_l_refine<64><<<grid, 64 * nlt, lds, s>>>(kp, qrows);
+    k_bf16_stage_l_refine<64><<<grid, nthr, lds, s>>>(kp, qrows);
   }
   return hipGetLastError();
 }
