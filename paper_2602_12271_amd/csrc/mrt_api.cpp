@@ -143,6 +143,18 @@ static int recommended_heads_per_pass(const Plan& pl) {
   return (int)g;
 }
 
+#ifdef MRT_TRACE
+hipError_t set_trace_buffer(void* buf, hipStream_t s);
+static char* g_trace_base = nullptr;
+static size_t g_trace_stride = 0;
+static int g_trace_next = 0;
+static void trace_next_launch(hipStream_t s) {
+  if (g_trace_base) (void)set_trace_buffer(g_trace_base + g_trace_stride * (g_trace_next++), s);
+}
+#else
+static inline void trace_next_launch(hipStream_t) {}
+#endif
+
 // ---- optional per-kernel timing (benchmarks only) --------------------------------------
 struct ProfRecord { hipEvent_t a, b; int kind; };
 static bool g_prof_on = false;
@@ -245,12 +257,14 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
     for (int t = 1; t <= pl.T; ++t) {
       const bool first = t == 1, last = t == pl.T;
       hipError_t e;
+      trace_next_launch(s);
       {
         ProfScope ps(s, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0));
         if (pl.f32_path()) e = launch_f32_stage_r(kp, pl.dtype, nbh, first, last, s);
         else e = launch_bf16_stage_r(kp, nbh, first, last, s);
       }
       if (e != hipSuccess) return hip_fail(e, "stage R launch");
+      trace_next_launch(s);
       {
         ProfScope ps(s, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0));
         if (pl.f32_path()) e = launch_f32_stage_l(kp, pl.dtype, nbh, last, s);
@@ -297,6 +311,15 @@ mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
   if (e != hipSuccess) return hip_fail(e, "dense launch");
   return MRT_OK;
 }
+
+#ifdef MRT_TRACE
+int mrt_debug_set_trace(void* buf, size_t stride_bytes) {
+  mrt::g_trace_base = (char*)buf;
+  mrt::g_trace_stride = stride_bytes;
+  mrt::g_trace_next = 0;
+  return 0;
+}
+#endif
 
 void mrt_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -36,6 +36,22 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef unsigned short u16;
 
+// Optional timeline instrumentation (development builds only, -DMRT_TRACE): thread 0 of every
+// workgroup stamps the 100 MHz wall clock at phase boundaries into a caller-provided buffer.
+#ifdef MRT_TRACE
+__device__ unsigned long long* g_trace_buf = nullptr;
+#define MRT_STAMP(slot)                                                                          \
+  do {                                                                                           \
+    if (threadIdx.x == 0 && g_trace_buf) {                                                       \
+      const size_t wg = ((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;  \
+      g_trace_buf[wg * 8 + (slot)] = wall_clock64();                                             \
+      if ((slot) == 0) g_trace_buf[wg * 8 + 7] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11)) | ((unsigned long long)__builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11)) << 32); \
+    }                                                                                            \
+  } while (0)
+#else
+#define MRT_STAMP(slot) do { } while (0)
+#endif
+
 constexpr int kPad = 16;   // bf16 elements of padding per LDS row: row stride = 8 banks mod 64
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -98,6 +114,34 @@ __device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane)
   }
 }
 
+// Same for NB probability operands sharing every value-side LDS read (operands >= nb idle).
+template <int D, int NB>
+__device__ inline void pv_step_multi(const u16* vals, const bf16x8 (&pb)[NB], int nb,
+                                     f32x4 (&acc)[NB][D / 16], int lane) {
+  constexpr int LD = D + kPad, NVT = D / 16, HALF = NVT / 2;
+  const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
+  const u16* base = vals + (4 * g + e) * LD + 8 * q;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    s16x4 lo[HALF], hi[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const int vt = h * HALF + i;
+      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+      lo[i] = ld_lds_tr(p0);
+      hi[i] = ld_lds_tr(p0 + 16 * LD);
+    }
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const bf16x8 av =
+          __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        if (b < nb) acc[b][h * HALF + i] = mfma(av, pb[b], acc[b][h * HALF + i]);
+    }
+  }
+}
+
 // Store a lane's D/16 accumulator tiles (scaled) as bf16: 16 bytes per pair of tiles at
 // feature 32q + 8g.
 template <int D>
@@ -148,6 +192,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + ktok0 * p.vs.token;
   const size_t NKtot = (size_t)p.ntk * b1;
 
+  MRT_STAMP(0);
   stage_rows<D>(Ks, Kp, p.ks.token, ROWS, b2, tid, NTHR);
   if (LAST) stage_rows<D>(Vs, Vp, p.vs.token, ROWS, b2, tid, NTHR);
 
@@ -164,6 +209,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
 #pragma unroll
   for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(arow + 32 * ks + 8 * g);
   __syncthreads();
+  MRT_STAMP(1);
 
   // Z_R^T tiles
   f32x4 s[NT];
@@ -220,11 +266,13 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
     pv_step<D>(Ks + 32 * st * LD, pb, oK, lane);
     if constexpr (LAST) pv_step<D>(Vs + 32 * st * LD, pb, oV, lane);
   }
+  MRT_STAMP(2);
   if (j < b2) {
     const size_t row = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk;
     store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
     if constexpr (LAST) store_rows<D>((u16*)p.Y + row * D, oV, 1.0f, g);
   }
+  MRT_STAMP(3);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -233,8 +281,13 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
 constexpr int kCK = 64;   // keys per LDS chunk (two 32-key steps)
 constexpr int kMinThreads = 256;   // the chunk copy below assumes at least this many threads
 
+template <int QT>
 struct FlashState {
-  float mrun, lrun;   // running max (reduced over the column) and this lane's partial sum
+  float mrun[QT], lrun[QT];   // running max (reduced over the column), this lane's partial sum
+  __device__ inline FlashState() {
+#pragma unroll
+    for (int q = 0; q < QT; ++q) { mrun[q] = -INFINITY; lrun[q] = 0.f; }
+  }
 };
 
 // One 64-row chunk of D bf16 held in registers between its global load and its LDS commit, so
@@ -269,20 +322,24 @@ struct ChunkRegs {
   }
 };
 
-// One 64-key chunk: logits against the wave's 16 queries, online softmax update; when
-// WITH_V also rescales and accumulates the output tiles.
+// One 64-key chunk against the wave's QT query tiles (16 queries each; tiles q >= nq are idle):
+// logits, online softmax update and, when WITH_V, rescale + accumulate of the output tiles.
+// Every key-side LDS operand is read once and used for all QT query tiles.
 // bias[i] is added to the scaled logit of key i (-inf for keys beyond the end); when MASKED,
-// kchunk[i] > qchunk hides key i from this lane's query.
-template <int D, bool WITH_V, bool MASKED>
+// kchunk[i] > qchunk[q] hides key i from this lane's query of tile q.
+template <int D, int QT, bool WITH_V, bool MASKED>
 __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bias,
-                                   const int* kchunk, int qchunk, const bf16x8* qv, float scale,
-                                   FlashState& st, f32x4* o, int lane) {
-  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+                                   const int* kchunk, const int (&qchunk)[QT],
+                                   const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
+                                   FlashState<QT>& st, f32x4 (&o)[QT][D / 16], int lane) {
+  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, c = lane & 15;
-  f32x4 s[4];
+  f32x4 s[QT][4];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // two key tiles at a time: all their operand reads are issued before the first MFMA, and
+  for (int q = 0; q < QT; ++q)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) s[q][it] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // two key tiles at a time: their operand reads are issued before the first MFMA, and
   // consecutive MFMAs alternate between independent accumulators
 #pragma unroll
   for (int ip = 0; ip < 2; ++ip) {
@@ -293,48 +350,88 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
       for (int ks = 0; ks < KS1; ++ks)
         a[t][ks] = ld_lds_16B(Kc + (16 * (2 * ip + t) + c) * LD + 32 * ks + 8 * g);
 #pragma unroll
-    for (int ks = 0; ks < KS1; ++ks)
+    for (int q = 0; q < QT; ++q) {
+      if (q < nq) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) s[2 * ip + t] = mfma(a[t][ks], qv[ks], s[2 * ip + t]);
+        for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) s[q][2 * ip + t] = mfma(a[t][ks], qv[q][ks], s[q][2 * ip + t]);
+      }
+    }
   }
-  float cm = -INFINITY;
+  f32x4 bi[4];
+  int4 kc[4];
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
-    const f32x4 bi = *(const f32x4*)(bias + 16 * it + 4 * g);
-    int kcs[4] = {0, 0, 0, 0};
-    if (MASKED) {
-      const int4 kc = *(const int4*)(kchunk + 16 * it + 4 * g);
-      kcs[0] = kc.x; kcs[1] = kc.y; kcs[2] = kc.z; kcs[3] = kc.w;
-    }
+    bi[it] = *(const f32x4*)(bias + 16 * it + 4 * g);
+    if (MASKED) kc[it] = *(const int4*)(kchunk + 16 * it + 4 * g);
+  }
+  bf16x8 pb[QT][2];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float z = fmaf(s[it][r], scale, bi[r]);
-      if (MASKED && kcs[r] > qchunk) z = -INFINITY;
-      s[it][r] = z;
-      cm = fmaxf(cm, z);
+  for (int q = 0; q < QT; ++q) {
+    if (q < nq) {
+      float cm = -INFINITY;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int kcs[4] = {MASKED ? kc[it].x : 0, MASKED ? kc[it].y : 0, MASKED ? kc[it].z : 0,
+                            MASKED ? kc[it].w : 0};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float z = fmaf(s[q][it][r], scale, bi[it][r]);
+          if (MASKED && kcs[r] > qchunk[q]) z = -INFINITY;
+          s[q][it][r] = z;
+          cm = fmaxf(cm, z);
+        }
+      }
+      cm = xmax(cm);
+      const float mnew = fmaxf(st.mrun[q], cm);
+      // mnew == -inf only if every key so far is hidden from this query: keep the state empty
+      const float msafe = (MASKED && mnew == -INFINITY) ? 0.f : mnew;
+      const float alpha = __expf(st.mrun[q] - msafe);   // mrun = -inf -> 0
+      float ps = 0.f;
+#pragma unroll
+      for (int it = 0; it < 4; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float e = __expf(s[q][it][r] - msafe);
+          s[q][it][r] = e;
+          ps += e;
+        }
+      st.lrun[q] = fmaf(st.lrun[q], alpha, ps);
+      st.mrun[q] = mnew;
+      if (WITH_V) {
+        pb[q][0] = pack8(s[q][0], s[q][1]);
+        pb[q][1] = pack8(s[q][2], s[q][3]);
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt) o[q][vt] = o[q][vt] * alpha;
+      }
     }
   }
-  cm = xmax(cm);
-  const float mnew = fmaxf(st.mrun, cm);
-  // mnew == -inf only if every key so far is hidden from this query: keep the state empty
-  const float msafe = (MASKED && mnew == -INFINITY) ? 0.f : mnew;
-  const float alpha = __expf(st.mrun - msafe);   // mrun = -inf -> 0
-  float ps = 0.f;
-#pragma unroll
-  for (int it = 0; it < 4; ++it)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float e = __expf(s[it][r] - msafe);
-      s[it][r] = e;
-      ps += e;
-    }
-  st.lrun = fmaf(st.lrun, alpha, ps);
-  st.mrun = mnew;
   if (WITH_V) {
+    const int sl = lane & 15, e = sl >> 2, qq = sl & 3;
 #pragma unroll
-    for (int vt = 0; vt < NVT; ++vt) o[vt] = o[vt] * alpha;
-    pv_step<D>(Vc, pack8(s[0], s[1]), o, lane);
-    pv_step<D>(Vc + 32 * LD, pack8(s[2], s[3]), o, lane);
+    for (int step = 0; step < 2; ++step) {
+      const u16* base = Vc + (32 * step + 4 * g + e) * LD + 8 * qq;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        s16x4 lo[HALF], hi[HALF];
+#pragma unroll
+        for (int i = 0; i < HALF; ++i) {
+          const int vt = h * HALF + i;
+          const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+          lo[i] = ld_lds_tr(p0);
+          hi[i] = ld_lds_tr(p0 + 16 * LD);
+        }
+#pragma unroll
+        for (int i = 0; i < HALF; ++i) {
+          const bf16x8 av =
+              __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+          for (int q = 0; q < QT; ++q)
+            if (q < nq) o[q][h * HALF + i] = mfma(av, pb[q][step], o[q][h * HALF + i]);
+        }
+      }
+    }
   }
 }
 
@@ -361,43 +458,88 @@ struct FlashLds {
 };
 
 // The streaming loop: keys [0, nkeys) of a row-major key array (and value array), 64 at a time,
-// software-pipelined over two LDS buffers with one barrier per chunk.  meta(key) fetches the
-// value whose negative is the key's bias, and the chunk id of the key.  Waves with active == false only help copying.
-template <int D, bool WITH_V, bool MASKED, typename Meta>
-__device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
-                                  long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V>& lds,
-                                  const bf16x8* qv, float scale, int qchunk, bool active,
-                                  FlashState& st, f32x4* o, int tid, int nthr, int lane) {
+// over two LDS buffers with one barrier per chunk.  Both buffers are filled before the first
+// barrier (their loads are in flight together), and while chunk c is consumed the loads of
+// chunk c+2 are in flight and chunk c+1 already sits in LDS.  meta(key) fetches the value whose
+// negative is the key's bias, and the chunk id of the key.
+// On return chunks (n-2, n-1) are still resident: with nkeys <= 2*kCK the whole key array and
+// its biases can be re-read from lds.K(0) / lds.bias(0) as 2*kCK contiguous rows.
+template <int D, bool WITH_V>
+struct ChunkFetch {
   ChunkRegs<D> rk, rv;
-  float rb = 0.f;    // raw per-key value fetched by meta(); turned into the bias at commit time
-  int rc = 0, rvalid = 0;
-  auto fetch = [&](int c0) {
+  float rb;    // raw per-key value fetched by meta(); turned into the bias at commit time
+  int rc, rvalid;
+  template <typename Meta>
+  __device__ inline void fetch(const u16* kbase, long long kstride, const u16* vbase,
+                               long long vstride, int nkeys, int c0, Meta& meta, int tid, int nthr) {
     const int valid = nkeys - c0 < kCK ? nkeys - c0 : kCK;
     rk.load(kbase + (long long)c0 * kstride, kstride, valid, tid, nthr);
     if (WITH_V) rv.load(vbase + (long long)c0 * vstride, vstride, valid, tid, nthr);
     rvalid = valid;
+    rb = 0.f; rc = 0;
     if (tid < kCK) meta(c0 + (tid < valid ? tid : valid - 1), rb, rc);
-  };
-  fetch(0);
-  int buf = 0;
-  for (int c0 = 0; c0 < nkeys; c0 += kCK, buf ^= 1) {
+  }
+  template <bool MASKED>
+  __device__ inline void commit(FlashLds<D, WITH_V>& lds, int buf, int tid, int nthr) const {
     rk.commit(lds.K(buf), tid, nthr);
     if (WITH_V) rv.commit(lds.V(buf), tid, nthr);
     if (tid < kCK) {
       lds.bias(buf)[tid] = tid < rvalid ? -rb : -INFINITY;
       if (MASKED) lds.kch(buf)[tid] = rc;
     }
-    __syncthreads();
-    if (c0 + kCK < nkeys) fetch(c0 + kCK);
-    if (active)
-      flash_chunk<D, WITH_V, MASKED>(lds.K(buf), lds.V(buf), lds.bias(buf), lds.kch(buf), qchunk, qv,
-                                     scale, st, o, lane);
+  }
+};
+
+template <int D, int QT, bool WITH_V, bool MASKED, typename Meta>
+__device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
+                                  long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V>& lds,
+                                  const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
+                                  const int (&qchunk)[QT], FlashState<QT>& st,
+                                  f32x4 (&o)[QT][D / 16], int tid, int nthr, int lane) {
+  ChunkFetch<D, WITH_V> f;
+  {
+    ChunkFetch<D, WITH_V> f1;
+    f.fetch(kbase, kstride, vbase, vstride, nkeys, 0, meta, tid, nthr);
+    const bool two = kCK < nkeys;
+    if (two) f1.fetch(kbase, kstride, vbase, vstride, nkeys, kCK, meta, tid, nthr);
+    f.template commit<MASKED>(lds, 0, tid, nthr);
+    if (two) f1.template commit<MASKED>(lds, 1, tid, nthr);
+  }
+  __syncthreads();
+  int buf = 0;
+  for (int c0 = 0; c0 < nkeys; c0 += kCK, buf ^= 1) {
+    const bool more = c0 + 2 * kCK < nkeys;
+    if (more) f.fetch(kbase, kstride, vbase, vstride, nkeys, c0 + 2 * kCK, meta, tid, nthr);
+    if (nq > 0)
+      flash_chunk<D, QT, WITH_V, MASKED>(lds.K(buf), lds.V(buf), lds.bias(buf), lds.kch(buf), qchunk,
+                                         qv, nq, scale, st, o, lane);
+    if (more) {
+      __syncthreads();                     // every wave is done with this buffer
+      f.template commit<MASKED>(lds, buf, tid, nthr);
+    } else if (c0 + kCK < nkeys) {
+      __syncthreads();                     // the next chunk was committed by other waves
+    }
   }
 }
 
+// Query tiles of a wave: tile q of wave w is l tile (q * nwaves + w); nq of them exist.
+template <int QT>
+struct WaveTiles {
+  int lt[QT];
+  int nq;
+  __device__ inline WaveTiles(int wave, int nwaves, int ntiles) {
+    nq = 0;
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      lt[q] = q * nwaves + wave;
+      if (lt[q] < ntiles) nq = q + 1;
+    }
+  }
+};
+
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
-template <int D>
-__global__ __launch_bounds__(768) void k_bf16_stage_l_out(KParams p) {
+template <int D, int QT, int MAXT>
+__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
   FlashLds<D, true> lds(smem);
@@ -410,35 +552,47 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_out(KParams p) {
   const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
+  const WaveTiles<QT> wt(wave, nthr >> 6, (b1 + 15) >> 4);
 
   const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
-  const int l = 16 * wave + c;
-  const int lc = l < b1 ? l : b1 - 1;
-  const u16* qrow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head +
-                    (qtok0 + (long long)lc * p.w) * p.qs.token;
-  bf16x8 qv[KS1];
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  bf16x8 qv[QT][KS1];
 #pragma unroll
-  for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
+  for (int q = 0; q < QT; ++q) {
+    const int l = 16 * wt.lt[q] + c;
+    const int lc = l < b1 ? l : b1 - 1;
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks)
+      qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+  }
 
   const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const u16* Yp = (const u16*)p.Y + row0 * D;
   const float* cLp = p.cL + row0;
 
-  FlashState st{-INFINITY, 0.f};
-  f32x4 o[NVT];
+  FlashState<QT> st;
+  f32x4 o[QT][NVT];
+  int qchunk[QT];
 #pragma unroll
-  for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-  flash_loop<D, true, false>(aLp, D, Yp, D, NK, meta, lds, qv, p.scale, 0, 16 * wave < b1, st, o, tid,
-                      nthr, lane);
-  const float lsum = xsum(st.lrun);
-  if (l < b1) {
-    u16* orow = (u16*)p.O + b * p.os.batch + hd * p.os.head +
-                (qtok0 + (long long)l * p.w) * p.os.token;
-    store_rows<D>(orow, o, 1.0f / lsum, g);
+  for (int q = 0; q < QT; ++q) {
+    qchunk[q] = 0;
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
+  MRT_STAMP(0);
+  auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
+  flash_loop<D, QT, true, false>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale, qchunk, st, o, tid,
+                                 nthr, lane);
+  MRT_STAMP(1);
+  u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    const int l = 16 * wt.lt[q] + c;
+    const float lsum = xsum(st.lrun[q]);
+    if (q < wt.nq && l < b1) store_rows<D>(Op + (long long)l * p.w * p.os.token, o[q], 1.0f / lsum, g);
+  }
+  MRT_STAMP(2);
 }
 
 // stage L, earlier iterations:
@@ -449,8 +603,8 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_out(KParams p) {
 // read transposed from LDS.
 constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
 
-template <int D>
-__global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrows) {
+template <int D, int QT, int MAXT, int MAXLT, int PT>
+__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
   constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   FlashLds<D, false> lds(smem);
@@ -469,134 +623,205 @@ __global__ __launch_bounds__(768) void k_bf16_stage_l_refine(KParams p, int qrow
 
   const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  MRT_STAMP(0);
   stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
 
   const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const float* cLp = p.cL + row0;
 
-  // ---- pass 1: wave w owns l tile w
+  // ---- pass 1
   {
-    const int l = 16 * wave + c;
-    const int lc = l < b1 ? l : b1 - 1;
-    const u16* qrow = Qp + (long long)lc * p.w * p.qs.token;
-    bf16x8 qv[KS1];
+    const WaveTiles<QT> wt(wave, nwaves, nlt);
+    bf16x8 qv[QT][KS1];
 #pragma unroll
-    for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
-    FlashState st{-INFINITY, 0.f};
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * wt.lt[q] + c;
+      const int lc = l < b1 ? l : b1 - 1;
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks)
+        qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+    }
+    FlashState<QT> st;
+    f32x4 odummy[QT][NVT];
+    int qchunk[QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) qchunk[q] = 0;
     auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-    flash_loop<D, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, p.scale, 0, wave < nlt, st, nullptr,
-                         tid, nthr, lane);
-    const float lsum = xsum(st.lrun);
-    if (wave < nlt && g == 0) lse[l] = st.mrun + __logf(lsum);
+    flash_loop<D, QT, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale, qchunk, st,
+                                    odummy, tid, nthr, lane);
+    MRT_STAMP(1);
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const float lsum = xsum(st.lrun[q]);
+      if (q < wt.nq && g == 0) lse[16 * wt.lt[q] + c] = st.mrun[q] + __logf(lsum);
+    }
   }
   __syncthreads();
+  MRT_STAMP(2);
 
-  // ---- pass 2: waves stride over nk tiles; the next tile's operands are fetched while the
-  // current one is processed
+  // ---- pass 2: waves stride over groups of PT adjacent nk tiles (every LDS read of Q serves
+  // all PT tiles); the next group's operands are fetched while the current one is processed
   u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + m) * NKtot * b2 * D;
   const int ntiles = (NK + 15) >> 4;
-  bf16x8 kb[KS1], kbn[KS1];
-  float cl = 0.f, cln = 0.f;
-  auto fetch = [&](int t, bf16x8* dst, float& cdst) {
-    const int nk = 16 * t + c;
-    const int nkc = nk < NK ? nk : NK - 1;
+  const int ngroups = (ntiles + PT - 1) / PT;
+  bf16x8 kb[PT][KS1], kbn[PT][KS1];
+  float cl[PT], cln[PT];
+  // when all of alpha_L[m, j] fits the two chunk buffers it is still resident after pass 1
+  const bool resident = NK <= 2 * kCK;
+  auto fetch = [&](int grp, bf16x8 (&dst)[PT][KS1], float (&cdst)[PT]) {
 #pragma unroll
-    for (int ks = 0; ks < KS1; ++ks) dst[ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
-    cdst = cLp[nkc];
-  };
-  if (wave < ntiles) fetch(wave, kbn, cln);
-  for (int t = wave; t < ntiles; t += nwaves) {
+    for (int pt = 0; pt < PT; ++pt) {
+      const int nk = 16 * (PT * grp + pt) + c;
+      const int nkc = nk < NK ? nk : NK - 1;
+      if (resident) {
 #pragma unroll
-    for (int ks = 0; ks < KS1; ++ks) kb[ks] = kbn[ks];
-    cl = cln;
-    if (t + nwaves < ntiles) fetch(t + nwaves, kbn, cln);
-    const int nk = 16 * t + c;
-    f32x4 z[kMaxLT];
-    float cmax = -INFINITY;
-#pragma unroll
-    for (int lt = 0; lt < kMaxLT; ++lt) {
-      if (lt < nlt) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int ks = 0; ks < KS1; ++ks) dst[pt][ks] = ld_lds_16B(lds.K(0) + nkc * LD + 32 * ks + 8 * g);
+        cdst[pt] = -lds.bias(0)[nkc];
+      } else {
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks)
-          acc = mfma(ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g), kb[ks], acc);
+          dst[pt][ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
+        cdst[pt] = cLp[nkc];
+      }
+    }
+  };
+  if (wave < ngroups) fetch(wave, kbn, cln);
+  for (int grp = wave; grp < ngroups; grp += nwaves) {
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks) kb[pt][ks] = kbn[pt][ks];
+      cl[pt] = cln[pt];
+    }
+    if (grp + nwaves < ngroups) fetch(grp + nwaves, kbn, cln);
+    const int npt = ntiles - PT * grp < PT ? ntiles - PT * grp : PT;   // tiles of this group
+    f32x4 z[PT][MAXLT];
+    float cmax[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) cmax[pt] = -INFINITY;
+#pragma unroll
+    for (int lt = 0; lt < MAXLT; ++lt) {
+      if (lt < nlt) {
+        bf16x8 av[KS1];
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
         const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool ok = 16 * lt + 4 * g + r < b1;
-          const float w = ok ? fmaf(acc[r], p.scale, -cl) - ls[r] : -INFINITY;   // log L[l, nk]
-          acc[r] = w;
-          cmax = fmaxf(cmax, w);
-        }
-        z[lt] = acc;
-      }
-    }
-    cmax = xmax(cmax);
-    float csum = 0.f;
+        for (int pt = 0; pt < PT; ++pt) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+          if (pt < npt) {
 #pragma unroll
-    for (int lt = 0; lt < kMaxLT; ++lt) {
-      if (lt < nlt) {
+            for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
+          }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float e = __expf(z[lt][r] - cmax);
-          z[lt][r] = e;
-          csum += e;
+          for (int r = 0; r < 4; ++r) {
+            const bool ok = 16 * lt + 4 * g + r < b1;
+            const float w = ok ? fmaf(acc[r], p.scale, -cl[pt]) - ls[r] : -INFINITY;   // log L[l, nk]
+            acc[r] = w;
+            cmax[pt] = fmaxf(cmax[pt], w);
+          }
+          z[pt][lt] = acc;
         }
       }
     }
-    csum = xsum(csum);
-    f32x4 o[NVT];
+    float csum[PT];
+    bf16x8 pb[MAXLT / 2][PT];
 #pragma unroll
-    for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int pt = 0; pt < PT; ++pt) {
+      cmax[pt] = xmax(cmax[pt]);
+      csum[pt] = 0.f;
 #pragma unroll
-    for (int st2 = 0; st2 < kMaxLT / 2; ++st2) {
-      if (2 * st2 < nlt) {
+      for (int lt = 0; lt < MAXLT; ++lt) {
+        if (lt < nlt) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float e = __expf(z[pt][lt][r] - cmax[pt]);
+            z[pt][lt][r] = e;
+            csum[pt] += e;
+          }
+        }
+      }
+      csum[pt] = xsum(csum[pt]);
+#pragma unroll
+      for (int st2 = 0; st2 < MAXLT / 2; ++st2) {
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        const f32x4 hi = (2 * st2 + 1 < nlt) ? z[2 * st2 + 1] : zero;
-        pv_step<D>(Qs + 32 * st2 * LD, pack8(z[2 * st2], hi), o, lane);
+        const f32x4 lo = (2 * st2 < nlt) ? z[pt][2 * st2] : zero;
+        const f32x4 hi = (2 * st2 + 1 < nlt) ? z[pt][2 * st2 + 1] : zero;
+        pb[st2][pt] = pack8(lo, hi);
       }
     }
-    if (nk < NK) store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o, 1.0f / csum, g);
+    f32x4 o[PT][NVT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st2 = 0; st2 < MAXLT / 2; ++st2)
+      if (2 * st2 < nlt) pv_step_multi<D, PT>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
+    if (grp == wave) MRT_STAMP(3);
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      const int nk = 16 * (PT * grp + pt) + c;
+      if (pt < npt && nk < NK)
+        store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
+    }
+    if (grp == wave) MRT_STAMP(4);
   }
+  MRT_STAMP(5);
 }
 
-// dense baseline: 64 queries per workgroup (16 per wave), flash loop over all visible keys
+// dense baseline: 128 queries per workgroup (4 waves x 2 tiles of 16), flash loop over all
+// visible keys
+constexpr int kDenseQT = 2, kDenseQ = 64 * kDenseQT;
+
 template <int D>
-__global__ __launch_bounds__(256) void k_bf16_dense(KParams p) {
-  constexpr int KS1 = D / 32, NVT = D / 16;
+__global__ __launch_bounds__(256, 2) void k_bf16_dense(KParams p) {
+  constexpr int KS1 = D / 32, NVT = D / 16, QT = kDenseQT;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
   FlashLds<D, true> lds(smem);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
-  const int q0 = blockIdx.x * 64, bh = blockIdx.y;
+  const int q0 = blockIdx.x * kDenseQ, bh = blockIdx.y;
   const int b = bh / p.H, hd = bh - b * p.H;
-  const int qi = q0 + 16 * wave + c;
-  const int qc = qi < p.Nq ? qi : p.Nq - 1;
-  const u16* qrow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + (long long)qc * p.qs.token;
-  bf16x8 qv[KS1];
+  const int qtiles = (p.Nq - q0 + 15) >> 4;
+  const WaveTiles<QT> wt(wave, 4, qtiles < 4 * QT ? qtiles : 4 * QT);
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
+  bf16x8 qv[QT][KS1];
+  int qchunk[QT];
 #pragma unroll
-  for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(qrow + 32 * ks + 8 * g);
+  for (int q = 0; q < QT; ++q) {
+    const int qi = q0 + 16 * wt.lt[q] + c;
+    const int qc = qi < p.Nq ? qi : p.Nq - 1;
+    qchunk[q] = p.cc > 0 ? (p.qoff + qc / p.hw) / p.cc : 0x7fffffff;
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks)
+      qv[q][ks] = ld_global_16B(Qp + (long long)qc * p.qs.token + 32 * ks + 8 * g);
+  }
   const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head;
   const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head;
-  int qchunk = 0x7fffffff, nkeys = p.Nkv;
+  int nkeys = p.Nkv;
   if (p.cc > 0) {
-    qchunk = (p.qoff + qc / p.hw) / p.cc;
-    const int qlast = (q0 + 63 < p.Nq ? q0 + 63 : p.Nq - 1);
+    const int qlast = (q0 + kDenseQ - 1 < p.Nq ? q0 + kDenseQ - 1 : p.Nq - 1);
     const long long lim = (long long)((p.qoff + qlast / p.hw) / p.cc + 1) * p.cc * p.hw;
     if (lim < nkeys) nkeys = (int)lim;
   }
-  FlashState st{-INFINITY, 0.f};
-  f32x4 o[NVT];
+  FlashState<QT> st;
+  f32x4 o[QT][NVT];
 #pragma unroll
-  for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < QT; ++q)
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int cc = p.cc, hw = p.hw;
   auto meta = [&](int key, float& raw, int& chunk) { raw = 0.f; chunk = cc > 0 ? (key / hw) / cc : 0; };
-  flash_loop<D, true, true>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, p.scale, qchunk, true,
-                      st, o, tid, 256, lane);
-  const float lsum = xsum(st.lrun);
-  if (qi < p.Nq) {
-    u16* orow = (u16*)p.O + b * p.os.batch + hd * p.os.head + (long long)qi * p.os.token;
-    store_rows<D>(orow, o, lsum > 0.f ? 1.0f / lsum : 0.f, g);
+  flash_loop<D, QT, true, true>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, wt.nq, p.scale,
+                                qchunk, st, o, tid, 256, lane);
+  u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head;
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    const int qi = q0 + 16 * wt.lt[q] + c;
+    const float lsum = xsum(st.lrun[q]);
+    if (q < wt.nq && qi < p.Nq)
+      store_rows<D>(Op + (long long)qi * p.os.token, o[q], lsum > 0.f ? 1.0f / lsum : 0.f, g);
   }
 }
 
@@ -622,7 +847,37 @@ hipError_t launch_r_d(const KParams& kp, dim3 grid, bool first, bool last, hipSt
   return hipErrorInvalidValue;
 }
 
+template <int D, int QT, int MAXT, int MAXLT, int PT>
+hipError_t launch_l(const KParams& kp, dim3 grid, int nthr, bool last, hipStream_t s) {
+  if (last) {
+    k_bf16_stage_l_out<D, QT, MAXT><<<grid, nthr, 0, s>>>(kp);
+    return hipGetLastError();
+  }
+  const int nlt = (kp.b1 + 15) / 16;
+  const int qrows = 32 * ((nlt + 1) / 2);
+  const size_t lds = FlashLds<D, false>::kBytes + (size_t)qrows * (D + kPad) * 2 + 16 * kMaxLT * 4;
+  hipError_t e;
+  if (lds > 64 * 1024 &&
+      (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, MAXLT, PT>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+    return e;
+  k_bf16_stage_l_refine<D, QT, MAXT, MAXLT, PT><<<grid, nthr, lds, s>>>(kp, qrows);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+#ifdef MRT_TRACE
+hipError_t set_trace_buffer(void* buf, hipStream_t s) {
+  static thread_local unsigned long long* slot[64];
+  static thread_local int next = 0;
+  slot[next] = (unsigned long long*)buf;
+  hipError_t e = hipMemcpyToSymbolAsync(HIP_SYMBOL(g_trace_buf), &slot[next], sizeof(void*), 0,
+                                        hipMemcpyHostToDevice, s);
+  next = (next + 1) % 64;
+  return e;
+}
+#endif
 
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s) {
   dim3 grid(kp.ntk * kp.b1, kp.ntq, nbh);
@@ -634,31 +889,20 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   dim3 grid(kp.b2, kp.ntq, nbh);
   const int nlt = (kp.b1 + 15) / 16;
   if (nlt > kMaxLT) return hipErrorInvalidValue;
-  const int nthr = 64 * (nlt < 4 ? 4 : nlt);   // the chunk copy needs >= 256 threads
-  hipError_t e;
-  if (last) {
-    if (kp.d == 128) k_bf16_stage_l_out<128><<<grid, nthr, 0, s>>>(kp);
-    else k_bf16_stage_l_out<64><<<grid, nthr, 0, s>>>(kp);
-    return hipGetLastError();
-  }
-  const int qrows = 32 * ((nlt + 1) / 2);
-  const int LD = kp.d + kPad;
-  const size_t lds = (kp.d == 128 ? FlashLds<128, false>::kBytes : FlashLds<64, false>::kBytes) +
-                     (size_t)qrows * LD * 2 + 16 * kMaxLT * 4;
-  if (kp.d == 128) {
-    if (lds > 64 * 1024 &&
-        (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<128>,
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
-      return e;
-    k_bf16_stage_l_refine<128><<<grid, nthr, lds, s>>>(kp, qrows);
-  } else {
-    k_bf16_stage_l_refine<64><<<grid, nthr, lds, s>>>(kp, qrows);
-  }
-  return hipGetLastError();
+  // Workgroups of 4 waves (one per SIMD), each wave owning up to two query tiles, so that two
+  // workgroups fit a compute unit whatever order their waves are dealt to the SIMDs in; only
+  // b1 > 128 needs a fifth and sixth wave.
+  if (nlt <= 4) return kp.d == 128 ? launch_l<128, 1, 256, 4, 2>(kp, grid, 256, last, s)
+                                   : launch_l<64, 1, 256, 4, 2>(kp, grid, 256, last, s);
+  if (nlt <= 8) return kp.d == 128 ? launch_l<128, 2, 256, 8, 2>(kp, grid, 256, last, s)
+                                   : launch_l<64, 2, 256, 8, 2>(kp, grid, 256, last, s);
+  const int nthr = 64 * ((nlt + 1) / 2);
+  return kp.d == 128 ? launch_l<128, 2, 384, 12, 1>(kp, grid, nthr, last, s)
+                     : launch_l<64, 2, 384, 12, 1>(kp, grid, nthr, last, s);
 }
 
 hipError_t launch_bf16_dense(const KParams& kp, int nbh, hipStream_t s) {
-  dim3 grid((kp.Nq + 63) / 64, nbh);
+  dim3 grid((kp.Nq + kDenseQ - 1) / kDenseQ, nbh);
   if (kp.d == 128) k_bf16_dense<128><<<grid, 256, 0, s>>>(kp);
   else k_bf16_dense<64><<<grid, 256, 0, s>>>(kp);
   return hipGetLastError();
