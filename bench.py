@@ -87,6 +87,9 @@ def main():
     ap.add_argument("--workload", default="C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="also run a plain device copy of this many MB (3 times) so that a "
+                         "rocprofv3 --pmc run of this command holds a dispatch of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -124,6 +127,14 @@ def main():
                                   wl.causal_chunk, pw, nws, stream)
         if st != 0:
             raise RuntimeError(f"monarch_attn_fwd failed: {pkg.last_error()}")
+
+    if args.calibration_copy_mb:
+        src = torch.empty(args.calibration_copy_mb * 1000 * 1000 // 4, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -79,6 +79,12 @@ __device__ inline f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+// Softmax arithmetic runs in the base-2 domain: logits are multiplied by scale*log2(e) (one
+// fma) and exponentiated with the hardware exp2, which saves a multiply per element.
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+__device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
+
 __device__ inline float xmax(float x) {
   x = fmaxf(x, __shfl_xor(x, 16));
   return fmaxf(x, __shfl_xor(x, 32));
@@ -220,14 +226,15 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
     for (int ks = 0; ks < KS1; ++ks)
       s[it] = mfma(ld_lds_16B(Ks + (16 * it + c) * LD + 32 * ks + 8 * g), qv[ks], s[it]);
   }
-  // softmax over i (rows of the tiles) for column j, and sum_i R log R
+  // softmax over i (rows of the tiles) for column j, and sum_i R log R (base-2 domain inside)
+  const float scale2 = p.scale * kLog2e;
   float mx = -INFINITY;
 #pragma unroll
   for (int it = 0; it < NT; ++it)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const bool ok = 16 * it + 4 * g + r < b2;
-      const float z = ok ? s[it][r] * p.scale : -INFINITY;
+      const float z = ok ? s[it][r] * scale2 : -INFINITY;
       s[it][r] = z;
       mx = fmaxf(mx, z);
     }
@@ -239,7 +246,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
     for (int r = 0; r < 4; ++r) {
       const bool ok = 16 * it + 4 * g + r < b2;
       const float z = ok ? s[it][r] - mx : 0.f;
-      const float e = ok ? __expf(z) : 0.f;
+      const float e = ok ? exp2_fast(z) : 0.f;
       sum += e;
       ent = fmaf(e, z, ent);
       s[it][r] = e;
@@ -248,7 +255,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   ent = xsum(ent);
   const float inv = 1.0f / sum;
   if (g == 0 && j < b2)
-    p.cL[(((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk] = ent * inv - __logf(sum);
+    p.cL[(((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk] = kLn2 * (ent * inv - log2_fast(sum));
 
   // alpha_L = R K (and Y = R V)
   f32x4 oK[NVT], oV[LAST ? NVT : 1];
@@ -387,13 +394,13 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
       const float mnew = fmaxf(st.mrun[q], cm);
       // mnew == -inf only if every key so far is hidden from this query: keep the state empty
       const float msafe = (MASKED && mnew == -INFINITY) ? 0.f : mnew;
-      const float alpha = __expf(st.mrun[q] - msafe);   // mrun = -inf -> 0
+      const float alpha = exp2_fast(st.mrun[q] - msafe);   // mrun = -inf -> 0
       float ps = 0.f;
 #pragma unroll
       for (int it = 0; it < 4; ++it)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float e = __expf(s[q][it][r] - msafe);
+          const float e = exp2_fast(s[q][it][r] - msafe);
           s[q][it][r] = e;
           ps += e;
         }
@@ -484,7 +491,7 @@ struct ChunkFetch {
     rk.commit(lds.K(buf), tid, nthr);
     if (WITH_V) rv.commit(lds.V(buf), tid, nthr);
     if (tid < kCK) {
-      lds.bias(buf)[tid] = tid < rvalid ? -rb : -INFINITY;
+      lds.bias(buf)[tid] = tid < rvalid ? -rb * kLog2e : -INFINITY;
       if (MASKED) lds.kch(buf)[tid] = rc;
     }
   }
@@ -582,7 +589,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   }
   MRT_STAMP(0);
   auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-  flash_loop<D, QT, true, false>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale, qchunk, st, o, tid,
+  flash_loop<D, QT, true, false>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st, o, tid,
                                  nthr, lane);
   MRT_STAMP(1);
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
@@ -603,7 +610,9 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
 // read transposed from LDS.
 constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
 
-template <int D, int QT, int MAXT, int MAXLT, int PT>
+// NLT = number of 16-row l tiles (compile time, so that the tile loops unroll without guards and
+// the scheduler can overlap one tile's LDS reads with another's MFMAs).
+template <int D, int QT, int MAXT, int NLT, int PT>
 __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
   constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -614,7 +623,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int nlt = (b1 + 15) >> 4;
+  constexpr int nlt = NLT;
   const int j = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
@@ -648,13 +657,13 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
 #pragma unroll
     for (int q = 0; q < QT; ++q) qchunk[q] = 0;
     auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-    flash_loop<D, QT, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale, qchunk, st,
+    flash_loop<D, QT, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st,
                                     odummy, tid, nthr, lane);
     MRT_STAMP(1);
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
       const float lsum = xsum(st.lrun[q]);
-      if (q < wt.nq && g == 0) lse[16 * wt.lt[q] + c] = st.mrun[q] + __logf(lsum);
+      if (q < wt.nq && g == 0) lse[16 * wt.lt[q] + c] = st.mrun[q] + log2_fast(lsum);   // base 2
     }
   }
   __syncthreads();
@@ -663,6 +672,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   // ---- pass 2: waves stride over groups of PT adjacent nk tiles (every LDS read of Q serves
   // all PT tiles); the next group's operands are fetched while the current one is processed
   u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + m) * NKtot * b2 * D;
+  const float scale2 = p.scale * kLog2e;
   const int ntiles = (NK + 15) >> 4;
   const int ngroups = (ntiles + PT - 1) / PT;
   bf16x8 kb[PT][KS1], kbn[PT][KS1];
@@ -692,83 +702,98 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
     for (int pt = 0; pt < PT; ++pt) {
 #pragma unroll
       for (int ks = 0; ks < KS1; ++ks) kb[pt][ks] = kbn[pt][ks];
-      cl[pt] = cln[pt];
+      cl[pt] = resident ? cln[pt] : cln[pt] * kLog2e;    // c_L in the base-2 domain
     }
     if (grp + nwaves < ngroups) fetch(grp + nwaves, kbn, cln);
     const int npt = ntiles - PT * grp < PT ? ntiles - PT * grp : PT;   // tiles of this group
-    f32x4 z[PT][MAXLT];
-    float cmax[PT];
+    f32x4 z[PT][NLT];     // log2 L[l, nk]
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt) cmax[pt] = -INFINITY;
+    for (int lt = 0; lt < NLT; ++lt) {
+      bf16x8 av[KS1];
 #pragma unroll
-    for (int lt = 0; lt < MAXLT; ++lt) {
-      if (lt < nlt) {
-        bf16x8 av[KS1];
+      for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
+      const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
-        const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
+      for (int pt = 0; pt < PT; ++pt) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (pt < npt) {
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) {
-          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-          if (pt < npt) {
+          for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
+        }
 #pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
-          }
+        for (int r = 0; r < 4; ++r) {
+          const bool ok = 16 * lt + 4 * g + r < b1;
+          acc[r] = ok ? fmaf(acc[r], scale2, -cl[pt]) - ls[r] : -INFINITY;
+        }
+        z[pt][lt] = acc;
+      }
+      // keep the scheduler from hoisting every tile's operand reads to the top (register blow-up)
+      if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+    if (grp == wave) MRT_STAMP(3);
+    // weights of the l-average: L[l, nk] itself; only if a whole column underflows in fp32 is the
+    // column maximum taken out first (the ratio alpha_R / c_R is unchanged by it)
+    float csum[PT], shift[PT];
+    bf16x8 pb[(NLT + 1) / 2][PT];
+    auto weigh = [&]() {
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) {
+        csum[pt] = 0.f;
+#pragma unroll
+        for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
+          f32x4 lo, hi = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
-            const bool ok = 16 * lt + 4 * g + r < b1;
-            const float w = ok ? fmaf(acc[r], p.scale, -cl[pt]) - ls[r] : -INFINITY;   // log L[l, nk]
-            acc[r] = w;
-            cmax[pt] = fmaxf(cmax[pt], w);
+            lo[r] = exp2_fast(z[pt][2 * st2][r] - shift[pt]);
+            csum[pt] += lo[r];
+            if (2 * st2 + 1 < NLT) {
+              hi[r] = exp2_fast(z[pt][2 * st2 + 1 < NLT ? 2 * st2 + 1 : 0][r] - shift[pt]);
+              csum[pt] += hi[r];
+            }
           }
-          z[pt][lt] = acc;
+          pb[st2][pt] = pack8(lo, hi);
         }
+        csum[pt] = xsum(csum[pt]);
       }
+    };
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
+    weigh();
+    bool under = false;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) under |= (pt < npt && csum[pt] == 0.f);
+    if (__any(under)) {
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) {
+        float cm = -INFINITY;
+#pragma unroll
+        for (int lt = 0; lt < NLT; ++lt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cm = fmaxf(cm, z[pt][lt][r]);
+        shift[pt] = xmax(cm);
+      }
+      weigh();
     }
-    float csum[PT];
-    bf16x8 pb[MAXLT / 2][PT];
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt) {
-      cmax[pt] = xmax(cmax[pt]);
-      csum[pt] = 0.f;
-#pragma unroll
-      for (int lt = 0; lt < MAXLT; ++lt) {
-        if (lt < nlt) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float e = __expf(z[pt][lt][r] - cmax[pt]);
-            z[pt][lt][r] = e;
-            csum[pt] += e;
-          }
-        }
-      }
-      csum[pt] = xsum(csum[pt]);
-#pragma unroll
-      for (int st2 = 0; st2 < MAXLT / 2; ++st2) {
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        const f32x4 lo = (2 * st2 < nlt) ? z[pt][2 * st2] : zero;
-        const f32x4 hi = (2 * st2 + 1 < nlt) ? z[pt][2 * st2 + 1] : zero;
-        pb[st2][pt] = pack8(lo, hi);
-      }
-    }
+    if (grp == wave) MRT_STAMP(4);
     f32x4 o[PT][NVT];
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int st2 = 0; st2 < MAXLT / 2; ++st2)
-      if (2 * st2 < nlt) pv_step_multi<D, PT>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
-    if (grp == wave) MRT_STAMP(3);
+    for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
+      pv_step_multi<D, PT>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (grp == wave) MRT_STAMP(5);
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
       const int nk = 16 * (PT * grp + pt) + c;
       if (pt < npt && nk < NK)
         store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
     }
-    if (grp == wave) MRT_STAMP(4);
+    if (grp == wave) MRT_STAMP(6);
   }
-  MRT_STAMP(5);
 }
 
 // dense baseline: 128 queries per workgroup (4 waves x 2 tiles of 16), flash loop over all
@@ -813,7 +838,7 @@ __global__ __launch_bounds__(256, 2) void k_bf16_dense(KParams p) {
     for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int cc = p.cc, hw = p.hw;
   auto meta = [&](int key, float& raw, int& chunk) { raw = 0.f; chunk = cc > 0 ? (key / hw) / cc : 0; };
-  flash_loop<D, QT, true, true>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, wt.nq, p.scale,
+  flash_loop<D, QT, true, true>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, wt.nq, p.scale * kLog2e,
                                 qchunk, st, o, tid, 256, lane);
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head;
 #pragma unroll
@@ -847,22 +872,43 @@ hipError_t launch_r_d(const KParams& kp, dim3 grid, bool first, bool last, hipSt
   return hipErrorInvalidValue;
 }
 
-template <int D, int QT, int MAXT, int MAXLT, int PT>
-hipError_t launch_l(const KParams& kp, dim3 grid, int nthr, bool last, hipStream_t s) {
-  if (last) {
-    k_bf16_stage_l_out<D, QT, MAXT><<<grid, nthr, 0, s>>>(kp);
-    return hipGetLastError();
-  }
-  const int nlt = (kp.b1 + 15) / 16;
-  const int qrows = 32 * ((nlt + 1) / 2);
+template <int D, int QT, int MAXT>
+hipError_t launch_l_out(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
+  k_bf16_stage_l_out<D, QT, MAXT><<<grid, nthr, 0, s>>>(kp);
+  return hipGetLastError();
+}
+
+template <int D, int NLT>
+hipError_t launch_l_refine(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
+  constexpr int QT = NLT <= 4 ? 1 : 2, MAXT = NLT <= 8 ? 256 : 384, PT = NLT <= 8 ? 2 : 1;
+  const int qrows = 32 * ((NLT + 1) / 2);
   const size_t lds = FlashLds<D, false>::kBytes + (size_t)qrows * (D + kPad) * 2 + 16 * kMaxLT * 4;
   hipError_t e;
   if (lds > 64 * 1024 &&
-      (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, MAXLT, PT>,
+      (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
     return e;
-  k_bf16_stage_l_refine<D, QT, MAXT, MAXLT, PT><<<grid, nthr, lds, s>>>(kp, qrows);
+  k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT><<<grid, nthr, lds, s>>>(kp, qrows);
   return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_l_refine_d(const KParams& kp, dim3 grid, int nthr, int nlt, hipStream_t s) {
+  switch (nlt) {
+    case 1: return launch_l_refine<D, 1>(kp, grid, nthr, s);
+    case 2: return launch_l_refine<D, 2>(kp, grid, nthr, s);
+    case 3: return launch_l_refine<D, 3>(kp, grid, nthr, s);
+    case 4: return launch_l_refine<D, 4>(kp, grid, nthr, s);
+    case 5: return launch_l_refine<D, 5>(kp, grid, nthr, s);
+    case 6: return launch_l_refine<D, 6>(kp, grid, nthr, s);
+    case 7: return launch_l_refine<D, 7>(kp, grid, nthr, s);
+    case 8: return launch_l_refine<D, 8>(kp, grid, nthr, s);
+    case 9: return launch_l_refine<D, 9>(kp, grid, nthr, s);
+    case 10: return launch_l_refine<D, 10>(kp, grid, nthr, s);
+    case 11: return launch_l_refine<D, 11>(kp, grid, nthr, s);
+    case 12: return launch_l_refine<D, 12>(kp, grid, nthr, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -892,13 +938,15 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   // Workgroups of 4 waves (one per SIMD), each wave owning up to two query tiles, so that two
   // workgroups fit a compute unit whatever order their waves are dealt to the SIMDs in; only
   // b1 > 128 needs a fifth and sixth wave.
-  if (nlt <= 4) return kp.d == 128 ? launch_l<128, 1, 256, 4, 2>(kp, grid, 256, last, s)
-                                   : launch_l<64, 1, 256, 4, 2>(kp, grid, 256, last, s);
-  if (nlt <= 8) return kp.d == 128 ? launch_l<128, 2, 256, 8, 2>(kp, grid, 256, last, s)
-                                   : launch_l<64, 2, 256, 8, 2>(kp, grid, 256, last, s);
-  const int nthr = 64 * ((nlt + 1) / 2);
-  return kp.d == 128 ? launch_l<128, 2, 384, 12, 1>(kp, grid, nthr, last, s)
-                     : launch_l<64, 2, 384, 12, 1>(kp, grid, nthr, last, s);
+  const int nthr = nlt <= 8 ? 256 : 64 * ((nlt + 1) / 2);
+  if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nthr, nlt, s)
+                                : launch_l_refine_d<64>(kp, grid, nthr, nlt, s);
+  if (nlt <= 4) return kp.d == 128 ? launch_l_out<128, 1, 256>(kp, grid, nthr, s)
+                                   : launch_l_out<64, 1, 256>(kp, grid, nthr, s);
+  if (nlt <= 8) return kp.d == 128 ? launch_l_out<128, 2, 256>(kp, grid, nthr, s)
+                                   : launch_l_out<64, 2, 256>(kp, grid, nthr, s);
+  return kp.d == 128 ? launch_l_out<128, 2, 384>(kp, grid, nthr, s)
+                     : launch_l_out<64, 2, 384>(kp, grid, nthr, s);
 }
 
 hipError_t launch_bf16_dense(const KParams& kp, int nbh, hipStream_t s) {

@@ -1,0 +1,139 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and its host-side argument validation returns the documented status codes.  No kernel is
+launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2602_12271_amd as pkg
+from paper_2602_12271_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "monarchrt.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", text)
+    return sorted(set(n for n in names if n.startswith(("monarch_", "dense_", "mrt_"))))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pkg.load_library()
+    decl = declared_functions()
+    assert {"monarch_attn_fwd", "dense_attn_fwd", "monarch_attn_check", "dense_attn_check",
+            "monarch_attn_workspace_bytes", "monarch_attn_workspace_min_bytes",
+            "mrt_status_string", "mrt_last_error", "mrt_profile_enable",
+            "mrt_profile_read"} <= set(decl)
+    for name in decl:
+        assert hasattr(lib, name), f"{name} is declared in the header but not exported"
+    assert sorted(B.EXPORTED) == decl
+
+
+def test_binding_struct_matches_header_layout():
+    # 8 ints, 4 x 3 long long, 2 enums, 1 float; natural alignment
+    assert ctypes.sizeof(B.MrtStrides) == 24
+    assert B.MrtProblem.q.offset == 32
+    assert B.MrtProblem.dtype.offset == 32 + 4 * 24
+    assert ctypes.sizeof(B.MrtProblem) == 32 + 96 + 16
+
+
+def problem(**kw):
+    base = dict(batch=1, heads=12, head_dim=128, f_q=3, f_kv=3, h=30, w=52, scale=128 ** -0.5)
+    base.update(kw)
+    return pkg.make_problem(**base)
+
+
+def test_named_configurations_are_accepted():
+    assert pkg.monarch_attn_check(problem(), 90, 52, 0, 2) == B.MRT_OK                  # C1
+    assert pkg.monarch_attn_check(problem(), 90, 26, 1, 2) == B.MRT_OK                  # C2
+    assert pkg.monarch_attn_check(problem(f_kv=21, q_frame_offset=18), 90, 26, 1, 2, 3) == B.MRT_OK   # C3
+    assert pkg.monarch_attn_check(problem(heads=40, f_kv=21, h=45, w=80, q_frame_offset=18),
+                                  135, 40, 1, 3, 3) == B.MRT_OK                         # C4
+    c0 = pkg.make_problem(batch=1, heads=1, head_dim=64, f_q=1, f_kv=1, h=24, w=24,
+                          dtype=B.MRT_F32, scale=1.0)
+    assert pkg.monarch_attn_check(c0, 24, 24, 0, 1) == B.MRT_OK                        # C0
+
+
+@pytest.mark.parametrize("kw,args,status", [
+    (dict(), (90, 50, 0, 2, 0), B.MRT_ERR_BLOCK),            # b2 != w for regular
+    (dict(), (45, 52, 0, 2, 0), B.MRT_ERR_BLOCK),            # b1 != f*h for regular
+    (dict(f_kv=21), (90, 52, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),   # rectangular needs tile=1
+    (dict(), (90, 52, 0, 2, 3), B.MRT_ERR_UNSUPPORTED),      # regular + mask
+    (dict(), (90, 52, 0, 0, 0), B.MRT_ERR_SHAPE),            # iters < 1
+    (dict(), (90, 52, 2, 1, 0), B.MRT_ERR_SHAPE),            # tile flag
+    (dict(), (90, 25, 1, 2, 0), B.MRT_ERR_BLOCK),            # 25 does not divide 52
+    (dict(), (15, 26, 1, 2, 0), B.MRT_ERR_UNSUPPORTED),      # tile of half a frame (n_h < h)
+    (dict(), (45, 26, 1, 2, 0), B.MRT_ERR_BLOCK),            # one and a half frames
+    (dict(), (60, 26, 1, 2, 0), B.MRT_ERR_BLOCK),            # 60 rows: two frames do not divide 3
+    (dict(f_kv=21), (90, 26, 1, 2, 2), B.MRT_ERR_BLOCK),     # 3-frame tiles straddle 2-frame chunks
+    (dict(f_kv=21, q_frame_offset=1), (90, 26, 1, 2, 3), B.MRT_ERR_BLOCK),   # offset inside a tile
+    (dict(head_dim=96), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),  # bf16 path: d in {64,128}
+    (dict(scale=0.0), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),
+    (dict(heads=0), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),
+    (dict(f_q=7, f_kv=7), (210, 52, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),   # b1 > 192
+    (dict(w=104), (90, 104, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),          # b2 > 96
+])
+def test_rejected_arguments(kw, args, status):
+    p = problem(**kw)
+    assert pkg.monarch_attn_check(p, *args) == status
+    assert pkg.last_error() != ""
+
+
+def test_null_problem_and_strides():
+    lib = pkg.load_library()
+    assert lib.monarch_attn_check(None, 90, 52, 0, 2, 0) == B.MRT_ERR_NULL
+    assert lib.dense_attn_check(None, 0) == B.MRT_ERR_NULL
+    bad = problem(q_strides=(1, 1, 64))          # token stride < head_dim
+    assert pkg.monarch_attn_check(bad, 90, 52, 0, 2) == B.MRT_ERR_SHAPE
+    odd = problem(q_strides=(12 * 4680 * 132, 4680 * 132, 132))   # not a multiple of 8 elements
+    assert pkg.monarch_attn_check(odd, 90, 52, 0, 2) == B.MRT_ERR_SHAPE
+    assert pkg.dense_attn_check(problem(), 3) == B.MRT_OK
+    assert pkg.dense_attn_check(problem(), -1) == B.MRT_ERR_SHAPE
+
+
+def test_fwd_rejects_before_touching_the_gpu():
+    # every check happens on the host before the first launch: NULL tensors and a short workspace
+    # are reported without a GPU in the machine
+    lib = pkg.load_library()
+    p = problem()
+    st = lib.monarch_attn_fwd(None, None, None, None, ctypes.byref(p), 90, 52, 0, 2, 0, None, 0, None)
+    assert st == B.MRT_ERR_NULL
+    fake = ctypes.c_void_p(4096)
+    st = lib.monarch_attn_fwd(fake, fake, fake, fake, ctypes.byref(p), 90, 52, 0, 2, 0, fake, 16, None)
+    assert st == B.MRT_ERR_WORKSPACE
+    st = lib.monarch_attn_fwd(fake, fake, fake, fake, ctypes.byref(p), 90, 52, 0, 2, 0,
+                              ctypes.c_void_p(4096 + 8), 1 << 30, None)
+    assert st == B.MRT_ERR_WORKSPACE              # misaligned workspace
+    st = lib.dense_attn_fwd(None, fake, fake, fake, ctypes.byref(p), 0, None)
+    assert st == B.MRT_ERR_NULL
+
+
+def test_workspace_sizes():
+    p = problem()
+    # one (batch, head): alpha_L, Y, alpha_R of N_q*ntk*d bf16 each plus c_L of N_q*ntk fp32
+    n = 4680
+    slab = 3 * n * 128 * 2 + n * 4
+    got = pkg.monarch_attn_workspace_bytes(p, 90, 52, 0, 2, minimum=True)
+    assert slab <= got <= slab + 4 * 256
+    assert pkg.monarch_attn_workspace_bytes(p, 90, 52, 0, 2) == 12 * got
+    # a single iteration needs no alpha_R
+    got1 = pkg.monarch_attn_workspace_bytes(p, 90, 52, 0, 1, minimum=True)
+    assert got1 < got and got1 >= 2 * n * 128 * 2 + n * 4
+    # tiled KV cache: ntk = 14 key tiles per query token
+    p3 = problem(f_kv=21)
+    got3 = pkg.monarch_attn_workspace_bytes(p3, 90, 26, 1, 2, minimum=True)
+    assert got3 >= 14 * slab and got3 <= 14 * slab + 4 * 256
+    assert pkg.monarch_attn_workspace_bytes(problem(), 90, 50, 0, 2) == 0      # invalid -> 0
+    # fp32 compute on bf16 storage keeps fp32 intermediates
+    pf = problem(compute=B.MRT_COMPUTE_F32)
+    assert pkg.monarch_attn_workspace_bytes(pf, 90, 52, 0, 2, minimum=True) > 1.9 * got
+
+
+def test_status_strings():
+    lib = pkg.load_library()
+    seen = {lib.mrt_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
