@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--workload", default="C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--head-groups", type=int, default=0,
+                    help="head groups run concurrently by the library (0 = library default)")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run a plain device copy of this many MB (3 times) so that a "
                          "rocprofv3 --pmc run of this command holds a dispatch of known traffic")
@@ -107,6 +109,8 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     lib = pkg.load_library()          # raises if the HIP library is missing: no fallback
+    if args.head_groups:
+        pkg.binding.set_head_groups(args.head_groups)
     wl = syn.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
@@ -237,7 +241,7 @@ def main():
                                f"{wl.h},{wl.w}), N_q={wl.n_q}, N_kv={wl.n_kv}, "
                                f"{'tiled' if wl.tile else 'regular'} Monarch ({wl.b1},{wl.b2}), T={wl.iters}, "
                                f"causal_chunk={wl.causal_chunk}",
-                   "scale": wl.scale, "workspace_mb": nws / 1e6, "heads_per_pass": (wl.batch * wl.heads + passes - 1) // passes},
+                   "scale": wl.scale, "workspace_mb": nws / 1e6, "head_groups": args.head_groups or "auto", "heads_per_pass": (wl.batch * wl.heads + passes - 1) // passes},
         "roofline": roof,
         "cpu_baseline": cpu,
         "whole_call": {"algorithmic_gflop": tot_flops / 1e9, "tflops": tot_flops / (ms_per_step / 1e3) / 1e12,

@@ -19,8 +19,8 @@
  * "(a l b j)" split); token = ((a*b1 + l)*c2 + b)*b2 + j with c2 = w / b2.
  *
  * All data pointers are DEVICE pointers owned by the caller.  The library allocates
- * nothing, enqueues its kernels on the given HIP stream and returns without
- * synchronising.  Entry points return a status code; nothing is thrown across the ABI.
+ * no device memory, orders its kernels after the work already on the given HIP stream and
+ * before anything enqueued on it later, and returns without synchronising.  Entry points return a status code; nothing is thrown across the ABI.
  * All argument checks happen on the host before the first launch.
  */
 #ifndef MONARCHRT_H
@@ -109,11 +109,19 @@ mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk);
 mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
                           const mrt_problem* p, int causal_chunk, void* hip_stream);
 
+/* Number of head groups monarch_attn_fwd runs concurrently: 1..4, or 0 (default) to let the library
+ * choose per call (one group unless the launches are long and their grids small).  With more than one
+ * group the library forks helper HIP streams from hip_stream and joins them back before it
+ * returns, so the call is still ordered like a single operation on hip_stream (and can be
+ * captured into a HIP graph from it).  The helper streams and their events are created once per
+ * device on first use, at the default priority, and live until the process ends.  Process-wide. */
+void mrt_set_head_groups(int n);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the two entry points
  * above is bracketed by a pair of HIP events recorded on the call's stream (this is the only
  * mode in which the library creates HIP objects).  mrt_profile_read waits for the recorded
  * events, writes up to `capacity` (elapsed milliseconds, kernel kind) pairs in launch order,
- * forgets them and returns how many it wrote.  Kernel kind = one of MRT_KERNEL_STAGE_R /
+ * forgets them and returns how many it wrote.  While enabled, head groups run one after the other.  Kernel kind = one of MRT_KERNEL_STAGE_R /
  * MRT_KERNEL_STAGE_L / MRT_KERNEL_DENSE, or-ed with MRT_KERNEL_FIRST (first iteration: alpha_R
  * is Q itself) and MRT_KERNEL_LAST (last iteration: stage R also forms Y, stage L forms O). */
 enum { MRT_KERNEL_STAGE_R = 1, MRT_KERNEL_STAGE_L = 2, MRT_KERNEL_DENSE = 4,

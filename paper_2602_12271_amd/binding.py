@@ -21,7 +21,7 @@ MRT_COMPUTE_DEFAULT, MRT_COMPUTE_F32 = 0, 1
 EXPORTED = [
     "monarch_attn_check", "monarch_attn_workspace_min_bytes", "monarch_attn_workspace_bytes",
     "monarch_attn_fwd", "dense_attn_check", "dense_attn_fwd", "mrt_status_string", "mrt_last_error",
-    "mrt_profile_enable", "mrt_profile_read",
+    "mrt_profile_enable", "mrt_profile_read", "mrt_set_head_groups",
 ]
 KERNEL_STAGE_R, KERNEL_STAGE_L, KERNEL_DENSE, KERNEL_FIRST, KERNEL_LAST = 1, 2, 4, 16, 32
 
@@ -76,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.mrt_status_string.restype = ctypes.c_char_p
     lib.mrt_last_error.argtypes = []
     lib.mrt_last_error.restype = ctypes.c_char_p
+    lib.mrt_set_head_groups.argtypes = [ci]
+    lib.mrt_set_head_groups.restype = None
     lib.mrt_profile_enable.argtypes = [ci]
     lib.mrt_profile_enable.restype = None
     lib.mrt_profile_read.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci), ci]
@@ -119,6 +121,10 @@ def monarch_attn_workspace_bytes(prob: MrtProblem, b1, b2, tile, iters, minimum=
     lib = load_library()
     f = lib.monarch_attn_workspace_min_bytes if minimum else lib.monarch_attn_workspace_bytes
     return int(f(ctypes.byref(prob), b1, b2, tile, iters))
+
+
+def set_head_groups(n: int) -> None:
+    load_library().mrt_set_head_groups(int(n))
 
 
 def profile_enable(on: bool) -> None:

@@ -176,6 +176,33 @@ struct ProfScope {
   }
 };
 
+// ---- helper streams for concurrent head groups ------------------------------------------
+constexpr int kMaxGroups = 4;
+static int g_max_groups = 0;   // 0 = choose per call
+struct StreamPool {
+  hipStream_t side[kMaxGroups - 1];
+  hipEvent_t fork, join[kMaxGroups - 1];
+};
+// One pool per device, created on first use and kept for the life of the process.  Streams are
+// created with the default priority.
+static StreamPool* get_pool() {
+  static std::mutex mu;
+  static StreamPool* pools[64] = {nullptr};
+  static bool failed[64] = {false};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lk(mu);
+  if (pools[dev] || failed[dev]) return pools[dev];
+  StreamPool* p = new StreamPool();
+  bool ok = hipEventCreateWithFlags(&p->fork, hipEventDisableTiming) == hipSuccess;
+  for (int i = 0; ok && i < kMaxGroups - 1; ++i)
+    ok = hipStreamCreateWithFlags(&p->side[i], hipStreamNonBlocking) == hipSuccess &&
+         hipEventCreateWithFlags(&p->join[i], hipEventDisableTiming) == hipSuccess;
+  if (!ok) { failed[dev] = true; delete p; return nullptr; }   // fall back to one stream
+  pools[dev] = p;
+  return p;
+}
+
 static mrt_status hip_fail(hipError_t e, const char* what) {
   set_error("%s: %s", what, hipGetErrorString(e));
   return MRT_ERR_HIP;
@@ -251,29 +278,67 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
   kp.aR = base + (pl.slab_aL + pl.slab_Y) * G;
   kp.cL = (float*)(base + (pl.slab_aL + pl.slab_Y + pl.slab_aR) * G);
 
-  for (int bh0 = 0; bh0 < BH; bh0 += G) {
+  // Heads are independent, so a pass is cut into up to kMaxGroups head groups whose kernel chains
+  // run on helper streams forked from and joined back to the caller's stream: the short tail of
+  // one group's launch (workgroup counts are rarely a multiple of what the chip holds) overlaps
+  // the next kernel of another group.  Per-kernel timing needs launches that do not overlap.
+  // Measured on MI355X: the fork/join costs ~10 us per extra group, so it only pays for launches
+  // that run for >= 100 us and whose stage L grid is within a few multiples of the 512 workgroups
+  // the chip holds (KV-cache shapes at 12 heads: -7 %); small calls run on the caller's stream.
+  int want_groups = g_max_groups;
+  if (want_groups == 0) {
+    const size_t inter_per_launch = pl.slab_aL * (size_t)G;
+    const long long l_wgs = (long long)pl.kp.ntq * pl.kp.b2 * G;
+    want_groups = (inter_per_launch >= (size_t(128) << 20) && l_wgs < 2048) ? 2 : 1;
+  }
+  StreamPool* pool = (g_prof_on || want_groups <= 1) ? nullptr : get_pool();
+  mrt_status status = MRT_OK;
+  for (int bh0 = 0; bh0 < BH && status == MRT_OK; bh0 += G) {
     const int nbh = BH - bh0 < G ? BH - bh0 : G;
-    kp.bh0 = bh0;
-    for (int t = 1; t <= pl.T; ++t) {
-      const bool first = t == 1, last = t == pl.T;
-      hipError_t e;
-      trace_next_launch(s);
-      {
-        ProfScope ps(s, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0));
-        if (pl.f32_path()) e = launch_f32_stage_r(kp, pl.dtype, nbh, first, last, s);
-        else e = launch_bf16_stage_r(kp, nbh, first, last, s);
+    int ngroups = pool ? (nbh < want_groups ? nbh : want_groups) : 1;
+    if (ngroups > 1) {
+      if (hipEventRecord(pool->fork, s) != hipSuccess) ngroups = 1;
+      for (int gi = 1; gi < ngroups; ++gi)
+        if (hipStreamWaitEvent(pool->side[gi - 1], pool->fork, 0) != hipSuccess) status = MRT_ERR_HIP;
+      if (status != MRT_OK) { set_error("helper stream fork failed"); break; }
+    }
+    for (int gi = 0; gi < ngroups; ++gi) {
+      const int lo = (int)((long long)nbh * gi / ngroups), hi = (int)((long long)nbh * (gi + 1) / ngroups);
+      hipStream_t gs = gi == 0 ? s : pool->side[gi - 1];
+      KParams kg = kp;
+      kg.bh0 = bh0 + lo;
+      kg.aL = (char*)kp.aL + pl.slab_aL * lo;
+      kg.Y = (char*)kp.Y + pl.slab_Y * lo;
+      kg.aR = (char*)kp.aR + pl.slab_aR * lo;
+      kg.cL = (float*)((char*)kp.cL + pl.slab_cL * lo);
+      for (int t = 1; t <= pl.T && status == MRT_OK; ++t) {
+        const bool first = t == 1, last = t == pl.T;
+        hipError_t e;
+        trace_next_launch(gs);
+        {
+          ProfScope ps(gs, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0));
+          if (pl.f32_path()) e = launch_f32_stage_r(kg, pl.dtype, hi - lo, first, last, gs);
+          else e = launch_bf16_stage_r(kg, hi - lo, first, last, gs);
+        }
+        if (e != hipSuccess) { status = hip_fail(e, "stage R launch"); break; }
+        trace_next_launch(gs);
+        {
+          ProfScope ps(gs, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0));
+          if (pl.f32_path()) e = launch_f32_stage_l(kg, pl.dtype, hi - lo, last, gs);
+          else e = launch_bf16_stage_l(kg, hi - lo, last, gs);
+        }
+        if (e != hipSuccess) { status = hip_fail(e, "stage L launch"); break; }
       }
-      if (e != hipSuccess) return hip_fail(e, "stage R launch");
-      trace_next_launch(s);
-      {
-        ProfScope ps(s, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0));
-        if (pl.f32_path()) e = launch_f32_stage_l(kp, pl.dtype, nbh, last, s);
-        else e = launch_bf16_stage_l(kp, nbh, last, s);
+    }
+    // join even after a failed launch, so that the helper streams never run ahead of the caller
+    for (int gi = 1; gi < ngroups; ++gi) {
+      if (hipEventRecord(pool->join[gi - 1], pool->side[gi - 1]) != hipSuccess ||
+          hipStreamWaitEvent(s, pool->join[gi - 1], 0) != hipSuccess) {
+        if (status == MRT_OK) { set_error("helper stream join failed"); status = MRT_ERR_HIP; }
       }
-      if (e != hipSuccess) return hip_fail(e, "stage L launch");
     }
   }
-  return MRT_OK;
+  return status;
 }
 
 mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk) {
@@ -320,6 +385,8 @@ int mrt_debug_set_trace(void* buf, size_t stride_bytes) {
   return 0;
 }
 #endif
+
+void mrt_set_head_groups(int n) { g_max_groups = n < 0 ? 0 : (n > kMaxGroups ? kMaxGroups : n); }
 
 void mrt_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -159,3 +159,52 @@ def test_rerun_is_bit_identical():
     O1 = run_monarch_gpu(wl, *dev)
     O2 = run_monarch_gpu(wl, *dev)
     assert torch.equal(O1, O2)
+
+
+def test_head_groups_do_not_change_the_result():
+    # concurrent head groups on helper streams vs one group on the caller's stream: bit identical
+    wl = syn.variant("C2", heads=5)
+    dev = to_device(wl, syn.make_inputs(wl))
+    try:
+        pkg.binding.set_head_groups(1)
+        O1 = run_monarch_gpu(wl, *dev)
+        for n in (2, 3, 4):
+            pkg.binding.set_head_groups(n)
+            assert torch.equal(run_monarch_gpu(wl, *dev), O1), f"{n} groups differ"
+    finally:
+        pkg.binding.set_head_groups(0)
+
+
+def test_hip_graph_replays_match_eager():
+    # the whole call (fork to helper streams, 2T kernels per head group, join) captured once and
+    # replayed several times with eager work in between
+    wl = syn.variant("C1", heads=6)
+    arrays = syn.make_inputs(wl)
+    Qd, Kd, Vd = to_device(wl, arrays)
+    eager = run_monarch_gpu(wl, Qd, Kd, Vd).clone()
+    prob_ws = pkg.monarch_attn_workspace_bytes(
+        pkg.make_problem(batch=1, heads=wl.heads, head_dim=wl.head_dim, f_q=wl.f_q, f_kv=wl.f_kv,
+                         h=wl.h, w=wl.w, scale=wl.scale), wl.b1, wl.b2, wl.tile, wl.iters)
+    ws = torch.empty(prob_ws, dtype=torch.uint8, device="cuda:0")
+    out = torch.empty_like(Qd)
+    run = lambda: pkg.monarch_attn_fwd(Qd, Kd, Vd, f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w,
+                                       b1=wl.b1, b2=wl.b2, tile=wl.tile, iters=wl.iters,
+                                       scale=wl.scale, out=out, workspace=ws)
+    pkg.binding.set_head_groups(3)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                   # warm-up outside capture (creates helper streams)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(4):
+        out.zero_()
+        ws.random_(0, 255)                      # eager work between replays; the workspace is scratch
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+    pkg.binding.set_head_groups(0)

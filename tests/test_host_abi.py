@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     assert {"monarch_attn_fwd", "dense_attn_fwd", "monarch_attn_check", "dense_attn_check",
             "monarch_attn_workspace_bytes", "monarch_attn_workspace_min_bytes",
             "mrt_status_string", "mrt_last_error", "mrt_profile_enable",
-            "mrt_profile_read"} <= set(decl)
+            "mrt_profile_read", "mrt_set_head_groups"} <= set(decl)
     for name in decl:
         assert hasattr(lib, name), f"{name} is declared in the header but not exported"
     assert sorted(B.EXPORTED) == decl
