@@ -83,13 +83,15 @@ mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, in
                               int causal_chunk);
 
 /* Smallest workspace (bytes) monarch_attn_fwd accepts: room for the alpha_L, c_L, Y and
- * alpha_R intermediates of ONE (batch, head) (App. A; Sec. 4.3 explains why these, unlike
- * L and R, have to live in device memory).  Returns 0 if the arguments are invalid. */
+ * alpha_R intermediates of ONE row of query tiles of one (batch, head) (App. A; Sec. 4.3 explains
+ * why these, unlike L and R, have to live in device memory, and that query chunks can be finished
+ * one after the other to cap it: the "mini-sequence" strategy).  Returns 0 if the arguments are
+ * invalid. */
 size_t monarch_attn_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 
 /* Recommended workspace: one slab per (batch, head), capped at 8 GiB.  Any size from the
- * minimum up is accepted; the library processes as many heads per pass as fit, and fewer heads
- * per pass means fewer workgroups per launch. */
+ * minimum up is accepted; the library processes as many heads per pass as fit (or, below one
+ * head, as many query tile rows of one head), and less per pass means fewer workgroups per launch. */
 size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 
 /* MonarchRT attention forward (Alg. 1 for tile = 0, Alg. 2 for tile = 1).

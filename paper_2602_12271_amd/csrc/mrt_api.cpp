@@ -89,7 +89,7 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
       set_error("regular Monarch needs (b1,b2) = (f*h, w) = (%d,%d), got (%d,%d)", p->f_q * p->h, p->w, b1, b2);
       return MRT_ERR_BLOCK;
     }
-    k.c2 = 1; k.ntq = 1; k.ntk = 1; k.c1k = 1;
+    k.c2 = 1; k.ntq = 1; k.ntk = 1; k.c1k = 1; pl.c1q = 1;
   } else {
     if (b1 % p->h != 0) {
       set_error("tiled Monarch needs b1 to be a whole number of frames (b1 %% h == 0)");
@@ -102,7 +102,8 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
     }
     k.c2 = p->w / b2;
     k.c1k = (p->f_kv * p->h) / b1;
-    k.ntq = ((p->f_q * p->h) / b1) * k.c2;
+    pl.c1q = (p->f_q * p->h) / b1;
+    k.ntq = pl.c1q * k.c2;
     k.ntk = k.c1k * k.c2;
   }
   if (causal_chunk > 0) {
@@ -121,7 +122,9 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
   pl.B = p->batch; pl.T = iters; pl.Nq = k.Nq; pl.Nkv = k.Nkv;
   pl.dtype = p->dtype; pl.compute = p->compute;
   const size_t es = pl.f32_path() ? 4 : 2;
-  const size_t rows = (size_t)k.Nq * k.ntk;          // (m, j, nk) triples
+  pl.ntq_total = k.ntq;
+  // one slab = the intermediates of one query tile row (c2 query tiles) of one (batch, head)
+  const size_t rows = (size_t)k.c2 * b1 * b2 * k.ntk;          // (m, j, nk) triples of the row
   pl.slab_aL = round256(rows * k.d * es);
   pl.slab_Y = pl.slab_aL;
   pl.slab_aR = iters >= 2 ? pl.slab_aL : 0;
@@ -130,17 +133,17 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
   return MRT_OK;
 }
 
-// heads per pass the recommended workspace is sized for
-static int recommended_heads_per_pass(const Plan& pl) {
+// (batch, head, query tile row) slabs the recommended workspace is sized for
+static size_t recommended_slabs(const Plan& pl) {
   // Measured on MI355X: more (batch, head) slabs per pass always won over keeping a pass inside
   // the 256 MB last-level cache (stage L has only ntq*b2 workgroups per head), so the only cap
   // is a bound on the workspace itself.
   const size_t budget = size_t(8) << 30;
-  const int BH = pl.B * pl.kp.H;
+  const size_t all = (size_t)pl.B * pl.kp.H * pl.c1q;
   size_t g = budget / pl.slab_bytes();
+  if (g >= (size_t)pl.c1q) g -= g % pl.c1q;        // whole heads when at least one fits
   if (g < 1) g = 1;
-  if (g > (size_t)BH) g = BH;
-  return (int)g;
+  return g > all ? all : g;
 }
 
 #ifdef MRT_TRACE
@@ -244,7 +247,7 @@ size_t monarch_attn_workspace_min_bytes(const mrt_problem* p, int b1, int b2, in
 size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
   Plan pl;
   if (make_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
-  return pl.slab_bytes() * recommended_heads_per_pass(pl);
+  return pl.slab_bytes() * recommended_slabs(pl);
 }
 
 mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
@@ -263,20 +266,33 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
   }
   const size_t slab = pl.slab_bytes();
   if (workspace_bytes < slab) {
-    set_error("workspace has %zu bytes, one (batch,head) needs %zu", workspace_bytes, slab);
+    set_error("workspace has %zu bytes, one query tile row of one (batch,head) needs %zu",
+              workspace_bytes, slab);
     return MRT_ERR_WORKSPACE;
   }
+  // A pass covers G (batch, head) entries x A query tile rows, whatever fits the workspace:
+  // all rows of as many heads as possible, or, if not even one head fits, A rows of one head at
+  // a time (query tiles are independent: the mini-sequence strategy of Sec. 4.3).
   const int BH = pl.B * pl.kp.H;
-  int G = (int)(workspace_bytes / slab < (size_t)BH ? workspace_bytes / slab : (size_t)BH);
+  const size_t units = workspace_bytes / slab;
+  int G, A;
+  if (units >= (size_t)pl.c1q) {
+    G = (int)(units / pl.c1q < (size_t)BH ? units / pl.c1q : (size_t)BH);
+    A = pl.c1q;
+  } else {
+    G = 1;
+    A = (int)units;
+  }
   hipStream_t s = (hipStream_t)hip_stream;
 
   KParams kp = pl.kp;
   kp.Q = Q; kp.K = K; kp.V = V; kp.O = O;
   char* base = (char*)workspace;
+  const size_t per_head = (size_t)A;               // slabs per head inside a pass
   kp.aL = base;
-  kp.Y = base + pl.slab_aL * G;
-  kp.aR = base + (pl.slab_aL + pl.slab_Y) * G;
-  kp.cL = (float*)(base + (pl.slab_aL + pl.slab_Y + pl.slab_aR) * G);
+  kp.Y = base + pl.slab_aL * per_head * G;
+  kp.aR = base + (pl.slab_aL + pl.slab_Y) * per_head * G;
+  kp.cL = (float*)(base + (pl.slab_aL + pl.slab_Y + pl.slab_aR) * per_head * G);
 
   // Heads are independent, so a pass is cut into up to kMaxGroups head groups whose kernel chains
   // run on helper streams forked from and joined back to the caller's stream: the short tail of
@@ -287,14 +303,18 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
   // the chip holds (KV-cache shapes at 12 heads: -7 %); small calls run on the caller's stream.
   int want_groups = g_max_groups;
   if (want_groups == 0) {
-    const size_t inter_per_launch = pl.slab_aL * (size_t)G;
-    const long long l_wgs = (long long)pl.kp.ntq * pl.kp.b2 * G;
+    const size_t inter_per_launch = pl.slab_aL * per_head * G;
+    const long long l_wgs = (long long)A * pl.kp.c2 * pl.kp.b2 * G;
     want_groups = (inter_per_launch >= (size_t(128) << 20) && l_wgs < 2048) ? 2 : 1;
   }
   StreamPool* pool = (g_prof_on || want_groups <= 1) ? nullptr : get_pool();
   mrt_status status = MRT_OK;
-  for (int bh0 = 0; bh0 < BH && status == MRT_OK; bh0 += G) {
+  for (int bh0 = 0; bh0 < BH && status == MRT_OK; bh0 += G)
+  for (int a0 = 0; a0 < pl.c1q && status == MRT_OK; a0 += A) {
     const int nbh = BH - bh0 < G ? BH - bh0 : G;
+    const int na = pl.c1q - a0 < A ? pl.c1q - a0 : A;
+    kp.m0 = a0 * pl.kp.c2;
+    kp.ntq = na * pl.kp.c2;
     int ngroups = pool ? (nbh < want_groups ? nbh : want_groups) : 1;
     if (ngroups > 1) {
       if (hipEventRecord(pool->fork, s) != hipSuccess) ngroups = 1;
@@ -307,10 +327,10 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
       hipStream_t gs = gi == 0 ? s : pool->side[gi - 1];
       KParams kg = kp;
       kg.bh0 = bh0 + lo;
-      kg.aL = (char*)kp.aL + pl.slab_aL * lo;
-      kg.Y = (char*)kp.Y + pl.slab_Y * lo;
-      kg.aR = (char*)kp.aR + pl.slab_aR * lo;
-      kg.cL = (float*)((char*)kp.cL + pl.slab_cL * lo);
+      kg.aL = (char*)kp.aL + pl.slab_aL * na * lo;
+      kg.Y = (char*)kp.Y + pl.slab_Y * na * lo;
+      kg.aR = (char*)kp.aR + pl.slab_aR * na * lo;
+      kg.cL = (float*)((char*)kp.cL + pl.slab_cL * na * lo);
       for (int t = 1; t <= pl.T && status == MRT_OK; ++t) {
         const bool first = t == 1, last = t == pl.T;
         hipError_t e;

@@ -185,7 +185,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int nk = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int nk = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int n = nk / b1, k = nk - n * b1;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int an = n / p.c2, bn = n - an * p.c2;
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   if (FIRST) {
     arow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + (qtok0 + jc) * p.qs.token;
   } else {
-    arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + m) * NKtot + nk) * b2 + jc) * D;
+    arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 + jc) * D;
   }
   bf16x8 qv[KS1];
 #pragma unroll
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   ent = xsum(ent);
   const float inv = 1.0f / sum;
   if (g == 0 && j < b2)
-    p.cL[(((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk] = kLn2 * (ent * inv - log2_fast(sum));
+    p.cL[(((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot + nk] = kLn2 * (ent * inv - log2_fast(sum));
 
   // alpha_L = R K (and Y = R V)
   f32x4 oK[NVT], oV[LAST ? NVT : 1];
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   }
   MRT_STAMP(2);
   if (j < b2) {
-    const size_t row = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk;
+    const size_t row = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot + nk;
     store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
     if constexpr (LAST) store_rows<D>((u16*)p.Y + row * D, oV, 1.0f, g);
   }
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int j = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -573,7 +573,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
       qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
   }
 
-  const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const u16* Yp = (const u16*)p.Y + row0 * D;
   const float* cLp = p.cL + row0;
@@ -624,7 +624,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   constexpr int nlt = NLT;
-  const int j = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -635,7 +635,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   MRT_STAMP(0);
   stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
 
-  const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const float* cLp = p.cL + row0;
 
@@ -671,7 +671,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
 
   // ---- pass 2: waves stride over groups of PT adjacent nk tiles (every LDS read of Q serves
   // all PT tiles); the next group's operands are fetched while the current one is processed
-  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + m) * NKtot * b2 * D;
+  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
   const float scale2 = p.scale * kLog2e;
   const int ntiles = (NK + 15) >> 4;
   const int ngroups = (ntiles + PT - 1) / PT;

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
   extern __shared__ float sm[];
   const int tid = threadIdx.x;
   const int d = p.d, b1 = p.b1, b2 = p.b2, ld = d + 1, ls = b2 + 1;
-  const int nk = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int nk = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int n = nk / b1, k = nk - n * b1;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int an = n / p.c2, bn = n - an * p.c2;
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
   const TIn* Kp = (const TIn*)p.K + b * p.ks.batch + hd * p.ks.head;
   const TIn* Vp = (const TIn*)p.V + b * p.vs.batch + hd * p.vs.head;
   const size_t NKtot = (size_t)p.ntk * b1;
-  const float* aRp = (const float*)p.aR + (((size_t)bhl * p.ntq + m) * NKtot + nk) * b2 * d;
+  const float* aRp = (const float*)p.aR + (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 * d;
 
   for (int idx = tid; idx < b2 * d; idx += kThreads) {
     const int j = idx / d, v = idx - j * d;
@@ -85,11 +85,11 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
     const float inv = 1.0f / sum;
     for (int i = 0; i < b2; ++i) S[j * ls + i] *= inv;
     // sum_i R log R = (sum_i e z)/sum - log(sum)
-    p.cL[(((size_t)bhl * p.ntq + m) * b2 + j) * NKtot + nk] = ent * inv - logf(sum);
+    p.cL[(((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot + nk] = ent * inv - logf(sum);
   }
   __syncthreads();
-  float* aLp = (float*)p.aL + ((((size_t)bhl * p.ntq + m) * b2) * NKtot + nk) * d;
-  float* Yp = (float*)p.Y + ((((size_t)bhl * p.ntq + m) * b2) * NKtot + nk) * d;
+  float* aLp = (float*)p.aL + ((((size_t)bhl * p.ntq + ml) * b2) * NKtot + nk) * d;
+  float* Yp = (float*)p.Y + ((((size_t)bhl * p.ntq + ml) * b2) * NKtot + nk) * d;
   const size_t jstride = NKtot * d;
   for (int idx = tid; idx < b2 * d; idx += kThreads) {
     const int j = idx / d, v = idx - j * d;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
   extern __shared__ float sm[];
   const int tid = threadIdx.x;
   const int d = p.d, b1 = p.b1, b2 = p.b2, ld = d + 1, lz = kCH + 1;
-  const int j = blockIdx.x, m = blockIdx.y, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
     const int l = idx / d, v = idx - l * d;
     Qj[l * ld + v] = ldf(Qp + (qtok0 + (long long)l * p.w) * p.qs.token + v);
   }
-  const size_t row0 = (((size_t)bhl * p.ntq + m) * b2 + j) * NKtot;
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const float* aLp = (const float*)p.aL + row0 * d;
   const float* Yp = (const float*)p.Y + row0 * d;
   const float* cLp = p.cL + row0;
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
 #pragma unroll
     for (int r = 0; r < kMaxRows; ++r) acc[r] = 0.f;
   }
-  float* aRout = (float*)p.aR + ((size_t)bhl * p.ntq + m) * NKtot * b2 * d;
+  float* aRout = (float*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * d;
 
   for (int c0 = 0; c0 < NK; c0 += kCH) {
     const int cn = NK - c0 < kCH ? NK - c0 : kCH;

@@ -29,7 +29,8 @@ struct KParams {
   int d;
   int b1, b2;
   int c2;       // column tiles
-  int ntq, ntk;
+  int ntq, ntk; // query tiles IN THIS PASS (workspace extent), key tiles of the whole grid
+  int m0;       // first query tile of this pass
   int c1k;      // key tile rows
   int w;        // grid width = c2*b2
   int fb;       // frames per tile row (b1/h); 0 when no mask
@@ -54,7 +55,8 @@ struct Plan {
   int B, T;
   int Nq, Nkv;
   int dtype, compute;
-  size_t slab_aL, slab_Y, slab_aR, slab_cL;   // bytes per (batch, head)
+  int ntq_total, c1q;                         // query tiles / query tile rows of the whole grid
+  size_t slab_aL, slab_Y, slab_aR, slab_cL;   // bytes per (batch, head, query tile row)
   size_t slab_bytes() const { return slab_aL + slab_Y + slab_aR + slab_cL; }
   bool f32_path() const { return dtype == MRT_F32 || compute == MRT_COMPUTE_F32; }
 };

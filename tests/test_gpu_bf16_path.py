@@ -208,3 +208,33 @@ def test_hip_graph_replays_match_eager():
         torch.cuda.synchronize()
         assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
     pkg.binding.set_head_groups(0)
+
+
+def test_mini_sequence_passes_match_single_pass_and_oracle():
+    # full bidirectional sequence (f_q = f_kv = 6) with 2-frame tiles: three query tile rows.  With
+    # the minimum workspace the library finishes one query tile row at a time (Sec. 4.3,
+    # mini-sequence); the result must equal the single-pass result bit for bit.
+    wl = small_bf16(heads=2, f_q=6, f_kv=6, h=8, w=28, b1=16, b2=14, tile=1, iters=2,
+                    causal_chunk=0, q_frame_offset=0)
+    arrays = syn.make_inputs(wl)
+    dev = to_device(wl, arrays)
+    prob = pkg.make_problem(batch=1, heads=wl.heads, head_dim=wl.head_dim, f_q=wl.f_q, f_kv=wl.f_kv,
+                            h=wl.h, w=wl.w, scale=wl.scale)
+    nmin = pkg.monarch_attn_workspace_bytes(prob, wl.b1, wl.b2, wl.tile, wl.iters, minimum=True)
+    nall = pkg.monarch_attn_workspace_bytes(prob, wl.b1, wl.b2, wl.tile, wl.iters)
+    assert nall == nmin * 3 * wl.heads
+    O_full = run_monarch_gpu(wl, *dev)
+    for units in (1, 2, 3, 4):                  # 1-2 rows per pass, one head, one head + change
+        ws = torch.empty(nmin * units, dtype=torch.uint8, device="cuda:0")
+        assert torch.equal(run_monarch_gpu(wl, *dev, workspace=ws), O_full), f"{units} slabs"
+    check(wl, arrays, O_full, label="bidirectional 6 frames")
+
+
+def test_bidirectional_480p_one_frame_tiles():
+    # the paper's s = 0.95 point for the 81-frame video: every frame its own tile row, tile blocks
+    # (h, w) = (30, 52), full 32760 x 32760 attention; one head through the oracle
+    wl = syn.variant("C3", heads=2, f_q=21, f_kv=21, b1=30, b2=52, iters=1, causal_chunk=0,
+                     q_frame_offset=0)
+    arrays = syn.make_inputs(wl)
+    O = run_monarch_gpu(wl, *to_device(wl, arrays))
+    check(wl, arrays, O, heads=[1], label="480p bidirectional (30,52) T=1")
