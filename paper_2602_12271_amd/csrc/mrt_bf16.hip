@@ -97,9 +97,9 @@ __device__ inline float xsum(float x) {
 // Second product for one 32-key step: acc[vt] += Val^T[phi(vt, .), keys] * P.
 // vals points at LDS row `32*step` of a row-major [rows][D + kPad] tile; output feature of
 // accumulator row (4g + r) of tile vt is phi = 32(vt/2) + 8g + 4(vt%2) + r.
-template <int D>
+template <int D, int LD = D + kPad>
 __device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane) {
-  constexpr int LD = D + kPad, NVT = D / 16, HALF = NVT / 2;
+  constexpr int NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
   const u16* base = vals + (4 * g + e) * LD + 8 * q;
 #pragma unroll
@@ -121,10 +121,10 @@ __device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane)
 }
 
 // Same for NB probability operands sharing every value-side LDS read (operands >= nb idle).
-template <int D, int NB>
+template <int D, int NB, int LD = D + kPad>
 __device__ inline void pv_step_multi(const u16* vals, const bf16x8 (&pb)[NB], int nb,
                                      f32x4 (&acc)[NB][D / 16], int lane) {
-  constexpr int LD = D + kPad, NVT = D / 16, HALF = NVT / 2;
+  constexpr int NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
   const u16* base = vals + (4 * g + e) * LD + 8 * q;
 #pragma unroll
@@ -161,15 +161,38 @@ __device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) 
 
 // Cooperative copy of `rows` rows of D bf16 (row r at src + r*stride) into a row-major LDS tile,
 // zero-filling rows >= valid.
-template <int D>
+template <int D, int LD = D + kPad>
 __device__ inline void stage_rows(u16* dst, const u16* src, long long stride, int rows, int valid,
                                   int tid, int nthr) {
-  constexpr int CPR = D / 8, LD = D + kPad;
+  constexpr int CPR = D / 8;
   for (int idx = tid; idx < rows * CPR; idx += nthr) {
     const int r = idx / CPR, c = idx - r * CPR;
     uint4 v = {0u, 0u, 0u, 0u};
     if (r < valid) v = *(const uint4*)(src + (long long)r * stride + 8 * c);
     *(uint4*)(dst + r * LD + 8 * c) = v;
+  }
+}
+
+// Same copy with compile-time extents: every load is issued before the first LDS store, so a
+// thread has all its loads in flight at once instead of one round trip per row.
+template <int D, int LD, int ROWS, int NTHR>
+__device__ inline void stage_rows_batched(u16* dst, const u16* src, long long stride, int valid, int tid) {
+  constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
+  uint4 v[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    int idx = tid + i * NTHR;
+    idx = idx < TOTAL ? idx : TOTAL - 1;
+    int r = idx / CPR;
+    const int c = idx - r * CPR;
+    r = r < valid ? r : valid - 1;
+    v[i] = *(const uint4*)(src + (long long)r * stride + 8 * c);
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const int idx = tid + i * NTHR;
+    const int r = idx / CPR, c = idx - r * CPR;
+    if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
   }
 }
 
@@ -602,83 +625,24 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   MRT_STAMP(2);
 }
 
-// stage L, earlier iterations:
-//   alpha_R[m, nk, j, :] / c_R[m, nk, j] = sum_l L[l, nk] Q[m, l, j, :] / sum_l L[l, nk]
-// with L = softmax_nk(Z_L).  Pass 1 finds the log-sum-exp of every row l (flash loop without
-// values); pass 2 recomputes Z_L one 16-wide nk tile per wave with l on the M side, forms
-// softmax over l of log L[l, nk] (the same ratio, safe against underflow) and contracts with Q
-// read transposed from LDS.
-constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
-
-// NLT = number of 16-row l tiles (compile time, so that the tile loops unroll without guards and
-// the scheduler can overlap one tile's LDS reads with another's MFMAs).
-template <int D, int QT, int MAXT, int NLT, int PT>
-__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
-  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  FlashLds<D, false> lds(smem);
-  u16* Qs = (u16*)(smem + FlashLds<D, false>::kBytes);   // [qrows][LD], rows >= b1 zero
-  float* lse = (float*)(Qs + (size_t)qrows * LD);        // [16 * kMaxLT]
-
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
-  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+// Pass 2 of the refine stage for one (m, j): waves stride over groups of PT adjacent 16-wide nk
+// tiles (every LDS read of Q serves all PT tiles).  Qs holds Q[m, :, j, :] row-major (rows >= b1
+// zero), lse the base-2 log-sum-exp of every row l.  When `resident`, alpha_L[m, j] and its
+// -c_L*log2(e) biases are read from LDS (Kres / bres, rows of LD elements), else from global
+// memory with the next group's operands in flight while the current one is processed.
+template <int D, int NLT, int PT, int LD>
+__device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float* lse, bool resident,
+                                    const u16* Kres, const float* bres, const u16* aLp,
+                                    const float* cLp, u16* aRout, int NK, int j, int wave,
+                                    int nwaves, int lane) {
+  constexpr int KS1 = D / 32, NVT = D / 16;
+  const int g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  constexpr int nlt = NLT;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
-  const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
-  const size_t NKtot = (size_t)p.ntk * b1;
-  const int b = bh / p.H, hd = bh - b * p.H;
-
-  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
-  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
-  MRT_STAMP(0);
-  stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
-
-  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
-  const u16* aLp = (const u16*)p.aL + row0 * D;
-  const float* cLp = p.cL + row0;
-
-  // ---- pass 1
-  {
-    const WaveTiles<QT> wt(wave, nwaves, nlt);
-    bf16x8 qv[QT][KS1];
-#pragma unroll
-    for (int q = 0; q < QT; ++q) {
-      const int l = 16 * wt.lt[q] + c;
-      const int lc = l < b1 ? l : b1 - 1;
-#pragma unroll
-      for (int ks = 0; ks < KS1; ++ks)
-        qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
-    }
-    FlashState<QT> st;
-    f32x4 odummy[QT][NVT];
-    int qchunk[QT];
-#pragma unroll
-    for (int q = 0; q < QT; ++q) qchunk[q] = 0;
-    auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-    flash_loop<D, QT, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st,
-                                    odummy, tid, nthr, lane);
-    MRT_STAMP(1);
-#pragma unroll
-    for (int q = 0; q < QT; ++q) {
-      const float lsum = xsum(st.lrun[q]);
-      if (q < wt.nq && g == 0) lse[16 * wt.lt[q] + c] = st.mrun[q] + log2_fast(lsum);   // base 2
-    }
-  }
-  __syncthreads();
-  MRT_STAMP(2);
-
-  // ---- pass 2: waves stride over groups of PT adjacent nk tiles (every LDS read of Q serves
-  // all PT tiles); the next group's operands are fetched while the current one is processed
-  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
   const float scale2 = p.scale * kLog2e;
   const int ntiles = (NK + 15) >> 4;
   const int ngroups = (ntiles + PT - 1) / PT;
   bf16x8 kb[PT][KS1], kbn[PT][KS1];
   float cl[PT], cln[PT];
-  // when all of alpha_L[m, j] fits the two chunk buffers it is still resident after pass 1
-  const bool resident = NK <= 2 * kCK;
   auto fetch = [&](int grp, bf16x8 (&dst)[PT][KS1], float (&cdst)[PT]) {
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
@@ -686,8 +650,8 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
       const int nkc = nk < NK ? nk : NK - 1;
       if (resident) {
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) dst[pt][ks] = ld_lds_16B(lds.K(0) + nkc * LD + 32 * ks + 8 * g);
-        cdst[pt] = -lds.bias(0)[nkc];
+        for (int ks = 0; ks < KS1; ++ks) dst[pt][ks] = ld_lds_16B(Kres + nkc * LD + 32 * ks + 8 * g);
+        cdst[pt] = -bres[nkc];
       } else {
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks)
@@ -782,7 +746,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
       for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
-      pv_step_multi<D, PT>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
+      pv_step_multi<D, PT, LD>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
     if (grp == wave) MRT_STAMP(5);
@@ -794,6 +758,325 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
     }
     if (grp == wave) MRT_STAMP(6);
   }
+}
+
+// stage L, earlier iterations:
+//   alpha_R[m, nk, j, :] / c_R[m, nk, j] = sum_l L[l, nk] Q[m, l, j, :] / sum_l L[l, nk]
+// with L = softmax_nk(Z_L).  Pass 1 finds the log-sum-exp of every row l (flash loop without
+// values); pass 2 recomputes Z_L one 16-wide nk tile per wave with l on the M side, forms
+// softmax over l of log L[l, nk] (the same ratio, safe against underflow) and contracts with Q
+// read transposed from LDS.
+constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
+
+// NLT = number of 16-row l tiles (compile time, so that the tile loops unroll without guards and
+// the scheduler can overlap one tile's LDS reads with another's MFMAs).
+template <int D, int QT, int MAXT, int NLT, int PT>
+__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
+  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  FlashLds<D, false> lds(smem);
+  u16* Qs = (u16*)(smem + FlashLds<D, false>::kBytes);   // [qrows][LD], rows >= b1 zero
+  float* lse = (float*)(Qs + (size_t)qrows * LD);        // [16 * kMaxLT]
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  constexpr int nlt = NLT;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+
+  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  MRT_STAMP(0);
+  stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const float* cLp = p.cL + row0;
+
+  // ---- pass 1
+  {
+    const WaveTiles<QT> wt(wave, nwaves, nlt);
+    bf16x8 qv[QT][KS1];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * wt.lt[q] + c;
+      const int lc = l < b1 ? l : b1 - 1;
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks)
+        qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+    }
+    FlashState<QT> st;
+    f32x4 odummy[QT][NVT];
+    int qchunk[QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) qchunk[q] = 0;
+    auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
+    flash_loop<D, QT, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st,
+                                    odummy, tid, nthr, lane);
+    MRT_STAMP(1);
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const float lsum = xsum(st.lrun[q]);
+      if (q < wt.nq && g == 0) lse[16 * wt.lt[q] + c] = st.mrun[q] + log2_fast(lsum);   // base 2
+    }
+  }
+  __syncthreads();
+  MRT_STAMP(2);
+
+  // ---- pass 2 (alpha_L[m, j] is still resident in the two chunk buffers when it fits them)
+  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
+  refine_pass2<D, NLT, PT, LD>(p, Qs, lse, NK <= 2 * kCK, lds.K(0), lds.bias(0), aLp, cLp, aRout, NK,
+                               j, wave, nwaves, lane);
+  MRT_STAMP(6);
+}
+
+// ---------------------------------------------------------------------------------------
+// stage L for short key ranges (NK <= 96: regular Monarch with b1 <= 96, or one small visible
+// tile).  Everything a workgroup needs is loaded once, so there is one memory round trip, an exact
+// (not online) softmax, and the footprint (52 KB of LDS, <= 168 registers) lets three workgroups
+// share a compute unit: the 52*heads workgroups of the 4680-token chunk run in a single round.
+// ---------------------------------------------------------------------------------------
+constexpr int kResRows = 96;    // key rows held resident
+constexpr int kResPad = 8;      // row padding of the resident tiles (row stride = 4 banks mod 64)
+
+// Exact softmax of QT query tiles (nq of them live) against NTK resident key tiles; every key
+// operand read from LDS serves all QT tiles.  On return s holds the exponentials (base-2 logits
+// minus the column maximum) and sum their column sums.
+template <int D, int NTK, int LD, int QT>
+__device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8 (&qv)[QT][D / 32],
+                                  int nq, float scale2, f32x4 (&s)[QT][NTK], float (&sum)[QT],
+                                  int lane) {
+  constexpr int KS1 = D / 32;
+  const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int q = 0; q < QT; ++q)
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) s[q][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kp = 0; kp < (NTK + 1) / 2; ++kp) {
+    bf16x8 a[2][KS1];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (2 * kp + t < NTK) {
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks)
+          a[t][ks] = ld_lds_16B(Ks + (16 * (2 * kp + t) + c) * LD + 32 * ks + 8 * g);
+      }
+#pragma unroll
+    for (int q = 0; q < QT; ++q)
+      if (q < nq) {
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+            if (2 * kp + t < NTK) s[q][2 * kp + t] = mfma(a[t][ks], qv[q][ks], s[q][2 * kp + t]);
+      }
+    __builtin_amdgcn_sched_barrier(0);   // one pair of key tiles in flight at a time
+  }
+  f32x4 bi[NTK];
+#pragma unroll
+  for (int kt = 0; kt < NTK; ++kt) bi[kt] = *(const f32x4*)(bias + 16 * kt + 4 * g);
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[q][kt][r] = fmaf(s[q][kt][r], scale2, bi[kt][r]);      // -inf beyond the last key
+        mx = fmaxf(mx, s[q][kt][r]);
+      }
+    mx = xmax(mx);
+    float sm = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[q][kt][r] = exp2_fast(s[q][kt][r] - mx);
+        sm += s[q][kt][r];
+      }
+    sum[q] = xsum(sm);
+  }
+}
+
+template <int D, int NTK>
+__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
+  constexpr int LD = D + kResPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  constexpr int QT = 2;
+  __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];
+  __shared__ __attribute__((aligned(16))) u16 Vs[ROWS * LD];
+  __shared__ __attribute__((aligned(16))) float bias[ROWS];
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;   // <= 16*NTK
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const int nlt = (b1 + 15) >> 4;
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const u16* Yp = (const u16*)p.Y + row0 * D;
+  const float* cLp = p.cL + row0;
+  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
+
+  MRT_STAMP(0);
+  // this wave's query tiles (2*wave, 2*wave+1) go to registers while the key side goes to LDS
+  bf16x8 qv[QT][KS1];
+  auto load_q = [&](int pair) {
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * (QT * pair + q) + c;
+      const int lc = l < b1 ? l : b1 - 1;
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks)
+        qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+    }
+  };
+  const int npairs = (nlt + QT - 1) / QT;
+  if (wave < npairs) load_q(wave);
+  stage_rows_batched<D, LD, ROWS, 256>(Ks, aLp, D, NK, tid);
+  stage_rows_batched<D, LD, ROWS, 256>(Vs, Yp, D, NK, tid);
+  for (int i = tid; i < ROWS; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+  __syncthreads();
+  MRT_STAMP(1);
+
+  const float scale2 = p.scale * kLog2e;
+  for (int pair = wave; pair < npairs; pair += nwaves) {
+    if (pair != wave) load_q(pair);
+    const int nq = nlt - QT * pair < QT ? nlt - QT * pair : QT;
+    f32x4 s[QT][NTK];
+    float sum[QT];
+    res_logits<D, NTK, LD, QT>(Ks, bias, qv, nq, scale2, s, sum, lane);
+    bf16x8 pb[KS2][QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q)
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        const f32x4 hi = (2 * st + 1 < NTK) ? s[q][(2 * st + 1 < NTK) ? 2 * st + 1 : 0] : zero;
+        pb[st][q] = pack8(s[q][2 * st], hi);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 o[QT][NVT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      pv_step_multi<D, QT, LD>(Vs + 32 * st * LD, pb[st], nq, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * (QT * pair + q) + c;
+      if (q < nq && l < b1) store_rows<D>(Op + (long long)l * p.w * p.os.token, o[q], 1.0f / sum[q], g);
+    }
+  }
+  MRT_STAMP(2);
+}
+
+template <int D, int NLT>
+__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_res(KParams p) {
+  constexpr int LD = D + kResPad, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), NTKMAX = kResRows / 16;
+  __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
+  __shared__ __attribute__((aligned(16))) u16 Ks[kResRows * LD];
+  __shared__ __attribute__((aligned(16))) float bias[kResRows];
+  __shared__ __attribute__((aligned(16))) float lse[16 * NLT];
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;   // <= kResRows
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const int nkt = (NK + 15) >> 4;
+
+  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const float* cLp = p.cL + row0;
+
+  MRT_STAMP(0);
+  stage_rows_batched<D, LD, QROWS, 256>(Qs, Qp, (long long)p.w * p.qs.token, b1, tid);
+  stage_rows_batched<D, LD, kResRows, 256>(Ks, aLp, D, NK, tid);
+  for (int i = tid; i < kResRows; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+  __syncthreads();
+  MRT_STAMP(1);
+
+  // ---- pass 1: base-2 log-sum-exp of every query row over the resident keys; a wave takes two
+  // query tiles at a time so that every key operand read from LDS feeds two MFMAs
+  const float scale2 = p.scale * kLog2e;
+  constexpr int QT = 2, NPAIRS = (NLT + QT - 1) / QT;
+  for (int pair = wave; pair < NPAIRS; pair += nwaves) {
+    const int nq = NLT - QT * pair < QT ? NLT - QT * pair : QT;
+    bf16x8 qv[QT][KS1];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int lt = QT * pair + q < NLT ? QT * pair + q : NLT - 1;
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks) qv[q][ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
+    }
+    float mx[QT];
+    f32x4 s[QT][NTKMAX];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) mx[q] = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NTKMAX; ++kt) {
+#pragma unroll
+      for (int q = 0; q < QT; ++q) s[q][kt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      if (kt < nkt) {
+        bf16x8 av[KS1];
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Ks + (16 * kt + c) * LD + 32 * ks + 8 * g);
+        const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+#pragma unroll
+        for (int q = 0; q < QT; ++q) {
+          if (q < nq) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], qv[q][ks], acc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              acc[r] = fmaf(acc[r], scale2, bi[r]);
+              mx[q] = fmaxf(mx[q], acc[r]);
+            }
+            s[q][kt] = acc;
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const float m2 = xmax(mx[q]);
+      float sum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < NTKMAX; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum += exp2_fast(s[q][kt][r] - m2);
+      sum = xsum(sum);
+      if (q < nq && g == 0) lse[16 * (QT * pair + q) + c] = m2 + log2_fast(sum);
+    }
+  }
+  __syncthreads();
+  MRT_STAMP(2);
+
+  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
+  refine_pass2<D, NLT, 2, LD>(p, Qs, lse, true, Ks, bias, aLp, cLp, aRout, NK, j, wave, nwaves, lane);
+  MRT_STAMP(6);
 }
 
 // dense baseline: 128 queries per workgroup (4 waves x 2 tiles of 16), flash loop over all
@@ -892,6 +1175,40 @@ hipError_t launch_l_refine(const KParams& kp, dim3 grid, int nthr, hipStream_t s
   return hipGetLastError();
 }
 
+template <int D, int NTK>
+hipError_t launch_l_out_res(const KParams& kp, dim3 grid, hipStream_t s) {
+  k_bf16_stage_l_out_res<D, NTK><<<grid, 256, 0, s>>>(kp);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_l_out_res_d(const KParams& kp, dim3 grid, int nkt, hipStream_t s) {
+  switch (nkt) {
+    case 1: return launch_l_out_res<D, 1>(kp, grid, s);
+    case 2: return launch_l_out_res<D, 2>(kp, grid, s);
+    case 3: return launch_l_out_res<D, 3>(kp, grid, s);
+    case 4: return launch_l_out_res<D, 4>(kp, grid, s);
+    case 5: return launch_l_out_res<D, 5>(kp, grid, s);
+    case 6: return launch_l_out_res<D, 6>(kp, grid, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int D>
+hipError_t launch_l_refine_res_d(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
+  const int nthr = 256;
+  switch (nlt) {
+    case 1: k_bf16_stage_l_refine_res<D, 1><<<grid, nthr, 0, s>>>(kp); break;
+    case 2: k_bf16_stage_l_refine_res<D, 2><<<grid, nthr, 0, s>>>(kp); break;
+    case 3: k_bf16_stage_l_refine_res<D, 3><<<grid, nthr, 0, s>>>(kp); break;
+    case 4: k_bf16_stage_l_refine_res<D, 4><<<grid, nthr, 0, s>>>(kp); break;
+    case 5: k_bf16_stage_l_refine_res<D, 5><<<grid, nthr, 0, s>>>(kp); break;
+    case 6: k_bf16_stage_l_refine_res<D, 6><<<grid, nthr, 0, s>>>(kp); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_l_refine_d(const KParams& kp, dim3 grid, int nthr, int nlt, hipStream_t s) {
   switch (nlt) {
@@ -938,6 +1255,14 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   // Workgroups of 4 waves (one per SIMD), each wave owning up to two query tiles, so that two
   // workgroups fit a compute unit whatever order their waves are dealt to the SIMDs in; only
   // b1 > 128 needs a fifth and sixth wave.
+  // short key ranges: everything resident, three workgroups per compute unit
+  const int nk_max = kp.ntk * kp.b1;
+  if (nk_max <= kResRows) {
+    if (last) return kp.d == 128 ? launch_l_out_res_d<128>(kp, grid, (nk_max + 15) / 16, s)
+                                 : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
+    return kp.d == 128 ? launch_l_refine_res_d<128>(kp, grid, nlt, s)
+                       : launch_l_refine_res_d<64>(kp, grid, nlt, s);
+  }
   const int nthr = nlt <= 8 ? 256 : 64 * ((nlt + 1) / 2);
   if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nthr, nlt, s)
                                 : launch_l_refine_d<64>(kp, grid, nthr, nlt, s);
