@@ -173,27 +173,43 @@ __device__ inline void stage_rows(u16* dst, const u16* src, long long stride, in
   }
 }
 
-// Same copy with compile-time extents: every load is issued before the first LDS store, so a
-// thread has all its loads in flight at once instead of one round trip per row.
+// Same copy with compile-time extents, split into its two halves: load() issues every global
+// load of the tile (rows beyond `valid` re-read the last valid row), store() writes the tile to
+// LDS and zero-fills the missing rows.  A thread has all its loads in flight at once instead of
+// one round trip per row, and other loads can be issued between the two calls.
+template <int D, int ROWS, int NTHR>
+struct RowRegs {
+  static constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
+  uint4 v[N];
+  int valid;
+  __device__ inline void load(const u16* src, long long stride, int nvalid, int tid) {
+    valid = nvalid;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      int idx = tid + i * NTHR;
+      idx = idx < TOTAL ? idx : TOTAL - 1;
+      int r = idx / CPR;
+      const int c = idx - r * CPR;
+      r = r < nvalid ? r : nvalid - 1;
+      v[i] = *(const uint4*)(src + (long long)r * stride + 8 * c);
+    }
+  }
+  template <int LD>
+  __device__ inline void store(u16* dst, int tid) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int idx = tid + i * NTHR;
+      const int r = idx / CPR, c = idx - r * CPR;
+      if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
+    }
+  }
+};
+
 template <int D, int LD, int ROWS, int NTHR>
 __device__ inline void stage_rows_batched(u16* dst, const u16* src, long long stride, int valid, int tid) {
-  constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
-  uint4 v[N];
-#pragma unroll
-  for (int i = 0; i < N; ++i) {
-    int idx = tid + i * NTHR;
-    idx = idx < TOTAL ? idx : TOTAL - 1;
-    int r = idx / CPR;
-    const int c = idx - r * CPR;
-    r = r < valid ? r : valid - 1;
-    v[i] = *(const uint4*)(src + (long long)r * stride + 8 * c);
-  }
-#pragma unroll
-  for (int i = 0; i < N; ++i) {
-    const int idx = tid + i * NTHR;
-    const int r = idx / CPR, c = idx - r * CPR;
-    if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
-  }
+  RowRegs<D, ROWS, NTHR> r;
+  r.load(src, stride, valid, tid);
+  r.template store<LD>(dst, tid);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -222,8 +238,12 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   const size_t NKtot = (size_t)p.ntk * b1;
 
   MRT_STAMP(0);
-  stage_rows<D>(Ks, Kp, p.ks.token, ROWS, b2, tid, NTHR);
-  if (LAST) stage_rows<D>(Vs, Vp, p.vs.token, ROWS, b2, tid, NTHR);
+  // all loads of the block (keys, values, this wave's query-side rows) are issued before the
+  // first LDS store
+  RowRegs<D, ROWS, NTHR> rk;
+  RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
+  rk.load(Kp, p.ks.token, b2, tid);
+  if (LAST) rv.load(Vp, p.vs.token, b2, tid);
 
   // query-side rows of this wave (row j = 16*wave + c), straight to registers
   const int j = 16 * wave + c;
@@ -237,6 +257,8 @@ __global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
   bf16x8 qv[KS1];
 #pragma unroll
   for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(arow + 32 * ks + 8 * g);
+  rk.template store<LD>(Ks, tid);
+  if (LAST) rv.template store<LD>(Vs, tid);
   __syncthreads();
   MRT_STAMP(1);
 
