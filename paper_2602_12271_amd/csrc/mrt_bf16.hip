@@ -216,7 +216,7 @@ __device__ inline void stage_rows_batched(u16* dst, const u16* src, long long st
 // stage R
 // ---------------------------------------------------------------------------------------
 template <int NT, int D, bool FIRST, bool LAST>
-__global__ __launch_bounds__(64 * NT) void k_bf16_stage_r(KParams p) {
+__global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p) {
   constexpr int LD = D + kPad, KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
   constexpr int NTHR = 64 * NT;
   __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];
