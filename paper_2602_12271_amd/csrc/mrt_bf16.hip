@@ -215,8 +215,12 @@ __device__ inline void stage_rows_batched(u16* dst, const u16* src, long long st
 // ---------------------------------------------------------------------------------------
 // stage R
 // ---------------------------------------------------------------------------------------
+// One workgroup = one key block (n, k) against a group of `gs` query tiles: the key (and value)
+// rows are staged in LDS once and every query tile of the group that sees key tile n is then
+// processed against them without further barriers (the next tile's query-side rows are
+// prefetched while the current tile is computed).
 template <int NT, int D, bool FIRST, bool LAST>
-__global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p) {
+__global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) {
   constexpr int LD = D + kPad, KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
   constexpr int NTHR = 64 * NT;
   __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];
@@ -224,105 +228,126 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int nk = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int nk = blockIdx.x, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int n = nk / b1, k = nk - n * b1;
-  const int a = m / p.c2, bq = m - a * p.c2;
   const int an = n / p.c2, bn = n - an * p.c2;
-  if (an >= visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff)) return;
+  // query tiles [ml0, ml1) of this group; the hidden ones form a prefix (a later query chunk
+  // sees more key tiles)
+  int ml0 = blockIdx.y * gs;
+  const int ml1 = ml0 + gs < p.ntq ? ml0 + gs : p.ntq;
+  while (ml0 < ml1 && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.fb, p.cc, p.qoff)) ++ml0;
+  if (ml0 >= ml1) return;
   const int b = bh / p.H, hd = bh - b * p.H;
 
-  const long long qtok0 = (long long)(a * b1 + k) * p.w + bq * b2;
   const long long ktok0 = (long long)(an * b1 + k) * p.w + bn * b2;
   const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + ktok0 * p.ks.token;
   const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + ktok0 * p.vs.token;
+  const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const size_t NKtot = (size_t)p.ntk * b1;
 
   MRT_STAMP(0);
-  // all loads of the block (keys, values, this wave's query-side rows) are issued before the
-  // first LDS store
+  // all loads of the block (keys, values, the first tile's query-side rows) are issued before
+  // the first LDS store
   RowRegs<D, ROWS, NTHR> rk;
   RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
   rk.load(Kp, p.ks.token, b2, tid);
   if (LAST) rv.load(Vp, p.vs.token, b2, tid);
 
-  // query-side rows of this wave (row j = 16*wave + c), straight to registers
+  // query-side rows of this wave (row j = 16*wave + c) go straight to registers: Q[m, k, j, :] in
+  // the first iteration (L is the identity), alpha_R / c_R afterwards
   const int j = 16 * wave + c;
   const int jc = j < b2 ? j : b2 - 1;
-  const u16* arow;
-  if (FIRST) {
-    arow = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + (qtok0 + jc) * p.qs.token;
-  } else {
-    arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 + jc) * D;
-  }
-  bf16x8 qv[KS1];
+  bf16x8 qv[KS1], qn[KS1];
+  auto load_q = [&](int ml) {
+    const u16* arow;
+    if (FIRST) {
+      const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
+      arow = Qbase + ((long long)(a * b1 + k) * p.w + bq * b2 + jc) * p.qs.token;
+    } else {
+      arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 + jc) * D;
+    }
 #pragma unroll
-  for (int ks = 0; ks < KS1; ++ks) qv[ks] = ld_global_16B(arow + 32 * ks + 8 * g);
+    for (int ks = 0; ks < KS1; ++ks) qn[ks] = ld_global_16B(arow + 32 * ks + 8 * g);
+  };
+  load_q(ml0);
   rk.template store<LD>(Ks, tid);
   if (LAST) rv.template store<LD>(Vs, tid);
   __syncthreads();
   MRT_STAMP(1);
 
-  // Z_R^T tiles
-  f32x4 s[NT];
-#pragma unroll
-  for (int it = 0; it < NT; ++it) {
-    s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS1; ++ks)
-      s[it] = mfma(ld_lds_16B(Ks + (16 * it + c) * LD + 32 * ks + 8 * g), qv[ks], s[it]);
-  }
-  // softmax over i (rows of the tiles) for column j, and sum_i R log R (base-2 domain inside)
   const float scale2 = p.scale * kLog2e;
-  float mx = -INFINITY;
+  for (int ml = ml0; ml < ml1; ++ml) {
 #pragma unroll
-  for (int it = 0; it < NT; ++it)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const bool ok = 16 * it + 4 * g + r < b2;
-      const float z = ok ? s[it][r] * scale2 : -INFINITY;
-      s[it][r] = z;
-      mx = fmaxf(mx, z);
-    }
-  mx = xmax(mx);
-  float sum = 0.f, ent = 0.f;
-#pragma unroll
-  for (int it = 0; it < NT; ++it)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const bool ok = 16 * it + 4 * g + r < b2;
-      const float z = ok ? s[it][r] - mx : 0.f;
-      const float e = ok ? exp2_fast(z) : 0.f;
-      sum += e;
-      ent = fmaf(e, z, ent);
-      s[it][r] = e;
-    }
-  sum = xsum(sum);
-  ent = xsum(ent);
-  const float inv = 1.0f / sum;
-  if (g == 0 && j < b2)
-    p.cL[(((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot + nk] = kLn2 * (ent * inv - log2_fast(sum));
+    for (int ks = 0; ks < KS1; ++ks) qv[ks] = qn[ks];
+    if (ml + 1 < ml1) load_q(ml + 1);
 
-  // alpha_L = R K (and Y = R V)
-  f32x4 oK[NVT], oV[LAST ? NVT : 1];
+    // Z_R^T tiles
+    f32x4 s[NT];
 #pragma unroll
-  for (int vt = 0; vt < NVT; ++vt) {
-    oK[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if constexpr (LAST) oV[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+    for (int it = 0; it < NT; ++it) {
+      s[it] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int st = 0; st < KS2; ++st) {
-    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    const f32x4 lo = s[2 * st] * inv;
-    const f32x4 hi = (2 * st + 1 < NT) ? s[(2 * st + 1 < NT) ? 2 * st + 1 : 0] * inv : zero;
-    const bf16x8 pb = pack8(lo, hi);
-    pv_step<D>(Ks + 32 * st * LD, pb, oK, lane);
-    if constexpr (LAST) pv_step<D>(Vs + 32 * st * LD, pb, oV, lane);
-  }
-  MRT_STAMP(2);
-  if (j < b2) {
+      for (int ks = 0; ks < KS1; ++ks)
+        s[it] = mfma(ld_lds_16B(Ks + (16 * it + c) * LD + 32 * ks + 8 * g), qv[ks], s[it]);
+      if (it % 2 == 1) __builtin_amdgcn_sched_barrier(0);   // bound the operand reads in flight
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // softmax over i (rows of the tiles) for column j, and sum_i R log R (base-2 domain inside)
+    float mx = -INFINITY;
+#pragma unroll
+    for (int it = 0; it < NT; ++it)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool ok = 16 * it + 4 * g + r < b2;
+        const float z = ok ? s[it][r] * scale2 : -INFINITY;
+        s[it][r] = z;
+        mx = fmaxf(mx, z);
+      }
+    mx = xmax(mx);
+    float sum = 0.f, ent = 0.f;
+#pragma unroll
+    for (int it = 0; it < NT; ++it)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool ok = 16 * it + 4 * g + r < b2;
+        const float z = ok ? s[it][r] - mx : 0.f;
+        const float e = ok ? exp2_fast(z) : 0.f;
+        sum += e;
+        ent = fmaf(e, z, ent);
+        s[it][r] = e;
+      }
+    sum = xsum(sum);
+    ent = xsum(ent);
+    const float inv = 1.0f / sum;
     const size_t row = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot + nk;
-    store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
-    if constexpr (LAST) store_rows<D>((u16*)p.Y + row * D, oV, 1.0f, g);
+    if (g == 0 && j < b2) p.cL[row] = kLn2 * (ent * inv - log2_fast(sum));
+
+    __builtin_amdgcn_sched_barrier(0);
+    // alpha_L = R K (and Y = R V)
+    f32x4 oK[NVT], oV[LAST ? NVT : 1];
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) {
+      oK[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if constexpr (LAST) oV[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      const f32x4 lo = s[2 * st] * inv;
+      const f32x4 hi = (2 * st + 1 < NT) ? s[(2 * st + 1 < NT) ? 2 * st + 1 : 0] * inv : zero;
+      const bf16x8 pb = pack8(lo, hi);
+      pv_step<D>(Ks + 32 * st * LD, pb, oK, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (LAST) {
+        pv_step<D>(Vs + 32 * st * LD, pb, oV, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (ml == ml0) MRT_STAMP(2);
+    if (j < b2) {
+      store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
+      if constexpr (LAST) store_rows<D>((u16*)p.Y + row * D, oV, 1.0f, g);
+    }
   }
   MRT_STAMP(3);
 }
@@ -1156,23 +1181,23 @@ __global__ __launch_bounds__(256, 2) void k_bf16_dense(KParams p) {
 }
 
 template <int NT, int D>
-hipError_t launch_r(const KParams& kp, dim3 grid, bool first, bool last, hipStream_t s) {
-  if (first && last) k_bf16_stage_r<NT, D, true, true><<<grid, 64 * NT, 0, s>>>(kp);
-  else if (first) k_bf16_stage_r<NT, D, true, false><<<grid, 64 * NT, 0, s>>>(kp);
-  else if (last) k_bf16_stage_r<NT, D, false, true><<<grid, 64 * NT, 0, s>>>(kp);
-  else k_bf16_stage_r<NT, D, false, false><<<grid, 64 * NT, 0, s>>>(kp);
+hipError_t launch_r(const KParams& kp, dim3 grid, int gs, bool first, bool last, hipStream_t s) {
+  if (first && last) k_bf16_stage_r<NT, D, true, true><<<grid, 64 * NT, 0, s>>>(kp, gs);
+  else if (first) k_bf16_stage_r<NT, D, true, false><<<grid, 64 * NT, 0, s>>>(kp, gs);
+  else if (last) k_bf16_stage_r<NT, D, false, true><<<grid, 64 * NT, 0, s>>>(kp, gs);
+  else k_bf16_stage_r<NT, D, false, false><<<grid, 64 * NT, 0, s>>>(kp, gs);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_r_d(const KParams& kp, dim3 grid, bool first, bool last, hipStream_t s) {
+hipError_t launch_r_d(const KParams& kp, dim3 grid, int gs, bool first, bool last, hipStream_t s) {
   switch ((kp.b2 + 15) / 16) {
-    case 1: return launch_r<1, D>(kp, grid, first, last, s);
-    case 2: return launch_r<2, D>(kp, grid, first, last, s);
-    case 3: return launch_r<3, D>(kp, grid, first, last, s);
-    case 4: return launch_r<4, D>(kp, grid, first, last, s);
-    case 5: return launch_r<5, D>(kp, grid, first, last, s);
-    case 6: return launch_r<6, D>(kp, grid, first, last, s);
+    case 1: return launch_r<1, D>(kp, grid, gs, first, last, s);
+    case 2: return launch_r<2, D>(kp, grid, gs, first, last, s);
+    case 3: return launch_r<3, D>(kp, grid, gs, first, last, s);
+    case 4: return launch_r<4, D>(kp, grid, gs, first, last, s);
+    case 5: return launch_r<5, D>(kp, grid, gs, first, last, s);
+    case 6: return launch_r<6, D>(kp, grid, gs, first, last, s);
   }
   return hipErrorInvalidValue;
 }
@@ -1265,9 +1290,15 @@ hipError_t set_trace_buffer(void* buf, hipStream_t s) {
 #endif
 
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s) {
-  dim3 grid(kp.ntk * kp.b1, kp.ntq, nbh);
-  return kp.d == 128 ? launch_r_d<128>(kp, grid, first, last, s)
-                     : launch_r_d<64>(kp, grid, first, last, s);
+  // query tiles per workgroup: as many as possible (each key block is then read once, not once
+  // per query tile) while the launch still has a few thousand workgroups
+  const long long blocks = (long long)kp.ntk * kp.b1 * kp.ntq * nbh;
+  long long gs = blocks / 4096;
+  if (gs < 1) gs = 1;
+  if (gs > kp.ntq) gs = kp.ntq;
+  dim3 grid(kp.ntk * kp.b1, (kp.ntq + (int)gs - 1) / (int)gs, nbh);
+  return kp.d == 128 ? launch_r_d<128>(kp, grid, (int)gs, first, last, s)
+                     : launch_r_d<64>(kp, grid, (int)gs, first, last, s);
 }
 
 hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_t s) {

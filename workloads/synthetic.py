@@ -73,6 +73,19 @@ WORKLOADS: Dict[str, Workload] = {
     "C3": Workload("C3", 1, 12, 128, 3, 21, 30, 52, 90, 26, 1, 2, 3, 18, "bf16", _INV_SQRT128, True),
     # 720p stress
     "C4": Workload("C4", 1, 40, 128, 3, 21, 45, 80, 135, 40, 1, 3, 3, 18, "bf16", _INV_SQRT128, True),
+    # Shapes of the paper's kernel-latency table for Self-Forcing final-chunk decoding (Tab. 6):
+    # 480p with tile blocks (3h, w) [density 3 %] and (h, w) [5 %], 720p likewise; the paper does
+    # not state T or the precision for those rows, so these run T = 1 (its finetuned setting).
+    "T6-480-3hw": Workload("T6-480-3hw", 1, 12, 128, 3, 21, 30, 52, 90, 52, 1, 1, 3, 18, "bf16", _INV_SQRT128, True),
+    "T6-480-hw": Workload("T6-480-hw", 1, 12, 128, 3, 21, 30, 52, 30, 52, 1, 1, 3, 18, "bf16", _INV_SQRT128, True),
+    "T6-720-3hw": Workload("T6-720-3hw", 1, 12, 128, 3, 21, 45, 80, 135, 80, 1, 1, 3, 18, "bf16", _INV_SQRT128, True),
+    "T6-720-hw": Workload("T6-720-hw", 1, 12, 128, 3, 21, 45, 80, 45, 80, 1, 1, 3, 18, "bf16", _INV_SQRT128, True),
+    # Shapes of the paper's Wan 2.1 kernel-latency table (Tab. 5): full bidirectional attention
+    # over the 21-frame latent video, same tile blocks; T = 1.
+    "T5-480-3hw": Workload("T5-480-3hw", 1, 12, 128, 21, 21, 30, 52, 90, 52, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
+    "T5-480-hw": Workload("T5-480-hw", 1, 12, 128, 21, 21, 30, 52, 30, 52, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
+    "T5-720-3hw": Workload("T5-720-3hw", 1, 12, 128, 21, 21, 45, 80, 135, 80, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
+    "T5-720-hw": Workload("T5-720-hw", 1, 12, 128, 21, 21, 45, 80, 45, 80, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
 }
 
 
