@@ -29,7 +29,18 @@ PEAK_HBM = 8.0e12            # B/s, MI355X published
 
 # HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries under profiles/); bytes.  None until measured for a workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # (workload, kernel): (fetched bytes, written bytes) per launch, from the committed
+    # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries (KiB counters x calibration factor x 1024)
+    ("C1", "stage_R_first"): (28.9e6, 16.1e6),
+    ("C1", "stage_L_refine"): (30.6e6, 17.7e6),
+    ("C1", "stage_R_last"): (43.2e6, 30.5e6),
+    ("C1", "stage_L_out"): (43.6e6, 14.4e6),
+    ("C3", "stage_R_first"): (103.5e6, 144.4e6),
+    ("C3", "stage_L_refine"): (267.4e6, 127.1e6),
+    ("C3", "stage_R_last"): (254.5e6, 273.1e6),
+    ("C3", "stage_L_out"): (265.5e6, 9.1e6),
+}
 
 
 def visible_pairs(wl):
@@ -150,12 +161,15 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # ---- per-kernel durations (HIP events recorded by the library around every launch)
-    pkg.binding.profile_enable(True)
+    # each launch is repeated inside its event bracket so that the bracket's own cost and the
+    # dispatch latency of a short kernel do not count as kernel time
+    reps = max(1, min(16, round(0.5 / ms_per_step)))
+    pkg.binding.profile_enable(reps)
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     recs = pkg.binding.profile_read()
-    pkg.binding.profile_enable(False)
+    pkg.binding.profile_enable(0)
     models = kernel_models(wl, es)
     per_call = len(recs) // args.steps
     passes = per_call // len(models)           # head groups per call
@@ -185,8 +199,11 @@ def main():
         ach = dmodel["flops"] / dom["launches_per_call"] / launch_s / 1e12
         roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_BF16 / 1e12, unit="TFLOP/s",
                     frac=ach / (PEAK_MFMA_BF16 / 1e12))
-    roof.update(kernel=dom["name"], launch_us=launch_s * 1e6,
-                traffic=MEASURED_TRAFFIC.get((wl.name, dom["name"])))
+    traffic = MEASURED_TRAFFIC.get((wl.name, dom["name"]))
+    roof.update(kernel=dom["name"], launch_us=launch_s * 1e6, launch_repeats=reps,
+                traffic=(sum(traffic) / dom["launches_per_call"]) if traffic else None,
+                traffic_unit="bytes per launch (fetch + write)",
+                algorithmic_bytes=dmodel["bytes"] / dom["launches_per_call"])
     tot_flops = sum(m["flops"] for m in models)
     compulsory = (wl.batch * wl.heads) * (2 * wl.n_q + 2 * wl.n_kv) * wl.head_dim * es
 

@@ -119,16 +119,20 @@ mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
  * device on first use, at the default priority, and live until the process ends.  Process-wide. */
 void mrt_set_head_groups(int n);
 
-/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the two entry points
- * above is bracketed by a pair of HIP events recorded on the call's stream (this is the only
- * mode in which the library creates HIP objects).  mrt_profile_read waits for the recorded
- * events, writes up to `capacity` (elapsed milliseconds, kernel kind) pairs in launch order,
- * forgets them and returns how many it wrote.  While enabled, head groups run one after the other.  Kernel kind = one of MRT_KERNEL_STAGE_R /
- * MRT_KERNEL_STAGE_L / MRT_KERNEL_DENSE, or-ed with MRT_KERNEL_FIRST (first iteration: alpha_R
- * is Q itself) and MRT_KERNEL_LAST (last iteration: stage R also forms Y, stage L forms O). */
+/* Per-kernel timing for benchmarks.  mrt_profile_enable(r) with r >= 1 (at most 64) makes the two
+ * entry points above issue every kernel launch r times in a row between a pair of HIP events
+ * recorded on the launch's stream; r = 0 switches this off.  Every kernel reads only buffers it
+ * does not write, so the repeated launches leave the same result; r > 1 spreads the cost of the
+ * event pair and of the first dispatch over r launches.  This is the only mode in which the
+ * library creates HIP objects, and while it is on head groups run one after the other.
+ * mrt_profile_read waits for the recorded events, writes up to `capacity` (elapsed milliseconds
+ * per launch, kernel kind) pairs in launch order, forgets them and returns how many it wrote.
+ * Kernel kind = one of MRT_KERNEL_STAGE_R / MRT_KERNEL_STAGE_L / MRT_KERNEL_DENSE, or-ed with
+ * MRT_KERNEL_FIRST (first iteration: alpha_R is Q itself) and MRT_KERNEL_LAST (last iteration:
+ * stage R also forms Y, stage L forms O). */
 enum { MRT_KERNEL_STAGE_R = 1, MRT_KERNEL_STAGE_L = 2, MRT_KERNEL_DENSE = 4,
        MRT_KERNEL_FIRST = 16, MRT_KERNEL_LAST = 32 };
-void mrt_profile_enable(int on);
+void mrt_profile_enable(int repeats);
 int mrt_profile_read(float* ms, int* kind, int capacity);
 
 const char* mrt_status_string(mrt_status s);

@@ -127,8 +127,9 @@ def set_head_groups(n: int) -> None:
     load_library().mrt_set_head_groups(int(n))
 
 
-def profile_enable(on: bool) -> None:
-    load_library().mrt_profile_enable(1 if on else 0)
+def profile_enable(repeats) -> None:
+    """0/False: off; r >= 1: every launch is issued r times inside one event bracket."""
+    load_library().mrt_profile_enable(int(repeats))
 
 
 def profile_read(capacity: int = 65536):

@@ -159,25 +159,27 @@ static inline void trace_next_launch(hipStream_t) {}
 #endif
 
 // ---- optional per-kernel timing (benchmarks only) --------------------------------------
-struct ProfRecord { hipEvent_t a, b; int kind; };
-static bool g_prof_on = false;
+struct ProfRecord { hipEvent_t a, b; int kind, reps; };
+static int g_prof_on = 0;      // 0 = off, r > 0 = each launch issued r times inside its bracket
 static std::vector<ProfRecord> g_prof;
 static std::mutex g_prof_mu;
 
-struct ProfScope {
-  hipStream_t s; int kind; hipEvent_t a = nullptr, b = nullptr; bool on;
-  ProfScope(hipStream_t s_, int kind_) : s(s_), kind(kind_), on(g_prof_on) {
-    if (!on) return;
-    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
-    (void)hipEventRecord(a, s);
-  }
-  ~ProfScope() {
-    if (!on) return;
-    (void)hipEventRecord(b, s);
-    std::lock_guard<std::mutex> lk(g_prof_mu);
-    g_prof.push_back({a, b, kind});
-  }
-};
+// Runs `launch` once, or, while profiling, g_prof_on times between two events.  Every kernel of
+// this library reads only buffers it does not write, so a repeated launch leaves the same result.
+template <class F>
+static hipError_t timed_launch(hipStream_t s, int kind, F launch) {
+  const int reps = g_prof_on;
+  if (reps <= 0) return launch();
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return launch();
+  (void)hipEventRecord(a, s);
+  hipError_t e = hipSuccess;
+  for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch();
+  (void)hipEventRecord(b, s);
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof.push_back({a, b, kind, reps});
+  return e;
+}
 
 // ---- helper streams for concurrent head groups ------------------------------------------
 constexpr int kMaxGroups = 4;
@@ -335,18 +337,16 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
         const bool first = t == 1, last = t == pl.T;
         hipError_t e;
         trace_next_launch(gs);
-        {
-          ProfScope ps(gs, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0));
-          if (pl.f32_path()) e = launch_f32_stage_r(kg, pl.dtype, hi - lo, first, last, gs);
-          else e = launch_bf16_stage_r(kg, hi - lo, first, last, gs);
-        }
+        e = timed_launch(gs, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0), [&] {
+          return pl.f32_path() ? launch_f32_stage_r(kg, pl.dtype, hi - lo, first, last, gs)
+                               : launch_bf16_stage_r(kg, hi - lo, first, last, gs);
+        });
         if (e != hipSuccess) { status = hip_fail(e, "stage R launch"); break; }
         trace_next_launch(gs);
-        {
-          ProfScope ps(gs, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0));
-          if (pl.f32_path()) e = launch_f32_stage_l(kg, pl.dtype, hi - lo, last, gs);
-          else e = launch_bf16_stage_l(kg, hi - lo, last, gs);
-        }
+        e = timed_launch(gs, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0), [&] {
+          return pl.f32_path() ? launch_f32_stage_l(kg, pl.dtype, hi - lo, last, gs)
+                               : launch_bf16_stage_l(kg, hi - lo, last, gs);
+        });
         if (e != hipSuccess) { status = hip_fail(e, "stage L launch"); break; }
       }
     }
@@ -387,12 +387,10 @@ mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
   kp.Nq = p->f_q * p->h * p->w; kp.Nkv = p->f_kv * p->h * p->w; kp.hw = p->h * p->w;
   kp.cc = causal_chunk; kp.qoff = p->q_frame_offset; kp.scale = p->scale;
   const int BH = p->batch * p->heads;
-  hipError_t e;
-  {
-    ProfScope ps((hipStream_t)hip_stream, MRT_KERNEL_DENSE);
-    e = f32 ? launch_f32_dense(kp, p->dtype, BH, (hipStream_t)hip_stream)
-            : launch_bf16_dense(kp, BH, (hipStream_t)hip_stream);
-  }
+  hipError_t e = timed_launch((hipStream_t)hip_stream, MRT_KERNEL_DENSE, [&] {
+    return f32 ? launch_f32_dense(kp, p->dtype, BH, (hipStream_t)hip_stream)
+               : launch_bf16_dense(kp, BH, (hipStream_t)hip_stream);
+  });
   if (e != hipSuccess) return hip_fail(e, "dense launch");
   return MRT_OK;
 }
@@ -410,7 +408,7 @@ void mrt_set_head_groups(int n) { g_max_groups = n < 0 ? 0 : (n > kMaxGroups ? k
 
 void mrt_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  g_prof_on = on != 0;
+  g_prof_on = on < 0 ? 0 : (on > 64 ? 64 : on);
 }
 
 int mrt_profile_read(float* ms, int* kind, int capacity) {
@@ -418,7 +416,8 @@ int mrt_profile_read(float* ms, int* kind, int capacity) {
   int n = 0;
   for (ProfRecord& r : g_prof) {
     float t = -1.f;
-    if (hipEventSynchronize(r.b) == hipSuccess) (void)hipEventElapsedTime(&t, r.a, r.b);
+    if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&t, r.a, r.b) == hipSuccess)
+      t /= (float)r.reps;
     if (n < capacity) { ms[n] = t; kind[n] = r.kind; ++n; }
     (void)hipEventDestroy(r.a);
     (void)hipEventDestroy(r.b);
