@@ -29,13 +29,23 @@ design document as well):
     tile iff the chunk of the key tile's frames is not later than the chunk of
     the query tile's frames; hidden pairs take no part at all (no R, not in the
     joint softmax of L).  A tile never straddles a chunk boundary.
+  * tiles are the contiguous row / column ranges of Alg. 2's rearrange, so any
+    b1 dividing the row count is a tiling (also a fraction of a frame: the
+    neighbourhood tiles of Sec. 4.2 with n_f = 1).
+  * the six aligned block assignments of Sec. 4.1 are the same algorithm on
+    tokens re-ordered so that the axes given to b1 become the row index and the
+    axes given to b2 the column index (block_assignment_order).
   * beta_R / c_R with c_R == 0 exactly: that row of Z_R is set to 0 (uniform R).
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
 (degenerate block sizes == dense softmax attention; separable logits == dense
 for every T; materialised M @ V == factored product; row-stochasticity;
 parameter tying; an independent index-loop transcription of the update
-equations; monotone KL along the iterations; constant V).
+equations; monotone KL along the iterations; constant V) and, for the block
+assignments and fractional-frame tiles, by tests/test_oracle_assignments.py
+(rank-one block structure of the materialised matrix under an index map
+written out in the test; position-only logits == dense for all six
+assignments; assignments that coincide on degenerate grids).
 """
 from __future__ import annotations
 
@@ -96,23 +106,24 @@ def chunk_causal_visibility(geom: TileGeometry, h: int, causal_chunk: int,
                             q_frame_offset: int) -> torch.Tensor:
     """visible[m, n] for the tile-level chunk-causal reading (see module header).
 
-    Frames per tile row = b1 / h.  Query tile row a covers absolute frames
-    q_frame_offset + a*fb ... ; key tile row a' covers frames a'*fb ... .
-    causal_chunk == 0 means no mask.
+    h = grid rows per frame.  Query tile row a covers grid rows a*b1 ... of
+    frames starting at q_frame_offset; key tile row a' covers rows a'*b1 ... of
+    frames starting at 0.  causal_chunk == 0 means no mask.
     """
     vis = torch.ones(geom.ntq, geom.ntk, dtype=torch.bool)
     if causal_chunk == 0:
         return vis
-    assert geom.b1 % h == 0
-    fb = geom.b1 // h
-    assert causal_chunk % fb == 0 and q_frame_offset % fb == 0
+
+    def chunk_of_tile_row(a: int, first_frame: int) -> int:
+        lo = (first_frame + (a * geom.b1) // h) // causal_chunk
+        hi = (first_frame + (a * geom.b1 + geom.b1 - 1) // h) // causal_chunk
+        assert lo == hi, "a tile straddles a causal chunk"
+        return lo
+
     for m in range(geom.ntq):
-        qa = m // geom.c2
-        q_chunk = (q_frame_offset + qa * fb) // causal_chunk
+        q_chunk = chunk_of_tile_row(m // geom.c2, q_frame_offset)
         for n in range(geom.ntk):
-            ka = n // geom.c2
-            k_chunk = (ka * fb) // causal_chunk
-            vis[m, n] = k_chunk <= q_chunk
+            vis[m, n] = chunk_of_tile_row(n // geom.c2, 0) <= q_chunk
     return vis
 
 
@@ -293,11 +304,53 @@ def geometry_from_grid(f_q: int, f_kv: int, h: int, w: int, b1: int, b2: int,
     return TileGeometry(b1, b2, (f_q * h) // b1, (f_kv * h) // b1, w // b2)
 
 
+# --------------------------------------------------------------------------
+# aligned block assignments (Sec. 4.1): which video axes index the b1 side and
+# which the b2 side.  "fh_w" is the order the tokens are stored in.
+# --------------------------------------------------------------------------
+ASSIGNMENTS = ("fh_w", "w_fh", "fw_h", "h_fw", "f_hw", "hw_f")
+
+
+def block_assignment_order(assign: str, f: int, h: int, w: int):
+    """(order, rows, cols, rows_per_frame): order[x * cols + y] is the stored token
+    (frame, height, width row-major) that sits at row x, column y of the block
+    grid when the axes before the underscore index rows (first letter slowest)
+    and the axes after it index columns.  rows_per_frame is rows / f when the
+    frame axis is the slowest row axis, else 0 (frames are then not a row range)."""
+    assert assign in ASSIGNMENTS
+    row_axes, col_axes = assign.split("_")
+    size = {"f": f, "h": h, "w": w}
+    grid = torch.arange(f * h * w).reshape(f, h, w)
+    names = "fhw"
+    axes = [names.index(c) for c in row_axes + col_axes]
+    rows = math.prod(size[c] for c in row_axes)
+    cols = math.prod(size[c] for c in col_axes)
+    order = grid.permute(*axes).reshape(rows * cols)
+    rpf = rows // f if row_axes[0] == "f" else 0
+    return order, rows, cols, rpf
+
+
 def monarch_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, b1: int, b2: int,
                  tile: int, iters: int, causal_chunk: int = 0, q_frame_offset: int = 0,
-                 scale: float = 1.0) -> torch.Tensor:
+                 scale: float = 1.0, assign: str = "fh_w") -> torch.Tensor:
     """One head of the operator the library exports: regular (tile=0, Alg. 1) or
-    tiled (tile=1, Alg. 2) MonarchAttention on (f,h,w) grids."""
+    tiled (tile=1, Alg. 2) MonarchAttention on (f,h,w) grids, for any of the six
+    aligned block assignments (Sec. 4.1)."""
+    if assign != "fh_w":
+        oq, rows_q, cols_q, rpf = block_assignment_order(assign, f_q, h, w)
+        ok, rows_k, cols_k, _ = block_assignment_order(assign, f_kv, h, w)
+        assert cols_q == cols_k, "the frame axis is on the column side: f_q must equal f_kv"
+        if rpf == 0:
+            assert causal_chunk == 0 and f_q == f_kv, "frames are not a row range"
+            fq2, fk2, h2 = 1, 1, rows_q
+        else:
+            fq2, fk2, h2 = f_q, f_kv, rpf
+        out = monarch_attn(Q[oq], K[ok], V[ok], f_q=fq2, f_kv=fk2, h=h2, w=cols_q, b1=b1, b2=b2,
+                           tile=tile, iters=iters, causal_chunk=causal_chunk,
+                           q_frame_offset=q_frame_offset, scale=scale)
+        O = torch.empty_like(out)
+        O[oq] = out
+        return O
     g = geometry_from_grid(f_q, f_kv, h, w, b1, b2, tile)
     if tile == 0:
         assert causal_chunk == 0
