@@ -47,15 +47,16 @@ def visible_pairs(wl):
     """sum over query tiles of their visible key tiles (tile-level chunk-causal reading)."""
     if wl.tile == 0:
         return 1
-    c2 = wl.w // wl.b2
-    c1q, c1k = wl.f_q * wl.h // wl.b1, wl.f_kv * wl.h // wl.b1
+    rows_q, rows_k, cols = wl.block_grid()
+    c2 = cols // wl.b2
+    c1q, c1k = rows_q // wl.b1, rows_k // wl.b1
+    rpf = rows_q // wl.f_q                     # block-grid rows per frame (mask: frame axis slowest)
     total = 0
     for a in range(c1q):
         rows = c1k
         if wl.causal_chunk:
-            fb = wl.b1 // wl.h
-            q_chunk = (wl.q_frame_offset + a * fb) // wl.causal_chunk
-            rows = min(c1k, (q_chunk + 1) * wl.causal_chunk // fb)
+            q_chunk = (wl.q_frame_offset * rpf + a * wl.b1) // (wl.causal_chunk * rpf)
+            rows = min(c1k, (q_chunk + 1) * wl.causal_chunk * rpf // wl.b1)
         total += c2 * rows * c2
     return total
 
@@ -130,7 +131,7 @@ def main():
     Q, K, V = (torch.from_numpy(x).to(dev).to(tdt) for x in (Qh, Kh, Vh))
     O = torch.empty_like(Q)
     prob = binding._torch_problem(Q, K, V, O, wl.f_q, wl.f_kv, wl.h, wl.w, wl.q_frame_offset,
-                                  wl.scale, pkg.MRT_COMPUTE_DEFAULT)
+                                  wl.scale, pkg.MRT_COMPUTE_DEFAULT, wl.assign)
     nws = pkg.monarch_attn_workspace_bytes(prob, wl.b1, wl.b2, wl.tile, wl.iters)
     ws = torch.empty(nws, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
@@ -235,7 +236,7 @@ def main():
                                    torch.from_numpy(Vh[0, hd]), f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h,
                                    w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile, iters=wl.iters,
                                    causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
-                                   scale=wl.scale)
+                                   scale=wl.scale, assign=wl.assign)
         ref0 = oracle_head(0)                       # also warms the CPU libraries up
         parity = (O[0, 0].float().cpu().double() - ref0).abs().max().item()
         heads_run, t_acc, budget = 0, 0.0, 15.0
@@ -256,7 +257,7 @@ def main():
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.heads} heads x d{wl.head_dim}, grid ({wl.f_q}|{wl.f_kv},"
                                f"{wl.h},{wl.w}), N_q={wl.n_q}, N_kv={wl.n_kv}, "
-                               f"{'tiled' if wl.tile else 'regular'} Monarch ({wl.b1},{wl.b2}), T={wl.iters}, "
+                               f"{'tiled' if wl.tile else 'regular'} Monarch ({wl.b1},{wl.b2}) on ({wl.assign.replace('_', ',')}), T={wl.iters}, "
                                f"causal_chunk={wl.causal_chunk}",
                    "scale": wl.scale, "workspace_mb": nws / 1e6, "head_groups": args.head_groups or "auto", "heads_per_pass": (wl.batch * wl.heads + passes - 1) // passes},
         "roofline": roof,

@@ -13,10 +13,12 @@
  *   key tile n) with tile-local block sizes (b1, b2), the softmax of L taken jointly
  *   over all visible key tiles and key rows (n, k).
  *
- * Token order is row-major (frame, height, width) (App. B.1).  Blocks are the aligned
- * choice of Sec. 4.1: grid rows (frame, height) go to the b1 side, width to the b2 side.
- * A tile is b1 consecutive grid rows by b2 consecutive columns (Alg. 2, the
- * "(a l b j)" split); token = ((a*b1 + l)*c2 + b)*b2 + j with c2 = w / b2.
+ * Token order is row-major (frame, height, width) (App. B.1).  Blocks are one of the six aligned
+ * choices of Sec. 4.1 (mrt_assignment): every video axis goes as a whole to the b1 side ("rows",
+ * index x) or to the b2 side ("columns", index y); the default gives (frame, height) to b1 and
+ * width to b2.  A tile is b1 consecutive rows by b2 consecutive columns (Alg. 2, the
+ * "(a l b j)" split): row x = a*b1 + l, column y = b*b2 + j; for the default assignment
+ * token = x*w + y.
  *
  * All data pointers are DEVICE pointers owned by the caller.  The library allocates
  * no device memory, orders its kernels after the work already on the given HIP stream and
@@ -51,6 +53,15 @@ typedef enum { MRT_F32 = 0, MRT_BF16 = 1 } mrt_dtype;
  *                         (slow; a device-side cross-check). */
 typedef enum { MRT_COMPUTE_DEFAULT = 0, MRT_COMPUTE_F32 = 1 } mrt_compute;
 
+/* Aligned block assignments (Sec. 4.1).  The axes before the underscore index the b1 side, those
+ * after it the b2 side, the first-named axis slowest: e.g. MRT_ASSIGN_FW_H has row index
+ * x = frame*w + column-of-the-frame and column index y = height.  rows x cols per grid of f frames:
+ * FH_W f*h x w, W_FH w x f*h, FW_H f*w x h, H_FW h x f*w, F_HW f x h*w, HW_F h*w x f. */
+typedef enum {
+  MRT_ASSIGN_FH_W = 0, MRT_ASSIGN_W_FH = 1, MRT_ASSIGN_FW_H = 2,
+  MRT_ASSIGN_H_FW = 3, MRT_ASSIGN_F_HW = 4, MRT_ASSIGN_HW_F = 5
+} mrt_assignment;
+
 /* Element strides of one [batch, heads, tokens, head_dim] tensor; head_dim is contiguous. */
 typedef struct {
   long long batch, head, token;
@@ -67,18 +78,25 @@ typedef struct {
   mrt_compute compute;
   float scale;         /* multiplies both logit contractions (beta_R and beta_L);
                           1.0 is the paper's softmax(Q K^T) (Sec. 2.2)                      */
+  mrt_assignment assignment; /* which axes index the b1 and the b2 side; 0 = (fh, w)        */
 } mrt_problem;
 
 /* Checks a MonarchRT call without touching the GPU (same rules monarch_attn_fwd applies).
- *   tile = 0  regular Monarch: needs f_q == f_kv, b1 == f*h, b2 == w, causal_chunk == 0.
- *   tile = 1  tiled: (b1,b2) are tile-local; needs b1 % h == 0, (f_q*h) % b1 == 0,
- *             (f_kv*h) % b1 == 0, w % b2 == 0.
+ * With rows_q x cols and rows_kv x cols the block grids of the query and key side under
+ * p->assignment (the column counts must agree: assignments with the frame axis on the column
+ * side need f_q == f_kv):
+ *   tile = 0  regular Monarch: needs f_q == f_kv, b1 == rows, b2 == cols, causal_chunk == 0.
+ *   tile = 1  tiled: (b1,b2) are tile-local; needs rows_q % b1 == 0, rows_kv % b1 == 0,
+ *             cols % b2 == 0.  A tile may be any contiguous row range, e.g. several frames or,
+ *             with n_f = 1, n_h = b1 rows of one frame (the neighbourhood tiles of Sec. 4.2).
  *   iters >= 1 (R is undefined before the first update, App. A.1).
  *   causal_chunk = 0: no mask.  > 0: frames per autoregressive chunk; a key tile is visible
  *             to a query tile iff its chunk is not later than the query tile's chunk, hidden
- *             tile pairs take no part at all.  Needs (b1/h) to divide causal_chunk and
- *             q_frame_offset, and tile = 1.
- *   Limits of this build: b1 <= 192, b2 <= 96 (else MRT_ERR_UNSUPPORTED). */
+ *             tile pairs take no part at all.  Needs tile = 1, an assignment whose slowest row
+ *             axis is the frame (FH_W, FW_H, F_HW), and tiles that do not straddle a chunk:
+ *             b1 divides (rows per frame)*causal_chunk and (rows per frame)*q_frame_offset.
+ *   Limits of this build: b1 <= 192, b2 <= 96 (else MRT_ERR_UNSUPPORTED); tiles that are
+ *   n_f > 1 frames by n_h < h rows (not a contiguous row range) are not built. */
 mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, int iters,
                               int causal_chunk);
 

@@ -23,6 +23,7 @@ EXPORTED = [
     "monarch_attn_fwd", "dense_attn_check", "dense_attn_fwd", "mrt_status_string", "mrt_last_error",
     "mrt_profile_enable", "mrt_profile_read", "mrt_set_head_groups",
 ]
+ASSIGNMENTS = {"fh_w": 0, "w_fh": 1, "fw_h": 2, "h_fw": 3, "f_hw": 4, "hw_f": 5}
 KERNEL_STAGE_R, KERNEL_STAGE_L, KERNEL_DENSE, KERNEL_FIRST, KERNEL_LAST = 1, 2, 4, 16, 32
 
 
@@ -37,6 +38,7 @@ class MrtProblem(ctypes.Structure):
         ("q_frame_offset", ctypes.c_int),
         ("q", MrtStrides), ("k", MrtStrides), ("v", MrtStrides), ("o", MrtStrides),
         ("dtype", ctypes.c_int), ("compute", ctypes.c_int), ("scale", ctypes.c_float),
+        ("assignment", ctypes.c_int),
     ]
 
 
@@ -92,7 +94,7 @@ def _raise(lib, st: int):
 
 def make_problem(*, batch, heads, head_dim, f_q, f_kv, h, w, q_frame_offset=0, dtype=MRT_BF16,
                  compute=MRT_COMPUTE_DEFAULT, scale=1.0, q_strides=None, k_strides=None,
-                 v_strides=None, o_strides=None) -> MrtProblem:
+                 v_strides=None, o_strides=None, assign="fh_w") -> MrtProblem:
     """Problem descriptor; default strides are those of contiguous [batch, heads, tokens, d]."""
     nq, nkv = f_q * h * w, f_kv * h * w
 
@@ -102,7 +104,7 @@ def make_problem(*, batch, heads, head_dim, f_q, f_kv, h, w, q_frame_offset=0, d
     vs, os_ = v_strides or contiguous(nkv), o_strides or contiguous(nq)
     return MrtProblem(batch, heads, head_dim, f_q, f_kv, h, w, q_frame_offset,
                       MrtStrides(*qs), MrtStrides(*ks), MrtStrides(*vs), MrtStrides(*os_),
-                      dtype, compute, scale)
+                      dtype, compute, scale, assign if isinstance(assign, int) else ASSIGNMENTS[assign])
 
 
 def monarch_attn_check(prob: MrtProblem, b1, b2, tile, iters, causal_chunk=0) -> int:
@@ -141,7 +143,7 @@ def profile_read(capacity: int = 65536):
 
 
 # ---- torch-facing helpers ------------------------------------------------------------
-def _torch_problem(Q, K, V, O, f_q, f_kv, h, w, q_frame_offset, scale, compute):
+def _torch_problem(Q, K, V, O, f_q, f_kv, h, w, q_frame_offset, scale, compute, assign="fh_w"):
     import torch
     assert Q.dim() == 4 and K.dim() == 4 and V.dim() == 4
     assert Q.is_cuda and K.is_cuda and V.is_cuda and O.is_cuda
@@ -157,17 +159,18 @@ def _torch_problem(Q, K, V, O, f_q, f_kv, h, w, q_frame_offset, scale, compute):
         return (t.stride(0), t.stride(1), t.stride(2))
     return make_problem(batch=B, heads=H, head_dim=d, f_q=f_q, f_kv=f_kv, h=h, w=w,
                         q_frame_offset=q_frame_offset, dtype=dt, compute=compute, scale=scale,
-                        q_strides=st(Q), k_strides=st(K), v_strides=st(V), o_strides=st(O))
+                        q_strides=st(Q), k_strides=st(K), v_strides=st(V), o_strides=st(O),
+                        assign=assign)
 
 
 def monarch_attn_fwd(Q, K, V, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,
                      q_frame_offset=0, scale=1.0, compute=MRT_COMPUTE_DEFAULT, out=None,
-                     workspace=None, stream=None):
+                     workspace=None, stream=None, assign="fh_w"):
     """MonarchRT attention forward on device tensors [batch, heads, tokens, head_dim]."""
     import torch
     lib = load_library()
     O = torch.empty_like(Q) if out is None else out
-    prob = _torch_problem(Q, K, V, O, f_q, f_kv, h, w, q_frame_offset, scale, compute)
+    prob = _torch_problem(Q, K, V, O, f_q, f_kv, h, w, q_frame_offset, scale, compute, assign)
     if workspace is None:
         nbytes = lib.monarch_attn_workspace_bytes(ctypes.byref(prob), b1, b2, tile, iters)
         if nbytes == 0:

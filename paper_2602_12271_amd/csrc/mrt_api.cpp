@@ -59,6 +59,10 @@ static mrt_status check_common(const mrt_problem* p) {
     }
   }
   if (p->q_frame_offset < 0) { set_error("q_frame_offset < 0"); return MRT_ERR_SHAPE; }
+  if ((int)p->assignment < 0 || (int)p->assignment > (int)MRT_ASSIGN_HW_F) {
+    set_error("unknown block assignment %d", (int)p->assignment);
+    return MRT_ERR_SHAPE;
+  }
   if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) { set_error("scale must be positive and finite"); return MRT_ERR_SHAPE; }
   return MRT_OK;
 }
@@ -79,44 +83,82 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
   Plan pl;
   memset(&pl, 0, sizeof(pl));
   KParams& k = pl.kp;
+  // block grid of the chosen assignment (Sec. 4.1): rows x cols per side, and the token offsets
+  // of a row / column index.  rpf = rows per frame when the frame is the slowest row axis.
+  const int f_q = p->f_q, f_kv = p->f_kv, h = p->h, w = p->w, hw = p->h * p->w;
+  int rows_q = 0, rows_k = 0, cols_q = 0, cols_k = 0, rpf = 0;
+  static const char* const kNames[] = {"(fh,w)", "(w,fh)", "(fw,h)", "(h,fw)", "(f,hw)", "(hw,f)"};
+  const char* aname = kNames[(int)p->assignment];
+  switch (p->assignment) {
+    case MRT_ASSIGN_FH_W:
+      rows_q = f_q * h; rows_k = f_kv * h; cols_q = cols_k = w; rpf = h;
+      k.rmap = AxisMap{0, 0, w}; k.cmap = AxisMap{0, 0, 1};
+      break;
+    case MRT_ASSIGN_W_FH:
+      rows_q = rows_k = w; cols_q = f_q * h; cols_k = f_kv * h;
+      k.rmap = AxisMap{0, 0, 1}; k.cmap = AxisMap{0, 0, w};
+      break;
+    case MRT_ASSIGN_FW_H:
+      rows_q = f_q * w; rows_k = f_kv * w; cols_q = cols_k = h; rpf = w;
+      k.rmap = AxisMap{w, hw, 1}; k.cmap = AxisMap{0, 0, w};
+      break;
+    case MRT_ASSIGN_H_FW:
+      rows_q = rows_k = h; cols_q = f_q * w; cols_k = f_kv * w;
+      k.rmap = AxisMap{0, 0, w}; k.cmap = AxisMap{w, hw, 1};
+      break;
+    case MRT_ASSIGN_F_HW:
+      rows_q = f_q; rows_k = f_kv; cols_q = cols_k = hw; rpf = 1;
+      k.rmap = AxisMap{0, 0, hw}; k.cmap = AxisMap{0, 0, 1};
+      break;
+    case MRT_ASSIGN_HW_F:
+      rows_q = rows_k = hw; cols_q = f_q; cols_k = f_kv;
+      k.rmap = AxisMap{0, 0, 1}; k.cmap = AxisMap{0, 0, hw};
+      break;
+  }
+  if (cols_q != cols_k) {
+    set_error("assignment %s has the frame axis on the b2 side: f_q must equal f_kv", aname);
+    return MRT_ERR_UNSUPPORTED;
+  }
+  const int cols = cols_q;
   if (tile == 0) {
     if (p->f_q != p->f_kv) {
       set_error("regular Monarch needs f_q == f_kv (use tile=1 for a KV cache)");
       return MRT_ERR_UNSUPPORTED;
     }
     if (causal_chunk != 0) { set_error("regular Monarch with a causal mask is not built"); return MRT_ERR_UNSUPPORTED; }
-    if (b1 != p->f_q * p->h || b2 != p->w) {
-      set_error("regular Monarch needs (b1,b2) = (f*h, w) = (%d,%d), got (%d,%d)", p->f_q * p->h, p->w, b1, b2);
+    if (b1 != rows_q || b2 != cols) {
+      set_error("regular Monarch with assignment %s needs (b1,b2) = (%d,%d), got (%d,%d)", aname, rows_q, cols, b1, b2);
       return MRT_ERR_BLOCK;
     }
     k.c2 = 1; k.ntq = 1; k.ntk = 1; k.c1k = 1; pl.c1q = 1;
   } else {
-    if (b1 % p->h != 0) {
-      set_error("tiled Monarch needs b1 to be a whole number of frames (b1 %% h == 0)");
-      return (p->h % b1 == 0 || b1 < p->h) ? MRT_ERR_UNSUPPORTED : MRT_ERR_BLOCK;
-    }
-    if ((p->f_q * p->h) % b1 || (p->f_kv * p->h) % b1 || p->w % b2) {
-      set_error("tile blocks (%d,%d) do not divide the grids (%d|%d rows, %d cols)", b1, b2,
-                p->f_q * p->h, p->f_kv * p->h, p->w);
+    if (rows_q % b1 || rows_k % b1 || cols % b2) {
+      set_error("tile blocks (%d,%d) do not divide the %s grids (%d|%d rows, %d cols)", b1, b2, aname,
+                rows_q, rows_k, cols);
       return MRT_ERR_BLOCK;
     }
-    k.c2 = p->w / b2;
-    k.c1k = (p->f_kv * p->h) / b1;
-    pl.c1q = (p->f_q * p->h) / b1;
+    k.c2 = cols / b2;
+    k.c1k = rows_k / b1;
+    pl.c1q = rows_q / b1;
     k.ntq = pl.c1q * k.c2;
     k.ntk = k.c1k * k.c2;
   }
   if (causal_chunk > 0) {
-    int fb = b1 / p->h;
-    if (causal_chunk % fb || p->q_frame_offset % fb) {
-      set_error("a tile (%d frames) must not straddle a causal chunk (%d frames, offset %d)", fb,
-                causal_chunk, p->q_frame_offset);
+    if (rpf == 0) {
+      set_error("a causal mask needs an assignment whose slowest b1 axis is the frame, not %s", aname);
+      return MRT_ERR_UNSUPPORTED;
+    }
+    const long long cr = (long long)causal_chunk * rpf, q0 = (long long)p->q_frame_offset * rpf;
+    if (cr % b1 || q0 % b1) {
+      set_error("a tile (%d rows, %d rows per frame) must not straddle a causal chunk (%d frames, offset %d)",
+                b1, rpf, causal_chunk, p->q_frame_offset);
       return MRT_ERR_BLOCK;
     }
-    k.fb = fb; k.cc = causal_chunk; k.qoff = p->q_frame_offset;
+    if (cr > (1 << 24) || q0 > (1 << 24)) { set_error("causal chunk or frame offset too large"); return MRT_ERR_SHAPE; }
+    k.cr = (int)cr; k.qrow0 = (int)q0; k.cc = causal_chunk; k.qoff = p->q_frame_offset;
   }
   k.qs = p->q; k.ks = p->k; k.vs = p->v; k.os = p->o;
-  k.H = p->heads; k.d = p->head_dim; k.b1 = b1; k.b2 = b2; k.w = p->w;
+  k.H = p->heads; k.d = p->head_dim; k.b1 = b1; k.b2 = b2;
   k.Nq = p->f_q * p->h * p->w; k.Nkv = p->f_kv * p->h * p->w; k.hw = p->h * p->w;
   k.scale = p->scale;
   pl.B = p->batch; pl.T = iters; pl.Nq = k.Nq; pl.Nkv = k.Nkv;
@@ -383,7 +425,7 @@ mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
   memset(&kp, 0, sizeof(kp));
   kp.Q = Q; kp.K = K; kp.V = V; kp.O = O;
   kp.qs = p->q; kp.ks = p->k; kp.vs = p->v; kp.os = p->o;
-  kp.H = p->heads; kp.d = p->head_dim; kp.w = p->w;
+  kp.H = p->heads; kp.d = p->head_dim;
   kp.Nq = p->f_q * p->h * p->w; kp.Nkv = p->f_kv * p->h * p->w; kp.hw = p->h * p->w;
   kp.cc = causal_chunk; kp.qoff = p->q_frame_offset; kp.scale = p->scale;
   const int BH = p->batch * p->heads;

@@ -159,16 +159,30 @@ __device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) 
   }
 }
 
-// Cooperative copy of `rows` rows of D bf16 (row r at src + r*stride) into a row-major LDS tile,
+// Element offset of row r of a tile of a token-indexed tensor (Q, K, V, O): the tile's rows are
+// the block-grid indices x0 + r along one side of the block grid.
+struct TokRows {
+  AxisMap m;
+  int x0;
+  long long tstride;   // elements per token
+  __device__ inline long long operator()(int r) const { return axis_offset(m, x0 + r) * tstride; }
+};
+// Rows at a fixed stride (the intermediates in the workspace).
+struct PlainRows {
+  long long stride;
+  __device__ inline long long operator()(int r) const { return (long long)r * stride; }
+};
+
+// Cooperative copy of `rows` rows of D bf16 (row r at src + rowoff(r)) into a row-major LDS tile,
 // zero-filling rows >= valid.
-template <int D, int LD = D + kPad>
-__device__ inline void stage_rows(u16* dst, const u16* src, long long stride, int rows, int valid,
+template <int D, int LD = D + kPad, typename RowFn>
+__device__ inline void stage_rows(u16* dst, const u16* src, RowFn rowoff, int rows, int valid,
                                   int tid, int nthr) {
   constexpr int CPR = D / 8;
   for (int idx = tid; idx < rows * CPR; idx += nthr) {
     const int r = idx / CPR, c = idx - r * CPR;
     uint4 v = {0u, 0u, 0u, 0u};
-    if (r < valid) v = *(const uint4*)(src + (long long)r * stride + 8 * c);
+    if (r < valid) v = *(const uint4*)(src + rowoff(r) + 8 * c);
     *(uint4*)(dst + r * LD + 8 * c) = v;
   }
 }
@@ -182,7 +196,8 @@ struct RowRegs {
   static constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
   uint4 v[N];
   int valid;
-  __device__ inline void load(const u16* src, long long stride, int nvalid, int tid) {
+  template <typename RowFn>
+  __device__ inline void load(const u16* src, RowFn rowoff, int nvalid, int tid) {
     valid = nvalid;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
@@ -191,7 +206,7 @@ struct RowRegs {
       int r = idx / CPR;
       const int c = idx - r * CPR;
       r = r < nvalid ? r : nvalid - 1;
-      v[i] = *(const uint4*)(src + (long long)r * stride + 8 * c);
+      v[i] = *(const uint4*)(src + rowoff(r) + 8 * c);
     }
   }
   template <int LD>
@@ -205,10 +220,10 @@ struct RowRegs {
   }
 };
 
-template <int D, int LD, int ROWS, int NTHR>
-__device__ inline void stage_rows_batched(u16* dst, const u16* src, long long stride, int valid, int tid) {
+template <int D, int LD, int ROWS, int NTHR, typename RowFn>
+__device__ inline void stage_rows_batched(u16* dst, const u16* src, RowFn rowoff, int valid, int tid) {
   RowRegs<D, ROWS, NTHR> r;
-  r.load(src, stride, valid, tid);
+  r.load(src, rowoff, valid, tid);
   r.template store<LD>(dst, tid);
 }
 
@@ -235,13 +250,14 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   // sees more key tiles)
   int ml0 = blockIdx.y * gs;
   const int ml1 = ml0 + gs < p.ntq ? ml0 + gs : p.ntq;
-  while (ml0 < ml1 && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.fb, p.cc, p.qoff)) ++ml0;
+  while (ml0 < ml1 && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.b1, p.cr, p.qrow0)) ++ml0;
   if (ml0 >= ml1) return;
   const int b = bh / p.H, hd = bh - b * p.H;
 
-  const long long ktok0 = (long long)(an * b1 + k) * p.w + bn * b2;
-  const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + ktok0 * p.ks.token;
-  const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + ktok0 * p.vs.token;
+  // key block (n, k): block-grid row an*b1 + k, columns bn*b2 + i
+  const long long krow = axis_offset(p.rmap, an * b1 + k);
+  const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + krow * p.ks.token;
+  const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + krow * p.vs.token;
   const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const size_t NKtot = (size_t)p.ntk * b1;
 
@@ -250,8 +266,8 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   // the first LDS store
   RowRegs<D, ROWS, NTHR> rk;
   RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
-  rk.load(Kp, p.ks.token, b2, tid);
-  if (LAST) rv.load(Vp, p.vs.token, b2, tid);
+  rk.load(Kp, TokRows{p.cmap, bn * b2, p.ks.token}, b2, tid);
+  if (LAST) rv.load(Vp, TokRows{p.cmap, bn * b2, p.vs.token}, b2, tid);
 
   // query-side rows of this wave (row j = 16*wave + c) go straight to registers: Q[m, k, j, :] in
   // the first iteration (L is the identity), alpha_R / c_R afterwards
@@ -262,7 +278,7 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
     const u16* arow;
     if (FIRST) {
       const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
-      arow = Qbase + ((long long)(a * b1 + k) * p.w + bq * b2 + jc) * p.qs.token;
+      arow = Qbase + (axis_offset(p.rmap, a * b1 + k) + axis_offset(p.cmap, bq * b2 + jc)) * p.qs.token;
     } else {
       arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 + jc) * D;
     }
@@ -626,12 +642,13 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const WaveTiles<QT> wt(wave, nthr >> 6, (b1 + 15) >> 4);
 
-  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
+  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   bf16x8 qv[QT][KS1];
 #pragma unroll
@@ -640,7 +657,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
     const int lc = l < b1 ? l : b1 - 1;
 #pragma unroll
     for (int ks = 0; ks < KS1; ++ks)
-      qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+      qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
   }
 
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
@@ -667,7 +684,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   for (int q = 0; q < QT; ++q) {
     const int l = 16 * wt.lt[q] + c;
     const float lsum = xsum(st.lrun[q]);
-    if (q < wt.nq && l < b1) store_rows<D>(Op + (long long)l * p.w * p.os.token, o[q], 1.0f / lsum, g);
+    if (q < wt.nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / lsum, g);
   }
   MRT_STAMP(2);
 }
@@ -831,14 +848,15 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   constexpr int nlt = NLT;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
 
-  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
+  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   MRT_STAMP(0);
-  stage_rows<D>(Qs, Qp, (long long)p.w * p.qs.token, qrows, b1, tid, nthr);
+  stage_rows<D>(Qs, Qp, qrow, qrows, b1, tid, nthr);
 
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
@@ -854,7 +872,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
       const int lc = l < b1 ? l : b1 - 1;
 #pragma unroll
       for (int ks = 0; ks < KS1; ++ks)
-        qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+        qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
     }
     FlashState<QT> st;
     f32x4 odummy[QT][NVT];
@@ -963,7 +981,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;   // <= 16*NTK
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= 16*NTK
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const int nlt = (b1 + 15) >> 4;
@@ -972,7 +990,8 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const u16* Yp = (const u16*)p.Y + row0 * D;
   const float* cLp = p.cL + row0;
-  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
+  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
 
@@ -986,13 +1005,13 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
       const int lc = l < b1 ? l : b1 - 1;
 #pragma unroll
       for (int ks = 0; ks < KS1; ++ks)
-        qv[q][ks] = ld_global_16B(Qp + (long long)lc * p.w * p.qs.token + 32 * ks + 8 * g);
+        qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
     }
   };
   const int npairs = (nlt + QT - 1) / QT;
   if (wave < npairs) load_q(wave);
-  stage_rows_batched<D, LD, ROWS, 256>(Ks, aLp, D, NK, tid);
-  stage_rows_batched<D, LD, ROWS, 256>(Vs, Yp, D, NK, tid);
+  stage_rows_batched<D, LD, ROWS, 256>(Ks, aLp, PlainRows{D}, NK, tid);
+  stage_rows_batched<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
   for (int i = tid; i < ROWS; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
@@ -1027,7 +1046,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
       const int l = 16 * (QT * pair + q) + c;
-      if (q < nq && l < b1) store_rows<D>(Op + (long long)l * p.w * p.os.token, o[q], 1.0f / sum[q], g);
+      if (q < nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
     }
   }
   MRT_STAMP(2);
@@ -1046,20 +1065,21 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_res(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;   // <= kResRows
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= kResRows
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const int nkt = (NK + 15) >> 4;
 
-  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
+  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const float* cLp = p.cL + row0;
 
   MRT_STAMP(0);
-  stage_rows_batched<D, LD, QROWS, 256>(Qs, Qp, (long long)p.w * p.qs.token, b1, tid);
-  stage_rows_batched<D, LD, kResRows, 256>(Ks, aLp, D, NK, tid);
+  stage_rows_batched<D, LD, QROWS, 256>(Qs, Qp, qrow, b1, tid);
+  stage_rows_batched<D, LD, kResRows, 256>(Ks, aLp, PlainRows{D}, NK, tid);
   for (int i = tid; i < kResRows; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);

@@ -42,15 +42,17 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
   const int n = nk / b1, k = nk - n * b1;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int an = n / p.c2, bn = n - an * p.c2;
-  if (an >= visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff)) return;
+  if (an >= visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0)) return;
   const int b = bh / p.H, hd = bh - b * p.H;
 
   float* A = sm;
   float* Kb = A + b2 * ld;
   float* S = Kb + b2 * ld;
 
-  const long long qtok0 = (long long)(a * b1 + k) * p.w + bq * b2;
-  const long long ktok0 = (long long)(an * b1 + k) * p.w + bn * b2;
+  // block-grid rows a*b1 + k (queries) and an*b1 + k (keys); columns bq*b2 + j and bn*b2 + i
+  const long long qrow = axis_offset(p.rmap, a * b1 + k), krow = axis_offset(p.rmap, an * b1 + k);
+  auto qtok = [&](int j) { return qrow + axis_offset(p.cmap, bq * b2 + j); };
+  auto ktok = [&](int i) { return krow + axis_offset(p.cmap, bn * b2 + i); };
   const TIn* Qp = (const TIn*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const TIn* Kp = (const TIn*)p.K + b * p.ks.batch + hd * p.ks.head;
   const TIn* Vp = (const TIn*)p.V + b * p.vs.batch + hd * p.vs.head;
@@ -59,8 +61,8 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
 
   for (int idx = tid; idx < b2 * d; idx += kThreads) {
     const int j = idx / d, v = idx - j * d;
-    A[j * ld + v] = first ? ldf(Qp + (qtok0 + j) * p.qs.token + v) : aRp[idx];
-    Kb[j * ld + v] = ldf(Kp + (ktok0 + j) * p.ks.token + v);
+    A[j * ld + v] = first ? ldf(Qp + qtok(j) * p.qs.token + v) : aRp[idx];
+    Kb[j * ld + v] = ldf(Kp + ktok(j) * p.ks.token + v);
   }
   __syncthreads();
   for (int idx = tid; idx < b2 * b2; idx += kThreads) {
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
     if (last) {
       float accv = 0.f;
       for (int i = 0; i < b2; ++i)
-        accv = fmaf(S[j * ls + i], ldf(Vp + (ktok0 + i) * p.vs.token + v), accv);
+        accv = fmaf(S[j * ls + i], ldf(Vp + ktok(i) * p.vs.token + v), accv);
       Yp[j * jstride + v] = accv;
     }
   }
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
   const int d = p.d, b1 = p.b1, b2 = p.b2, ld = d + 1, lz = kCH + 1;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.fb, p.cc, p.qoff) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
 
@@ -135,10 +137,11 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
   float* cinv = cmx + kCH;           // [kCH]
 
   const TIn* Qp = (const TIn*)p.Q + b * p.qs.batch + hd * p.qs.head;
-  const long long qtok0 = (long long)(a * b1) * p.w + bq * b2 + j;   // + l*w
+  const long long qcol = axis_offset(p.cmap, bq * b2 + j);
+  auto qtok = [&](int l) { return axis_offset(p.rmap, a * b1 + l) + qcol; };
   for (int idx = tid; idx < b1 * d; idx += kThreads) {
     const int l = idx / d, v = idx - l * d;
-    Qj[l * ld + v] = ldf(Qp + (qtok0 + (long long)l * p.w) * p.qs.token + v);
+    Qj[l * ld + v] = ldf(Qp + qtok(l) * p.qs.token + v);
   }
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const float* aLp = (const float*)p.aL + row0 * d;
@@ -247,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
 #pragma unroll
     for (int r = 0; r < kMaxRows; ++r) {
       const int l = lg + r * ngroups;
-      if (l < b1) stf(Op + (qtok0 + (long long)l * p.w) * p.os.token + vt, acc[r]);
+      if (l < b1) stf(Op + qtok(l) * p.os.token + vt, acc[r]);
     }
   }
 }

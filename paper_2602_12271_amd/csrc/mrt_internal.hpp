@@ -8,6 +8,19 @@
 
 namespace mrt {
 
+// Offset, in tokens, of block-grid index x along one side of the block grid:
+//   div == 0:  x * lo          div > 0:  (x / div) * hi + (x % div) * lo
+// (the two-level form is needed when that side is (frame, width): Sec. 4.1's (fw, h) and (h, fw)).
+struct AxisMap {
+  int div;
+  int hi, lo;
+};
+__host__ __device__ inline long long axis_offset(const AxisMap& m, int x) {
+  if (m.div == 0) return (long long)x * m.lo;
+  const int q = x / m.div;
+  return (long long)q * m.hi + (long long)(x - q * m.div) * m.lo;
+}
+
 // Geometry and addressing of one call, passed by value to every kernel.
 //
 // Index names follow App. A: m query tile, n key tile, l query row, j column, k key row,
@@ -32,21 +45,23 @@ struct KParams {
   int ntq, ntk; // query tiles IN THIS PASS (workspace extent), key tiles of the whole grid
   int m0;       // first query tile of this pass
   int c1k;      // key tile rows
-  int w;        // grid width = c2*b2
-  int fb;       // frames per tile row (b1/h); 0 when no mask
-  int cc;       // frames per causal chunk; 0 = no mask
-  int qoff;     // absolute frame of query frame 0
+  AxisMap rmap, cmap;   // token of block-grid cell (x, y) = axis_offset(rmap, x) + axis_offset(cmap, y)
+  int cr;       // block-grid rows per causal chunk; 0 = no mask
+  int qrow0;    // block-grid row (of the key grid) at which query row 0 sits (mask only)
+  int cc;       // frames per causal chunk (dense baseline); 0 = no mask
+  int qoff;     // absolute frame of query frame 0 (dense baseline)
   int Nq, Nkv;  // tokens per head on the query / key side
   int hw;       // tokens per frame (h*w)
   float scale;
 };
 
-// Number of visible key-tile ROWS for query tile row a (tile-level chunk-causal reading:
-// key tile row a' is visible iff floor(a'*fb / cc) <= floor((qoff + a*fb) / cc)).
-__host__ __device__ inline int visible_key_tile_rows(int a, int c1k, int fb, int cc, int qoff) {
-  if (cc == 0) return c1k;
-  int q_chunk = (qoff + a * fb) / cc;
-  int rows = ((q_chunk + 1) * cc) / fb;
+// Number of visible key-tile ROWS for query tile row a (tile-level chunk-causal reading: key
+// tile row a' is visible iff its chunk floor(a'*b1 / cr) is not later than the query tile row's
+// chunk floor((qrow0 + a*b1) / cr); no tile straddles a chunk, so cr and qrow0 are multiples of b1).
+__host__ __device__ inline int visible_key_tile_rows(int a, int c1k, int b1, int cr, int qrow0) {
+  if (cr == 0) return c1k;
+  const int q_chunk = (qrow0 + a * b1) / cr;
+  const int rows = ((q_chunk + 1) * cr) / b1;
   return rows < c1k ? rows : c1k;
 }
 

@@ -34,11 +34,16 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_binding_struct_matches_header_layout():
-    # 8 ints, 4 x 3 long long, 2 enums, 1 float; natural alignment
+    # 8 ints, 4 x 3 long long, 2 enums, 1 float, 1 enum; natural alignment
     assert ctypes.sizeof(B.MrtStrides) == 24
     assert B.MrtProblem.q.offset == 32
     assert B.MrtProblem.dtype.offset == 32 + 4 * 24
+    assert B.MrtProblem.assignment.offset == 32 + 96 + 12
     assert ctypes.sizeof(B.MrtProblem) == 32 + 96 + 16
+    # the header lists the assignments in the binding's order
+    text = open(HEADER).read()
+    for name, val in B.ASSIGNMENTS.items():
+        assert re.search(rf"MRT_ASSIGN_{name.upper()}\s*=\s*{val}\b", text), name
 
 
 def problem(**kw):
@@ -56,6 +61,14 @@ def test_named_configurations_are_accepted():
     c0 = pkg.make_problem(batch=1, heads=1, head_dim=64, f_q=1, f_kv=1, h=24, w=24,
                           dtype=B.MRT_F32, scale=1.0)
     assert pkg.monarch_attn_check(c0, 24, 24, 0, 1) == B.MRT_OK                        # C0
+    # other aligned assignments within the block limits, and tiles that are a row range of a frame
+    assert pkg.monarch_attn_check(problem(assign="w_fh"), 52, 90, 0, 2) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(assign="fw_h"), 156, 30, 0, 2) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(assign="fw_h", f_kv=21, q_frame_offset=18), 52, 30, 1, 2, 3) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(assign="h_fw"), 30, 52, 1, 2) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(assign="hw_f"), 156, 3, 1, 1) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(f_kv=21, q_frame_offset=18), 15, 26, 1, 2, 3) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(), 45, 26, 1, 2) == B.MRT_OK     # 1.5 frames, no mask
 
 
 @pytest.mark.parametrize("kw,args,status", [
@@ -66,9 +79,16 @@ def test_named_configurations_are_accepted():
     (dict(), (90, 52, 0, 0, 0), B.MRT_ERR_SHAPE),            # iters < 1
     (dict(), (90, 52, 2, 1, 0), B.MRT_ERR_SHAPE),            # tile flag
     (dict(), (90, 25, 1, 2, 0), B.MRT_ERR_BLOCK),            # 25 does not divide 52
-    (dict(), (15, 26, 1, 2, 0), B.MRT_ERR_UNSUPPORTED),      # tile of half a frame (n_h < h)
-    (dict(), (45, 26, 1, 2, 0), B.MRT_ERR_BLOCK),            # one and a half frames
-    (dict(), (60, 26, 1, 2, 0), B.MRT_ERR_BLOCK),            # 60 rows: two frames do not divide 3
+    (dict(), (60, 26, 1, 2, 0), B.MRT_ERR_BLOCK),            # 60 rows do not divide 90
+    (dict(f_kv=21), (45, 26, 1, 2, 1), B.MRT_ERR_BLOCK),     # 1.5-frame tiles straddle 1-frame chunks
+    (dict(f_kv=21), (20, 26, 1, 2, 1), B.MRT_ERR_BLOCK),     # 20 rows divide neither frame nor grid
+    (dict(assign="w_fh", f_kv=21), (52, 30, 1, 2, 0), B.MRT_ERR_UNSUPPORTED),  # frames on the b2 side, f_q != f_kv
+    (dict(assign="w_fh"), (52, 30, 1, 2, 3), B.MRT_ERR_UNSUPPORTED),           # mask needs frames on the b1 side
+    (dict(assign="h_fw"), (30, 52, 1, 2, 3), B.MRT_ERR_UNSUPPORTED),
+    (dict(assign="fw_h"), (90, 52, 0, 2, 0), B.MRT_ERR_BLOCK),                 # regular (fw,h) is (156,30)
+    (dict(assign="f_hw"), (3, 1560, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),          # b2 beyond this build
+    (dict(assign="hw_f"), (1560, 3, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),          # b1 beyond this build
+    (dict(assign=9), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),                      # unknown assignment
     (dict(f_kv=21), (90, 26, 1, 2, 2), B.MRT_ERR_BLOCK),     # 3-frame tiles straddle 2-frame chunks
     (dict(f_kv=21, q_frame_offset=1), (90, 26, 1, 2, 3), B.MRT_ERR_BLOCK),   # offset inside a tile
     (dict(head_dim=96), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),  # bf16 path: d in {64,128}

@@ -41,6 +41,15 @@ class Workload:
     sigma_qk: float = 1.0
     sigma_v: float = 1.0
     seed: int = 0
+    assign: str = "fh_w"  # aligned block assignment (Sec. 4.1): axes of the b1 side _ axes of the b2 side
+
+    def block_grid(self):
+        """(rows_q, rows_kv, cols) of the block grid under the assignment."""
+        size = lambda axes, f: int(np.prod([{"f": f, "h": self.h, "w": self.w}[c] for c in axes]))
+        ra, ca = self.assign.split("_")
+        cols_q, cols_k = size(ca, self.f_q), size(ca, self.f_kv)
+        assert cols_q == cols_k, "frame axis on the b2 side needs f_q == f_kv"
+        return size(ra, self.f_q), size(ra, self.f_kv), cols_q
 
     @property
     def n_q(self) -> int:
@@ -52,11 +61,13 @@ class Workload:
 
     @property
     def ntq(self) -> int:
-        return 1 if self.tile == 0 else (self.f_q * self.h // self.b1) * (self.w // self.b2)
+        rq, _, cols = self.block_grid()
+        return 1 if self.tile == 0 else (rq // self.b1) * (cols // self.b2)
 
     @property
     def ntk(self) -> int:
-        return 1 if self.tile == 0 else (self.f_kv * self.h // self.b1) * (self.w // self.b2)
+        _, rk, cols = self.block_grid()
+        return 1 if self.tile == 0 else (rk // self.b1) * (cols // self.b2)
 
 
 _INV_SQRT128 = 1.0 / np.sqrt(128.0)
@@ -86,6 +97,17 @@ WORKLOADS: Dict[str, Workload] = {
     "T5-480-hw": Workload("T5-480-hw", 1, 12, 128, 21, 21, 30, 52, 30, 52, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
     "T5-720-3hw": Workload("T5-720-3hw", 1, 12, 128, 21, 21, 45, 80, 135, 80, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
     "T5-720-hw": Workload("T5-720-hw", 1, 12, 128, 21, 21, 45, 80, 45, 80, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
+    # C1's tensors under the other aligned block assignments that fit the kernels' block limits
+    # (Sec. 4.1): (w, fh) = (52, 90) and (fw, h) = (156, 30), regular Monarch, T = 2
+    "C1-w_fh": Workload("C1-w_fh", 1, 12, 128, 3, 3, 30, 52, 52, 90, 0, 2, 0, 0, "bf16", _INV_SQRT128, True,
+                        assign="w_fh"),
+    "C1-fw_h": Workload("C1-fw_h", 1, 12, 128, 3, 3, 30, 52, 156, 30, 0, 2, 0, 0, "bf16", _INV_SQRT128, True,
+                        assign="fw_h"),
+    # KV-cache step with (frame, width) rows: tiles of one frame (52 rows) by 30 columns, chunk-causal
+    "C3-fw_h": Workload("C3-fw_h", 1, 12, 128, 3, 21, 30, 52, 52, 30, 1, 2, 3, 18, "bf16", _INV_SQRT128, True,
+                        assign="fw_h"),
+    # neighbourhood tiles of half a frame: (n_f, n_h, n_w) = (1, 15, 26)
+    "C3-half": Workload("C3-half", 1, 12, 128, 3, 21, 30, 52, 15, 26, 1, 2, 3, 18, "bf16", _INV_SQRT128, True),
 }
 
 
