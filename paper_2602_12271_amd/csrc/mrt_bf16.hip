@@ -1310,12 +1310,14 @@ hipError_t set_trace_buffer(void* buf, hipStream_t s) {
 #endif
 
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s) {
-  // query tiles per workgroup: as many as possible (each key block is then read once, not once
-  // per query tile) while the launch still has a few thousand workgroups
+  // query tiles per workgroup: each key block is then staged once for gs query tiles instead of
+  // once per tile.  Measured: 2..3 tiles per workgroup win whenever the launch keeps about a
+  // thousand workgroups; more only lengthen the workgroups.
   const long long blocks = (long long)kp.ntk * kp.b1 * kp.ntq * nbh;
-  long long gs = blocks / 4096;
-  if (gs < 1) gs = 1;
+  long long gs = blocks / 1024;
+  if (gs > 3) gs = 3;
   if (gs > kp.ntq) gs = kp.ntq;
+  if (gs < 1) gs = 1;
   dim3 grid(kp.ntk * kp.b1, (kp.ntq + (int)gs - 1) / (int)gs, nbh);
   return kp.d == 128 ? launch_r_d<128>(kp, grid, (int)gs, first, last, s)
                      : launch_r_d<64>(kp, grid, (int)gs, first, last, s);

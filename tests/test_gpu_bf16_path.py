@@ -51,6 +51,10 @@ SMALL = {
                              causal_chunk=0, q_frame_offset=0),
     "tiled-b1-1": small_bf16(f_q=3, f_kv=3, h=1, w=40, b1=1, b2=20, tile=1, iters=2,
                              causal_chunk=0, q_frame_offset=0),
+    # block-causal self-attention over a whole 6-frame sequence (2-frame chunks): every query tile
+    # row sees a different prefix of key tiles, and stage R runs several query tiles per workgroup
+    "tiled-self-causal": small_bf16(heads=3, f_q=6, f_kv=6, h=10, w=28, b1=10, b2=14, tile=1, iters=2,
+                                    causal_chunk=2, q_frame_offset=0),
     # largest block sizes of this build
     "max-blocks": small_bf16(heads=1, f_q=2, f_kv=2, h=96, w=96, b1=192, b2=96, tile=0, iters=2,
                              causal_chunk=0, q_frame_offset=0),
