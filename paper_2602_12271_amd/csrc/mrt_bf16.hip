@@ -1228,6 +1228,253 @@ hipError_t launch_l_out(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// stage L for medium key ranges (96 < NK <= 192, b1 <= 128): still one workgroup per (m, j) and
+// three workgroups per compute unit, with ONE 52 KB LDS tile used twice.  Last iteration: the
+// tile first holds alpha_L[m, j] (every wave forms the exact softmax of its one or two query
+// tiles against all keys and keeps the probabilities as packed bf16 in registers), then Y[m, j]
+// (second product).  Earlier iterations: the tile holds alpha_L for the row log-sum-exp, then Q
+// for the second pass, which streams alpha_L again from global memory.
+// ---------------------------------------------------------------------------------------
+constexpr int kMidRows = 192;
+
+// Base-2 logits (bias added, -inf beyond the last key) of one query tile against NTK resident key
+// tiles (NTK <= 12), and their column maximum.
+template <int D, int NTK, int LD>
+__device__ inline float mid_logits(const u16* Ks, const float* bias, const bf16x8 (&qv)[D / 32],
+                                   float scale2, f32x4 (&s)[2 * ((NTK + 1) / 2)], int lane) {
+  constexpr int KS1 = D / 32, KS2 = (NTK + 1) / 2;
+  const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int kp = 0; kp < KS2; ++kp) {
+    bf16x8 a[2][KS1];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (2 * kp + t < NTK) {
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks)
+          a[t][ks] = ld_lds_16B(Ks + (16 * (2 * kp + t) + c) * LD + 32 * ks + 8 * g);
+      }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      if (2 * kp + t < NTK) {
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) acc = mfma(a[t][ks], qv[ks], acc);
+      }
+      s[2 * kp + t] = acc;
+    }
+    __builtin_amdgcn_sched_barrier(0);   // one pair of key tiles in flight at a time
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int kt = 0; kt < 2 * KS2; ++kt) {
+    const f32x4 ninf = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    const f32x4 bi = kt < NTK ? *(const f32x4*)(bias + 16 * kt + 4 * g) : ninf;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
+      mx = fmaxf(mx, s[kt][r]);
+    }
+  }
+  return xmax(mx);
+}
+
+template <int D, int NTK>
+__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
+  constexpr int LD = D + kResPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  constexpr int QT = 2;
+  __shared__ __attribute__((aligned(16))) u16 tile[ROWS * LD];
+  __shared__ __attribute__((aligned(16))) float bias[ROWS];
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= 16*NTK
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const WaveTiles<QT> wt(wave, nwaves, (b1 + 15) >> 4);      // b1 <= 128: at most two tiles a wave
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const u16* Yp = (const u16*)p.Y + row0 * D;
+  const float* cLp = p.cL + row0;
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);
+  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
+
+  MRT_STAMP(0);
+  bf16x8 qv[QT][KS1];
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    const int l = 16 * wt.lt[q] + c;
+    const int lc = l < b1 ? l : b1 - 1;
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
+  }
+  stage_rows_batched<D, LD, ROWS, 256>(tile, aLp, PlainRows{D}, NK, tid);
+  for (int i = tid; i < ROWS; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+  __syncthreads();
+  MRT_STAMP(1);
+
+  // ---- first product and exact softmax, one query tile at a time
+  const float scale2 = p.scale * kLog2e;
+  bf16x8 pb[KS2][QT];
+  float sum[QT];
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    sum[q] = 1.f;
+    if (q < wt.nq) {
+      f32x4 s[2 * KS2];
+      const float mx = mid_logits<D, NTK, LD>(tile, bias, qv[q], scale2, s, lane);
+      float sm = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 2 * KS2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          s[kt][r] = exp2_fast(s[kt][r] - mx);
+          sm += s[kt][r];
+        }
+      sum[q] = xsum(sm);
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) pb[st][q] = pack8(s[2 * st], s[2 * st + 1]);
+    } else {
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) pb[st][q] = bf16x8{};
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __syncthreads();                      // every wave is done with alpha_L
+  MRT_STAMP(2);
+  stage_rows_batched<D, LD, ROWS, 256>(tile, Yp, PlainRows{D}, NK, tid);
+  __syncthreads();
+  MRT_STAMP(3);
+
+  // ---- second product: both query tiles of the wave share every value read
+  if (wt.nq > 0) {
+    f32x4 o[QT][NVT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      pv_step_multi<D, QT, LD>(tile + 32 * st * LD, pb[st], wt.nq, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * wt.lt[q] + c;
+      if (q < wt.nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
+    }
+  }
+  MRT_STAMP(4);
+}
+
+template <int D, int NLT, int PT>
+__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_mid(KParams p) {
+  constexpr int LD = D + kResPad, KS1 = D / 32, NTK = kMidRows / 16;
+  constexpr int QROWS = 32 * ((NLT + 1) / 2), QT = 2;
+  static_assert(QROWS <= kMidRows, "the Q tile must fit the shared buffer");
+  __shared__ __attribute__((aligned(16))) u16 tile[kMidRows * LD];
+  __shared__ __attribute__((aligned(16))) float bias[kMidRows];
+  __shared__ __attribute__((aligned(16))) float lse[16 * NLT];
+
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= kMidRows
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const WaveTiles<QT> wt(wave, nwaves, NLT);
+
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);
+  const TokRows qrow{p.rmap, a * b1, p.qs.token};
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * D;
+  const float* cLp = p.cL + row0;
+
+  MRT_STAMP(0);
+  bf16x8 qv[QT][KS1];
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    const int l = 16 * wt.lt[q] + c;
+    const int lc = l < b1 ? l : b1 - 1;
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
+  }
+  stage_rows_batched<D, LD, kMidRows, 256>(tile, aLp, PlainRows{D}, NK, tid);
+  for (int i = tid; i < kMidRows; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+  __syncthreads();
+  MRT_STAMP(1);
+
+  // ---- pass 1: base-2 log-sum-exp of every query row over the resident keys
+  const float scale2 = p.scale * kLog2e;
+#pragma unroll
+  for (int q = 0; q < QT; ++q) {
+    if (q < wt.nq) {
+      f32x4 s[NTK];
+      const float mx = mid_logits<D, NTK, LD>(tile, bias, qv[q], scale2, s, lane);
+      float sm = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < NTK; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm += exp2_fast(s[kt][r] - mx);
+      sm = xsum(sm);
+      if (g == 0) lse[16 * wt.lt[q] + c] = mx + log2_fast(sm);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __syncthreads();                      // every wave is done with alpha_L in LDS
+  MRT_STAMP(2);
+  stage_rows_batched<D, LD, QROWS, 256>(tile, Qp, qrow, b1, tid);
+  __syncthreads();
+
+  // ---- pass 2: alpha_L streamed from global memory, Q transposed from LDS
+  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
+  refine_pass2<D, NLT, PT, LD>(p, tile, lse, false, nullptr, nullptr, aLp, cLp, aRout, NK, j, wave,
+                               nwaves, lane);
+  MRT_STAMP(6);
+}
+
+template <int D, int NTK>
+hipError_t launch_l_out_mid(const KParams& kp, dim3 grid, hipStream_t s) {
+  k_bf16_stage_l_out_mid<D, NTK><<<grid, 256, 0, s>>>(kp);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_l_out_mid_d(const KParams& kp, dim3 grid, int nkt, hipStream_t s) {
+  switch (nkt) {
+    case 7: case 8: return launch_l_out_mid<D, 8>(kp, grid, s);
+    case 9: case 10: return launch_l_out_mid<D, 10>(kp, grid, s);
+    case 11: case 12: return launch_l_out_mid<D, 12>(kp, grid, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <int D>
+hipError_t launch_l_refine_mid_d(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
+  switch (nlt) {
+    case 1: k_bf16_stage_l_refine_mid<D, 1, 2><<<grid, 256, 0, s>>>(kp); break;
+    case 2: k_bf16_stage_l_refine_mid<D, 2, 2><<<grid, 256, 0, s>>>(kp); break;
+    case 3: k_bf16_stage_l_refine_mid<D, 3, 2><<<grid, 256, 0, s>>>(kp); break;
+    case 4: k_bf16_stage_l_refine_mid<D, 4, 2><<<grid, 256, 0, s>>>(kp); break;
+    case 5: k_bf16_stage_l_refine_mid<D, 5, 2><<<grid, 256, 0, s>>>(kp); break;
+    case 6: k_bf16_stage_l_refine_mid<D, 6, 2><<<grid, 256, 0, s>>>(kp); break;
+    case 7: k_bf16_stage_l_refine_mid<D, 7, 1><<<grid, 256, 0, s>>>(kp); break;
+    case 8: k_bf16_stage_l_refine_mid<D, 8, 1><<<grid, 256, 0, s>>>(kp); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 template <int D, int NLT>
 hipError_t launch_l_refine(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
   constexpr int QT = NLT <= 4 ? 1 : 2, MAXT = NLT <= 8 ? 256 : 384, PT = NLT <= 8 ? 2 : 1;
@@ -1337,6 +1584,13 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
                                  : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
     return kp.d == 128 ? launch_l_refine_res_d<128>(kp, grid, nlt, s)
                        : launch_l_refine_res_d<64>(kp, grid, nlt, s);
+  }
+  // medium key ranges: one LDS tile used twice, still three workgroups per compute unit
+  if (nk_max <= kMidRows && nlt <= 8) {
+    if (last) return kp.d == 128 ? launch_l_out_mid_d<128>(kp, grid, (nk_max + 15) / 16, s)
+                                 : launch_l_out_mid_d<64>(kp, grid, (nk_max + 15) / 16, s);
+    return kp.d == 128 ? launch_l_refine_mid_d<128>(kp, grid, nlt, s)
+                       : launch_l_refine_mid_d<64>(kp, grid, nlt, s);
   }
   const int nthr = nlt <= 8 ? 256 : 64 * ((nlt + 1) / 2);
   if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nthr, nlt, s)
