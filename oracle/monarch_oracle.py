@@ -45,7 +45,10 @@ equations; monotone KL along the iterations; constant V) and, for the block
 assignments and fractional-frame tiles, by tests/test_oracle_assignments.py
 (rank-one block structure of the materialised matrix under an index map
 written out in the test; position-only logits == dense for all six
-assignments; assignments that coincide on degenerate grids).
+assignments; assignments that coincide on degenerate grids).  monarch_attn_grad is
+pinned by tests/test_oracle_backward.py (central differences of the forward oracle,
+dV = M^T dO with the materialised matrix, the closed-form gradient of dense attention
+for degenerate block sizes).
 """
 from __future__ import annotations
 
@@ -357,6 +360,16 @@ def monarch_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, b1: int, b2: i
         return monarch_attention_regular(Q, K, V, iters, b1, b2, scale)
     vis = chunk_causal_visibility(g, h, causal_chunk, q_frame_offset)
     return monarch_attention_tiled(Q, K, V, iters, g, scale, vis)
+
+
+def monarch_attn_grad(Q, K, V, dO, **kw):
+    """Gradients (dQ, dK, dV) of sum(O * dO) for O = monarch_attn(Q, K, V, **kw): the backward
+    pass that Monarch finetuning needs (Sec. 4.3).  Reverse-mode differentiation of the fp64
+    definition above, every iteration included (nothing is treated as a constant)."""
+    Qg, Kg, Vg = (x.detach().to(F64).clone().requires_grad_(True) for x in (Q, K, V))
+    O = monarch_attn(Qg, Kg, Vg, **kw)
+    gQ, gK, gV = torch.autograd.grad(O, (Qg, Kg, Vg), grad_outputs=dO.to(F64))
+    return gQ, gK, gV
 
 
 def dense_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, causal_chunk: int = 0,
