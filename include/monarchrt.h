@@ -122,6 +122,25 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
                             int causal_chunk, void* workspace, size_t workspace_bytes,
                             void* hip_stream);
 
+/* Backward pass: gradients of  sum(O * dO)  with respect to Q, K and V for the O of
+ * monarch_attn_fwd with the same arguments, differentiating through every refinement iteration
+ * (this is what Monarch finetuning trains through, Sec. 4.3).
+ *   dO: device memory, storage type and element strides of O (p->o).  dQ [batch, heads, N_q,
+ *   head_dim], dK and dV [batch, heads, N_kv, head_dim]: device memory, fp32, contiguous, fully
+ *   overwritten.  The arithmetic is fp32 whatever p->dtype and p->compute say.  The forward
+ *   intermediates of every iteration are recomputed into the workspace first (fp32), so nothing
+ *   has to be kept from the forward call; the workspace holds whole (batch, head) entries and the
+ *   library runs as many of them per pass as fit (workspace rules as for monarch_attn_fwd).
+ *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers fit the 160 KB
+ *   of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128), iters <= 16; otherwise
+ *   MRT_ERR_UNSUPPORTED.  These kernels are plain-ALU code, not tuned. */
+size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
+size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
+mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
+                            float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
+                            int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+
 /* Dense baseline  O = softmax(scale * Q K^T + mask) V  (Sec. 2.2), flash-style, no workspace.
  * causal_chunk > 0 masks, per token, keys whose frame's chunk is later than the query frame's
  * chunk (query frames offset by q_frame_offset). */

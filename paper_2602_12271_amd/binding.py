@@ -22,6 +22,7 @@ EXPORTED = [
     "monarch_attn_check", "monarch_attn_workspace_min_bytes", "monarch_attn_workspace_bytes",
     "monarch_attn_fwd", "dense_attn_check", "dense_attn_fwd", "mrt_status_string", "mrt_last_error",
     "mrt_profile_enable", "mrt_profile_read", "mrt_set_head_groups",
+    "monarch_attn_bwd", "monarch_attn_bwd_workspace_bytes", "monarch_attn_bwd_workspace_min_bytes",
 ]
 ASSIGNMENTS = {"fh_w": 0, "w_fh": 1, "fw_h": 2, "h_fw": 3, "f_hw": 4, "hw_f": 5}
 KERNEL_STAGE_R, KERNEL_STAGE_L, KERNEL_DENSE, KERNEL_FIRST, KERNEL_LAST = 1, 2, 4, 16, 32
@@ -70,6 +71,13 @@ def load_library() -> ctypes.CDLL:
     lib.monarch_attn_workspace_bytes.restype = sz
     lib.monarch_attn_fwd.argtypes = [vp, vp, vp, vp, P, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.monarch_attn_fwd.restype = ci
+    fp = ctypes.c_void_p
+    lib.monarch_attn_bwd_workspace_min_bytes.argtypes = [P, ci, ci, ci, ci]
+    lib.monarch_attn_bwd_workspace_min_bytes.restype = sz
+    lib.monarch_attn_bwd_workspace_bytes.argtypes = [P, ci, ci, ci, ci]
+    lib.monarch_attn_bwd_workspace_bytes.restype = sz
+    lib.monarch_attn_bwd.argtypes = [vp, vp, vp, vp, fp, fp, fp, P, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.monarch_attn_bwd.restype = ci
     lib.dense_attn_check.argtypes = [P, ci]
     lib.dense_attn_check.restype = ci
     lib.dense_attn_fwd.argtypes = [vp, vp, vp, vp, P, ci, vp]
@@ -183,6 +191,32 @@ def monarch_attn_fwd(Q, K, V, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_ch
     if st != MRT_OK:
         _raise(lib, st)
     return O
+
+
+def monarch_attn_bwd(Q, K, V, dO, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,
+                     q_frame_offset=0, scale=1.0, workspace=None, stream=None, assign="fh_w"):
+    """Gradients (dQ, dK, dV), fp32, of sum(O * dO) for the forward call with the same arguments."""
+    import torch
+    lib = load_library()
+    assert dO.shape == Q.shape and dO.dtype == Q.dtype and dO.is_cuda
+    prob = _torch_problem(Q, K, V, dO, f_q, f_kv, h, w, q_frame_offset, scale, MRT_COMPUTE_DEFAULT, assign)
+    if workspace is None:
+        nbytes = lib.monarch_attn_bwd_workspace_bytes(ctypes.byref(prob), b1, b2, tile, iters)
+        if nbytes == 0:
+            st = lib.monarch_attn_check(ctypes.byref(prob), b1, b2, tile, iters, causal_chunk)
+            _raise(lib, st if st != MRT_OK else MRT_ERR_UNSUPPORTED)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
+    dQ = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
+    dK = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
+    dV = torch.empty(V.shape, dtype=torch.float32, device=Q.device)
+    s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+    st = lib.monarch_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(),
+                              dK.data_ptr(), dV.data_ptr(), ctypes.byref(prob), b1, b2, tile, iters,
+                              causal_chunk, workspace.data_ptr(),
+                              workspace.numel() * workspace.element_size(), s)
+    if st != MRT_OK:
+        _raise(lib, st)
+    return dQ, dK, dV
 
 
 def dense_attn_fwd(Q, K, V, *, f_q, f_kv, h, w, causal_chunk=0, q_frame_offset=0, scale=1.0,

@@ -403,6 +403,134 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
   return status;
 }
 
+// ---- backward pass -------------------------------------------------------------------------
+// fp32 workspace of one (batch, head): alpha_L and c_L of every iteration, abar of iterations
+// 2..T, Y, and the gradient buffers d alpha_L, d c_L, d Y, d abar.
+namespace {
+struct BwdLayout {
+  size_t rowsD, rowsS;    // bytes of one [m][j][nk][d] / [m][j][nk] array of one head
+  size_t per_head;
+  int T;
+  size_t off_aL(int t) const { return rowsD * (size_t)(t - 1); }                 // t = 1..T
+  size_t off_aR(int t) const { return rowsD * (size_t)(T + t - 2); }             // t = 2..T
+  size_t off_Y() const { return rowsD * (size_t)(2 * T - 1); }
+  size_t off_daL() const { return rowsD * (size_t)(2 * T); }
+  size_t off_dY() const { return rowsD * (size_t)(2 * T + 1); }
+  size_t off_dA() const { return rowsD * (size_t)(2 * T + 2); }
+  size_t off_cL(int t) const { return rowsD * (size_t)(2 * T + 3) + rowsS * (size_t)(t - 1); }
+  size_t off_dcL() const { return rowsD * (size_t)(2 * T + 3) + rowsS * (size_t)T; }
+};
+BwdLayout bwd_layout(const mrt::Plan& pl) {
+  BwdLayout L;
+  const size_t rows = (size_t)pl.kp.c2 * pl.kp.b1 * pl.kp.b2 * pl.kp.ntk * pl.c1q;   // (m, j, nk) triples
+  L.rowsD = mrt::round256(rows * pl.kp.d * sizeof(float));
+  L.rowsS = mrt::round256(rows * sizeof(float));
+  L.T = pl.T;
+  L.per_head = L.rowsD * (size_t)(2 * pl.T + 3) + L.rowsS * (size_t)(pl.T + 1);
+  return L;
+}
+mrt_status bwd_plan(const mrt_problem* p, int b1, int b2, int tile, int iters, int causal_chunk,
+                    mrt::Plan* pl) {
+  mrt_status st = mrt::make_plan(p, b1, b2, tile, iters, causal_chunk, pl);
+  if (st != MRT_OK) return st;
+  if (!mrt::bwd_fits(b1, b2, p->head_dim)) {
+    mrt::set_error("backward pass: blocks (%d,%d) at head_dim %d exceed this build's on-chip buffers", b1, b2,
+                   p->head_dim);
+    return MRT_ERR_UNSUPPORTED;
+  }
+  if (iters > 16) { mrt::set_error("backward pass supports at most 16 iterations"); return MRT_ERR_UNSUPPORTED; }
+  return MRT_OK;
+}
+}  // namespace
+
+size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
+  mrt::Plan pl;
+  if (bwd_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
+  return bwd_layout(pl).per_head;
+}
+
+size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
+  mrt::Plan pl;
+  if (bwd_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
+  const size_t per = bwd_layout(pl).per_head, budget = size_t(16) << 30;
+  size_t heads = (size_t)pl.B * pl.kp.H;
+  if (per * heads > budget) heads = budget / per > 0 ? budget / per : 1;
+  return per * heads;
+}
+
+mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
+                            float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
+                            int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  using namespace mrt;
+  Plan pl;
+  mrt_status st = bwd_plan(p, b1, b2, tile, iters, causal_chunk, &pl);
+  if (st != MRT_OK) return st;
+  if (!Q || !K || !V || !dO || !dQ || !dK || !dV || !workspace) {
+    set_error("Q, K, V, dO, dQ, dK, dV and workspace must be non-NULL");
+    return MRT_ERR_NULL;
+  }
+  if ((uintptr_t)workspace % 256) { set_error("workspace must be 256-byte aligned"); return MRT_ERR_WORKSPACE; }
+  const BwdLayout L = bwd_layout(pl);
+  if (workspace_bytes < L.per_head) {
+    set_error("workspace has %zu bytes, the backward pass of one (batch,head) needs %zu", workspace_bytes,
+              L.per_head);
+    return MRT_ERR_WORKSPACE;
+  }
+  const int BH = pl.B * pl.kp.H, T = pl.T;
+  const int G = (int)(workspace_bytes / L.per_head < (size_t)BH ? workspace_bytes / L.per_head : (size_t)BH);
+  hipStream_t s = (hipStream_t)hip_stream;
+  char* base = (char*)workspace;
+  // array X of the pass starts at base + off_X * G (every array holds G heads back to back)
+  auto arr = [&](size_t off) { return base + off * (size_t)G; };
+
+  for (int bh0 = 0; bh0 < BH; bh0 += G) {
+    const int nbh = BH - bh0 < G ? BH - bh0 : G;
+    KParams kp = pl.kp;
+    kp.Q = Q; kp.K = K; kp.V = V; kp.O = nullptr;
+    kp.bh0 = bh0; kp.m0 = 0; kp.ntq = pl.ntq_total;
+    kp.Y = arr(L.off_Y());
+    hipError_t e;
+    // forward intermediates of every iteration (the last iteration's stage L is not needed)
+    for (int t = 1; t <= T; ++t) {
+      kp.aL = arr(L.off_aL(t));
+      kp.cL = (float*)arr(L.off_cL(t));
+      kp.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
+      if ((e = launch_f32_stage_r(kp, pl.dtype, nbh, t == 1, t == T, s)) != hipSuccess)
+        return hip_fail(e, "backward: forward stage R launch");
+      if (t < T) {
+        kp.aR = arr(L.off_aR(t + 1));
+        if ((e = launch_f32_stage_l(kp, pl.dtype, nbh, false, s)) != hipSuccess)
+          return hip_fail(e, "backward: forward stage L launch");
+      }
+    }
+    // reverse sweep
+    BwdParams bp;
+    memset(&bp, 0, sizeof(bp));
+    bp.k = kp;
+    bp.dO = dO;
+    bp.daL = (float*)arr(L.off_daL());
+    bp.dcL = (float*)arr(L.off_dcL());
+    bp.dY = (float*)arr(L.off_dY());
+    bp.dA = (float*)arr(L.off_dA());
+    bp.dQ = dQ; bp.dK = dK; bp.dV = dV;
+    for (int t = T; t >= 1; --t) {
+      const bool last = t == T;
+      bp.k.aL = arr(L.off_aL(t));
+      bp.k.cL = (float*)arr(L.off_cL(t));
+      bp.Anext = last ? nullptr : (const float*)arr(L.off_aR(t + 1));
+      bp.accumulate = last ? 0 : 1;
+      if ((e = launch_bwd_stage_l(bp, pl.dtype, nbh, last, s)) != hipSuccess)
+        return hip_fail(e, "backward stage L launch");
+      bp.k.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
+      if ((e = launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s)) != hipSuccess)
+        return hip_fail(e, "backward stage R launch");
+    }
+    if ((e = launch_bwd_q_first(bp, nbh, s)) != hipSuccess) return hip_fail(e, "backward dQ launch");
+  }
+  return MRT_OK;
+}
+
 mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk) {
   mrt_status st = check_common(p);
   if (st != MRT_OK) return st;

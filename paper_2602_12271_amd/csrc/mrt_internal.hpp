@@ -65,6 +65,23 @@ __host__ __device__ inline int visible_key_tile_rows(int a, int c1k, int b1, int
   return rows < c1k ? rows : c1k;
 }
 
+// Arguments of the backward kernels: the forward geometry plus gradient buffers.
+// k.aL / k.cL / k.Y are the saved intermediates of the iteration being differentiated, k.aR its
+// abar (for iterations >= 2).  All gradient buffers are fp32.
+struct BwdParams {
+  KParams k;
+  const void* dO;       // storage dtype, strides k.os
+  const float* Anext;   // abar of iteration t+1   [bh][m][nk][j][d]   (stage L backward, t < T)
+  float* dA;            // d abar: stage L backward (t < T) reads that of t+1, stage R backward writes that of t
+  float* daL;           // [bh][m][j][nk][d]
+  float* dcL;           // [bh][m][j][nk]
+  float* dY;            // [bh][m][j][nk][d]
+  float* dQ;            // [batch*heads][N_q][d]
+  float* dK;            // [batch*heads][N_kv][d]
+  float* dV;
+  int accumulate;       // add to dQ (stage L backward) / dK (stage R backward) instead of overwriting
+};
+
 struct Plan {
   KParams kp;          // everything but the pointers
   int B, T;
@@ -83,6 +100,13 @@ hipError_t launch_f32_stage_r(const KParams& kp, int dtype, int nbh, bool first,
                               hipStream_t s);
 hipError_t launch_f32_stage_l(const KParams& kp, int dtype, int nbh, bool last, hipStream_t s);
 hipError_t launch_f32_dense(const KParams& kp, int dtype, int nbh, hipStream_t s);
+
+// backward pass, fp32 (mrt_bwd_f32.hip)
+bool bwd_fits(int b1, int b2, int d);
+hipError_t launch_bwd_stage_l(const BwdParams& bp, int dtype, int nbh, bool last, hipStream_t s);
+hipError_t launch_bwd_stage_r(const BwdParams& bp, int dtype, int nbh, bool first, bool last,
+                              hipStream_t s);
+hipError_t launch_bwd_q_first(const BwdParams& bp, int nbh, hipStream_t s);
 
 // bf16 MFMA path (mrt_bf16.hip)
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s);

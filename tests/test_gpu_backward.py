@@ -1,0 +1,105 @@
+"""GPU parity of the backward pass (gradients w.r.t. Q, K, V through every refinement iteration,
+Sec. 4.3) against the fp64 oracle's gradients, through the C ABI.  The kernels compute in fp32
+whatever the storage type, so the bar is the fp32 one, scaled by the size of the gradients."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_12271_amd as pkg
+from oracle import monarch_oracle as mo
+from workloads import synthetic as syn
+
+from gpu_harness import to_device
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def small(dtype="f32", **kw):
+    d = kw.pop("head_dim", 64)
+    base = dict(name="small", batch=1, heads=2, head_dim=d, dtype=dtype, rope=False, scale=d ** -0.5,
+                sigma_qk=1.0, sigma_v=1.0, causal_chunk=0, q_frame_offset=0, iters=2)
+    base.update(kw)
+    return syn.Workload(**base)
+
+
+CASES = {
+    "regular-T1": small(f_q=2, f_kv=2, h=5, w=13, b1=10, b2=13, tile=0, iters=1, head_dim=40),
+    "regular-T2": small(batch=2, f_q=2, f_kv=2, h=5, w=13, b1=10, b2=13, tile=0, iters=2, head_dim=40),
+    "regular-T3": small(f_q=2, f_kv=2, h=6, w=12, b1=12, b2=12, tile=0, iters=3),
+    "tiled-rect-mask": small(f_q=2, f_kv=6, h=5, w=14, b1=10, b2=7, tile=1, iters=2, causal_chunk=2,
+                             q_frame_offset=2),
+    "tiled-rect-mask-T1": small(f_q=2, f_kv=6, h=5, w=14, b1=10, b2=7, tile=1, iters=1, causal_chunk=2,
+                                q_frame_offset=2),
+    "tiled-half-frames-T3": small(f_q=2, f_kv=4, h=6, w=8, b1=3, b2=4, tile=1, iters=3, causal_chunk=2,
+                                  q_frame_offset=2),
+    "fw_h-T2": small(f_q=2, f_kv=2, h=5, w=6, b1=12, b2=5, tile=0, iters=2, assign="fw_h"),
+    "h_fw-tiled": small(f_q=2, f_kv=2, h=6, w=6, b1=3, b2=4, tile=1, iters=2, assign="h_fw"),
+    "bf16-storage": small("bf16", head_dim=128, f_q=2, f_kv=4, h=8, w=24, b1=16, b2=12, tile=1, iters=2),
+    "bf16-ragged-T1": small("bf16", head_dim=128, f_q=2, f_kv=2, h=11, w=21, b1=22, b2=21, tile=0, iters=1),
+}
+
+
+def run_case(wl, heads=None):
+    arrays = syn.make_inputs(wl)
+    rng = np.random.default_rng(1234)
+    dO = rng.standard_normal(arrays[0].shape).astype(np.float32)
+    if wl.dtype == "bf16":
+        dO = syn.round_to_bf16(dO)
+    Qd, Kd, Vd, dOd = to_device(wl, arrays + (dO,))
+    kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
+              iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+              scale=wl.scale, assign=wl.assign)
+    dQ, dK, dV = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, **kw)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for b in range(wl.batch):
+        for hd in (range(wl.heads) if heads is None else heads):
+            ref = mo.monarch_attn_grad(*(torch.from_numpy(x[b, hd]) for x in arrays),
+                                       torch.from_numpy(dO[b, hd]), **kw)
+            for name, got, want in zip("QKV", (dQ, dK, dV), ref):
+                g = got[b, hd].double().cpu()
+                assert torch.isfinite(g).all(), f"non-finite d{name}"
+                err = (g - want).abs().max().item()
+                bar = TOL * max(1.0, want.abs().max().item())
+                print(f"  head {hd} d{name}: max err {err:.3e} (max |grad| {want.abs().max().item():.3e})",
+                      flush=True)
+                assert err <= bar, (name, err, bar)
+                worst = max(worst, err)
+    return worst
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_backward_matches_oracle(name):
+    print(f"case {name}: {CASES[name]}", flush=True)
+    run_case(CASES[name])
+
+
+def test_backward_on_the_4680_token_chunk():
+    # the headline shape (12 heads, d = 128, regular (90, 52), T = 2), two heads through the oracle
+    wl = syn.variant("C1")
+    run_case(wl, heads=[0, 11])
+
+
+def test_backward_minimum_workspace_gives_same_result():
+    wl = CASES["tiled-rect-mask"]
+    arrays = syn.make_inputs(wl)
+    dO = np.ones_like(arrays[0])
+    Qd, Kd, Vd, dOd = to_device(wl, arrays + (dO,))
+    kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
+              iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+              scale=wl.scale)
+    prob = pkg.make_problem(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, f_q=wl.f_q,
+                            f_kv=wl.f_kv, h=wl.h, w=wl.w, dtype=pkg.MRT_F32, scale=wl.scale,
+                            q_frame_offset=wl.q_frame_offset)
+    lib = pkg.load_library()
+    import ctypes
+    nmin = lib.monarch_attn_bwd_workspace_min_bytes(ctypes.byref(prob), wl.b1, wl.b2, wl.tile, wl.iters)
+    assert 0 < nmin < lib.monarch_attn_bwd_workspace_bytes(ctypes.byref(prob), wl.b1, wl.b2, wl.tile, wl.iters)
+    ws = torch.empty(nmin, dtype=torch.uint8, device="cuda:0")
+    g1 = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, workspace=ws, **kw)
+    g2 = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, **kw)
+    torch.cuda.synchronize()
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
