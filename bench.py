@@ -91,12 +91,96 @@ def kernel_models(wl, es):
     return out
 
 
+def backward_flops(wl):
+    """2 x MACs of the products the backward pass has to form once (recomputation of logits in
+    extra passes not counted): the forward intermediates (T stage R, T-1 stage L), and per
+    iteration 5 products of b1 x NK x d on the L side and 5 (7 at t = T) of b2 x b2 x d on the R
+    side, per visible tile pair."""
+    H = wl.batch * wl.heads
+    P = visible_pairs(wl)
+    nt, d, T = wl.b1 * wl.b2, wl.head_dim, wl.iters
+    r_prod, l_prod = nt * wl.b2 * d, nt * wl.b1 * d          # MACs of one product per tile pair
+    fwd = T * 2 * r_prod + r_prod + (T - 1) * 2 * l_prod
+    bwd = T * 5 * l_prod + T * 5 * r_prod + 2 * r_prod
+    return 2 * H * P * (fwd + bwd)
+
+
+def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
+    Qh, Kh, Vh = host
+    Q, K, V = dev
+    rng = np.random.default_rng(1234)
+    dOh = rng.standard_normal(Qh.shape).astype(np.float32)
+    if wl.dtype == "bf16":
+        dOh = syn.round_to_bf16(dOh)
+    dO = torch.from_numpy(dOh).to(Q.device).to(Q.dtype)
+    pref = ctypes.byref(prob)
+    nws = lib.monarch_attn_bwd_workspace_bytes(pref, wl.b1, wl.b2, wl.tile, wl.iters)
+    if nws == 0:
+        raise RuntimeError(f"backward pass not available for {wl.name}: {pkg.last_error()}")
+    ws = torch.empty(nws, dtype=torch.uint8, device=Q.device)
+    dQ = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
+    dK = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
+    dV = torch.empty(V.shape, dtype=torch.float32, device=Q.device)
+
+    def step():
+        st = lib.monarch_attn_bwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(),
+                                  dK.data_ptr(), dV.data_ptr(), pref, wl.b1, wl.b2, wl.tile, wl.iters,
+                                  wl.causal_chunk, ws.data_ptr(), nws, stream)
+        if st != 0:
+            raise RuntimeError(f"monarch_attn_bwd failed: {pkg.last_error()}")
+
+    steps, warmup = min(args.steps, 20), min(args.warmup, 3)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flops = backward_flops(wl)
+    ach = flops / (ms / 1e3) / 1e12
+    cpu = parity = None
+    if not args.no_cpu_baseline:
+        from oracle import monarch_oracle as mo
+        kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
+                  iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+                  scale=wl.scale, assign=wl.assign)
+        t0 = time.perf_counter()
+        heads_run = 0
+        while heads_run < wl.heads and time.perf_counter() - t0 < 15.0:
+            ref = mo.monarch_attn_grad(*(torch.from_numpy(x[0, heads_run]) for x in (Qh, Kh, Vh)),
+                                       torch.from_numpy(dOh[0, heads_run]), **kw)
+            if heads_run == 0:
+                parity = max((g[0, 0].double().cpu() - r).abs().max().item() for g, r in zip((dQ, dK, dV), ref))
+            heads_run += 1
+        dt = time.perf_counter() - t0
+        cpu = dict(value=dt / heads_run * wl.batch * wl.heads * 1e3, unit="ms/call",
+                   cores=torch.get_num_threads(), kind="oracle",
+                   sample=f"{heads_run} of {wl.heads} heads of {wl.name} (reverse-mode gradients of the fp64 "
+                          f"oracle) in {dt:.1f} s, scaled to all heads")
+    print(json.dumps({
+        "metric": "monarch_attn_bwd_ms", "value": ms, "unit": "ms/call", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name} backward: {wl.heads} heads x d{wl.head_dim}, N_q={wl.n_q}, "
+                               f"N_kv={wl.n_kv}, blocks ({wl.b1},{wl.b2}), T={wl.iters}",
+                   "workspace_mb": nws / 1e6},
+        "roofline": {"bound": "alu", "achieved": ach, "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3,
+                     "traffic": None, "algorithmic_gflop": flops / 1e9,
+                     "note": "plain fp32 ALU kernels (not MFMA), whole call: forward recomputation + reverse sweep"},
+        "cpu_baseline": cpu, "parity_max_abs_err_head0": parity,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C1")
+    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd"],
+                    help="fwd: the forward operator (the headline metric); bwd: the fp32 backward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--head-groups", type=int, default=0,
@@ -137,6 +221,9 @@ def main():
     stream = torch.cuda.current_stream(dev).cuda_stream
     pq, pk, pv, po, pw = Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), ws.data_ptr()
     pref = ctypes.byref(prob)
+
+    if args.op == "bwd":
+        return bench_backward(args, wl, lib, pkg, syn, torch, np, (Qh, Kh, Vh), (Q, K, V), prob, stream)
 
     def step():
         st = lib.monarch_attn_fwd(pq, pk, pv, po, pref, wl.b1, wl.b2, wl.tile, wl.iters,
