@@ -157,3 +157,27 @@ def test_status_strings():
     lib = pkg.load_library()
     seen = {lib.mrt_status_string(i).decode() for i in range(7)}
     assert len(seen) == 7 and "ok" in seen
+
+
+def test_backward_entry_checks_on_the_host():
+    lib = pkg.load_library()
+    p = problem()
+    ref = ctypes.byref(p)
+    # one head: alpha_L and c_L of T iterations, abar of T-1, Y, and four gradient buffers, all fp32
+    n, d, T = 4680, 128, 2
+    per_head = lib.monarch_attn_bwd_workspace_min_bytes(ref, 90, 52, 0, T)
+    want = (2 * T + 3) * n * d * 4 + (T + 1) * n * 4
+    assert want <= per_head <= want + 12 * 256
+    assert lib.monarch_attn_bwd_workspace_bytes(ref, 90, 52, 0, T) == 12 * per_head
+    # block sizes whose buffers do not fit on chip, and invalid blocks, give 0
+    big = problem(heads=40, f_kv=21, h=45, w=80, q_frame_offset=18)
+    assert lib.monarch_attn_bwd_workspace_bytes(ctypes.byref(big), 135, 40, 1, 3) == 0
+    assert "backward" in pkg.last_error()
+    assert lib.monarch_attn_bwd_workspace_bytes(ref, 90, 50, 0, T) == 0
+    fake = ctypes.c_void_p(4096)
+    args = (ref, 90, 52, 0, T, 0)
+    assert lib.monarch_attn_bwd(None, fake, fake, fake, fake, fake, fake, *args, fake, 1 << 40, None) == B.MRT_ERR_NULL
+    assert lib.monarch_attn_bwd(fake, fake, fake, fake, fake, fake, None, *args, fake, 1 << 40, None) == B.MRT_ERR_NULL
+    assert lib.monarch_attn_bwd(fake, fake, fake, fake, fake, fake, fake, *args, fake, 1024, None) == B.MRT_ERR_WORKSPACE
+    assert lib.monarch_attn_bwd(fake, fake, fake, fake, fake, fake, fake, ctypes.byref(big), 135, 40, 1, 3, 3,
+                                fake, 1 << 40, None) == B.MRT_ERR_UNSUPPORTED
