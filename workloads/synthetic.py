@@ -219,3 +219,33 @@ def make_separable_head(wl: Workload, b: int, hd: int):
     if wl.dtype == "bf16":
         Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
     return Q, K, V
+
+
+def make_structured_head(wl: Workload, b: int, hd: int, n_semantic: int = 8, strength: float = 4.0,
+                         noise: float = 0.25):
+    """Inputs whose attention map follows the paper's informal model (Sec. 3.1): a separable
+    positional part (one content vector under the 3-D rotary encoding), a sparse semantic part
+    (n_semantic keys that a random 2 % of the queries match whatever their position: a shared
+    direction added to those rows after the rotation) and noise (independent N(0, noise^2)
+    content added to every row).  V ~ N(0,1).  Values are rounded to the storage type."""
+    rng = np.random.default_rng((wl.seed, 11, b, hd))
+    d = wl.head_dim
+    q0 = rng.standard_normal(d).astype(np.float32)
+    k0 = rng.standard_normal(d).astype(np.float32)
+    Q = np.broadcast_to(q0, (wl.n_q, d)).copy()
+    K = np.broadcast_to(k0, (wl.n_kv, d)).copy()
+    Q = apply_rope(Q, rope_angles(wl.q_frame_offset + np.arange(wl.f_q), wl.h, wl.w, d))
+    K = apply_rope(K, rope_angles(np.arange(wl.f_kv), wl.h, wl.w, d))
+    for _ in range(n_semantic):
+        u = rng.standard_normal(d).astype(np.float32)
+        u *= strength / np.linalg.norm(u)
+        key = int(rng.integers(wl.n_kv))
+        queries = rng.choice(wl.n_q, size=max(1, wl.n_q // 50), replace=False)
+        K[key] += u
+        Q[queries] += u
+    Q += noise * rng.standard_normal(Q.shape).astype(np.float32)
+    K += noise * rng.standard_normal(K.shape).astype(np.float32)
+    V = rng.standard_normal((wl.n_kv, d)).astype(np.float32)
+    if wl.dtype == "bf16":
+        Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
+    return Q, K, V
