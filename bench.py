@@ -50,13 +50,16 @@ def visible_pairs(wl):
     rows_q, rows_k, cols = wl.block_grid()
     c2 = cols // wl.b2
     c1q, c1k = rows_q // wl.b1, rows_k // wl.b1
-    rpf = rows_q // wl.f_q                     # block-grid rows per frame (mask: frame axis slowest)
+    if wl.tile_h:
+        # neighbourhood tiles: tile rows per chunk = (chunk frames / n_f) * (h / n_h)
+        n_f, bands = wl.b1 // wl.tile_h, wl.h // wl.tile_h
+        ct, qt0 = (wl.causal_chunk // n_f) * bands, (wl.q_frame_offset // n_f) * bands
+    else:
+        rpf = rows_q // wl.f_q                 # block-grid rows per frame (mask: frame axis slowest)
+        ct, qt0 = wl.causal_chunk * rpf // wl.b1, wl.q_frame_offset * rpf // wl.b1
     total = 0
     for a in range(c1q):
-        rows = c1k
-        if wl.causal_chunk:
-            q_chunk = (wl.q_frame_offset * rpf + a * wl.b1) // (wl.causal_chunk * rpf)
-            rows = min(c1k, (q_chunk + 1) * wl.causal_chunk * rpf // wl.b1)
+        rows = min(c1k, ((qt0 + a) // ct + 1) * ct) if wl.causal_chunk else c1k
         total += c2 * rows * c2
     return total
 
@@ -145,7 +148,7 @@ def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
         from oracle import monarch_oracle as mo
         kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
                   iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
-                  scale=wl.scale, assign=wl.assign)
+                  scale=wl.scale, assign=wl.assign, tile_h=wl.tile_h)
         t0 = time.perf_counter()
         heads_run = 0
         while heads_run < wl.heads and time.perf_counter() - t0 < 15.0:
@@ -215,7 +218,7 @@ def main():
     Q, K, V = (torch.from_numpy(x).to(dev).to(tdt) for x in (Qh, Kh, Vh))
     O = torch.empty_like(Q)
     prob = binding._torch_problem(Q, K, V, O, wl.f_q, wl.f_kv, wl.h, wl.w, wl.q_frame_offset,
-                                  wl.scale, pkg.MRT_COMPUTE_DEFAULT, wl.assign)
+                                  wl.scale, pkg.MRT_COMPUTE_DEFAULT, wl.assign, wl.tile_h)
     nws = pkg.monarch_attn_workspace_bytes(prob, wl.b1, wl.b2, wl.tile, wl.iters)
     ws = torch.empty(nws, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
@@ -323,7 +326,7 @@ def main():
                                    torch.from_numpy(Vh[0, hd]), f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h,
                                    w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile, iters=wl.iters,
                                    causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
-                                   scale=wl.scale, assign=wl.assign)
+                                   scale=wl.scale, assign=wl.assign, tile_h=wl.tile_h)
         ref0 = oracle_head(0)                       # also warms the CPU libraries up
         parity = (O[0, 0].float().cpu().double() - ref0).abs().max().item()
         heads_run, t_acc, budget = 0, 0.0, 15.0

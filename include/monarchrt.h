@@ -79,6 +79,9 @@ typedef struct {
   float scale;         /* multiplies both logit contractions (beta_R and beta_L);
                           1.0 is the paper's softmax(Q K^T) (Sec. 2.2)                      */
   mrt_assignment assignment; /* which axes index the b1 and the b2 side; 0 = (fh, w)        */
+  int tile_h;          /* 0: a tile is b1 consecutive block-grid rows.  n_h > 0 (tiled calls with
+                          the (fh, w) assignment only): a tile is the neighbourhood of Sec. 4.2,
+                          n_h grid rows of each of n_f = b1 / n_h consecutive frames          */
 } mrt_problem;
 
 /* Checks a MonarchRT call without touching the GPU (same rules monarch_attn_fwd applies).
@@ -95,8 +98,12 @@ typedef struct {
  *             tile pairs take no part at all.  Needs tile = 1, an assignment whose slowest row
  *             axis is the frame (FH_W, FW_H, F_HW), and tiles that do not straddle a chunk:
  *             b1 divides (rows per frame)*causal_chunk and (rows per frame)*q_frame_offset.
- *   Limits of this build: b1 <= 192, b2 <= 96 (else MRT_ERR_UNSUPPORTED); tiles that are
- *   n_f > 1 frames by n_h < h rows (not a contiguous row range) are not built. */
+ *   p->tile_h = n_h > 0 selects neighbourhood tiles (n_f, n_h, n_w) = (b1 / n_h, n_h, b2) of
+ *             Sec. 4.2: needs tile = 1, assignment (fh, w), n_h | h, n_h | b1, n_f | f_q, n_f | f_kv,
+ *             b2 | w, and for a mask n_f | causal_chunk and n_f | q_frame_offset.  Tile rows are
+ *             ordered (frame group, row band); with n_h = h or n_f = 1 this is the same tiling as
+ *             tile_h = 0.
+ *   Limits of this build: b1 <= 192, b2 <= 96 (else MRT_ERR_UNSUPPORTED). */
 mrt_status monarch_attn_check(const mrt_problem* p, int b1, int b2, int tile, int iters,
                               int causal_chunk);
 

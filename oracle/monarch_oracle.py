@@ -32,6 +32,10 @@ design document as well):
   * tiles are the contiguous row / column ranges of Alg. 2's rearrange, so any
     b1 dividing the row count is a tiling (also a fraction of a frame: the
     neighbourhood tiles of Sec. 4.2 with n_f = 1).
+  * Sec. 4.2's neighbourhood tiles (n_f frames x n_h rows x n_w columns) with
+    n_f > 1 and n_h < h are not a contiguous row range of the stored order; they
+    are the same algorithm on tokens re-ordered so that each neighbourhood's rows
+    are consecutive (neighbourhood_order), the mask taken per frame group.
   * the six aligned block assignments of Sec. 4.1 are the same algorithm on
     tokens re-ordered so that the axes given to b1 become the row index and the
     axes given to b2 the column index (block_assignment_order).
@@ -106,20 +110,27 @@ def from_tiles(Z: torch.Tensor, c1: int, b1: int, c2: int, b2: int) -> torch.Ten
 
 
 def chunk_causal_visibility(geom: TileGeometry, h: int, causal_chunk: int,
-                            q_frame_offset: int) -> torch.Tensor:
+                            q_frame_offset: int, tile_h: int = 0) -> torch.Tensor:
     """visible[m, n] for the tile-level chunk-causal reading (see module header).
 
     h = grid rows per frame.  Query tile row a covers grid rows a*b1 ... of
     frames starting at q_frame_offset; key tile row a' covers rows a'*b1 ... of
-    frames starting at 0.  causal_chunk == 0 means no mask.
+    frames starting at 0.  With neighbourhood tiles (tile_h = n_h > 0, rows
+    ordered by neighbourhood_order) tile row a covers the n_f = b1 / n_h frames
+    of frame group a // (h / n_h).  causal_chunk == 0 means no mask.
     """
     vis = torch.ones(geom.ntq, geom.ntk, dtype=torch.bool)
     if causal_chunk == 0:
         return vis
 
     def chunk_of_tile_row(a: int, first_frame: int) -> int:
-        lo = (first_frame + (a * geom.b1) // h) // causal_chunk
-        hi = (first_frame + (a * geom.b1 + geom.b1 - 1) // h) // causal_chunk
+        if tile_h > 0:
+            n_f = geom.b1 // tile_h
+            f0 = (a // (h // tile_h)) * n_f
+            f1 = f0 + n_f - 1
+        else:
+            f0, f1 = (a * geom.b1) // h, (a * geom.b1 + geom.b1 - 1) // h
+        lo, hi = (first_frame + f0) // causal_chunk, (first_frame + f1) // causal_chunk
         assert lo == hi, "a tile straddles a causal chunk"
         return lo
 
@@ -333,12 +344,34 @@ def block_assignment_order(assign: str, f: int, h: int, w: int):
     return order, rows, cols, rpf
 
 
+def neighbourhood_order(f: int, h: int, w: int, n_f: int, n_h: int) -> torch.Tensor:
+    """Stored tokens re-ordered so that every spatiotemporal neighbourhood of n_f frames by n_h
+    grid rows (Sec. 4.2's example: tiles of n_f * n_h rows by n_w columns) is a run of
+    n_f * n_h consecutive rows of w tokens: neighbourhoods ordered by (frame group, row band),
+    rows inside one by (frame, row)."""
+    assert f % n_f == 0 and h % n_h == 0
+    g = torch.arange(f * h * w).reshape(f // n_f, n_f, h // n_h, n_h, w)   # fa u ha v x
+    return g.permute(0, 2, 1, 3, 4).reshape(f * h * w)                      # fa ha u v x
+
+
 def monarch_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, b1: int, b2: int,
                  tile: int, iters: int, causal_chunk: int = 0, q_frame_offset: int = 0,
-                 scale: float = 1.0, assign: str = "fh_w") -> torch.Tensor:
+                 scale: float = 1.0, assign: str = "fh_w", tile_h: int = 0) -> torch.Tensor:
     """One head of the operator the library exports: regular (tile=0, Alg. 1) or
     tiled (tile=1, Alg. 2) MonarchAttention on (f,h,w) grids, for any of the six
-    aligned block assignments (Sec. 4.1)."""
+    aligned block assignments (Sec. 4.1); tile_h = n_h > 0 tiles the (fh, w) grid into
+    neighbourhoods of (b1 / n_h) frames x n_h rows x b2 columns (Sec. 4.2)."""
+    if tile_h > 0:
+        assert tile == 1 and assign == "fh_w" and b1 % tile_h == 0 and h % tile_h == 0
+        n_f = b1 // tile_h
+        oq = neighbourhood_order(f_q, h, w, n_f, tile_h)
+        ok = neighbourhood_order(f_kv, h, w, n_f, tile_h)
+        g = geometry_from_grid(f_q, f_kv, h, w, b1, b2, 1)
+        vis = chunk_causal_visibility(g, h, causal_chunk, q_frame_offset, tile_h)
+        out = monarch_attention_tiled(Q[oq], K[ok], V[ok], iters, g, scale, vis)
+        O = torch.empty_like(out)
+        O[oq] = out
+        return O
     if assign != "fh_w":
         oq, rows_q, cols_q, rpf = block_assignment_order(assign, f_q, h, w)
         ok, rows_k, cols_k, _ = block_assignment_order(assign, f_kv, h, w)

@@ -64,6 +64,7 @@ static mrt_status check_common(const mrt_problem* p) {
     return MRT_ERR_SHAPE;
   }
   if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) { set_error("scale must be positive and finite"); return MRT_ERR_SHAPE; }
+  if (p->tile_h < 0) { set_error("tile_h < 0"); return MRT_ERR_SHAPE; }
   return MRT_OK;
 }
 
@@ -126,11 +127,35 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
       return MRT_ERR_UNSUPPORTED;
     }
     if (causal_chunk != 0) { set_error("regular Monarch with a causal mask is not built"); return MRT_ERR_UNSUPPORTED; }
+    if (p->tile_h != 0) { set_error("tile_h needs tile = 1"); return MRT_ERR_SHAPE; }
     if (b1 != rows_q || b2 != cols) {
       set_error("regular Monarch with assignment %s needs (b1,b2) = (%d,%d), got (%d,%d)", aname, rows_q, cols, b1, b2);
       return MRT_ERR_BLOCK;
     }
     k.c2 = 1; k.ntq = 1; k.ntk = 1; k.c1k = 1; pl.c1q = 1;
+  } else if (p->tile_h > 0) {
+    // neighbourhood tiles (n_f, n_h, n_w) = (b1 / n_h, n_h, b2) of Sec. 4.2
+    const int nh = p->tile_h;
+    if (p->assignment != MRT_ASSIGN_FH_W) {
+      set_error("neighbourhood tiles (tile_h > 0) need the (fh,w) assignment");
+      return MRT_ERR_UNSUPPORTED;
+    }
+    if (h % nh || b1 % nh || w % b2) {
+      set_error("neighbourhood tiles: tile_h = %d must divide h = %d and b1 = %d, and b2 = %d must divide w = %d",
+                nh, h, b1, b2, w);
+      return MRT_ERR_BLOCK;
+    }
+    const int nf = b1 / nh;
+    if (f_q % nf || f_kv % nf) {
+      set_error("neighbourhood tiles of %d frames do not divide the grids (%d | %d frames)", nf, f_q, f_kv);
+      return MRT_ERR_BLOCK;
+    }
+    k.nh = nh; k.nhb = h / nh; k.tf_tok = nf * hw; k.th_tok = nh * w;
+    k.c2 = w / b2;
+    k.c1k = (f_kv / nf) * k.nhb;
+    pl.c1q = (f_q / nf) * k.nhb;
+    k.ntq = pl.c1q * k.c2;
+    k.ntk = k.c1k * k.c2;
   } else {
     if (rows_q % b1 || rows_k % b1 || cols % b2) {
       set_error("tile blocks (%d,%d) do not divide the %s grids (%d|%d rows, %d cols)", b1, b2, aname,
@@ -148,14 +173,28 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
       set_error("a causal mask needs an assignment whose slowest b1 axis is the frame, not %s", aname);
       return MRT_ERR_UNSUPPORTED;
     }
-    const long long cr = (long long)causal_chunk * rpf, q0 = (long long)p->q_frame_offset * rpf;
-    if (cr % b1 || q0 % b1) {
-      set_error("a tile (%d rows, %d rows per frame) must not straddle a causal chunk (%d frames, offset %d)",
-                b1, rpf, causal_chunk, p->q_frame_offset);
-      return MRT_ERR_BLOCK;
+    long long ct, qt0;
+    if (k.nh > 0) {
+      const int nf = b1 / k.nh;
+      if (causal_chunk % nf || p->q_frame_offset % nf) {
+        set_error("a tile (%d frames) must not straddle a causal chunk (%d frames, offset %d)", nf,
+                  causal_chunk, p->q_frame_offset);
+        return MRT_ERR_BLOCK;
+      }
+      ct = (long long)(causal_chunk / nf) * k.nhb;
+      qt0 = (long long)(p->q_frame_offset / nf) * k.nhb;
+    } else {
+      const long long cr = (long long)causal_chunk * rpf, q0 = (long long)p->q_frame_offset * rpf;
+      if (cr % b1 || q0 % b1) {
+        set_error("a tile (%d rows, %d rows per frame) must not straddle a causal chunk (%d frames, offset %d)",
+                  b1, rpf, causal_chunk, p->q_frame_offset);
+        return MRT_ERR_BLOCK;
+      }
+      ct = cr / b1;
+      qt0 = q0 / b1;
     }
-    if (cr > (1 << 24) || q0 > (1 << 24)) { set_error("causal chunk or frame offset too large"); return MRT_ERR_SHAPE; }
-    k.cr = (int)cr; k.qrow0 = (int)q0; k.cc = causal_chunk; k.qoff = p->q_frame_offset;
+    if (ct > (1 << 24) || qt0 > (1 << 24)) { set_error("causal chunk or frame offset too large"); return MRT_ERR_SHAPE; }
+    k.ct = (int)ct; k.qt0 = (int)qt0; k.cc = causal_chunk; k.qoff = p->q_frame_offset;
   }
   k.qs = p->q; k.ks = p->k; k.vs = p->v; k.os = p->o;
   k.H = p->heads; k.d = p->head_dim; k.b1 = b1; k.b2 = b2;

@@ -162,11 +162,19 @@ __device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) 
 // Element offset of row r of a tile of a token-indexed tensor (Q, K, V, O): the tile's rows are
 // the block-grid indices x0 + r along one side of the block grid.
 struct TokRows {
+  long long base;      // tokens
   AxisMap m;
   int x0;
   long long tstride;   // elements per token
-  __device__ inline long long operator()(int r) const { return axis_offset(m, x0 + r) * tstride; }
+  __device__ inline long long operator()(int r) const { return (base + axis_offset(m, x0 + r)) * tstride; }
 };
+// Rows of tile row a: contiguous block-grid rows, or nh rows of each of the tile's frames.
+__device__ inline TokRows tile_rows(const KParams& p, int a, long long tstride) {
+  if (p.nh == 0) return TokRows{0, p.rmap, a * p.b1, tstride};
+  const int fa = a / p.nhb, ha = a - fa * p.nhb;
+  return TokRows{(long long)fa * p.tf_tok + (long long)ha * p.th_tok, AxisMap{p.nh, p.hw, p.rmap.lo}, 0,
+                 tstride};
+}
 // Rows at a fixed stride (the intermediates in the workspace).
 struct PlainRows {
   long long stride;
@@ -250,12 +258,12 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   // sees more key tiles)
   int ml0 = blockIdx.y * gs;
   const int ml1 = ml0 + gs < p.ntq ? ml0 + gs : p.ntq;
-  while (ml0 < ml1 && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.b1, p.cr, p.qrow0)) ++ml0;
+  while (ml0 < ml1 && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.ct, p.qt0)) ++ml0;
   if (ml0 >= ml1) return;
   const int b = bh / p.H, hd = bh - b * p.H;
 
   // key block (n, k): block-grid row an*b1 + k, columns bn*b2 + i
-  const long long krow = axis_offset(p.rmap, an * b1 + k);
+  const long long krow = row_offset(p, an, k);
   const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + krow * p.ks.token;
   const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + krow * p.vs.token;
   const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
@@ -266,8 +274,8 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   // the first LDS store
   RowRegs<D, ROWS, NTHR> rk;
   RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
-  rk.load(Kp, TokRows{p.cmap, bn * b2, p.ks.token}, b2, tid);
-  if (LAST) rv.load(Vp, TokRows{p.cmap, bn * b2, p.vs.token}, b2, tid);
+  rk.load(Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
+  if (LAST) rv.load(Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
 
   // query-side rows of this wave (row j = 16*wave + c) go straight to registers: Q[m, k, j, :] in
   // the first iteration (L is the identity), alpha_R / c_R afterwards
@@ -278,7 +286,7 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
     const u16* arow;
     if (FIRST) {
       const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
-      arow = Qbase + (axis_offset(p.rmap, a * b1 + k) + axis_offset(p.cmap, bq * b2 + jc)) * p.qs.token;
+      arow = Qbase + (row_offset(p, a, k) + axis_offset(p.cmap, bq * b2 + jc)) * p.qs.token;
     } else {
       arow = (const u16*)p.aR + ((((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 + jc) * D;
     }
@@ -642,13 +650,13 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const WaveTiles<QT> wt(wave, nthr >> 6, (b1 + 15) >> 4);
 
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
-  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   bf16x8 qv[QT][KS1];
 #pragma unroll
@@ -848,12 +856,12 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   constexpr int nlt = NLT;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
 
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
-  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   MRT_STAMP(0);
   stage_rows<D>(Qs, Qp, qrow, qrows, b1, tid, nthr);
@@ -981,7 +989,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= 16*NTK
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 16*NTK
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const int nlt = (b1 + 15) >> 4;
@@ -991,7 +999,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   const u16* Yp = (const u16*)p.Y + row0 * D;
   const float* cLp = p.cL + row0;
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
-  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
+  const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
 
@@ -1046,7 +1054,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
       const int l = 16 * (QT * pair + q) + c;
-      if (q < nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
+      if (q < nq && l < b1) store_rows<D>(Op + tile_rows(p, a, p.os.token)(l), o[q], 1.0f / sum[q], g);
     }
   }
   MRT_STAMP(2);
@@ -1065,13 +1073,13 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_res(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= kResRows
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= kResRows
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const int nkt = (NK + 15) >> 4;
 
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
-  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
@@ -1292,7 +1300,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= 16*NTK
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 16*NTK
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const WaveTiles<QT> wt(wave, nwaves, (b1 + 15) >> 4);      // b1 <= 128: at most two tiles a wave
@@ -1302,7 +1310,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   const u16* Yp = (const u16*)p.Y + row0 * D;
   const float* cLp = p.cL + row0;
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);
-  const TokRows qrow{p.rmap, a * b1, p.qs.token}, orow{p.rmap, a * b1, p.os.token};
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
 
@@ -1388,13 +1396,13 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_mid(KParams p) {
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;   // <= kMidRows
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= kMidRows
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
   const WaveTiles<QT> wt(wave, nwaves, NLT);
 
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);
-  const TokRows qrow{p.rmap, a * b1, p.qs.token};
+  const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
   const int d = p.d, b1 = p.b1, b2 = p.b2, ld = d + 1, lz = kCH + 1;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
 
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
   const TIn* Qp = (const TIn*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const TIn* dOp = (const TIn*)bp.dO + b * p.os.batch + hd * p.os.head;
   const long long qcol = axis_offset(p.cmap, bq * b2 + j);
-  auto qtok = [&](int l) { return axis_offset(p.rmap, a * b1 + l) + qcol; };
+  auto qtok = [&](int l) { return row_offset(p, a, l) + qcol; };
   for (int idx = tid; idx < b1 * d; idx += kThreads) {
     const int l = idx / d, v = idx - l * d;
     Qj[l * ld + v] = ldf(Qp + qtok(l) * p.qs.token + v);
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_r(BwdParams bp, int firs
   float* DR = LR + b2 * ls;       // [b2][ls]  dR, then dS
   float* dcl = DR + b2 * ls;      // [b2]
 
-  const long long krow = axis_offset(p.rmap, an * b1 + k);
+  const long long krow = row_offset(p, an, k);
   auto ktok = [&](int i) { return krow + axis_offset(p.cmap, bn * b2 + i); };
   const TIn* Qp = (const TIn*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const TIn* Kp = (const TIn*)p.K + b * p.ks.batch + hd * p.ks.head;
@@ -281,8 +281,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_r(BwdParams bp, int firs
 
   for (int ml = 0; ml < p.ntq; ++ml) {
     const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
-    if (an >= visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0)) continue;   // uniform per workgroup
-    const long long qrow = axis_offset(p.rmap, a * b1 + k);
+    if (an >= visible_key_tile_rows(a, p.c1k, p.ct, p.qt0)) continue;   // uniform per workgroup
+    const long long qrow = row_offset(p, a, k);
     const float* aRp = (const float*)p.aR + (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 * d;
     auto load_A = [&]() {
       load_rows(B1, [&](int jj, int v) {
@@ -407,11 +407,11 @@ __global__ __launch_bounds__(kThreads) void k_bwd_q_first(BwdParams bp) {
   const int d = p.d, b1 = p.b1, b2 = p.b2;
   const int k = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int nvis = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2;
+  const int nvis = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2;
   const size_t NKtot = (size_t)p.ntk * b1;
   const float* dAp = bp.dA + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * d;
   float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
-  const long long qrow = axis_offset(p.rmap, a * b1 + k);
+  const long long qrow = row_offset(p, a, k);
   for (int idx = threadIdx.x; idx < b2 * d; idx += kThreads) {
     const int jj = idx / d, v = idx - jj * d;
     float s = 0.f;

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
   const int n = nk / b1, k = nk - n * b1;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int an = n / p.c2, bn = n - an * p.c2;
-  if (an >= visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0)) return;
+  if (an >= visible_key_tile_rows(a, p.c1k, p.ct, p.qt0)) return;
   const int b = bh / p.H, hd = bh - b * p.H;
 
   float* A = sm;
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
   float* S = Kb + b2 * ld;
 
   // block-grid rows a*b1 + k (queries) and an*b1 + k (keys); columns bq*b2 + j and bn*b2 + i
-  const long long qrow = axis_offset(p.rmap, a * b1 + k), krow = axis_offset(p.rmap, an * b1 + k);
+  const long long qrow = row_offset(p, a, k), krow = row_offset(p, an, k);
   auto qtok = [&](int j) { return qrow + axis_offset(p.cmap, bq * b2 + j); };
   auto ktok = [&](int i) { return krow + axis_offset(p.cmap, bn * b2 + i); };
   const TIn* Qp = (const TIn*)p.Q + b * p.qs.batch + hd * p.qs.head;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
   const int d = p.d, b1 = p.b1, b2 = p.b2, ld = d + 1, lz = kCH + 1;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.b1, p.cr, p.qrow0) * p.c2 * b1;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
 
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
 
   const TIn* Qp = (const TIn*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const long long qcol = axis_offset(p.cmap, bq * b2 + j);
-  auto qtok = [&](int l) { return axis_offset(p.rmap, a * b1 + l) + qcol; };
+  auto qtok = [&](int l) { return row_offset(p, a, l) + qcol; };
   for (int idx = tid; idx < b1 * d; idx += kThreads) {
     const int l = idx / d, v = idx - l * d;
     Qj[l * ld + v] = ldf(Qp + qtok(l) * p.qs.token + v);

@@ -46,8 +46,14 @@ struct KParams {
   int m0;       // first query tile of this pass
   int c1k;      // key tile rows
   AxisMap rmap, cmap;   // token of block-grid cell (x, y) = axis_offset(rmap, x) + axis_offset(cmap, y)
-  int cr;       // block-grid rows per causal chunk; 0 = no mask
-  int qrow0;    // block-grid row (of the key grid) at which query row 0 sits (mask only)
+  // neighbourhood tiles (Sec. 4.2): a tile row is n_f frames x nh grid rows of each, nh < h.
+  // nh == 0: tile row a is the contiguous block-grid rows a*b1 .. a*b1 + b1 - 1.
+  int nh;       // grid rows of one frame per tile (0 = contiguous rows)
+  int nhb;      // tile rows per frame group = h / nh
+  int tf_tok;   // tokens from one frame group to the next = n_f * h * w
+  int th_tok;   // tokens from one row band to the next = nh * w
+  int ct;       // tile rows per causal chunk; 0 = no mask
+  int qt0;      // tile row (of the key grid) at which query tile row 0 sits (mask only)
   int cc;       // frames per causal chunk (dense baseline); 0 = no mask
   int qoff;     // absolute frame of query frame 0 (dense baseline)
   int Nq, Nkv;  // tokens per head on the query / key side
@@ -55,13 +61,20 @@ struct KParams {
   float scale;
 };
 
+// Token offset of row l of tile row a (add the column offset axis_offset(cmap, y) to it).
+__host__ __device__ inline long long row_offset(const KParams& p, int a, int l) {
+  if (p.nh == 0) return axis_offset(p.rmap, a * p.b1 + l);
+  const int fa = a / p.nhb, ha = a - fa * p.nhb;
+  const int u = l / p.nh, v = l - u * p.nh;
+  return (long long)fa * p.tf_tok + (long long)ha * p.th_tok + (long long)u * p.hw + (long long)v * p.rmap.lo;
+}
+
 // Number of visible key-tile ROWS for query tile row a (tile-level chunk-causal reading: key
-// tile row a' is visible iff its chunk floor(a'*b1 / cr) is not later than the query tile row's
-// chunk floor((qrow0 + a*b1) / cr); no tile straddles a chunk, so cr and qrow0 are multiples of b1).
-__host__ __device__ inline int visible_key_tile_rows(int a, int c1k, int b1, int cr, int qrow0) {
-  if (cr == 0) return c1k;
-  const int q_chunk = (qrow0 + a * b1) / cr;
-  const int rows = ((q_chunk + 1) * cr) / b1;
+// tile row a' is visible iff its chunk floor(a' / ct) is not later than the query tile row's
+// chunk floor((qt0 + a) / ct); no tile straddles a chunk).
+__host__ __device__ inline int visible_key_tile_rows(int a, int c1k, int ct, int qt0) {
+  if (ct == 0) return c1k;
+  const int rows = ((qt0 + a) / ct + 1) * ct;
   return rows < c1k ? rows : c1k;
 }
 

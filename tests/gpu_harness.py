@@ -22,7 +22,7 @@ def run_monarch_gpu(wl, Qd, Kd, Vd, compute=pkg.MRT_COMPUTE_DEFAULT, workspace=N
     O = pkg.monarch_attn_fwd(Qd, Kd, Vd, f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1,
                              b2=wl.b2, tile=wl.tile, iters=wl.iters, causal_chunk=wl.causal_chunk,
                              q_frame_offset=wl.q_frame_offset, scale=wl.scale, compute=compute,
-                             workspace=workspace, assign=wl.assign)
+                             workspace=workspace, assign=wl.assign, tile_h=wl.tile_h)
     torch.cuda.synchronize()
     return O
 
@@ -39,7 +39,7 @@ def oracle_monarch_head(wl, Q, K, V):
     return mo.monarch_attn(torch.from_numpy(Q), torch.from_numpy(K), torch.from_numpy(V),
                            f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2,
                            tile=wl.tile, iters=wl.iters, causal_chunk=wl.causal_chunk,
-                           q_frame_offset=wl.q_frame_offset, scale=wl.scale, assign=wl.assign)
+                           q_frame_offset=wl.q_frame_offset, scale=wl.scale, assign=wl.assign, tile_h=wl.tile_h)
 
 
 def oracle_dense_head(wl, Q, K, V):

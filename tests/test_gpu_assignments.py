@@ -52,6 +52,11 @@ F32_CASES.update({
     # half-frame tiles with the stored assignment, chunk-causal with hidden chunks
     "half-frame-mask": small("f32", f_q=2, f_kv=6, h=6, w=8, b1=3, b2=4, tile=1, causal_chunk=2,
                              q_frame_offset=2, iters=3),
+    # neighbourhood tiles of 2 frames x 2 rows x 4 columns; queries at frames 0..1 of a 4-frame
+    # cache with 2-frame chunks: the second frame group is hidden
+    "neighbourhood-mask": small("f32", f_q=2, f_kv=4, h=4, w=8, b1=4, b2=4, tile=1, causal_chunk=2,
+                                q_frame_offset=0, tile_h=2, iters=3),
+    "neighbourhood-3x5": small("f32", f_q=3, f_kv=3, h=10, w=6, b1=15, b2=3, tile=1, tile_h=5),
     # one and a half frames per tile, no mask
     "frame-and-a-half": small("f32", f_q=3, f_kv=3, h=4, w=6, b1=6, b2=3, tile=1),
 })
@@ -85,6 +90,10 @@ BF16_CASES = {
     "hw_f-tiled": small("bf16", f_q=6, f_kv=6, h=8, w=10, b1=40, b2=3, tile=1, assign="hw_f"),
     "f_hw-cache-mask": small("bf16", f_q=2, f_kv=6, h=4, w=12, b1=2, b2=24, tile=1, assign="f_hw",
                              causal_chunk=2, q_frame_offset=2),
+    # neighbourhood tiles of 2 frames x 5 rows x 14 columns, hidden chunks
+    "neighbourhood-mask": small("bf16", f_q=2, f_kv=8, h=10, w=28, b1=10, b2=14, tile=1, tile_h=5,
+                                causal_chunk=2, q_frame_offset=4),
+    "neighbourhood-ragged": small("bf16", f_q=3, f_kv=3, h=14, w=20, b1=21, b2=10, tile=1, tile_h=7, iters=3),
     # half-frame tiles, stored assignment, hidden chunks; the key range spans several chunks of 64
     "half-frame-mask": small("bf16", f_q=2, f_kv=8, h=10, w=28, b1=5, b2=14, tile=1,
                              causal_chunk=2, q_frame_offset=4),
@@ -110,7 +119,7 @@ def test_assignments_bf16_match_oracle(name):
 
 
 @pytest.mark.parametrize("name,heads", [("C1-w_fh", None), ("C1-fw_h", None), ("C3-fw_h", [0, 11]),
-                                        ("C3-half", [0, 11])])
+                                        ("C3-half", [0, 11]), ("C3-nbh", [0, 11])])
 def test_assignments_bf16_named_shapes(name, heads):
     """The 4680-token chunk under the other assignments that fit the block limits, and the
     KV-cache step with (frame, width) rows and with half-frame tiles, at full size."""

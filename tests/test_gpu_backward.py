@@ -36,6 +36,8 @@ CASES = {
                                   q_frame_offset=2),
     "fw_h-T2": small(f_q=2, f_kv=2, h=5, w=6, b1=12, b2=5, tile=0, iters=2, assign="fw_h"),
     "h_fw-tiled": small(f_q=2, f_kv=2, h=6, w=6, b1=3, b2=4, tile=1, iters=2, assign="h_fw"),
+    "neighbourhood-mask": small(f_q=2, f_kv=4, h=4, w=8, b1=4, b2=4, tile=1, iters=2, causal_chunk=2,
+                                q_frame_offset=0, tile_h=2),
     "bf16-storage": small("bf16", head_dim=128, f_q=2, f_kv=4, h=8, w=24, b1=16, b2=12, tile=1, iters=2),
     "bf16-ragged-T1": small("bf16", head_dim=128, f_q=2, f_kv=2, h=11, w=21, b1=22, b2=21, tile=0, iters=1),
 }
@@ -50,7 +52,7 @@ def run_case(wl, heads=None):
     Qd, Kd, Vd, dOd = to_device(wl, arrays + (dO,))
     kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
               iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
-              scale=wl.scale, assign=wl.assign)
+              scale=wl.scale, assign=wl.assign, tile_h=wl.tile_h)
     dQ, dK, dV = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, **kw)
     torch.cuda.synchronize()
     worst = 0.0

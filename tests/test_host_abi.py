@@ -39,7 +39,8 @@ def test_binding_struct_matches_header_layout():
     assert B.MrtProblem.q.offset == 32
     assert B.MrtProblem.dtype.offset == 32 + 4 * 24
     assert B.MrtProblem.assignment.offset == 32 + 96 + 12
-    assert ctypes.sizeof(B.MrtProblem) == 32 + 96 + 16
+    assert B.MrtProblem.tile_h.offset == 32 + 96 + 16
+    assert ctypes.sizeof(B.MrtProblem) == 32 + 96 + 24
     # the header lists the assignments in the binding's order
     text = open(HEADER).read()
     for name, val in B.ASSIGNMENTS.items():
@@ -69,6 +70,8 @@ def test_named_configurations_are_accepted():
     assert pkg.monarch_attn_check(problem(assign="hw_f"), 156, 3, 1, 1) == B.MRT_OK
     assert pkg.monarch_attn_check(problem(f_kv=21, q_frame_offset=18), 15, 26, 1, 2, 3) == B.MRT_OK
     assert pkg.monarch_attn_check(problem(), 45, 26, 1, 2) == B.MRT_OK     # 1.5 frames, no mask
+    # neighbourhood tiles (n_f, n_h, n_w) = (3, 15, 26)
+    assert pkg.monarch_attn_check(problem(f_kv=21, q_frame_offset=18, tile_h=15), 45, 26, 1, 2, 3) == B.MRT_OK
 
 
 @pytest.mark.parametrize("kw,args,status", [
@@ -89,6 +92,13 @@ def test_named_configurations_are_accepted():
     (dict(assign="f_hw"), (3, 1560, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),          # b2 beyond this build
     (dict(assign="hw_f"), (1560, 3, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),          # b1 beyond this build
     (dict(assign=9), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),                      # unknown assignment
+    (dict(tile_h=15), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),                     # neighbourhoods need tile = 1
+    (dict(tile_h=7), (21, 26, 1, 2, 0), B.MRT_ERR_BLOCK),                      # 7 does not divide h = 30
+    (dict(tile_h=15), (40, 26, 1, 2, 0), B.MRT_ERR_BLOCK),                     # b1 not a multiple of n_h
+    (dict(tile_h=15), (30, 26, 1, 2, 0), B.MRT_ERR_BLOCK),                     # 2-frame neighbourhoods, 3 frames
+    (dict(tile_h=15, assign="fw_h"), (45, 30, 1, 2, 0), B.MRT_ERR_UNSUPPORTED),
+    (dict(tile_h=15, f_kv=21, q_frame_offset=18), (45, 26, 1, 2, 2), B.MRT_ERR_BLOCK),   # 3-frame tiles, 2-frame chunks
+    (dict(tile_h=-1), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),
     (dict(f_kv=21), (90, 26, 1, 2, 2), B.MRT_ERR_BLOCK),     # 3-frame tiles straddle 2-frame chunks
     (dict(f_kv=21, q_frame_offset=1), (90, 26, 1, 2, 3), B.MRT_ERR_BLOCK),   # offset inside a tile
     (dict(head_dim=96), (90, 52, 0, 2, 0), B.MRT_ERR_SHAPE),  # bf16 path: d in {64,128}

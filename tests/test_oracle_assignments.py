@@ -249,3 +249,108 @@ def test_masked_kv_cache_with_frames_and_width_on_the_row_side():
         D = mo.dense_attn(Q, K, V, f_q=f_q, f_kv=f_kv, h=h, w=w, causal_chunk=1, q_frame_offset=1,
                           scale=wl.scale)
         assert torch.allclose(O, D, atol=1e-6)
+
+
+# ---- neighbourhood tiles of several frames by a band of rows (Sec. 4.2's example) -----------------
+
+def neighbourhood_loops(Q, K, V, T, f_q, f_kv, h, w, n_f, n_h, n_w, cc, qoff, scale):
+    """Alg. 2's update equations with explicit loops; every tile is addressed through the grid
+    coordinates of its tokens: tile (fa, ha, b), row (u, v), column c is grid cell
+    (fa*n_f + u, ha*n_h + v, b*n_w + c)."""
+    Qn, Kn, Vn = Q.numpy(), K.numpy(), V.numpy()
+    d = Qn.shape[1]
+    b1, b2 = n_f * n_h, n_w
+
+    def tok(tile, r, c):
+        fa, ha, b = tile
+        u, v = divmod(r, n_h)
+        return ((fa * n_f + u) * h + ha * n_h + v) * w + b * n_w + c
+
+    def tiles(f):
+        return [(fa, ha, b) for fa in range(f // n_f) for ha in range(h // n_h) for b in range(w // n_w)]
+
+    O = np.zeros_like(Qn)
+    for qt in tiles(f_q):
+        keys = [kt for kt in tiles(f_kv)
+                if cc == 0 or (kt[0] * n_f) // cc <= (qoff + qt[0] * n_f) // cc]
+        L = {kt: np.eye(b1)[None].repeat(b2, 0) for kt in keys}            # [j][k][l]
+        R = {}
+        for _ in range(T):
+            for kt in keys:
+                Rn = np.zeros((b1, b2, b2))
+                for k, j in itertools.product(range(b1), range(b2)):
+                    a = sum(L[kt][j, k, l] * Qn[tok(qt, l, j)] for l in range(b1))
+                    c = sum(L[kt][j, k, l] for l in range(b1))
+                    z = np.array([scale * np.dot(a, Kn[tok(kt, k, i)]) / c for i in range(b2)])
+                    e = np.exp(z - z.max())
+                    Rn[k, j] = e / e.sum()
+                R[kt] = Rn
+            Z = {}
+            for kt in keys:
+                Zn = np.zeros((b2, b1, b1))
+                for j, k in itertools.product(range(b2), range(b1)):
+                    r = R[kt][k, j]
+                    aL = sum(r[i] * Kn[tok(kt, k, i)] for i in range(b2))
+                    cL = sum(r[i] * np.log(r[i]) for i in range(b2) if r[i] > 0)
+                    for l in range(b1):
+                        Zn[j, k, l] = scale * np.dot(aL, Qn[tok(qt, l, j)]) - cL
+                Z[kt] = Zn
+            for j, l in itertools.product(range(b2), range(b1)):
+                z = np.array([Z[kt][j, k, l] for kt in keys for k in range(b1)])
+                e = np.exp(z - z.max())
+                e /= e.sum()
+                for t, kt in enumerate(keys):
+                    L[kt][j, :, l] = e[t * b1:(t + 1) * b1]
+        for j, l in itertools.product(range(b2), range(b1)):
+            acc = np.zeros(d)
+            for kt in keys:
+                for k in range(b1):
+                    Y = sum(R[kt][k, j, i] * Vn[tok(kt, k, i)] for i in range(b2))
+                    acc += L[kt][j, k, l] * Y
+            O[tok(qt, l, j)] = acc
+    return torch.from_numpy(O)
+
+
+@pytest.mark.parametrize("cc,qoff", [(0, 0), (2, 2)])
+def test_neighbourhood_tiles_against_explicit_loops(cc, qoff):
+    # neighbourhoods of 2 frames x 2 rows x 2 columns on grids of 2 (queries) and 4 (keys) frames of
+    # 4 x 4; with 2-frame chunks and the queries at frames 2..3 everything is visible, so also run
+    # the queries at frames 0..1, which hides the second frame group
+    f_q, f_kv, h, w, d = 2, 4, 4, 4, 5
+    Q, K, V = rnd((f_q * h * w, d), 21), rnd((f_kv * h * w, d), 22), rnd((f_kv * h * w, d), 23)
+    for off in ({qoff, 0} if cc else {0}):
+        O = mo.monarch_attn(Q, K, V, f_q=f_q, f_kv=f_kv, h=h, w=w, b1=4, b2=2, tile=1, iters=2,
+                            causal_chunk=cc, q_frame_offset=off, scale=0.7, tile_h=2)
+        ref = neighbourhood_loops(Q, K, V, 2, f_q, f_kv, h, w, 2, 2, 2, cc, off, 0.7)
+        assert torch.allclose(O, ref, atol=1e-10)
+    # and the neighbourhood tiling differs from the contiguous split with the same block sizes
+    Oc = mo.monarch_attn(Q, K, V, f_q=f_q, f_kv=f_kv, h=h, w=w, b1=4, b2=2, tile=1, iters=2, scale=0.7)
+    On = mo.monarch_attn(Q, K, V, f_q=f_q, f_kv=f_kv, h=h, w=w, b1=4, b2=2, tile=1, iters=2, scale=0.7, tile_h=2)
+    assert (Oc - On).abs().max() > 1e-3
+
+
+def test_neighbourhood_tiles_reduce_to_the_contiguous_split():
+    f, h, w, d = 2, 4, 6, 6
+    Q, K, V = rnd((f * h * w, d), 31), rnd((f * h * w, d), 32), rnd((f * h * w, d), 33)
+    base = dict(f_q=f, f_kv=f, h=h, w=w, b2=3, tile=1, iters=2, scale=0.5)
+    # whole-height bands: neighbourhoods are whole frames
+    assert torch.allclose(mo.monarch_attn(Q, K, V, b1=8, tile_h=4, **base), mo.monarch_attn(Q, K, V, b1=8, **base),
+                          atol=1e-12)
+    # one frame per neighbourhood: bands of 2 rows are contiguous rows
+    assert torch.allclose(mo.monarch_attn(Q, K, V, b1=2, tile_h=2, **base), mo.monarch_attn(Q, K, V, b1=2, **base),
+                          atol=1e-12)
+    order = mo.neighbourhood_order(2, 4, 3, 2, 2)
+    # written out for a (2, 4, 3) grid: band 0 = rows 0,1 of frame 0 then rows 0,1 of frame 1, ...
+    assert order.tolist() == [0, 1, 2, 3, 4, 5, 12, 13, 14, 15, 16, 17,
+                              6, 7, 8, 9, 10, 11, 18, 19, 20, 21, 22, 23]
+
+
+def test_neighbourhood_tiles_with_position_only_logits_give_dense():
+    f_q, f_kv, h, w = 2, 4, 4, 6
+    wl = syn.variant("C3", heads=1, f_q=f_q, f_kv=f_kv, h=h, w=w, b1=4, b2=3, causal_chunk=2,
+                     q_frame_offset=2, dtype="f32")
+    Q, K, V = (torch.from_numpy(x).double() for x in syn.make_separable_head(wl, 0, 0))
+    O = mo.monarch_attn(Q, K, V, f_q=f_q, f_kv=f_kv, h=h, w=w, b1=4, b2=3, tile=1, iters=2, causal_chunk=2,
+                        q_frame_offset=2, scale=wl.scale, tile_h=2)
+    D = mo.dense_attn(Q, K, V, f_q=f_q, f_kv=f_kv, h=h, w=w, causal_chunk=2, q_frame_offset=2, scale=wl.scale)
+    assert torch.allclose(O, D, atol=1e-6)

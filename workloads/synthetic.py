@@ -42,6 +42,7 @@ class Workload:
     sigma_v: float = 1.0
     seed: int = 0
     assign: str = "fh_w"  # aligned block assignment (Sec. 4.1): axes of the b1 side _ axes of the b2 side
+    tile_h: int = 0       # n_h > 0: neighbourhood tiles of (b1 / n_h) frames x n_h rows x b2 columns (Sec. 4.2)
 
     def block_grid(self):
         """(rows_q, rows_kv, cols) of the block grid under the assignment."""
@@ -108,6 +109,9 @@ WORKLOADS: Dict[str, Workload] = {
                         assign="fw_h"),
     # neighbourhood tiles of half a frame: (n_f, n_h, n_w) = (1, 15, 26)
     "C3-half": Workload("C3-half", 1, 12, 128, 3, 21, 30, 52, 15, 26, 1, 2, 3, 18, "bf16", _INV_SQRT128, True),
+    # neighbourhood tiles of 3 frames x 15 rows x 26 columns: (n_f, n_h, n_w) = (3, 15, 26), b1 = 45
+    "C3-nbh": Workload("C3-nbh", 1, 12, 128, 3, 21, 30, 52, 45, 26, 1, 2, 3, 18, "bf16", _INV_SQRT128, True,
+                       tile_h=15),
 }
 
 
