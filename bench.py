@@ -175,7 +175,7 @@ def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
                    "workspace_mb": nws / 1e6},
         "roofline": {"bound": "alu", "achieved": ach, "peak": 157.3, "unit": "TFLOP/s", "frac": ach / 157.3,
                      "traffic": None, "algorithmic_gflop": flops / 1e9,
-                     "note": "plain fp32 ALU kernels (not MFMA), whole call: forward recomputation + reverse sweep"},
+                     "note": "fp32 kernels (fp32 MFMA contractions), whole call: forward recomputation + reverse sweep; peak = fp32 matrix/vector rate"},
         "cpu_baseline": cpu, "parity_max_abs_err_head0": parity,
     }))
 

@@ -140,7 +140,8 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
  *   library runs as many of them per pass as fit (workspace rules as for monarch_attn_fwd).
  *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers fit the 160 KB
  *   of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128), iters <= 16; otherwise
- *   MRT_ERR_UNSUPPORTED.  These kernels are plain-ALU code, not tuned. */
+ *   MRT_ERR_UNSUPPORTED.  These kernels keep fp32 operands and use the fp32 matrix instructions;
+ *   they are far from the tuning of the bf16 forward kernels. */
 size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,

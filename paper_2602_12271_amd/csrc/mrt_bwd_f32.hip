@@ -1,4 +1,5 @@
-// Backward pass of the operator (gradients w.r.t. Q, K, V), fp32 plain-ALU kernels.
+// Backward pass of the operator (gradients w.r.t. Q, K, V) in fp32: operands staged in LDS as
+// fp32, contractions on the matrix unit in fp32 (mrt_f32_tiles.hpp), the rest plain ALU code.
 //
 // Monarch finetuning trains through the refinement iterations (Sec. 4.3), so every iteration
 // is differentiated.  With the forward quantities of iteration t (App. A notation)
@@ -11,15 +12,14 @@
 // The forward intermediates of every iteration are recomputed by the forward kernels into the
 // workspace before the sweep; softmax factors are rebuilt from them on the fly.
 #include "mrt_internal.hpp"
+#include "mrt_f32_tiles.hpp"
 
 namespace mrt {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kCH = 16;        // nk rows per chunk in stage L backward
-constexpr int kMaxRows = 96;   // rows per thread in the dQ accumulation (b1 <= 192, d <= 128)
-constexpr int kMaxAcc = 48;    // (i, v) elements per thread in the dK / dV accumulation
+constexpr int kMaxTiles = 24;  // 16x16 tiles of dQ[m, :, j, :] per wave (b1 <= 192, d <= 128, 4 waves)
+constexpr int kMaxAccT = 12;   // 16x16 tiles of dK / dV of one key block per wave (b2 <= 96, d <= 128)
 
 template <typename T> __device__ inline float ldf(const T* p);
 template <> __device__ inline float ldf<float>(const float* p) { return *p; }
@@ -40,7 +40,7 @@ template <> __device__ inline float ldf<uint16_t>(const uint16_t* p) {
 // (w is formed as a softmax over l of log L, which cannot produce 0/0.)
 // ---------------------------------------------------------------------------------------
 template <typename TIn, bool LAST>
-__global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
+__global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp, int kCH) {
   const KParams& p = bp.k;
   extern __shared__ float sm[];
   const int tid = threadIdx.x;
@@ -89,12 +89,10 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
       Kc[c * ld + v] = aLp[(size_t)(c0 + c) * d + v];
     }
     __syncthreads();
-    for (int idx = tid; idx < b1 * cn; idx += kThreads) {
-      const int l = idx / cn, c = idx - l * cn;
-      float acc = 0.f;
-      for (int v = 0; v < d; ++v) acc = fmaf(Qj[l * ld + v], Kc[c * ld + v], acc);
-      Lc[l * lz + c] = p.scale * acc - cLp[c0 + c];
-    }
+    gemm_tiles(b1, cn, d,
+               [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
+               [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
+               [&](int l, int c, float x) { Lc[l * lz + c] = p.scale * x - cLp[c0 + c]; }, tid);
     __syncthreads();
     if (tid < b1) {
       float mx = rmax;
@@ -106,12 +104,13 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
   }
   if (tid < b1) { lse[tid] = rmax + logf(rsum); delta[tid] = 0.f; }
 
-  const int dp = d <= 64 ? 64 : 128;
-  const int ngroups = kThreads / dp;
-  const int vt = tid % dp, lg = tid / dp;
-  float acc[kMaxRows];
+  // dQ[m, :, j, :] accumulates over the chunks in registers: 16x16 tiles (l tile, v tile) dealt
+  // to the waves, tile t = wave + kWaves * n in dq[n]
+  const int wave = tid >> 6, lane = tid & 63;
+  const int tnv = (d + 15) >> 4, qtiles = ((b1 + 15) >> 4) * tnv;
+  f32x4 dq[kMaxTiles];
 #pragma unroll
-  for (int r = 0; r < kMaxRows; ++r) acc[r] = 0.f;
+  for (int n = 0; n < kMaxTiles; ++n) dq[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // ---- pass 1 (delta) and pass 2 (gradients)
   for (int pass = 1; pass <= 2; ++pass) {
@@ -131,16 +130,17 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
         tc[tid] = t;
       }
       __syncthreads();
-      for (int idx = tid; idx < b1 * cn; idx += kThreads) {
-        const int l = idx / cn, c = idx - l * cn;
-        float z = 0.f, u = 0.f;
-        for (int v = 0; v < d; ++v) {
-          z = fmaf(Qj[l * ld + v], Kc[c * ld + v], z);
-          u = fmaf((LAST ? Xj : Qj)[l * ld + v], Wc[c * ld + v], u);
-        }
-        Lc[l * lz + c] = p.scale * z - cLp[c0 + c] - lse[l];     // log L[l,c]
-        Uc[l * lz + c] = LAST ? u : u - tc[c];                    // dL (LAST) or u
-      }
+      const float* Xrows = LAST ? Xj : Qj;
+      gemm_tiles(b1, cn, d,
+                 [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
+                 [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
+                 [&](int l, int c, float x) { Lc[l * lz + c] = p.scale * x - cLp[c0 + c] - lse[l]; },   // log L
+                 tid);
+      gemm_tiles(b1, cn, d,
+                 [&](int l, int v) { return l < b1 && v < d ? Xrows[l * ld + v] : 0.f; },
+                 [&](int v, int c) { return c < cn && v < d ? Wc[c * ld + v] : 0.f; },
+                 [&](int l, int c, float x) { Uc[l * lz + c] = LAST ? x : x - tc[c]; },                  // dL or u
+                 tid);
       __syncthreads();
       if (!LAST) {
         if (tid < cn) {
@@ -187,47 +187,52 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp) {
         __syncthreads();
       }
       // per-column outputs: d aL, d cL, (d Y)
-      for (int idx = tid; idx < cn * d; idx += kThreads) {
-        const int c = idx / d, v = idx - c * d;
-        float s = 0.f, y = 0.f;
-        for (int l = 0; l < b1; ++l) {
-          s = fmaf(Uc[l * lz + c], Qj[l * ld + v], s);
-          if (LAST) y = fmaf(Lc[l * lz + c], Xj[l * ld + v], y);
-        }
-        bp.daL[(row0 + c0 + c) * d + v] = p.scale * s;
-        if (LAST) bp.dY[(row0 + c0 + c) * d + v] = y;
-      }
+      gemm_tiles(cn, d, b1,
+                 [&](int c, int l) { return c < cn && l < b1 ? Uc[l * lz + c] : 0.f; },
+                 [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
+                 [&](int c, int v, float x) { bp.daL[(row0 + c0 + c) * d + v] = p.scale * x; }, tid);
+      if (LAST)
+        gemm_tiles(cn, d, b1,
+                   [&](int c, int l) { return c < cn && l < b1 ? Lc[l * lz + c] : 0.f; },
+                   [&](int l, int v) { return l < b1 && v < d ? Xj[l * ld + v] : 0.f; },
+                   [&](int c, int v, float x) { bp.dY[(row0 + c0 + c) * d + v] = x; }, tid);
       if (tid < cn) {
         float s = 0.f;
         for (int l = 0; l < b1; ++l) s += Uc[l * lz + tid];
         bp.dcL[row0 + c0 + tid] = -s;
       }
       // per-row accumulation of dQ
-      if (vt < d) {
 #pragma unroll
-        for (int r = 0; r < kMaxRows; ++r) {
-          const int l = lg + r * ngroups;
-          if (l < b1) {
-            float s = acc[r];
-            for (int c = 0; c < cn; ++c) {
-              s = fmaf(p.scale * Uc[l * lz + c], Kc[c * ld + vt], s);
-              if (!LAST) s = fmaf(Lc[l * lz + c], Wc[c * ld + vt], s);
-            }
-            acc[r] = s;
-          }
+      for (int n = 0; n < kMaxTiles; ++n) {
+        const int t = wave + kWaves * n;
+        if (t < qtiles) {
+          const int l0 = 16 * (t / tnv), v0 = 16 * (t % tnv);
+          dq[n] = mma16([&](int r, int c) { return l0 + r < b1 && c < cn ? p.scale * Uc[(l0 + r) * lz + c] : 0.f; },
+                        [&](int c, int v) { return c < cn && v0 + v < d ? Kc[c * ld + v0 + v] : 0.f; }, cn, dq[n], lane);
+          if (!LAST)
+            dq[n] = mma16([&](int r, int c) { return l0 + r < b1 && c < cn ? Lc[(l0 + r) * lz + c] : 0.f; },
+                          [&](int c, int v) { return c < cn && v0 + v < d ? Wc[c * ld + v0 + v] : 0.f; }, cn, dq[n], lane);
         }
       }
     }
     __syncthreads();
   }
-  if (vt < d) {
+  {
     float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
+    const int i = lane & 15, q = lane >> 4;
 #pragma unroll
-    for (int r = 0; r < kMaxRows; ++r) {
-      const int l = lg + r * ngroups;
-      if (l < b1) {
-        float* dst = dQp + qtok(l) * d + vt;
-        *dst = bp.accumulate ? *dst + acc[r] : acc[r];
+    for (int n = 0; n < kMaxTiles; ++n) {
+      const int t = wave + kWaves * n;
+      if (t < qtiles) {
+        const int l0 = 16 * (t / tnv), v0 = 16 * (t % tnv);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int l = l0 + 4 * q + r, v = v0 + i;
+          if (l < b1 && v < d) {
+            float* dst = dQp + qtok(l) * d + v;
+            *dst = bp.accumulate ? *dst + dq[n][r] : dq[n][r];
+          }
+        }
       }
     }
   }
@@ -267,9 +272,34 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_r(BwdParams bp, int firs
   const size_t NKtot = (size_t)p.ntk * b1;
   const int nel = b2 * d;
 
-  float accK[kMaxAcc], accV[kMaxAcc];
+  // dK and dV of the block accumulate over the query tiles in registers: 16x16 tiles
+  // (i tile, v tile) dealt to the waves, tile t = wave + kWaves * n in accK[n] / accV[n]
+  const int wave = tid >> 6, lane = tid & 63;
+  const int tnv = (d + 15) >> 4, ktiles = ((b2 + 15) >> 4) * tnv;
+  f32x4 accK[kMaxAccT], accV[kMaxAccT];
 #pragma unroll
-  for (int r = 0; r < kMaxAcc; ++r) { accK[r] = 0.f; accV[r] = 0.f; }
+  for (int n = 0; n < kMaxAccT; ++n) {
+    accK[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    accV[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // acc[n] += P^T X for P[jj][i] (b2 x b2, row stride ls) and X[jj][v] (b2 x d, row stride ld)
+  auto accumulate_t = [&](f32x4 (&acc)[kMaxAccT], const float* P, const float* X, float mul) {
+#pragma unroll
+    for (int n = 0; n < kMaxAccT; ++n) {
+      const int t = wave + kWaves * n;
+      if (t < ktiles) {
+        const int i0 = 16 * (t / tnv), v0 = 16 * (t % tnv);
+        acc[n] = mma16([&](int r, int jj) { return i0 + r < b2 && jj < b2 ? mul * P[jj * ls + i0 + r] : 0.f; },
+                       [&](int jj, int v) { return jj < b2 && v0 + v < d ? X[jj * ld + v0 + v] : 0.f; }, b2,
+                       acc[n], lane);
+      }
+    }
+  };
+  auto rows_dot = [&](const float* X, const float* Y, auto done) {   // done(jj, i, X[jj].Y[i])
+    gemm_tiles(b2, b2, d,
+               [&](int jj, int v) { return jj < b2 && v < d ? X[jj * ld + v] : 0.f; },
+               [&](int v, int i) { return i < b2 && v < d ? Y[i * ld + v] : 0.f; }, done, tid);
+  };
 
   auto load_rows = [&](float* dst, auto src) {     // dst[j][v] = src(j, v)
     for (int idx = tid; idx < nel; idx += kThreads) {
@@ -300,12 +330,7 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_r(BwdParams bp, int firs
     if (tid < b2) dcl[tid] = bp.dcL[jrow(tid)];
     __syncthreads();
     // logits
-    for (int idx = tid; idx < b2 * b2; idx += kThreads) {
-      const int jj = idx / b2, i = idx - jj * b2;
-      float s = 0.f;
-      for (int v = 0; v < d; ++v) s = fmaf(B1[jj * ld + v], B2[i * ld + v], s);
-      LR[jj * ls + i] = p.scale * s;
-    }
+    rows_dot(B1, B2, [&](int jj, int i, float x) { LR[jj * ls + i] = p.scale * x; });
     __syncthreads();
     if (tid < b2) {
       float mx = -INFINITY;
@@ -319,84 +344,58 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_r(BwdParams bp, int firs
     // d aL into B1 (K still in B2)
     load_rows(B1, [&](int jj, int v) { return bp.daL[jrow(jj) * d + v]; });
     __syncthreads();
+    rows_dot(B1, B2, [&](int jj, int i, float x) { DR[jj * ls + i] = x + dcl[jj] * (LR[jj * ls + i] + 1.0f); });
+    __syncthreads();
+    // from here on LR holds R itself (log R was only needed for the entropy term above)
     for (int idx = tid; idx < b2 * b2; idx += kThreads) {
       const int jj = idx / b2, i = idx - jj * b2;
-      float s = 0.f;
-      for (int v = 0; v < d; ++v) s = fmaf(B1[jj * ld + v], B2[i * ld + v], s);
-      DR[jj * ls + i] = s + dcl[jj] * (LR[jj * ls + i] + 1.0f);
+      LR[jj * ls + i] = expf(LR[jj * ls + i]);
     }
-    // dK += R^T d aL
-#pragma unroll
-    for (int r = 0; r < kMaxAcc; ++r) {
-      const int idx = tid + r * kThreads;
-      if (idx < nel) {
-        const int i = idx / d, v = idx - i * d;
-        float s = accK[r];
-        for (int jj = 0; jj < b2; ++jj) s = fmaf(expf(LR[jj * ls + i]), B1[jj * ld + v], s);
-        accK[r] = s;
-      }
-    }
+    __syncthreads();
+    accumulate_t(accK, LR, B1, 1.0f);          // dK += R^T d aL
     __syncthreads();
     if (last) {
       load_rows(B1, [&](int jj, int v) { return bp.dY[jrow(jj) * d + v]; });
       load_rows(B2, [&](int i, int v) { return ldf(Vp + ktok(i) * p.vs.token + v); });
       __syncthreads();
-      for (int idx = tid; idx < b2 * b2; idx += kThreads) {
-        const int jj = idx / b2, i = idx - jj * b2;
-        float s = 0.f;
-        for (int v = 0; v < d; ++v) s = fmaf(B1[jj * ld + v], B2[i * ld + v], s);
-        DR[jj * ls + i] += s;
-      }
-#pragma unroll
-      for (int r = 0; r < kMaxAcc; ++r) {
-        const int idx = tid + r * kThreads;
-        if (idx < nel) {
-          const int i = idx / d, v = idx - i * d;
-          float s = accV[r];
-          for (int jj = 0; jj < b2; ++jj) s = fmaf(expf(LR[jj * ls + i]), B1[jj * ld + v], s);
-          accV[r] = s;
-        }
-      }
+      rows_dot(B1, B2, [&](int jj, int i, float x) { DR[jj * ls + i] += x; });
+      accumulate_t(accV, LR, B1, 1.0f);        // dV += R^T d Y
       __syncthreads();
     }
     // dS = R (dR - sum_i R dR), in place
     if (tid < b2) {
       float dot = 0.f;
-      for (int i = 0; i < b2; ++i) dot = fmaf(expf(LR[tid * ls + i]), DR[tid * ls + i], dot);
-      for (int i = 0; i < b2; ++i) DR[tid * ls + i] = expf(LR[tid * ls + i]) * (DR[tid * ls + i] - dot);
+      for (int i = 0; i < b2; ++i) dot = fmaf(LR[tid * ls + i], DR[tid * ls + i], dot);
+      for (int i = 0; i < b2; ++i) DR[tid * ls + i] = LR[tid * ls + i] * (DR[tid * ls + i] - dot);
     }
     load_A();
     if (last) load_K();
     __syncthreads();
     // dK += scale dS^T abar ;  d abar = scale dS K
-#pragma unroll
-    for (int r = 0; r < kMaxAcc; ++r) {
-      const int idx = tid + r * kThreads;
-      if (idx < nel) {
-        const int i = idx / d, v = idx - i * d;
-        float s = 0.f;
-        for (int jj = 0; jj < b2; ++jj) s = fmaf(DR[jj * ls + i], B1[jj * ld + v], s);
-        accK[r] = fmaf(p.scale, s, accK[r]);
-      }
-    }
+    accumulate_t(accK, DR, B1, p.scale);
     float* dAp = bp.dA + (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2 * d;
-    for (int idx = tid; idx < nel; idx += kThreads) {
-      const int jj = idx / d, v = idx - jj * d;
-      float s = 0.f;
-      for (int i = 0; i < b2; ++i) s = fmaf(DR[jj * ls + i], B2[i * ld + v], s);
-      dAp[idx] = p.scale * s;
-    }
+    gemm_tiles(b2, d, b2,
+               [&](int jj, int i) { return jj < b2 && i < b2 ? DR[jj * ls + i] : 0.f; },
+               [&](int i, int v) { return i < b2 && v < d ? B2[i * ld + v] : 0.f; },
+               [&](int jj, int v, float x) { dAp[(size_t)jj * d + v] = p.scale * x; }, tid);
   }
   float* dKp = bp.dK + (size_t)bh * p.Nkv * d;
   float* dVp = bp.dV + (size_t)bh * p.Nkv * d;
+  const int li = lane & 15, lq = lane >> 4;
 #pragma unroll
-  for (int r = 0; r < kMaxAcc; ++r) {
-    const int idx = tid + r * kThreads;
-    if (idx < nel) {
-      const int i = idx / d, v = idx - i * d;
-      const size_t off = (size_t)ktok(i) * d + v;
-      dKp[off] = bp.accumulate ? dKp[off] + accK[r] : accK[r];
-      if (last) dVp[off] = accV[r];
+  for (int n = 0; n < kMaxAccT; ++n) {
+    const int t = wave + kWaves * n;
+    if (t < ktiles) {
+      const int i0 = 16 * (t / tnv), v0 = 16 * (t % tnv);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int i = i0 + 4 * lq + r, v = v0 + li;
+        if (i < b2 && v < d) {
+          const size_t off = (size_t)ktok(i) * d + v;
+          dKp[off] = bp.accumulate ? dKp[off] + accK[n][r] : accK[n][r];
+          if (last) dVp[off] = accV[n][r];
+        }
+      }
     }
   }
 }
@@ -428,28 +427,32 @@ hipError_t allow_lds(K kernel, size_t bytes) {
 
 }  // namespace
 
-size_t bwd_stage_l_lds(int b1, int d, bool last) {
-  return ((size_t)(last ? 2 : 1) * b1 * (d + 1) + (size_t)2 * kCH * (d + 1) + (size_t)2 * b1 * (kCH + 1) +
-          2 * b1 + 3 * kCH) * 4;
+size_t bwd_stage_l_lds(int b1, int d, bool last, int ch) {
+  return ((size_t)(last ? 2 : 1) * b1 * (d + 1) + (size_t)2 * ch * (d + 1) + (size_t)2 * b1 * (ch + 1) +
+          2 * b1 + 3 * ch) * 4;
 }
 size_t bwd_stage_r_lds(int b2, int d) {
   return ((size_t)2 * b2 * (d + 1) + (size_t)2 * b2 * (b2 + 1) + b2) * 4;
 }
 bool bwd_fits(int b1, int b2, int d) {
   const size_t lim = 160 * 1024;
-  return bwd_stage_l_lds(b1, d, true) <= lim && bwd_stage_r_lds(b2, d) <= lim &&
-         (size_t)b2 * d <= (size_t)kMaxAcc * kThreads;
+  return bwd_stage_l_lds(b1, d, true, 16) <= lim && bwd_stage_r_lds(b2, d) <= lim &&
+         ((b2 + 15) / 16) * ((d + 15) / 16) <= kMaxAccT * kWaves &&
+         ((b1 + 15) / 16) * ((d + 15) / 16) <= kMaxTiles * kWaves;
 }
 
 hipError_t launch_bwd_stage_l(const BwdParams& bp, int dtype, int nbh, bool last, hipStream_t s) {
   const KParams& kp = bp.k;
-  const size_t lds = bwd_stage_l_lds(kp.b1, kp.d, last);
+  // nk rows per chunk: the largest of 64 / 32 / 16 whose buffers fit on chip
+  int ch = 64;
+  while (ch > 16 && bwd_stage_l_lds(kp.b1, kp.d, last, ch) > 160 * 1024) ch /= 2;
+  const size_t lds = bwd_stage_l_lds(kp.b1, kp.d, last, ch);
   dim3 grid(kp.b2, kp.ntq, nbh);
   hipError_t e;
 #define MRT_LAUNCH_BL(T, LASTV)                                                        \
   do {                                                                                 \
     if ((e = allow_lds(k_bwd_stage_l<T, LASTV>, lds)) != hipSuccess) return e;         \
-    k_bwd_stage_l<T, LASTV><<<grid, kThreads, lds, s>>>(bp);                           \
+    k_bwd_stage_l<T, LASTV><<<grid, kThreads, lds, s>>>(bp, ch);                          \
   } while (0)
   if (dtype == MRT_F32) { if (last) MRT_LAUNCH_BL(float, true); else MRT_LAUNCH_BL(float, false); }
   else { if (last) MRT_LAUNCH_BL(uint16_t, true); else MRT_LAUNCH_BL(uint16_t, false); }

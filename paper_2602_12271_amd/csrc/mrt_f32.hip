@@ -1,4 +1,5 @@
-// fp32 path: plain-ALU kernels, fp32 arithmetic and fp32 intermediates.
+// fp32 path: fp32 arithmetic and fp32 intermediates; the contractions run on the matrix unit in
+// fp32 (v_mfma_f32_16x16x4_f32 on fp32 operands held in LDS), everything else is plain ALU code.
 //
 // Used for f32 storage (the 1e-4 parity class) and, on request, as a device-side
 // cross-check for bf16 storage.  Same three stages as the MFMA path:
@@ -6,12 +7,11 @@
 //   stage L  (one workgroup per (m, j)):     Z_L, L = softmax_(n,k), then alpha_R/c_R or O
 // Equation references: App. A.1 / A.2 update equations.
 #include "mrt_internal.hpp"
+#include "mrt_f32_tiles.hpp"
 
 namespace mrt {
 
 namespace {
-
-constexpr int kThreads = 256;
 
 template <typename T> __device__ inline float ldf(const T* p);
 template <> __device__ inline float ldf<float>(const float* p) { return *p; }
@@ -65,12 +65,10 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
     Kb[j * ld + v] = ldf(Kp + ktok(j) * p.ks.token + v);
   }
   __syncthreads();
-  for (int idx = tid; idx < b2 * b2; idx += kThreads) {
-    const int j = idx / b2, i = idx - j * b2;
-    float acc = 0.f;
-    for (int v = 0; v < d; ++v) acc = fmaf(A[j * ld + v], Kb[i * ld + v], acc);
-    S[j * ls + i] = p.scale * acc;
-  }
+  gemm_tiles(b2, b2, d,
+             [&](int j, int v) { return j < b2 && v < d ? A[j * ld + v] : 0.f; },
+             [&](int v, int i) { return i < b2 && v < d ? Kb[i * ld + v] : 0.f; },
+             [&](int j, int i, float x) { S[j * ls + i] = p.scale * x; }, tid);
   __syncthreads();
   if (tid < b2) {
     const int j = tid;
@@ -93,17 +91,21 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
   float* aLp = (float*)p.aL + ((((size_t)bhl * p.ntq + ml) * b2) * NKtot + nk) * d;
   float* Yp = (float*)p.Y + ((((size_t)bhl * p.ntq + ml) * b2) * NKtot + nk) * d;
   const size_t jstride = NKtot * d;
-  for (int idx = tid; idx < b2 * d; idx += kThreads) {
-    const int j = idx / d, v = idx - j * d;
-    float acc = 0.f;
-    for (int i = 0; i < b2; ++i) acc = fmaf(S[j * ls + i], Kb[i * ld + v], acc);
-    aLp[j * jstride + v] = acc;
-    if (last) {
-      float accv = 0.f;
-      for (int i = 0; i < b2; ++i)
-        accv = fmaf(S[j * ls + i], ldf(Vp + ktok(i) * p.vs.token + v), accv);
-      Yp[j * jstride + v] = accv;
+  gemm_tiles(b2, d, b2,
+             [&](int j, int i) { return j < b2 && i < b2 ? S[j * ls + i] : 0.f; },
+             [&](int i, int v) { return i < b2 && v < d ? Kb[i * ld + v] : 0.f; },
+             [&](int j, int v, float x) { aLp[j * jstride + v] = x; }, tid);
+  if (last) {
+    __syncthreads();                  // every wave is done with K: the tile now holds V
+    for (int idx = tid; idx < b2 * d; idx += kThreads) {
+      const int i = idx / d, v = idx - i * d;
+      Kb[i * ld + v] = ldf(Vp + ktok(i) * p.vs.token + v);
     }
+    __syncthreads();
+    gemm_tiles(b2, d, b2,
+               [&](int j, int i) { return j < b2 && i < b2 ? S[j * ls + i] : 0.f; },
+               [&](int i, int v) { return i < b2 && v < d ? Kb[i * ld + v] : 0.f; },
+               [&](int j, int v, float x) { Yp[j * jstride + v] = x; }, tid);
   }
 }
 
@@ -116,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
 // which is the same ratio and cannot underflow to 0/0.
 // ---------------------------------------------------------------------------------------
 constexpr int kCH = 16;     // nk rows per chunk
-constexpr int kMaxRows = 96;  // output rows per thread in the last stage (b1 <= 192, d <= 128)
+constexpr int kMaxTiles = 24;  // 16x16 output tiles per wave in the last stage (b1 <= 192, d <= 128)
 
 template <typename TIn, bool LAST>
 __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
@@ -158,12 +160,10 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
       Kc[c * ld + v] = aLp[(size_t)(c0 + c) * d + v];
     }
     __syncthreads();
-    for (int idx = tid; idx < b1 * cn; idx += kThreads) {
-      const int l = idx / cn, c = idx - l * cn;
-      float acc = 0.f;
-      for (int v = 0; v < d; ++v) acc = fmaf(Qj[l * ld + v], Kc[c * ld + v], acc);
-      Zc[l * lz + c] = p.scale * acc - cLp[c0 + c];
-    }
+    gemm_tiles(b1, cn, d,
+               [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
+               [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
+               [&](int l, int c, float x) { Zc[l * lz + c] = p.scale * x - cLp[c0 + c]; }, tid);
     __syncthreads();
     if (tid < b1) {
       float mx = rmax;
@@ -176,13 +176,14 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
   if (tid < b1) lse[tid] = rmax + logf(rsum);
 
   // pass 2
-  const int dp = d <= 64 ? 64 : 128;
-  const int ngroups = kThreads / dp;
-  const int vt = tid % dp, lg = tid / dp;
-  float acc[kMaxRows];
+  // O[m, :, j, :] accumulates over the chunks in registers: 16x16 tiles (l tile, v tile) dealt to
+  // the waves, tile t = wave + kWaves * n in acc[n]
+  const int wave = tid >> 6, lane = tid & 63;
+  const int tnv = (d + 15) >> 4, otiles = ((b1 + 15) >> 4) * tnv;
+  f32x4 acc[kMaxTiles];
   if (LAST) {
 #pragma unroll
-    for (int r = 0; r < kMaxRows; ++r) acc[r] = 0.f;
+    for (int n = 0; n < kMaxTiles; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
   float* aRout = (float*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * d;
 
@@ -194,13 +195,13 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
       Kc[c * ld + v] = aLp[(size_t)(c0 + c) * d + v];
     }
     __syncthreads();
-    for (int idx = tid; idx < b1 * cn; idx += kThreads) {
-      const int l = idx / cn, c = idx - l * cn;
-      float acc1 = 0.f;
-      for (int v = 0; v < d; ++v) acc1 = fmaf(Qj[l * ld + v], Kc[c * ld + v], acc1);
-      const float z = p.scale * acc1 - cLp[c0 + c] - lse[l];   // log L[l,nk]
-      Zc[l * lz + c] = LAST ? expf(z) : z;
-    }
+    gemm_tiles(b1, cn, d,
+               [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
+               [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
+               [&](int l, int c, float x) {
+                 const float z = p.scale * x - cLp[c0 + c] - lse[l];   // log L[l,nk]
+                 Zc[l * lz + c] = LAST ? expf(z) : z;
+               }, tid);
     __syncthreads();
     if (LAST) {
       for (int idx = tid; idx < cn * d; idx += kThreads) {
@@ -208,15 +209,14 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
         Kc[c * ld + v] = Yp[(size_t)(c0 + c) * d + v];
       }
       __syncthreads();
-      if (vt < d) {
 #pragma unroll
-        for (int r = 0; r < kMaxRows; ++r) {
-          const int l = lg + r * ngroups;
-          if (l < b1) {
-            float s = acc[r];
-            for (int c = 0; c < cn; ++c) s = fmaf(Zc[l * lz + c], Kc[c * ld + vt], s);
-            acc[r] = s;
-          }
+      for (int n = 0; n < kMaxTiles; ++n) {
+        const int t = wave + kWaves * n;
+        if (t < otiles) {
+          const int l0 = 16 * (t / tnv), v0 = 16 * (t % tnv);
+          acc[n] = mma16([&](int r, int c) { return l0 + r < b1 && c < cn ? Zc[(l0 + r) * lz + c] : 0.f; },
+                         [&](int c, int v) { return c < cn && v0 + v < d ? Kc[c * ld + v0 + v] : 0.f; }, cn,
+                         acc[n], lane);
         }
       }
     } else {
@@ -237,20 +237,26 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
         cinv[tid] = 1.0f / s;      // s >= 1: the column maximum contributes exp(0)
       }
       __syncthreads();
-      for (int idx = tid; idx < cn * d; idx += kThreads) {
-        const int c = idx / d, v = idx - c * d;
-        float s = 0.f;
-        for (int l = 0; l < b1; ++l) s = fmaf(Zc[l * lz + c], Qj[l * ld + v], s);
-        aRout[((size_t)(c0 + c) * b2 + j) * d + v] = s * cinv[c];
-      }
+      gemm_tiles(cn, d, b1,
+                 [&](int c, int l) { return c < cn && l < b1 ? Zc[l * lz + c] : 0.f; },
+                 [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
+                 [&](int c, int v, float x) { aRout[((size_t)(c0 + c) * b2 + j) * d + v] = x * cinv[c]; }, tid);
     }
   }
-  if (LAST && vt < d) {
+  if (LAST) {
     TIn* Op = (TIn*)p.O + b * p.os.batch + hd * p.os.head;
+    const int li = lane & 15, lq = lane >> 4;
 #pragma unroll
-    for (int r = 0; r < kMaxRows; ++r) {
-      const int l = lg + r * ngroups;
-      if (l < b1) stf(Op + qtok(l) * p.os.token + vt, acc[r]);
+    for (int n = 0; n < kMaxTiles; ++n) {
+      const int t = wave + kWaves * n;
+      if (t < otiles) {
+        const int l0 = 16 * (t / tnv), v0 = 16 * (t % tnv);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int l = l0 + 4 * lq + r, v = v0 + li;
+          if (l < b1 && v < d) stf(Op + qtok(l) * p.os.token + v, acc[n][r]);
+        }
+      }
     }
   }
 }
