@@ -18,8 +18,8 @@ namespace mrt {
 
 namespace {
 
-constexpr int kMaxTiles = 24;  // 16x16 tiles of dQ[m, :, j, :] per wave (b1 <= 192, d <= 128, 4 waves)
-constexpr int kMaxAccT = 12;   // 16x16 tiles of dK / dV of one key block per wave (b2 <= 96, d <= 128)
+constexpr int kMaxTiles = 6;   // 16x16 tiles of dQ[m, :, j, :] per wave (b1 <= 192, d <= 128, 4 waves)
+constexpr int kMaxAccT = 3;    // 16x16 tiles of dK / dV of one key block per wave (b2 <= 96, d <= 128)
 
 template <typename T> __device__ inline float ldf(const T* p);
 template <> __device__ inline float ldf<float>(const float* p) { return *p; }

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_r(KParams p, int first, 
 // which is the same ratio and cannot underflow to 0/0.
 // ---------------------------------------------------------------------------------------
 constexpr int kCH = 16;     // nk rows per chunk
-constexpr int kMaxTiles = 24;  // 16x16 output tiles per wave in the last stage (b1 <= 192, d <= 128)
+constexpr int kMaxTiles = 6;   // 16x16 output tiles per wave in the last stage (b1 <= 192, d <= 128)
 
 template <typename TIn, bool LAST>
 __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {

@@ -7,7 +7,7 @@
 namespace mrt {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 1024;
 using f32x4 = float __attribute__((ext_vector_type(4)));
 constexpr int kWaves = kThreads / 64;
 
