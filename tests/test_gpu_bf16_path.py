@@ -165,6 +165,28 @@ def test_rerun_is_bit_identical():
     assert torch.equal(O1, O2)
 
 
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_tokens_major_layout_gives_the_same_bits(name):
+    # [batch, tokens, heads, d] memory (what a fused QKV projection leaves behind) viewed as
+    # [batch, heads, tokens, d]: only the element strides change
+    wl = syn.variant(name, heads=3)
+    Qd, Kd, Vd = to_device(wl, syn.make_inputs(wl))
+    Oc = run_monarch_gpu(wl, Qd, Kd, Vd)
+    Dc = run_dense_gpu(wl, Qd, Kd, Vd)
+    Qs, Ks, Vs = (x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for x in (Qd, Kd, Vd))
+    assert not Qs.is_contiguous() and Qs.stride(2) == 3 * wl.head_dim
+    out = torch.empty_like(Qs)
+    O = pkg.monarch_attn_fwd(Qs, Ks, Vs, f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2,
+                             tile=wl.tile, iters=wl.iters, causal_chunk=wl.causal_chunk,
+                             q_frame_offset=wl.q_frame_offset, scale=wl.scale, out=out)
+    D = pkg.dense_attn_fwd(Qs, Ks, Vs, f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w,
+                           causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset, scale=wl.scale,
+                           out=torch.empty_like(Qs))
+    torch.cuda.synchronize()
+    assert O.stride() == Qs.stride()
+    assert torch.equal(O, Oc) and torch.equal(D, Dc)
+
+
 def test_head_groups_do_not_change_the_result():
     # concurrent head groups on helper streams vs one group on the caller's stream: bit identical
     wl = syn.variant("C2", heads=5)
