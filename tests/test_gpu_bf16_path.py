@@ -118,6 +118,33 @@ def test_monarch_bf16_c4_sampled_heads():
     check(wl, arrays, O, heads=[0, 39], label="C4")
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_properties_that_hold_at_any_size(name):
+    """Every head of the large configurations, without the oracle: the factored matrix is
+    row-stochastic and independent of V, so (i) a constant V comes back unchanged (up to the
+    rounding of the probabilities) and (ii) the output is linear in V."""
+    wl = syn.WORKLOADS[name]
+    Qd, Kd, Vd = to_device(wl, syn.make_inputs(wl))
+    const = torch.full_like(Vd, 0.75)
+    Oc = run_monarch_gpu(wl, Qd, Kd, const).float()
+    assert torch.isfinite(Oc).all()
+    dev = (Oc - 0.75).abs().max().item()
+    print(f"  {name}: constant V deviates by {dev:.3e}", flush=True)
+    assert dev <= 1e-2
+    # linearity in V: negating V negates O up to the rounding of the matrix unit's accumulation
+    # (which is not exactly symmetric in sign), and scaling V by a power of two scales every
+    # product and every rounding boundary alike, so O scales exactly
+    O1 = run_monarch_gpu(wl, Qd, Kd, Vd).float()
+    O2 = run_monarch_gpu(wl, Qd, Kd, -Vd).float()
+    omax = O1.abs().max().item()
+    sym = (O1 + O2).abs().max().item()
+    print(f"  {name}: max |O(V) + O(-V)| = {sym:.3e} at max |O| = {omax:.3e}", flush=True)
+    assert sym <= 2.0 ** -7 * omax
+    O4 = run_monarch_gpu(wl, Qd, Kd, 4 * Vd).float()
+    assert torch.equal(4 * O1, O4)
+
+
 @pytest.mark.parametrize("name", ["C1", "C3"])
 def test_dense_bf16_named_configs_sampled(name):
     wl = syn.WORKLOADS[name]
