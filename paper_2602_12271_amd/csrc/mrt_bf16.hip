@@ -503,8 +503,12 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
       if (WITH_V) {
         pb[q][0] = pack8(s[q][0], s[q][1]);
         pb[q][1] = pack8(s[q][2], s[q][3]);
+        // once the running maxima have settled (after the first few chunks) alpha is 1 in every
+        // lane and the rescaling of the accumulators can be skipped for the whole wave
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) o[q][vt] = o[q][vt] * alpha;
+          for (int vt = 0; vt < NVT; ++vt) o[q][vt] = o[q][vt] * alpha;
+        }
       }
     }
   }
