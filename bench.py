@@ -198,7 +198,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(heads are independent and would shard without exchange, see DESIGN.md).",
+              "(heads are independent and would shard over GPUs without any exchange).",
               file=sys.stderr)
         sys.exit(2)
 
