@@ -195,13 +195,15 @@ def monarch_attn_fwd(Q, K, V, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_ch
 
 
 def monarch_attn_bwd(Q, K, V, dO, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,
-                     q_frame_offset=0, scale=1.0, workspace=None, stream=None, assign="fh_w", tile_h=0):
-    """Gradients (dQ, dK, dV), fp32, of sum(O * dO) for the forward call with the same arguments."""
+                     q_frame_offset=0, scale=1.0, workspace=None, stream=None, assign="fh_w", tile_h=0,
+                     compute=MRT_COMPUTE_DEFAULT):
+    """Gradients (dQ, dK, dV), fp32, of sum(O * dO) for the forward call with the same arguments.
+    compute=MRT_COMPUTE_F32 forces fp32 arithmetic everywhere (bf16 storage otherwise uses the bf16
+    matrix unit where the library has such kernels)."""
     import torch
     lib = load_library()
     assert dO.shape == Q.shape and dO.dtype == Q.dtype and dO.is_cuda
-    prob = _torch_problem(Q, K, V, dO, f_q, f_kv, h, w, q_frame_offset, scale, MRT_COMPUTE_DEFAULT, assign,
-                          tile_h)
+    prob = _torch_problem(Q, K, V, dO, f_q, f_kv, h, w, q_frame_offset, scale, compute, assign, tile_h)
     if workspace is None:
         nbytes = lib.monarch_attn_bwd_workspace_bytes(ctypes.byref(prob), b1, b2, tile, iters)
         if nbytes == 0:

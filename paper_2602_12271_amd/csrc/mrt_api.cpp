@@ -448,24 +448,32 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
 namespace {
 struct BwdLayout {
   size_t rowsD, rowsS;    // bytes of one [m][j][nk][d] / [m][j][nk] array of one head
+  size_t scratch;         // bytes of the matrix-unit kernels' own arrays of one head (0 if unused)
   size_t per_head;
   int T;
+  bool mfma;              // stage L backward runs on the bf16 matrix unit
   size_t off_aL(int t) const { return rowsD * (size_t)(t - 1); }                 // t = 1..T
   size_t off_aR(int t) const { return rowsD * (size_t)(T + t - 2); }             // t = 2..T
   size_t off_Y() const { return rowsD * (size_t)(2 * T - 1); }
   size_t off_daL() const { return rowsD * (size_t)(2 * T); }
   size_t off_dY() const { return rowsD * (size_t)(2 * T + 1); }
   size_t off_dA() const { return rowsD * (size_t)(2 * T + 2); }
-  size_t off_cL(int t) const { return rowsD * (size_t)(2 * T + 3) + rowsS * (size_t)(t - 1); }
-  size_t off_dcL() const { return rowsD * (size_t)(2 * T + 3) + rowsS * (size_t)T; }
+  size_t base_S() const { return rowsD * (size_t)(2 * T + 3); }
+  size_t off_cL(int t) const { return base_S() + rowsS * (size_t)(t - 1); }
+  size_t off_dcL() const { return base_S() + rowsS * (size_t)T; }
+  size_t off_cmx(int t) const { return base_S() + rowsS * (size_t)(T + t - 1); }        // t = 2..T
+  size_t off_cinv(int t) const { return base_S() + rowsS * (size_t)(2 * T + t - 2); }   // t = 2..T
+  size_t off_scratch() const { return base_S() + rowsS * (size_t)(3 * T - 1); }
 };
-BwdLayout bwd_layout(const mrt::Plan& pl) {
+BwdLayout bwd_layout(const mrt::Plan& pl, const mrt_problem* p) {
   BwdLayout L;
   const size_t rows = (size_t)pl.kp.c2 * pl.kp.b1 * pl.kp.b2 * pl.kp.ntk * pl.c1q;   // (m, j, nk) triples
   L.rowsD = mrt::round256(rows * pl.kp.d * sizeof(float));
   L.rowsS = mrt::round256(rows * sizeof(float));
   L.T = pl.T;
-  L.per_head = L.rowsD * (size_t)(2 * pl.T + 3) + L.rowsS * (size_t)(pl.T + 1);
+  L.mfma = p->dtype == MRT_BF16 && p->compute == MRT_COMPUTE_DEFAULT && mrt::bwd_bf16_fits(pl.kp);
+  L.scratch = L.mfma ? mrt::round256(mrt::bwd_bf16_scratch_bytes(pl.kp, pl.ntq_total)) : 0;
+  L.per_head = L.off_scratch() + L.scratch;
   return L;
 }
 mrt_status bwd_plan(const mrt_problem* p, int b1, int b2, int tile, int iters, int causal_chunk,
@@ -485,13 +493,13 @@ mrt_status bwd_plan(const mrt_problem* p, int b1, int b2, int tile, int iters, i
 size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
   mrt::Plan pl;
   if (bwd_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
-  return bwd_layout(pl).per_head;
+  return bwd_layout(pl, p).per_head;
 }
 
 size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
   mrt::Plan pl;
   if (bwd_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
-  const size_t per = bwd_layout(pl).per_head, budget = size_t(16) << 30;
+  const size_t per = bwd_layout(pl, p).per_head, budget = size_t(16) << 30;
   size_t heads = (size_t)pl.B * pl.kp.H;
   if (per * heads > budget) heads = budget / per > 0 ? budget / per : 1;
   return per * heads;
@@ -510,7 +518,12 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     return MRT_ERR_NULL;
   }
   if ((uintptr_t)workspace % 256) { set_error("workspace must be 256-byte aligned"); return MRT_ERR_WORKSPACE; }
-  const BwdLayout L = bwd_layout(pl);
+  const BwdLayout L = bwd_layout(pl, p);
+  if (L.mfma) {
+    const void* ptrs[2] = {Q, dO};
+    for (const void* q : ptrs)
+      if ((uintptr_t)q % 16) { set_error("bf16 path needs 16-byte aligned tensors"); return MRT_ERR_SHAPE; }
+  }
   if (workspace_bytes < L.per_head) {
     set_error("workspace has %zu bytes, the backward pass of one (batch,head) needs %zu", workspace_bytes,
               L.per_head);
@@ -539,6 +552,8 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
         return hip_fail(e, "backward: forward stage R launch");
       if (t < T) {
         kp.aR = arr(L.off_aR(t + 1));
+        kp.cmx_out = (float*)arr(L.off_cmx(t + 1));
+        kp.cinv_out = (float*)arr(L.off_cinv(t + 1));
         if ((e = launch_f32_stage_l(kp, pl.dtype, nbh, false, s)) != hipSuccess)
           return hip_fail(e, "backward: forward stage L launch");
       }
@@ -558,9 +573,12 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
       bp.k.aL = arr(L.off_aL(t));
       bp.k.cL = (float*)arr(L.off_cL(t));
       bp.Anext = last ? nullptr : (const float*)arr(L.off_aR(t + 1));
+      bp.cmx = last ? nullptr : (const float*)arr(L.off_cmx(t + 1));
+      bp.cinv = last ? nullptr : (const float*)arr(L.off_cinv(t + 1));
       bp.accumulate = last ? 0 : 1;
-      if ((e = launch_bwd_stage_l(bp, pl.dtype, nbh, last, s)) != hipSuccess)
-        return hip_fail(e, "backward stage L launch");
+      e = L.mfma ? launch_bwd_bf16_stage_l(bp, nbh, last, arr(L.off_scratch()), s)
+                 : launch_bwd_stage_l(bp, pl.dtype, nbh, last, s);
+      if (e != hipSuccess) return hip_fail(e, "backward stage L launch");
       bp.k.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
       if ((e = launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s)) != hipSuccess)
         return hip_fail(e, "backward stage R launch");

@@ -25,16 +25,11 @@
 //   stage L out  one workgroup per (m, j): flash loop over nk: L = softmax(Z_L), O = L Y
 //   stage L ref  one workgroup per (m, j): log-sum-exp pass over nk, then alpha_R / c_R
 #include "mrt_internal.hpp"
+#include "mrt_bf16_tiles.hpp"
 
 namespace mrt {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef unsigned short u16;
 
 // Optional timeline instrumentation (development builds only, -DMRT_TRACE): thread 0 of every
 // workgroup stamps the 100 MHz wall clock at phase boundaries into a caller-provided buffer.
@@ -51,189 +46,6 @@ __device__ unsigned long long* g_trace_buf = nullptr;
 #else
 #define MRT_STAMP(slot) do { } while (0)
 #endif
-
-constexpr int kPad = 16;   // bf16 elements of padding per LDS row: row stride = 8 banks mod 64
-
-__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-__device__ inline bf16x8 ld_global_16B(const u16* p) { return as_bf16x8(*(const uint4*)p); }
-
-__device__ inline bf16x8 ld_lds_16B(const u16* p) { return as_bf16x8(*(const uint4*)p); }
-
-// transposed LDS read: the 16 lanes of a group address 4 rows x 16 columns (lane s -> row s/4,
-// columns 4(s%4)..+3); lane c receives column c of those 4 rows.
-__device__ inline s16x4 ld_lds_tr(const u16* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)p);
-}
-
-__device__ inline u16 f2bf(float x) { return __builtin_bit_cast(u16, (__bf16)x); }
-
-__device__ inline bf16x8 pack8(f32x4 a, f32x4 b) {
-  bf16x8 r;
-  r[0] = (__bf16)a[0]; r[1] = (__bf16)a[1]; r[2] = (__bf16)a[2]; r[3] = (__bf16)a[3];
-  r[4] = (__bf16)b[0]; r[5] = (__bf16)b[1]; r[6] = (__bf16)b[2]; r[7] = (__bf16)b[3];
-  return r;
-}
-
-__device__ inline f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
-
-// Softmax arithmetic runs in the base-2 domain: logits are multiplied by scale*log2(e) (one
-// fma) and exponentiated with the hardware exp2, which saves a multiply per element.
-constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
-__device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
-__device__ inline float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
-
-__device__ inline float xmax(float x) {
-  x = fmaxf(x, __shfl_xor(x, 16));
-  return fmaxf(x, __shfl_xor(x, 32));
-}
-__device__ inline float xsum(float x) {
-  x += __shfl_xor(x, 16);
-  return x + __shfl_xor(x, 32);
-}
-
-// Second product for one 32-key step: acc[vt] += Val^T[phi(vt, .), keys] * P.
-// vals points at LDS row `32*step` of a row-major [rows][D + kPad] tile; output feature of
-// accumulator row (4g + r) of tile vt is phi = 32(vt/2) + 8g + 4(vt%2) + r.
-template <int D, int LD = D + kPad>
-__device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane) {
-  constexpr int NVT = D / 16, HALF = NVT / 2;
-  const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
-  const u16* base = vals + (4 * g + e) * LD + 8 * q;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    s16x4 lo[HALF], hi[HALF];
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      const int vt = h * HALF + i;
-      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
-      lo[i] = ld_lds_tr(p0);
-      hi[i] = ld_lds_tr(p0 + 16 * LD);
-    }
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      s16x8 a = __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7);
-      acc[h * HALF + i] = mfma(__builtin_bit_cast(bf16x8, a), pb, acc[h * HALF + i]);
-    }
-  }
-}
-
-// Same for NB probability operands sharing every value-side LDS read (operands >= nb idle).
-template <int D, int NB, int LD = D + kPad>
-__device__ inline void pv_step_multi(const u16* vals, const bf16x8 (&pb)[NB], int nb,
-                                     f32x4 (&acc)[NB][D / 16], int lane) {
-  constexpr int NVT = D / 16, HALF = NVT / 2;
-  const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
-  const u16* base = vals + (4 * g + e) * LD + 8 * q;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    s16x4 lo[HALF], hi[HALF];
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      const int vt = h * HALF + i;
-      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
-      lo[i] = ld_lds_tr(p0);
-      hi[i] = ld_lds_tr(p0 + 16 * LD);
-    }
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      const bf16x8 av =
-          __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-      for (int b = 0; b < NB; ++b)
-        if (b < nb) acc[b][h * HALF + i] = mfma(av, pb[b], acc[b][h * HALF + i]);
-    }
-  }
-}
-
-// Store a lane's D/16 accumulator tiles (scaled) as bf16: 16 bytes per pair of tiles at
-// feature 32q + 8g.
-template <int D>
-__device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) {
-#pragma unroll
-  for (int q = 0; q < D / 32; ++q) {
-    bf16x8 o = pack8(acc[2 * q] * mul, acc[2 * q + 1] * mul);
-    *(uint4*)(row + 32 * q + 8 * g) = __builtin_bit_cast(uint4, o);
-  }
-}
-
-// Element offset of row r of a tile of a token-indexed tensor (Q, K, V, O): the tile's rows are
-// the block-grid indices x0 + r along one side of the block grid.
-struct TokRows {
-  long long base;      // tokens
-  AxisMap m;
-  int x0;
-  long long tstride;   // elements per token
-  __device__ inline long long operator()(int r) const { return (base + axis_offset(m, x0 + r)) * tstride; }
-};
-// Rows of tile row a: contiguous block-grid rows, or nh rows of each of the tile's frames.
-__device__ inline TokRows tile_rows(const KParams& p, int a, long long tstride) {
-  if (p.nh == 0) return TokRows{0, p.rmap, a * p.b1, tstride};
-  const int fa = a / p.nhb, ha = a - fa * p.nhb;
-  return TokRows{(long long)fa * p.tf_tok + (long long)ha * p.th_tok, AxisMap{p.nh, p.hw, p.rmap.lo}, 0,
-                 tstride};
-}
-// Rows at a fixed stride (the intermediates in the workspace).
-struct PlainRows {
-  long long stride;
-  __device__ inline long long operator()(int r) const { return (long long)r * stride; }
-};
-
-// Cooperative copy of `rows` rows of D bf16 (row r at src + rowoff(r)) into a row-major LDS tile,
-// zero-filling rows >= valid.
-template <int D, int LD = D + kPad, typename RowFn>
-__device__ inline void stage_rows(u16* dst, const u16* src, RowFn rowoff, int rows, int valid,
-                                  int tid, int nthr) {
-  constexpr int CPR = D / 8;
-  for (int idx = tid; idx < rows * CPR; idx += nthr) {
-    const int r = idx / CPR, c = idx - r * CPR;
-    uint4 v = {0u, 0u, 0u, 0u};
-    if (r < valid) v = *(const uint4*)(src + rowoff(r) + 8 * c);
-    *(uint4*)(dst + r * LD + 8 * c) = v;
-  }
-}
-
-// Same copy with compile-time extents, split into its two halves: load() issues every global
-// load of the tile (rows beyond `valid` re-read the last valid row), store() writes the tile to
-// LDS and zero-fills the missing rows.  A thread has all its loads in flight at once instead of
-// one round trip per row, and other loads can be issued between the two calls.
-template <int D, int ROWS, int NTHR>
-struct RowRegs {
-  static constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
-  uint4 v[N];
-  int valid;
-  template <typename RowFn>
-  __device__ inline void load(const u16* src, RowFn rowoff, int nvalid, int tid) {
-    valid = nvalid;
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      int idx = tid + i * NTHR;
-      idx = idx < TOTAL ? idx : TOTAL - 1;
-      int r = idx / CPR;
-      const int c = idx - r * CPR;
-      r = r < nvalid ? r : nvalid - 1;
-      v[i] = *(const uint4*)(src + rowoff(r) + 8 * c);
-    }
-  }
-  template <int LD>
-  __device__ inline void store(u16* dst, int tid) const {
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int idx = tid + i * NTHR;
-      const int r = idx / CPR, c = idx - r * CPR;
-      if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
-    }
-  }
-};
-
-template <int D, int LD, int ROWS, int NTHR, typename RowFn>
-__device__ inline void stage_rows_batched(u16* dst, const u16* src, RowFn rowoff, int valid, int tid) {
-  RowRegs<D, ROWS, NTHR> r;
-  r.load(src, rowoff, valid, tid);
-  r.template store<LD>(dst, tid);
-}
 
 // ---------------------------------------------------------------------------------------
 // stage R

@@ -1,0 +1,394 @@
+// Backward pass on the bf16 matrix unit for short key ranges (NK = visible key tiles * b1 <= 96,
+// b1 <= 96: regular Monarch at the 4680-token chunk, small tiles): bf16 MFMA operands, fp32
+// accumulation and fp32 softmax arithmetic, same register layouts as the forward kernels
+// (mrt_bf16.hip).  The workspace arrays stay fp32 (shared with the fp32 kernels of
+// mrt_bwd_f32.hip, which remain the path for every other shape and for fp32 storage); operands are
+// rounded to bf16 when they are staged into LDS.
+//
+// Stage L backward is split in two kernels per (m, j):
+//   rows kernel  (lanes own query rows l):  L, dL, delta, dZ;  dQ[l] += scale dZ aL (+ w dA);
+//                writes L (or w) and dZ transposed, as bf16 [nk][l], for the second kernel
+//   cols kernel  (lanes own key rows nk):   d aL[nk] = scale sum_l dZ[l,nk] Q[l],
+//                d cL[nk] = -sum_l dZ[l,nk], d Y[nk] = sum_l L[l,nk] dO[l]
+// so that every contraction has its summation index on the K side of an MFMA.
+#include "mrt_internal.hpp"
+#include "mrt_bf16_tiles.hpp"
+
+namespace mrt {
+
+namespace {
+
+constexpr int kBRows = 96;     // key rows / query rows held in LDS
+constexpr int kBPad = 8;       // row padding of the LDS tiles (as the forward resident kernels)
+constexpr int kLP = 96;        // row pitch (elements) of the transposed L / dZ arrays
+
+// fp32 rows -> bf16 LDS tile: row r of the tile comes from src + rowoff(r); rows >= valid are zero.
+template <int D, int LD, int ROWS, int NTHR, typename RowFn>
+__device__ inline void stage_rows_f32(u16* dst, const float* src, RowFn rowoff, int valid, int tid) {
+  constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
+  f32x4 lo[N], hi[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    int idx = tid + i * NTHR;
+    idx = idx < TOTAL ? idx : TOTAL - 1;
+    int r = idx / CPR;
+    const int c = idx - r * CPR;
+    r = r < valid ? r : valid - 1;
+    const float* p = src + rowoff(r) + 8 * c;
+    lo[i] = *(const f32x4*)p;
+    hi[i] = *(const f32x4*)(p + 4);
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const int idx = tid + i * NTHR;
+    const int r = idx / CPR, c = idx - r * CPR;
+    if (idx < TOTAL) {
+      const bf16x8 v = pack8(lo[i], hi[i]);
+      *(uint4*)(dst + r * LD + 8 * c) = r < valid ? __builtin_bit_cast(uint4, v) : uint4{0u, 0u, 0u, 0u};
+    }
+  }
+}
+
+// S^T tiles of one query tile against NTK resident row tiles: out[kt][r] = rows[16kt + 4g + r] . q
+template <int D, int NTK, int LD>
+__device__ inline void rows_dot(const u16* rows, const bf16x8 (&qv)[D / 32], f32x4 (&out)[NTK], int lane) {
+  constexpr int KS1 = D / 32;
+  const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int kt = 0; kt < NTK; ++kt) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks)
+      acc = mfma(ld_lds_16B(rows + (16 * kt + c) * LD + 32 * ks + 8 * g), qv[ks], acc);
+    out[kt] = acc;
+    if (kt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Second-product step with the contraction slots in natural order (slot (g, e) <-> row 8g + e of
+// the 32-row step), for B operands that come from memory rather than from accumulator registers.
+template <int D, int NB, int LD>
+__device__ inline void pv_step_nat(const u16* vals, const bf16x8 (&pb)[NB], int nb,
+                                   f32x4 (&acc)[NB][D / 16], int lane) {
+  constexpr int NVT = D / 16, HALF = NVT / 2;
+  const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
+  const u16* base = vals + (8 * g + e) * LD + 8 * q;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    s16x4 lo[HALF], hi[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const int vt = h * HALF + i;
+      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+      lo[i] = ld_lds_tr(p0);
+      hi[i] = ld_lds_tr(p0 + 4 * LD);
+    }
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const bf16x8 av =
+          __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        if (b < nb) acc[b][h * HALF + i] = mfma(av, pb[b], acc[b][h * HALF + i]);
+    }
+  }
+}
+
+// A lane's D/16 accumulator tiles as fp32: 8 consecutive features at 32q + 8g per pair of tiles.
+template <int D>
+__device__ inline void store_rows_f32(float* row, const f32x4* acc, float mul, int g, bool add) {
+#pragma unroll
+  for (int q = 0; q < D / 32; ++q) {
+    f32x4* p = (f32x4*)(row + 32 * q + 8 * g);
+    f32x4 a = acc[2 * q] * mul, b = acc[2 * q + 1] * mul;
+    if (add) { a += p[0]; b += p[1]; }
+    p[0] = a;
+    p[1] = b;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// stage L backward, rows kernel, one workgroup per (m, j)
+// ---------------------------------------------------------------------------------------
+template <int D, int NTK, bool LAST>
+__global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u16* Zw) {
+  const KParams& p = bp.k;
+  constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];    // alpha_L rows
+  __shared__ __attribute__((aligned(16))) u16 Vs[ROWS * LD];    // Y rows (LAST) or d abar rows
+  __shared__ __attribute__((aligned(16))) float bias[ROWS];     // -c_L log2(e), -inf beyond NK
+  __shared__ __attribute__((aligned(16))) float tcs[ROWS];      // d abar . abar                  (not LAST)
+  __shared__ __attribute__((aligned(16))) float cms[ROWS];      // max_l log2 L[l, nk]            (not LAST)
+  __shared__ __attribute__((aligned(16))) float cis[ROWS];      // 1 / sum_l 2^(log2 L - max)     (not LAST)
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2, d = D;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 16 * NTK
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const int nlt = (b1 + 15) >> 4;
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const float* aLp = (const float*)p.aL + row0 * d;
+  const float* Yp = (const float*)p.Y + row0 * d;
+  const float* cLp = p.cL + row0;
+  // rows (nk, j) of the [m][nk][j][d] arrays
+  const size_t arow0 = ((size_t)bhl * p.ntq + ml) * NKtot * b2;
+  auto arow = [&](int nk) { return (long long)((arow0 + (size_t)nk * b2 + j) * d); };
+  const long long qcol = axis_offset(p.cmap, bq * b2 + j);
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qcol * p.qs.token;
+  const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
+
+  stage_rows_f32<D, LD, ROWS, 256>(Ks, aLp, PlainRows{D}, NK, tid);
+  if (LAST) stage_rows_f32<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
+  else stage_rows_f32<D, LD, ROWS, 256>(Vs, bp.dA, arow, NK, tid);
+  for (int i = tid; i < ROWS; i += 256) {
+    bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+    if (!LAST) {
+      float t = 0.f, cm = 0.f, ci = 0.f;
+      if (i < NK) {
+        const float* da = bp.dA + arow(i);
+        const float* ab = bp.Anext + arow(i);
+        for (int v = 0; v < D; ++v) t = fmaf(da[v], ab[v], t);
+        const size_t at = arow0 + (size_t)i * b2 + j;
+        cm = bp.cmx[at] * kLog2e;
+        ci = bp.cinv[at];
+      }
+      tcs[i] = t;
+      cms[i] = cm;
+      cis[i] = ci;
+    }
+  }
+  __syncthreads();
+
+  const float scale2 = p.scale * kLog2e;
+  float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
+  u16* Pt = Pw + row0 * kLP;
+  u16* Zt = Zw + row0 * kLP;
+  // the cols kernel reads query rows in steps of 32: an odd tile count leaves one tile of zeros
+  for (int lt = wave; lt < 2 * ((nlt + 1) / 2); lt += 4) {
+    const int l = 16 * lt + c;
+    if (lt >= nlt) {
+      for (int nk = g; nk < NK; nk += 4) {
+        Pt[(size_t)nk * kLP + l] = 0;
+        Zt[(size_t)nk * kLP + l] = 0;
+      }
+      continue;
+    }
+    const int lc = l < b1 ? l : b1 - 1;
+    bf16x8 qv[KS1], xv[KS1];
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) {
+      qv[ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
+      xv[ks] = LAST ? ld_global_16B(dOp + orow(lc) + 32 * ks + 8 * g) : qv[ks];
+    }
+    f32x4 s[NTK], dl[NTK], z[NTK];
+    rows_dot<D, NTK, LD>(Ks, qv, s, lane);
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) z[kt] = s[kt];              // raw logits, for log2 L below
+    __builtin_amdgcn_sched_barrier(0);
+    rows_dot<D, NTK, LD>(Vs, xv, dl, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    // L = softmax over nk (exact: the whole key range is resident)
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) {
+      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
+        mx = fmaxf(mx, s[kt][r]);
+      }
+    }
+    mx = xmax(mx);
+    float sm = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[kt][r] = exp2_fast(s[kt][r] - mx);
+        sm += s[kt][r];
+      }
+    const float inv = 1.0f / xsum(sm);
+    const float lse2 = mx + log2_fast(xsum(sm));              // base-2 log-sum-exp of the row
+    const bool live = l < b1;                                  // rows beyond b1 contribute nothing
+    // s <- L; wq <- L (LAST) or w = L / sum_l L, formed as 2^(log2 L - column max) / column sum;
+    // dl <- L dL (LAST) or w u (else)
+    float delta = 0.f;
+    f32x4 wq[NTK];
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) {
+      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {0.f, 0.f, 0.f, 0.f}, tc = {0.f, 0.f, 0.f, 0.f};
+      if (!LAST) {
+        cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
+        ci = *(const f32x4*)(cis + 16 * kt + 4 * g);
+        tc = *(const f32x4*)(tcs + 16 * kt + 4 * g);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float logl = fmaf(z[kt][r], scale2, bi[r]) - lse2;           // log2 L, -inf beyond NK
+        const float L = live ? s[kt][r] * inv : 0.f;
+        s[kt][r] = L;
+        const float w = LAST ? L : (live ? exp2_fast(logl - cm[r]) * ci[r] : 0.f);
+        wq[kt][r] = w;
+        dl[kt][r] = w * (dl[kt][r] - tc[r]);
+        delta += dl[kt][r];
+      }
+    }
+    delta = xsum(delta);
+    // dZ, and the transposed copies for the cols kernel
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float dz = dl[kt][r] - s[kt][r] * delta;
+        dl[kt][r] = dz;
+        const int nk = 16 * kt + 4 * g + r;
+        if (nk < NK) {
+          Pt[(size_t)nk * kLP + l] = f2bf(wq[kt][r]);
+          Zt[(size_t)nk * kLP + l] = f2bf(dz);
+        }
+      }
+    __builtin_amdgcn_sched_barrier(0);
+    // dQ[l] = scale sum_nk dZ[l,nk] aL[nk] (+ sum_nk w[l,nk] dA[nk])
+    f32x4 o[NVT];
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      const bool has = 2 * st + 1 < NTK;
+      const bf16x8 pz = pack8(dl[2 * st] * p.scale, has ? dl[has ? 2 * st + 1 : 0] * p.scale : zero);
+      pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!LAST) {
+        const bf16x8 pw = pack8(wq[2 * st], has ? wq[has ? 2 * st + 1 : 0] : zero);
+        pv_step<D, LD>(Vs + 32 * st * LD, pw, o, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    if (l < b1) store_rows_f32<D>(dQp + (row_offset(p, a, l) + qcol) * d, o, 1.0f, g, bp.accumulate != 0);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// stage L backward, cols kernel, one workgroup per (m, j)
+// ---------------------------------------------------------------------------------------
+template <int D, int NLT, bool LAST>
+__global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16* Pw, const u16* Zw) {
+  const KParams& p = bp.k;
+  constexpr int LD = D + kBPad, NVT = D / 16, KS2 = (NLT + 1) / 2, QROWS = 32 * KS2;
+  __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
+  __shared__ __attribute__((aligned(16))) u16 Xs[LAST ? QROWS * LD : 8];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2, d = D;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const int nkt = (NK + 15) >> 4;
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const long long qcol = axis_offset(p.cmap, bq * b2 + j);
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qcol * p.qs.token;
+  const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
+  stage_rows_batched<D, LD, QROWS, 256>(Qs, Qp, tile_rows(p, a, p.qs.token), b1, tid);
+  if (LAST) stage_rows_batched<D, LD, QROWS, 256>(Xs, dOp, tile_rows(p, a, p.os.token), b1, tid);
+  __syncthreads();
+
+  const u16* Pt = Pw + row0 * kLP;
+  const u16* Zt = Zw + row0 * kLP;
+  for (int kt = wave; kt < nkt; kt += 4) {
+    const int nk = 16 * kt + c;
+    const int nkc = nk < NK ? nk : NK - 1;
+    bf16x8 zb[1][KS2];
+    float zsum = 0.f;
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      zb[0][st] = ld_global_16B(Zt + (size_t)nkc * kLP + 32 * st + 8 * g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) zsum += (float)zb[0][st][e];
+    }
+    zsum = xsum(zsum);
+    if (g == 0 && nk < NK) bp.dcL[row0 + nk] = -zsum;
+    f32x4 o[1][NVT];
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      const bf16x8 one[1] = {zb[0][st]};
+      pv_step_nat<D, 1, LD>(Qs + 32 * st * LD, one, 1, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (nk < NK) store_rows_f32<D>(bp.daL + (row0 + nk) * d, o[0], p.scale, g, false);
+    if (LAST) {
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) {
+        const bf16x8 one[1] = {ld_global_16B(Pt + (size_t)nkc * kLP + 32 * st + 8 * g)};
+        pv_step_nat<D, 1, LD>(Xs + 32 * st * LD, one, 1, o, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (nk < NK) store_rows_f32<D>(bp.dY + (row0 + nk) * d, o[0], 1.0f, g, false);
+    }
+  }
+}
+
+}  // namespace
+
+bool bwd_bf16_fits(const KParams& kp) {
+  return kp.ntk * kp.b1 <= kBRows && kp.b1 <= kBRows && (kp.d == 64 || kp.d == 128);
+}
+size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total) {
+  // the transposed L and dZ arrays: (m, j, nk) rows of kLP bf16 each, two arrays
+  return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * kLP * 2 * 2;
+}
+
+template <int D, bool LAST>
+static hipError_t launch_rows(const BwdParams& bp, dim3 grid, int nkt, u16* Pw, u16* Zw, hipStream_t s) {
+  switch (nkt) {
+    case 1: case 2: k_bwdm_l_rows<D, 2, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 3: case 4: k_bwdm_l_rows<D, 4, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 5: case 6: k_bwdm_l_rows<D, 6, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+template <int D, bool LAST>
+static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16* Pw, const u16* Zw,
+                              hipStream_t s) {
+  switch (nlt) {
+    case 1: case 2: k_bwdm_l_cols<D, 2, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 3: case 4: k_bwdm_l_cols<D, 4, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 5: case 6: k_bwdm_l_cols<D, 6, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// Stage L backward on the matrix unit; scratch = bwd_bf16_scratch_bytes() of device memory.
+hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, void* scratch, hipStream_t s) {
+  const KParams& kp = bp.k;
+  dim3 grid(kp.b2, kp.ntq, nbh);
+  const int nkt = (kp.ntk * kp.b1 + 15) / 16, nlt = (kp.b1 + 15) / 16;
+  u16* Pw = (u16*)scratch;
+  u16* Zw = Pw + (size_t)nbh * kp.ntq * kp.b2 * kp.ntk * kp.b1 * kLP;
+  hipError_t e;
+  if (kp.d == 128) {
+    e = last ? launch_rows<128, true>(bp, grid, nkt, Pw, Zw, s) : launch_rows<128, false>(bp, grid, nkt, Pw, Zw, s);
+    if (e != hipSuccess) return e;
+    return last ? launch_cols<128, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<128, false>(bp, grid, nlt, Pw, Zw, s);
+  }
+  e = last ? launch_rows<64, true>(bp, grid, nkt, Pw, Zw, s) : launch_rows<64, false>(bp, grid, nkt, Pw, Zw, s);
+  if (e != hipSuccess) return e;
+  return last ? launch_cols<64, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<64, false>(bp, grid, nlt, Pw, Zw, s);
+}
+
+}  // namespace mrt

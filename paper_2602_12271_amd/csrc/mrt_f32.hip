@@ -235,6 +235,11 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
         float s = 0.f;
         for (int l = 0; l < b1; ++l) s += Zc[l * lz + tid];
         cinv[tid] = 1.0f / s;      // s >= 1: the column maximum contributes exp(0)
+        if (p.cmx_out) {
+          const size_t at = ((size_t)bhl * p.ntq + ml) * NKtot * b2 + (size_t)(c0 + tid) * b2 + j;
+          p.cmx_out[at] = cmx[tid];
+          p.cinv_out[at] = cinv[tid];
+        }
       }
       __syncthreads();
       gemm_tiles(cn, d, b1,

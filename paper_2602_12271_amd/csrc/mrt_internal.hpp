@@ -37,6 +37,8 @@ struct KParams {
   void* Y;      // Y       [bh][m][j][nk][d]
   void* aR;     // alpha_R / c_R  [bh][m][nk][j][d]
   float* cL;    // c_L     [bh][m][j][nk]
+  float* cmx_out;   // optional outputs of the fp32 stage L (earlier iterations): column maximum of
+  float* cinv_out;  //   log L and inverse column sum behind alpha_R / c_R   [bh][m][nk][j]
   int H;        // heads (to split the flat batch*head index)
   int bh0;      // first flat (batch,head) index of this pass
   int d;
@@ -85,6 +87,8 @@ struct BwdParams {
   KParams k;
   const void* dO;       // storage dtype, strides k.os
   const float* Anext;   // abar of iteration t+1   [bh][m][nk][j][d]   (stage L backward, t < T)
+  const float* cmx;     // max_l log L[l, nk] and 1 / sum_l exp(log L - max) of the L that formed
+  const float* cinv;    //   abar of iteration t+1   [bh][m][nk][j]     (matrix-unit stage L backward)
   float* dA;            // d abar: stage L backward (t < T) reads that of t+1, stage R backward writes that of t
   float* daL;           // [bh][m][j][nk][d]
   float* dcL;           // [bh][m][j][nk]
@@ -120,6 +124,11 @@ hipError_t launch_bwd_stage_l(const BwdParams& bp, int dtype, int nbh, bool last
 hipError_t launch_bwd_stage_r(const BwdParams& bp, int dtype, int nbh, bool first, bool last,
                               hipStream_t s);
 hipError_t launch_bwd_q_first(const BwdParams& bp, int nbh, hipStream_t s);
+
+// backward pass on the bf16 matrix unit for short key ranges (mrt_bwd_bf16.hip)
+bool bwd_bf16_fits(const KParams& kp);
+size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total);
+hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, void* scratch, hipStream_t s);
 
 // bf16 MFMA path (mrt_bf16.hip)
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s);
