@@ -173,11 +173,16 @@ def test_backward_entry_checks_on_the_host():
     lib = pkg.load_library()
     p = problem()
     ref = ctypes.byref(p)
-    # one head: alpha_L and c_L of T iterations, abar of T-1, Y, and four gradient buffers, all fp32
+    # one head, fp32: alpha_L and c_L of T iterations, abar and its two column statistics of T-1, Y,
+    # four gradient buffers; bf16 storage with default arithmetic adds the transposed L / dZ arrays
+    # of the matrix-unit kernels (two bf16 arrays of 96 columns per (m, j, nk) row)
     n, d, T = 4680, 128, 2
     per_head = lib.monarch_attn_bwd_workspace_min_bytes(ref, 90, 52, 0, T)
-    want = (2 * T + 3) * n * d * 4 + (T + 1) * n * 4
-    assert want <= per_head <= want + 12 * 256
+    want = (2 * T + 3) * n * d * 4 + (3 * T - 1) * n * 4 + 2 * n * 96 * 2
+    assert want <= per_head <= want + 16 * 256
+    pf = problem(compute=B.MRT_COMPUTE_F32)
+    per_head_f32 = lib.monarch_attn_bwd_workspace_min_bytes(ctypes.byref(pf), 90, 52, 0, T)
+    assert want - 2 * n * 96 * 2 <= per_head_f32 <= want - 2 * n * 96 * 2 + 16 * 256
     assert lib.monarch_attn_bwd_workspace_bytes(ref, 90, 52, 0, T) == 12 * per_head
     # block sizes whose buffers do not fit on chip, and invalid blocks, give 0
     big = problem(heads=40, f_kv=21, h=45, w=80, q_frame_offset=18)
