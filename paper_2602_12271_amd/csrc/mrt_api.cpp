@@ -530,6 +530,7 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     return MRT_ERR_WORKSPACE;
   }
   const int BH = pl.B * pl.kp.H, T = pl.T;
+  const bool bf16_ops = p->dtype == MRT_BF16 && p->compute == MRT_COMPUTE_DEFAULT;
   const int G = (int)(workspace_bytes / L.per_head < (size_t)BH ? workspace_bytes / L.per_head : (size_t)BH);
   hipStream_t s = (hipStream_t)hip_stream;
   char* base = (char*)workspace;
@@ -580,8 +581,9 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
                  : launch_bwd_stage_l(bp, pl.dtype, nbh, last, s);
       if (e != hipSuccess) return hip_fail(e, "backward stage L launch");
       bp.k.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
-      if ((e = launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s)) != hipSuccess)
-        return hip_fail(e, "backward stage R launch");
+      e = (bf16_ops && bwd_bf16_r_fits(bp.k)) ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, s)
+                                              : launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s);
+      if (e != hipSuccess) return hip_fail(e, "backward stage R launch");
     }
     if ((e = launch_bwd_q_first(bp, nbh, s)) != hipSuccess) return hip_fail(e, "backward dQ launch");
   }

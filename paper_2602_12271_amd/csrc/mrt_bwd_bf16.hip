@@ -341,6 +341,171 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// stage R backward, one workgroup (NT waves) per key block (n, k), looping over the query tiles m
+// that see it.  Wave w owns query columns j = 16w + c for the softmax side (as the forward stage R)
+// and key rows i = 16w + c for the dK / dV accumulation, whose contraction runs over j: R and
+// scale dS pass through LDS transposed ([i][j], bf16) in between.
+// ---------------------------------------------------------------------------------------
+template <int NT, int D, bool LAST>
+__global__ __launch_bounds__(64 * NT, 1) void k_bwdm_r(BwdParams bp, int first) {
+  const KParams& p = bp.k;
+  constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NT + 1) / 2, ROWS = 32 * KS2;
+  constexpr int LR = ROWS + 8, NTHR = 64 * NT;
+  __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];              // K[n, k, i, :]
+  __shared__ __attribute__((aligned(16))) u16 Vs[LAST ? ROWS * LD : 8];   // V[n, k, i, :]
+  __shared__ __attribute__((aligned(16))) u16 As[ROWS * LD];              // abar[m, n, k, j, :]
+  __shared__ __attribute__((aligned(16))) u16 Gs[ROWS * LD];              // d alpha_L[m, n, j, k, :]
+  __shared__ __attribute__((aligned(16))) u16 Ys[LAST ? ROWS * LD : 8];   // d Y[m, n, j, k, :]
+  __shared__ __attribute__((aligned(16))) u16 RT[ROWS * LR];              // R[j, i] as [i][j]
+  __shared__ __attribute__((aligned(16))) u16 ST[ROWS * LR];              // scale dS[j, i] as [i][j]
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2, d = D;
+  const int nk = blockIdx.x, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int n = nk / b1, k = nk - n * b1;
+  const int an = n / p.c2, bn = n - an * p.c2;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const size_t NKtot = (size_t)p.ntk * b1;
+
+  const long long krow = row_offset(p, an, k);
+  const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + krow * p.ks.token;
+  const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + krow * p.vs.token;
+  const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
+  stage_rows_batched<D, LD, ROWS, NTHR>(Ks, Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
+  if (LAST) stage_rows_batched<D, LD, ROWS, NTHR>(Vs, Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
+  for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
+
+  const int j = 16 * wave + c;                  // query column (softmax side) / key row (dK side)
+  const float scale2 = p.scale * kLog2e;
+  f32x4 oK[1][NVT], oV[1][NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) {
+    oK[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int ml = 0; ml < p.ntq; ++ml) {
+    const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
+    if (an >= visible_key_tile_rows(a, p.c1k, p.ct, p.qt0)) continue;   // uniform per workgroup
+    // rows (j, nk) of the [m][j][nk][..] arrays and the (m, nk) block of the [m][nk][j][d] arrays
+    const size_t jrow0 = ((size_t)bhl * p.ntq + ml) * b2;
+    auto jrow = [&](int jj) { return (long long)(((jrow0 + jj) * NKtot + nk) * d); };
+    const size_t ablk = (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2;
+    __syncthreads();                               // the previous tile's reads of As / Gs / Ys / RT / ST
+    if (first) {
+      const long long qrow = row_offset(p, a, k);
+      stage_rows_batched<D, LD, ROWS, NTHR>(As, Qbase + qrow * p.qs.token,
+                                            TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
+    } else {
+      stage_rows_f32<D, LD, ROWS, NTHR>(As, (const float*)p.aR + ablk * d, PlainRows{D}, b2, tid);
+    }
+    stage_rows_f32<D, LD, ROWS, NTHR>(Gs, bp.daL, jrow, b2, tid);
+    if (LAST) stage_rows_f32<D, LD, ROWS, NTHR>(Ys, bp.dY, jrow, b2, tid);
+    __syncthreads();
+
+    // ---- softmax side: lanes own query column j
+    {
+      const bool live = j < b2;
+      bf16x8 qv[KS1], gv[KS1], yv[KS1];
+#pragma unroll
+      for (int ks = 0; ks < KS1; ++ks) {
+        qv[ks] = ld_lds_16B(As + j * LD + 32 * ks + 8 * g);
+        gv[ks] = ld_lds_16B(Gs + j * LD + 32 * ks + 8 * g);
+        if (LAST) yv[ks] = ld_lds_16B(Ys + j * LD + 32 * ks + 8 * g);
+      }
+      const float dcl = live ? bp.dcL[(jrow0 + j) * NKtot + nk] : 0.f;
+      f32x4 s[NT], dr[NT];
+      rows_dot<D, NT, LD>(Ks, qv, s, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      rows_dot<D, NT, LD>(Ks, gv, dr, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if (LAST) {
+        f32x4 dy[NT];
+        rows_dot<D, NT, LD>(Vs, yv, dy, lane);
+#pragma unroll
+        for (int it = 0; it < NT; ++it) dr[it] += dy[it];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int it = 0; it < NT; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool ok = 16 * it + 4 * g + r < b2;
+          s[it][r] = ok ? s[it][r] * scale2 : -INFINITY;
+          mx = fmaxf(mx, s[it][r]);
+        }
+      mx = xmax(mx);
+      float sum = 0.f;
+#pragma unroll
+      for (int it = 0; it < NT; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sum += exp2_fast(s[it][r] - mx);
+      const float lse2 = mx + log2_fast(xsum(sum));
+      // R, dR (with the entropy term), dS
+      float dot = 0.f;
+#pragma unroll
+      for (int it = 0; it < NT; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool ok = live && 16 * it + 4 * g + r < b2;
+          const float logr2 = s[it][r] - lse2;                     // log2 R, -inf beyond b2
+          const float R = ok ? exp2_fast(logr2) : 0.f;
+          const float dR = ok ? dr[it][r] + dcl * fmaf(logr2, kLn2, 1.0f) : 0.f;
+          s[it][r] = R;
+          dr[it][r] = dR;
+          dot = fmaf(R, dR, dot);
+        }
+      dot = xsum(dot);
+#pragma unroll
+      for (int it = 0; it < NT; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float ds = p.scale * s[it][r] * (dr[it][r] - dot);   // scale dS
+          dr[it][r] = ds;
+          const int i = 16 * it + 4 * g + r;
+          RT[i * LR + j] = f2bf(s[it][r]);
+          ST[i * LR + j] = f2bf(ds);
+        }
+      // d abar[j] = sum_i (scale dS[j, i]) K[i]
+      f32x4 o[NVT];
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        const bool has = 2 * st + 1 < NT;
+        const bf16x8 pz = pack8(dr[2 * st], has ? dr[has ? 2 * st + 1 : 0] : zero);
+        pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (live) store_rows_f32<D>(bp.dA + (ablk + j) * d, o, 1.0f, g, false);
+    }
+    __syncthreads();                               // RT / ST complete
+
+    // ---- accumulation side: lanes own key row i = j
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      const bf16x8 bR[1] = {ld_lds_16B(RT + j * LR + 32 * st + 8 * g)};
+      const bf16x8 bS[1] = {ld_lds_16B(ST + j * LR + 32 * st + 8 * g)};
+      pv_step_nat<D, 1, LD>(Gs + 32 * st * LD, bR, 1, oK, lane);     // dK += R^T d alpha_L
+      __builtin_amdgcn_sched_barrier(0);
+      pv_step_nat<D, 1, LD>(As + 32 * st * LD, bS, 1, oK, lane);     // dK += scale dS^T abar
+      __builtin_amdgcn_sched_barrier(0);
+      if (LAST) {
+        pv_step_nat<D, 1, LD>(Ys + 32 * st * LD, bR, 1, oV, lane);   // dV += R^T d Y
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+  if (j < b2) {
+    const long long tok = krow + axis_offset(p.cmap, bn * b2 + j);
+    store_rows_f32<D>(bp.dK + ((size_t)bh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
+    if (LAST) store_rows_f32<D>(bp.dV + ((size_t)bh * p.Nkv + tok) * d, oV[0], 1.0f, g, false);
+  }
+}
+
 }  // namespace
 
 bool bwd_bf16_fits(const KParams& kp) {
@@ -371,6 +536,32 @@ static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+bool bwd_bf16_r_fits(const KParams& kp) { return kp.b2 <= 64 && (kp.d == 64 || kp.d == 128); }
+
+template <int NT, int D>
+static hipError_t launch_r_nt(const BwdParams& bp, dim3 grid, bool first, bool last, hipStream_t s) {
+  if (last) k_bwdm_r<NT, D, true><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
+  else k_bwdm_r<NT, D, false><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
+  return hipGetLastError();
+}
+template <int D>
+static hipError_t launch_r_d(const BwdParams& bp, dim3 grid, bool first, bool last, hipStream_t s) {
+  switch ((bp.k.b2 + 15) / 16) {
+    case 1: return launch_r_nt<1, D>(bp, grid, first, last, s);
+    case 2: return launch_r_nt<2, D>(bp, grid, first, last, s);
+    case 3: return launch_r_nt<3, D>(bp, grid, first, last, s);
+    case 4: return launch_r_nt<4, D>(bp, grid, first, last, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// Stage R backward on the matrix unit (b2 <= 64).
+hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, hipStream_t s) {
+  const KParams& kp = bp.k;
+  dim3 grid(kp.ntk * kp.b1, 1, nbh);
+  return kp.d == 128 ? launch_r_d<128>(bp, grid, first, last, s) : launch_r_d<64>(bp, grid, first, last, s);
 }
 
 // Stage L backward on the matrix unit; scratch = bwd_bf16_scratch_bytes() of device memory.

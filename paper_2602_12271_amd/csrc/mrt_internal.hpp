@@ -129,6 +129,8 @@ hipError_t launch_bwd_q_first(const BwdParams& bp, int nbh, hipStream_t s);
 bool bwd_bf16_fits(const KParams& kp);
 size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total);
 hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, void* scratch, hipStream_t s);
+bool bwd_bf16_r_fits(const KParams& kp);
+hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, hipStream_t s);
 
 // bf16 MFMA path (mrt_bf16.hip)
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s);

@@ -47,9 +47,9 @@ CASES = {
 
 
 def on_matrix_unit(wl):
-    """bf16 storage with a key range of at most 96 rows: stage L backward runs on the bf16 matrix unit
-    (bf16 operands, fp32 accumulation), everything else of the backward pass in fp32."""
-    return wl.dtype == "bf16" and wl.ntk * wl.b1 <= 96 and wl.b1 <= 96
+    """bf16 storage: stage L backward runs on the bf16 matrix unit (bf16 operands, fp32 accumulation)
+    when the key range has at most 96 rows, stage R backward when b2 <= 64; the rest stays fp32."""
+    return wl.dtype == "bf16" and ((wl.ntk * wl.b1 <= 96 and wl.b1 <= 96) or wl.b2 <= 64)
 
 
 def run_case(wl, heads=None, compute=None):
