@@ -531,6 +531,8 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
   }
   const int BH = pl.B * pl.kp.H, T = pl.T;
   const bool bf16_ops = p->dtype == MRT_BF16 && p->compute == MRT_COMPUTE_DEFAULT;
+  // every stage on the matrix unit: the forward intermediates can then be bf16 as well
+  const bool ws_bf16 = L.mfma && bwd_bf16_r_fits(pl.kp);
   const int G = (int)(workspace_bytes / L.per_head < (size_t)BH ? workspace_bytes / L.per_head : (size_t)BH);
   hipStream_t s = (hipStream_t)hip_stream;
   char* base = (char*)workspace;
@@ -544,21 +546,26 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     kp.bh0 = bh0; kp.m0 = 0; kp.ntq = pl.ntq_total;
     kp.Y = arr(L.off_Y());
     hipError_t e;
-    // forward intermediates of every iteration (the last iteration's stage L is not needed)
+    // forward intermediates of every iteration (the last iteration's stage L is not needed): by
+    // the bf16 forward kernels when every backward stage runs on the matrix unit (the arrays then
+    // hold bf16), else by the fp32 kernels
     for (int t = 1; t <= T; ++t) {
       kp.aL = arr(L.off_aL(t));
       kp.cL = (float*)arr(L.off_cL(t));
       kp.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
-      if ((e = launch_f32_stage_r(kp, pl.dtype, nbh, t == 1, t == T, s)) != hipSuccess)
-        return hip_fail(e, "backward: forward stage R launch");
+      kp.cmx_out = nullptr; kp.cinv_out = nullptr;
+      e = ws_bf16 ? launch_bf16_stage_r(kp, nbh, t == 1, t == T, s)
+                  : launch_f32_stage_r(kp, pl.dtype, nbh, t == 1, t == T, s);
+      if (e != hipSuccess) return hip_fail(e, "backward: forward stage R launch");
       if (t < T) {
         kp.aR = arr(L.off_aR(t + 1));
         kp.cmx_out = (float*)arr(L.off_cmx(t + 1));
         kp.cinv_out = (float*)arr(L.off_cinv(t + 1));
-        if ((e = launch_f32_stage_l(kp, pl.dtype, nbh, false, s)) != hipSuccess)
-          return hip_fail(e, "backward: forward stage L launch");
+        e = ws_bf16 ? launch_bf16_stage_l(kp, nbh, false, s) : launch_f32_stage_l(kp, pl.dtype, nbh, false, s);
+        if (e != hipSuccess) return hip_fail(e, "backward: forward stage L launch");
       }
     }
+    kp.cmx_out = nullptr; kp.cinv_out = nullptr;
     // reverse sweep
     BwdParams bp;
     memset(&bp, 0, sizeof(bp));
@@ -577,11 +584,11 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
       bp.cmx = last ? nullptr : (const float*)arr(L.off_cmx(t + 1));
       bp.cinv = last ? nullptr : (const float*)arr(L.off_cinv(t + 1));
       bp.accumulate = last ? 0 : 1;
-      e = L.mfma ? launch_bwd_bf16_stage_l(bp, nbh, last, arr(L.off_scratch()), s)
+      e = L.mfma ? launch_bwd_bf16_stage_l(bp, nbh, last, ws_bf16, arr(L.off_scratch()), s)
                  : launch_bwd_stage_l(bp, pl.dtype, nbh, last, s);
       if (e != hipSuccess) return hip_fail(e, "backward stage L launch");
       bp.k.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
-      e = (bf16_ops && bwd_bf16_r_fits(bp.k)) ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, s)
+      e = (bf16_ops && bwd_bf16_r_fits(bp.k)) ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, ws_bf16, s)
                                               : launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s);
       if (e != hipSuccess) return hip_fail(e, "backward stage R launch");
     }

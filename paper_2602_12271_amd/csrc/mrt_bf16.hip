@@ -641,8 +641,15 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
       const int nk = 16 * (PT * grp + pt) + c;
-      if (pt < npt && nk < NK)
+      if (pt < npt && nk < NK) {
         store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
+        // the backward pass rebuilds the weights as exp(log L - cmx) * cinv
+        if (p.cmx_out != nullptr && g == 0) {
+          const size_t at = (size_t)(aRout - (u16*)p.aR) / D + (size_t)nk * b2 + j;
+          p.cmx_out[at] = shift[pt] * kLn2;
+          p.cinv_out[at] = 1.0f / csum[pt];
+        }
+      }
     }
     if (grp == wave) MRT_STAMP(6);
   }

@@ -49,6 +49,18 @@ __device__ inline void stage_rows_f32(u16* dst, const float* src, RowFn rowoff, 
   }
 }
 
+// Rows of a workspace array into a bf16 LDS tile, whichever type the array is stored in.
+template <int D, int LD, int ROWS, int NTHR, typename RowFn>
+__device__ inline void stage_ws(u16* dst, const float* src, RowFn rowoff, int valid, int tid) {
+  stage_rows_f32<D, LD, ROWS, NTHR>(dst, src, rowoff, valid, tid);
+}
+template <int D, int LD, int ROWS, int NTHR, typename RowFn>
+__device__ inline void stage_ws(u16* dst, const u16* src, RowFn rowoff, int valid, int tid) {
+  stage_rows_batched<D, LD, ROWS, NTHR>(dst, src, rowoff, valid, tid);
+}
+__device__ inline float ldw(const float* p) { return *p; }
+__device__ inline float ldw(const u16* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+
 // S^T tiles of one query tile against NTK resident row tiles: out[kt][r] = rows[16kt + 4g + r] . q
 template <int D, int NTK, int LD>
 __device__ inline void rows_dot(const u16* rows, const bf16x8 (&qv)[D / 32], f32x4 (&out)[NTK], int lane) {
@@ -110,7 +122,9 @@ __device__ inline void store_rows_f32(float* row, const f32x4* acc, float mul, i
 // ---------------------------------------------------------------------------------------
 // stage L backward, rows kernel, one workgroup per (m, j)
 // ---------------------------------------------------------------------------------------
-template <int D, int NTK, bool LAST>
+// TW: storage type of the forward intermediates alpha_L, Y and abar in the workspace (fp32 when
+// the fp32 kernels recomputed them, bf16 when the bf16 forward kernels did).
+template <int D, int NTK, bool LAST, typename TW>
 __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u16* Zw) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
@@ -131,8 +145,8 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
   const int nlt = (b1 + 15) >> 4;
 
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
-  const float* aLp = (const float*)p.aL + row0 * d;
-  const float* Yp = (const float*)p.Y + row0 * d;
+  const TW* aLp = (const TW*)p.aL + row0 * d;
+  const TW* Yp = (const TW*)p.Y + row0 * d;
   const float* cLp = p.cL + row0;
   // rows (nk, j) of the [m][nk][j][d] arrays
   const size_t arow0 = ((size_t)bhl * p.ntq + ml) * NKtot * b2;
@@ -142,8 +156,8 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
   const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
   const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
 
-  stage_rows_f32<D, LD, ROWS, 256>(Ks, aLp, PlainRows{D}, NK, tid);
-  if (LAST) stage_rows_f32<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
+  stage_ws<D, LD, ROWS, 256>(Ks, aLp, PlainRows{D}, NK, tid);
+  if (LAST) stage_ws<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
   else stage_rows_f32<D, LD, ROWS, 256>(Vs, bp.dA, arow, NK, tid);
   for (int i = tid; i < ROWS; i += 256) {
     bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
@@ -151,8 +165,8 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
       float t = 0.f, cm = 0.f, ci = 0.f;
       if (i < NK) {
         const float* da = bp.dA + arow(i);
-        const float* ab = bp.Anext + arow(i);
-        for (int v = 0; v < D; ++v) t = fmaf(da[v], ab[v], t);
+        const TW* ab = (const TW*)bp.Anext + arow(i);
+        for (int v = 0; v < D; ++v) t = fmaf(da[v], ldw(ab + v), t);
         const size_t at = arow0 + (size_t)i * b2 + j;
         cm = bp.cmx[at] * kLog2e;
         ci = bp.cinv[at];
@@ -347,7 +361,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
 // and key rows i = 16w + c for the dK / dV accumulation, whose contraction runs over j: R and
 // scale dS pass through LDS transposed ([i][j], bf16) in between.
 // ---------------------------------------------------------------------------------------
-template <int NT, int D, bool LAST>
+template <int NT, int D, bool LAST, typename TW>
 __global__ __launch_bounds__(64 * NT, 1) void k_bwdm_r(BwdParams bp, int first) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NT + 1) / 2, ROWS = 32 * KS2;
@@ -398,7 +412,7 @@ __global__ __launch_bounds__(64 * NT, 1) void k_bwdm_r(BwdParams bp, int first) 
       stage_rows_batched<D, LD, ROWS, NTHR>(As, Qbase + qrow * p.qs.token,
                                             TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
     } else {
-      stage_rows_f32<D, LD, ROWS, NTHR>(As, (const float*)p.aR + ablk * d, PlainRows{D}, b2, tid);
+      stage_ws<D, LD, ROWS, NTHR>(As, (const TW*)p.aR + ablk * d, PlainRows{D}, b2, tid);
     }
     stage_rows_f32<D, LD, ROWS, NTHR>(Gs, bp.daL, jrow, b2, tid);
     if (LAST) stage_rows_f32<D, LD, ROWS, NTHR>(Ys, bp.dY, jrow, b2, tid);
@@ -516,12 +530,12 @@ size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total) {
   return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * kLP * 2 * 2;
 }
 
-template <int D, bool LAST>
+template <int D, bool LAST, typename TW>
 static hipError_t launch_rows(const BwdParams& bp, dim3 grid, int nkt, u16* Pw, u16* Zw, hipStream_t s) {
   switch (nkt) {
-    case 1: case 2: k_bwdm_l_rows<D, 2, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
-    case 3: case 4: k_bwdm_l_rows<D, 4, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
-    case 5: case 6: k_bwdm_l_rows<D, 6, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 1: case 2: k_bwdm_l_rows<D, 2, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 3: case 4: k_bwdm_l_rows<D, 4, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 5: case 6: k_bwdm_l_rows<D, 6, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -540,46 +554,56 @@ static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16
 
 bool bwd_bf16_r_fits(const KParams& kp) { return kp.b2 <= 64 && (kp.d == 64 || kp.d == 128); }
 
-template <int NT, int D>
+template <int NT, int D, typename TW>
 static hipError_t launch_r_nt(const BwdParams& bp, dim3 grid, bool first, bool last, hipStream_t s) {
-  if (last) k_bwdm_r<NT, D, true><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
-  else k_bwdm_r<NT, D, false><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
+  if (last) k_bwdm_r<NT, D, true, TW><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
+  else k_bwdm_r<NT, D, false, TW><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
   return hipGetLastError();
 }
-template <int D>
+template <int D, typename TW>
 static hipError_t launch_r_d(const BwdParams& bp, dim3 grid, bool first, bool last, hipStream_t s) {
   switch ((bp.k.b2 + 15) / 16) {
-    case 1: return launch_r_nt<1, D>(bp, grid, first, last, s);
-    case 2: return launch_r_nt<2, D>(bp, grid, first, last, s);
-    case 3: return launch_r_nt<3, D>(bp, grid, first, last, s);
-    case 4: return launch_r_nt<4, D>(bp, grid, first, last, s);
+    case 1: return launch_r_nt<1, D, TW>(bp, grid, first, last, s);
+    case 2: return launch_r_nt<2, D, TW>(bp, grid, first, last, s);
+    case 3: return launch_r_nt<3, D, TW>(bp, grid, first, last, s);
+    case 4: return launch_r_nt<4, D, TW>(bp, grid, first, last, s);
   }
   return hipErrorInvalidValue;
 }
 
-// Stage R backward on the matrix unit (b2 <= 64).
-hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, hipStream_t s) {
+// Stage R backward on the matrix unit (b2 <= 64).  ws_bf16: the forward intermediates in the
+// workspace are bf16 (written by the bf16 forward kernels) rather than fp32.
+hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, bool ws_bf16,
+                                   hipStream_t s) {
   const KParams& kp = bp.k;
   dim3 grid(kp.ntk * kp.b1, 1, nbh);
-  return kp.d == 128 ? launch_r_d<128>(bp, grid, first, last, s) : launch_r_d<64>(bp, grid, first, last, s);
+  if (ws_bf16)
+    return kp.d == 128 ? launch_r_d<128, u16>(bp, grid, first, last, s) : launch_r_d<64, u16>(bp, grid, first, last, s);
+  return kp.d == 128 ? launch_r_d<128, float>(bp, grid, first, last, s) : launch_r_d<64, float>(bp, grid, first, last, s);
 }
 
 // Stage L backward on the matrix unit; scratch = bwd_bf16_scratch_bytes() of device memory.
-hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, void* scratch, hipStream_t s) {
+template <int D, typename TW>
+static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, bool last, u16* Pw, u16* Zw,
+                             hipStream_t s) {
+  hipError_t e = last ? launch_rows<D, true, TW>(bp, grid, nkt, Pw, Zw, s)
+                      : launch_rows<D, false, TW>(bp, grid, nkt, Pw, Zw, s);
+  if (e != hipSuccess) return e;
+  return last ? launch_cols<D, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<D, false>(bp, grid, nlt, Pw, Zw, s);
+}
+
+hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, bool ws_bf16, void* scratch,
+                                   hipStream_t s) {
   const KParams& kp = bp.k;
   dim3 grid(kp.b2, kp.ntq, nbh);
   const int nkt = (kp.ntk * kp.b1 + 15) / 16, nlt = (kp.b1 + 15) / 16;
   u16* Pw = (u16*)scratch;
   u16* Zw = Pw + (size_t)nbh * kp.ntq * kp.b2 * kp.ntk * kp.b1 * kLP;
-  hipError_t e;
-  if (kp.d == 128) {
-    e = last ? launch_rows<128, true>(bp, grid, nkt, Pw, Zw, s) : launch_rows<128, false>(bp, grid, nkt, Pw, Zw, s);
-    if (e != hipSuccess) return e;
-    return last ? launch_cols<128, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<128, false>(bp, grid, nlt, Pw, Zw, s);
-  }
-  e = last ? launch_rows<64, true>(bp, grid, nkt, Pw, Zw, s) : launch_rows<64, false>(bp, grid, nkt, Pw, Zw, s);
-  if (e != hipSuccess) return e;
-  return last ? launch_cols<64, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<64, false>(bp, grid, nlt, Pw, Zw, s);
+  if (kp.d == 128)
+    return ws_bf16 ? launch_l_d<128, u16>(bp, grid, nkt, nlt, last, Pw, Zw, s)
+                   : launch_l_d<128, float>(bp, grid, nkt, nlt, last, Pw, Zw, s);
+  return ws_bf16 ? launch_l_d<64, u16>(bp, grid, nkt, nlt, last, Pw, Zw, s)
+                 : launch_l_d<64, float>(bp, grid, nkt, nlt, last, Pw, Zw, s);
 }
 
 }  // namespace mrt

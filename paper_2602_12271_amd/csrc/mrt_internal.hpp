@@ -128,9 +128,11 @@ hipError_t launch_bwd_q_first(const BwdParams& bp, int nbh, hipStream_t s);
 // backward pass on the bf16 matrix unit for short key ranges (mrt_bwd_bf16.hip)
 bool bwd_bf16_fits(const KParams& kp);
 size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total);
-hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, void* scratch, hipStream_t s);
+hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, bool ws_bf16, void* scratch,
+                                   hipStream_t s);
 bool bwd_bf16_r_fits(const KParams& kp);
-hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, hipStream_t s);
+hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, bool ws_bf16,
+                                   hipStream_t s);
 
 // bf16 MFMA path (mrt_bf16.hip)
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s);
