@@ -134,14 +134,20 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
  * (this is what Monarch finetuning trains through, Sec. 4.3).
  *   dO: device memory, storage type and element strides of O (p->o).  dQ [batch, heads, N_q,
  *   head_dim], dK and dV [batch, heads, N_kv, head_dim]: device memory, fp32, contiguous, fully
- *   overwritten.  The arithmetic is fp32 whatever p->dtype and p->compute say.  The forward
- *   intermediates of every iteration are recomputed into the workspace first (fp32), so nothing
- *   has to be kept from the forward call; the workspace holds whole (batch, head) entries and the
- *   library runs as many of them per pass as fit (workspace rules as for monarch_attn_fwd).
- *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers fit the 160 KB
- *   of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128), iters <= 16; otherwise
- *   MRT_ERR_UNSUPPORTED.  These kernels keep fp32 operands and use the fp32 matrix instructions;
- *   they are far from the tuning of the bf16 forward kernels. */
+ *   overwritten.  Arithmetic: with p->dtype = MRT_BF16 and p->compute = MRT_COMPUTE_DEFAULT the
+ *   contractions run on the bf16 matrix unit with fp32 accumulation wherever the blocks fit its
+ *   kernels (stage L backward: key range of a query tile, tile rows x b1, at most 96 and
+ *   head_dim 64 or 128; stage R backward: b2 <= 64; if both hold the forward intermediates are
+ *   recomputed by the bf16 forward kernels too) and Q, dO must be 16-byte aligned; everything
+ *   else, and every call with MRT_FP32 storage or MRT_COMPUTE_F32, runs in fp32.  Gradients of
+ *   the bf16 kernels differ from exact ones by up to about 2e-2 of the largest gradient entry, of
+ *   the fp32 kernels by 1e-4 of it.  The forward intermediates of every iteration are recomputed
+ *   into the workspace first, so nothing has to be kept from the forward call; the workspace
+ *   holds whole (batch, head) entries and the library runs as many of them per pass as fit
+ *   (workspace rules as for monarch_attn_fwd).
+ *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers of the fp32
+ *   kernels fit the 160 KB of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128),
+ *   iters <= 16; otherwise MRT_ERR_UNSUPPORTED. */
 size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
