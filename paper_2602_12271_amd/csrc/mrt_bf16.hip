@@ -160,30 +160,48 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
 
     __builtin_amdgcn_sched_barrier(0);
     // alpha_L = R K (and Y = R V)
-    f32x4 oK[NVT], oV[LAST ? NVT : 1];
-#pragma unroll
-    for (int vt = 0; vt < NVT; ++vt) {
-      oK[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if constexpr (LAST) oV[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    bf16x8 pb[KS2];
 #pragma unroll
     for (int st = 0; st < KS2; ++st) {
       const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
       const f32x4 lo = s[2 * st] * inv;
       const f32x4 hi = (2 * st + 1 < NT) ? s[(2 * st + 1 < NT) ? 2 * st + 1 : 0] * inv : zero;
-      const bf16x8 pb = pack8(lo, hi);
-      pv_step<D>(Ks + 32 * st * LD, pb, oK, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      if constexpr (LAST) {
-        pv_step<D>(Vs + 32 * st * LD, pb, oV, lane);
+      pb[st] = pack8(lo, hi);
+    }
+    if constexpr (!LAST) {
+      f32x4 oK[NVT];
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) oK[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) {
+        pv_step<D, LD>(Ks + 32 * st * LD, pb[st], oK, lane);
         __builtin_amdgcn_sched_barrier(0);
+      }
+      if (j < b2) store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
+    } else {
+      // both products, one half of the features at a time: the same interleaving of key-side and
+      // value-side steps with half the live accumulators
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        f32x4 oK[NVT / 2], oV[NVT / 2];
+#pragma unroll
+        for (int vt = 0; vt < NVT / 2; ++vt) {
+          oK[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          oV[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int st = 0; st < KS2; ++st) {
+          pv_step_half<D, LD>(Ks + 32 * st * LD, pb[st], oK, lane, h);
+          pv_step_half<D, LD>(Vs + 32 * st * LD, pb[st], oV, lane, h);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (j < b2) {
+          store_rows_half<D>((u16*)p.aL + row * D, oK, 1.0f, g, h);
+          store_rows_half<D>((u16*)p.Y + row * D, oV, 1.0f, g, h);
+        }
       }
     }
     if (ml == ml0) MRT_STAMP(2);
-    if (j < b2) {
-      store_rows<D>((u16*)p.aL + row * D, oK, 1.0f, g);
-      if constexpr (LAST) store_rows<D>((u16*)p.Y + row * D, oV, 1.0f, g);
-    }
   }
   MRT_STAMP(3);
 }
@@ -840,10 +858,17 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
     }
   };
   const int npairs = (nlt + QT - 1) / QT;
+  // every global load of the workgroup is issued before the first LDS store: one memory round
+  // trip instead of one per tile (the query rows, needed last, are requested last)
+  RowRegs<D, ROWS, 256> rk, rv;
+  rk.load(aLp, PlainRows{D}, NK, tid);
+  rv.load(Yp, PlainRows{D}, NK, tid);
+  static_assert(ROWS <= 256, "one bias value per thread");
+  const float cl = cLp[tid < NK ? tid : NK - 1];
   if (wave < npairs) load_q(wave);
-  stage_rows_batched<D, LD, ROWS, 256>(Ks, aLp, PlainRows{D}, NK, tid);
-  stage_rows_batched<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
-  for (int i = tid; i < ROWS; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+  rk.template store<LD>(Ks, tid);
+  rv.template store<LD>(Vs, tid);
+  if (tid < ROWS) bias[tid] = tid < NK ? -cl * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
 
@@ -909,9 +934,16 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_res(KParams p) {
   const float* cLp = p.cL + row0;
 
   MRT_STAMP(0);
-  stage_rows_batched<D, LD, QROWS, 256>(Qs, Qp, qrow, b1, tid);
-  stage_rows_batched<D, LD, kResRows, 256>(Ks, aLp, PlainRows{D}, NK, tid);
-  for (int i = tid; i < kResRows; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
+  // every global load of the workgroup is issued before the first LDS store
+  RowRegs<D, QROWS, 256> rq;
+  RowRegs<D, kResRows, 256> rk;
+  rq.load(Qp, qrow, b1, tid);
+  rk.load(aLp, PlainRows{D}, NK, tid);
+  static_assert(kResRows <= 256, "one bias value per thread");
+  const float cl = cLp[tid < NK ? tid : NK - 1];
+  rq.template store<LD>(Qs, tid);
+  rk.template store<LD>(Ks, tid);
+  if (tid < kResRows) bias[tid] = tid < NK ? -cl * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
 

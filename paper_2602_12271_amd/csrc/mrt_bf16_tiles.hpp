@@ -81,6 +81,28 @@ __device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane)
   }
 }
 
+// One half of pv_step: tiles h*D/32 .. (h+1)*D/32 - 1 (features 64h' .. of each 32-feature pair
+// group) into acc[0 .. D/32).
+template <int D, int LD = D + kPad>
+__device__ inline void pv_step_half(const u16* vals, bf16x8 pb, f32x4* acc, int lane, int h) {
+  constexpr int HALF = D / 32;
+  const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
+  const u16* base = vals + (4 * g + e) * LD + 8 * q;
+  s16x4 lo[HALF], hi[HALF];
+#pragma unroll
+  for (int i = 0; i < HALF; ++i) {
+    const int vt = h * HALF + i;
+    const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+    lo[i] = ld_lds_tr(p0);
+    hi[i] = ld_lds_tr(p0 + 16 * LD);
+  }
+#pragma unroll
+  for (int i = 0; i < HALF; ++i) {
+    s16x8 a = __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7);
+    acc[i] = mfma(__builtin_bit_cast(bf16x8, a), pb, acc[i]);
+  }
+}
+
 // Same for NB probability operands sharing every value-side LDS read (operands >= nb idle).
 template <int D, int NB, int LD = D + kPad>
 __device__ inline void pv_step_multi(const u16* vals, const bf16x8 (&pb)[NB], int nb,
@@ -117,6 +139,16 @@ __device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) 
   for (int q = 0; q < D / 32; ++q) {
     bf16x8 o = pack8(acc[2 * q] * mul, acc[2 * q + 1] * mul);
     *(uint4*)(row + 32 * q + 8 * g) = __builtin_bit_cast(uint4, o);
+  }
+}
+
+// Half h of such a row from the D/32 tiles pv_step_half accumulates.
+template <int D>
+__device__ inline void store_rows_half(u16* row, const f32x4* acc, float mul, int g, int h) {
+#pragma unroll
+  for (int q = 0; q < D / 64; ++q) {
+    bf16x8 o = pack8(acc[2 * q] * mul, acc[2 * q + 1] * mul);
+    *(uint4*)(row + 32 * (h * (D / 64) + q) + 8 * g) = __builtin_bit_cast(uint4, o);
   }
 }
 
