@@ -50,6 +50,41 @@ __device__ inline void stage_rows_f32(u16* dst, const float* src, RowFn rowoff, 
 }
 
 // Rows of a workspace array into a bf16 LDS tile, whichever type the array is stored in.
+// The same copy split into its two halves (see RowRegs): load() issues every global load,
+// store() converts and writes the tile.
+template <int D, int ROWS, int NTHR>
+struct RowRegsF32 {
+  static constexpr int CPR = D / 8, TOTAL = ROWS * CPR, N = (TOTAL + NTHR - 1) / NTHR;
+  f32x4 lo[N], hi[N];
+  int valid;
+  template <typename RowFn>
+  __device__ inline void load(const float* src, RowFn rowoff, int nvalid, int tid) {
+    valid = nvalid;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      int idx = tid + i * NTHR;
+      idx = idx < TOTAL ? idx : TOTAL - 1;
+      int r = idx / CPR;
+      const int c = idx - r * CPR;
+      r = r < nvalid ? r : nvalid - 1;
+      const float* p = src + rowoff(r) + 8 * c;
+      lo[i] = *(const f32x4*)p;
+      hi[i] = *(const f32x4*)(p + 4);
+    }
+  }
+  template <int LD>
+  __device__ inline void store(u16* dst, int tid) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int idx = tid + i * NTHR;
+      const int r = idx / CPR, c = idx - r * CPR;
+      if (idx < TOTAL) {
+        const bf16x8 v = pack8(lo[i], hi[i]);
+        *(uint4*)(dst + r * LD + 8 * c) = r < valid ? __builtin_bit_cast(uint4, v) : uint4{0u, 0u, 0u, 0u};
+      }
+    }
+  }
+};
 template <int D, int LD, int ROWS, int NTHR, typename RowFn>
 __device__ inline void stage_ws(u16* dst, const float* src, RowFn rowoff, int valid, int tid) {
   stage_rows_f32<D, LD, ROWS, NTHR>(dst, src, rowoff, valid, tid);
@@ -362,7 +397,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
 // scale dS pass through LDS transposed ([i][j], bf16) in between.
 // ---------------------------------------------------------------------------------------
 template <int NT, int D, bool LAST, typename TW>
-__global__ __launch_bounds__(64 * NT, 1) void k_bwdm_r(BwdParams bp, int first) {
+__global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, int first) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NT + 1) / 2, ROWS = 32 * KS2;
   constexpr int LR = ROWS + 8, NTHR = 64 * NT;
@@ -386,10 +421,6 @@ __global__ __launch_bounds__(64 * NT, 1) void k_bwdm_r(BwdParams bp, int first) 
   const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + krow * p.ks.token;
   const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + krow * p.vs.token;
   const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
-  stage_rows_batched<D, LD, ROWS, NTHR>(Ks, Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
-  if (LAST) stage_rows_batched<D, LD, ROWS, NTHR>(Vs, Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
-  for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
-
   const int j = 16 * wave + c;                  // query column (softmax side) / key row (dK side)
   const float scale2 = p.scale * kLog2e;
   f32x4 oK[1][NVT], oV[1][NVT];
@@ -399,23 +430,55 @@ __global__ __launch_bounds__(64 * NT, 1) void k_bwdm_r(BwdParams bp, int first) 
     oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int ml = 0; ml < p.ntq; ++ml) {
+  // the query tiles that do not see this key tile form a prefix (a later chunk sees more)
+  int ml0 = 0;
+  while (ml0 < p.ntq && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.ct, p.qt0)) ++ml0;
+
+  // register stages: every global load of a tile is issued before the first LDS store
+  constexpr bool kF32Ws = sizeof(TW) == 4;
+  RowRegs<D, ROWS, NTHR> ra;                          // Q rows, or abar stored as bf16
+  RowRegsF32<D, kF32Ws ? ROWS : 1, NTHR> raf;         // abar stored as fp32
+  RowRegsF32<D, ROWS, NTHR> rg;
+  RowRegsF32<D, LAST ? ROWS : 1, NTHR> ry;
+  auto issue = [&](int ml) {
     const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
-    if (an >= visible_key_tile_rows(a, p.c1k, p.ct, p.qt0)) continue;   // uniform per workgroup
-    // rows (j, nk) of the [m][j][nk][..] arrays and the (m, nk) block of the [m][nk][j][d] arrays
     const size_t jrow0 = ((size_t)bhl * p.ntq + ml) * b2;
     auto jrow = [&](int jj) { return (long long)(((jrow0 + jj) * NKtot + nk) * d); };
     const size_t ablk = (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2;
-    __syncthreads();                               // the previous tile's reads of As / Gs / Ys / RT / ST
     if (first) {
       const long long qrow = row_offset(p, a, k);
-      stage_rows_batched<D, LD, ROWS, NTHR>(As, Qbase + qrow * p.qs.token,
-                                            TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
+      ra.load(Qbase + qrow * p.qs.token, TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
+    } else if constexpr (kF32Ws) {
+      raf.load((const float*)p.aR + ablk * d, PlainRows{D}, b2, tid);
     } else {
-      stage_ws<D, LD, ROWS, NTHR>(As, (const TW*)p.aR + ablk * d, PlainRows{D}, b2, tid);
+      ra.load((const u16*)p.aR + ablk * d, PlainRows{D}, b2, tid);
     }
-    stage_rows_f32<D, LD, ROWS, NTHR>(Gs, bp.daL, jrow, b2, tid);
-    if (LAST) stage_rows_f32<D, LD, ROWS, NTHR>(Ys, bp.dY, jrow, b2, tid);
+    rg.load(bp.daL, jrow, b2, tid);
+    if (LAST) ry.load(bp.dY, jrow, b2, tid);
+  };
+  {
+    RowRegs<D, ROWS, NTHR> rk;
+    RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
+    rk.load(Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
+    if (LAST) rv.load(Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
+    if (ml0 < p.ntq) issue(ml0);
+    rk.template store<LD>(Ks, tid);
+    if (LAST) rv.template store<LD>(Vs, tid);
+  }
+  for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
+
+  for (int ml = ml0; ml < p.ntq; ++ml) {
+    // rows (j, nk) of the [m][j][nk][..] arrays and the (m, nk) block of the [m][nk][j][d] arrays
+    const size_t jrow0 = ((size_t)bhl * p.ntq + ml) * b2;
+    const size_t ablk = (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2;
+    if (ml > ml0) {
+      issue(ml);
+      __syncthreads();                             // the previous tile's reads of As / Gs / Ys / RT / ST
+    }
+    if (first || !kF32Ws) ra.template store<LD>(As, tid);
+    else raf.template store<LD>(As, tid);
+    rg.template store<LD>(Gs, tid);
+    if (LAST) ry.template store<LD>(Ys, tid);
     __syncthreads();
 
     // ---- softmax side: lanes own query column j
