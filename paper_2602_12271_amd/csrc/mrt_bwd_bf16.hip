@@ -325,6 +325,225 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
 }
 
 // ---------------------------------------------------------------------------------------
+// stage L backward, rows kernel for key ranges that do not fit LDS: one workgroup per (m, j),
+// wave w owns query tile w, the key range is streamed in segments of 64 rows, twice.  The first
+// sweep forms the row statistics online (running maximum and sum of the logits for the
+// log-sum-exp, and delta[l] = sum_c (L dL)[l, c] against a running maximum of its own, so that the
+// column shift of the weights never meets a positive exponent); the second sweep forms L (or w),
+// dZ and the dQ products with them.
+// ---------------------------------------------------------------------------------------
+constexpr int kSegTiles = 4, kSeg = 16 * kSegTiles;
+
+template <int D, bool LAST, typename TW>
+__global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16* Pw, u16* Zw) {
+  const KParams& p = bp.k;
+  constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, NTK = kSegTiles, KS2 = NTK / 2;
+  constexpr int CPR = D / 8, TOTAL = kSeg * CPR, NTMAX = 384, NI = (TOTAL + NTMAX - 1) / NTMAX;
+  __shared__ __attribute__((aligned(16))) u16 Ks[kSeg * LD];    // alpha_L rows of the segment
+  __shared__ __attribute__((aligned(16))) u16 Vs[kSeg * LD];    // Y rows (LAST) or d abar rows
+  __shared__ __attribute__((aligned(16))) float bias[kSeg];     // -c_L log2(e), -inf beyond NK
+  __shared__ __attribute__((aligned(16))) float tcs[kSeg];      // d abar . abar                  (not LAST)
+  __shared__ __attribute__((aligned(16))) float cms[kSeg];      // max_l log2 L[l, nk]            (not LAST)
+  __shared__ __attribute__((aligned(16))) float cis[kSeg];      // 1 / sum_l 2^(log2 L - max)     (not LAST)
+
+  constexpr int nthr = NTMAX;                  // launched with exactly this many threads
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2, d = D;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+  const int nlt = (b1 + 15) >> 4;
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const TW* aLp = (const TW*)p.aL + row0 * d;
+  const TW* Yp = (const TW*)p.Y + row0 * d;
+  const float* cLp = p.cL + row0;
+  // rows (nk, j) of the [m][nk][j][d] arrays
+  const size_t arow0 = ((size_t)bhl * p.ntq + ml) * NKtot * b2;
+  const long long qcol = axis_offset(p.cmap, bq * b2 + j);
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qcol * p.qs.token;
+  const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
+
+  // one segment of the key side into LDS; d abar . abar is formed on the way from the fp32 rows
+  auto stage = [&](int k0) {
+    const int valid = NK - k0 < kSeg ? NK - k0 : kSeg;
+    stage_ws<D, LD, kSeg, NTMAX>(Ks, aLp + (size_t)k0 * d, PlainRows{D}, valid, tid);
+    if (LAST) {
+      stage_ws<D, LD, kSeg, NTMAX>(Vs, Yp + (size_t)k0 * d, PlainRows{D}, valid, tid);
+    } else {
+      // D/8 consecutive lanes share a row: 8 features each
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        const int idx = tid + i * nthr;
+        const bool in = idx < TOTAL;
+        const int r = (in ? idx : TOTAL - 1) / CPR, ch = idx % CPR;
+        const bool ok = in && r < valid;
+        const size_t at = (arow0 + (size_t)(k0 + (ok ? r : 0)) * b2 + j) * d + 8 * ch;
+        f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
+        float t = 0.f;
+        if (ok) {
+          lo = *(const f32x4*)(bp.dA + at);
+          hi = *(const f32x4*)(bp.dA + at + 4);
+          const TW* ab = (const TW*)bp.Anext + at;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
+        }
+#pragma unroll
+        for (int sh = 1; sh < CPR; sh *= 2) t += __shfl_xor(t, sh);
+        if (in) {
+          *(uint4*)(Vs + r * LD + 8 * ch) = __builtin_bit_cast(uint4, pack8(lo, hi));
+          if (ch == 0) tcs[r] = t;
+        }
+      }
+    }
+    if (tid < kSeg) {
+      const int nk = k0 + tid;
+      const bool ok = nk < NK;
+      bias[tid] = ok ? -cLp[nk] * kLog2e : -INFINITY;
+      if (!LAST) {
+        const size_t at = arow0 + (size_t)(ok ? nk : 0) * b2 + j;
+        cms[tid] = ok ? bp.cmx[at] * kLog2e : 0.f;
+        cis[tid] = ok ? bp.cinv[at] : 0.f;
+      }
+    }
+  };
+
+  const int lt = wave, l = 16 * lt + c;
+  const bool tile_live = lt < nlt;           // an odd tile count leaves one wave that only writes zeros
+  const bool live = l < b1;
+  const int lc = l < b1 ? l : b1 - 1;
+  bf16x8 qv[KS1], xv[KS1];
+#pragma unroll
+  for (int ks = 0; ks < KS1; ++ks) {
+    qv[ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
+    xv[ks] = LAST ? ld_global_16B(dOp + orow(lc) + 32 * ks + 8 * g) : qv[ks];
+  }
+  const float scale2 = p.scale * kLog2e;
+
+  // ---- sweep 1: lse2[l] and delta[l]
+  float mz = -INFINITY, sz = 0.f;            // running maximum / sum of 2^(z - mz)
+  float mw = -INFINITY, dw = 0.f;            // the same for the shifted logits, weighted sum of u
+  for (int k0 = 0; k0 < NK; k0 += kSeg) {
+    __syncthreads();
+    stage(k0);
+    __syncthreads();
+    if (!tile_live) continue;
+    f32x4 s[NTK], dl[NTK];
+    rows_dot<D, NTK, LD>(Ks, qv, s, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    rows_dot<D, NTK, LD>(Vs, xv, dl, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    float mx = -INFINITY, mxw = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) {
+      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      f32x4 cm = {0.f, 0.f, 0.f, 0.f};
+      if (!LAST) cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
+        mx = fmaxf(mx, s[kt][r]);
+        if (!LAST) mxw = fmaxf(mxw, s[kt][r] - cm[r]);
+      }
+    }
+    const float mzn = fmaxf(mz, xmax(mx));
+    const float mwn = LAST ? mzn : fmaxf(mw, xmax(mxw));
+    float ps = 0.f, pd = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) {
+      f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {1.f, 1.f, 1.f, 1.f}, tc = {0.f, 0.f, 0.f, 0.f};
+      if (!LAST) {
+        cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
+        ci = *(const f32x4*)(cis + 16 * kt + 4 * g);
+        tc = *(const f32x4*)(tcs + 16 * kt + 4 * g);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float e = exp2_fast(s[kt][r] - mzn);
+        ps += e;
+        const float ew = LAST ? e : exp2_fast(s[kt][r] - cm[r] - mwn) * ci[r];
+        pd = fmaf(ew, dl[kt][r] - tc[r], pd);
+      }
+    }
+    sz = fmaf(sz, exp2_fast(mz - mzn), xsum(ps));
+    dw = fmaf(dw, exp2_fast((LAST ? mz : mw) - mwn), xsum(pd));
+    mz = mzn;
+    mw = mwn;
+  }
+  const float lse2 = mz + log2_fast(sz);
+  const float delta = dw * exp2_fast((LAST ? mz : mw) - lse2);
+
+  // ---- sweep 2: L (or w), dZ, their transposed copies, dQ
+  float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
+  u16* Pt = Pw + row0 * kLP;
+  u16* Zt = Zw + row0 * kLP;
+  f32x4 o[NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int k0 = 0; k0 < NK; k0 += kSeg) {
+    __syncthreads();
+    stage(k0);
+    __syncthreads();
+    if (!tile_live) {
+      // the cols kernel reads query rows in steps of 32: an odd tile count leaves one tile of zeros
+      if (lt < 2 * ((nlt + 1) / 2))
+        for (int nk = k0 + g; nk < NK && nk < k0 + kSeg; nk += 4) {
+          Pt[(size_t)nk * kLP + l] = 0;
+          Zt[(size_t)nk * kLP + l] = 0;
+        }
+      continue;
+    }
+    f32x4 s[NTK], dl[NTK], wq[NTK];
+    rows_dot<D, NTK, LD>(Ks, qv, s, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    rows_dot<D, NTK, LD>(Vs, xv, dl, lane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kt = 0; kt < NTK; ++kt) {
+      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {0.f, 0.f, 0.f, 0.f}, tc = {0.f, 0.f, 0.f, 0.f};
+      if (!LAST) {
+        cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
+        ci = *(const f32x4*)(cis + 16 * kt + 4 * g);
+        tc = *(const f32x4*)(tcs + 16 * kt + 4 * g);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float logl = fmaf(s[kt][r], scale2, bi[r]) - lse2;           // log2 L, -inf beyond NK
+        const float L = live ? exp2_fast(logl) : 0.f;
+        const float w = LAST ? L : (live ? exp2_fast(logl - cm[r]) * ci[r] : 0.f);
+        const float dz = w * (dl[kt][r] - tc[r]) - L * delta;
+        wq[kt][r] = w;
+        dl[kt][r] = dz;
+        const int nk = k0 + 16 * kt + 4 * g + r;
+        if (nk < NK) {
+          Pt[(size_t)nk * kLP + l] = f2bf(w);
+          Zt[(size_t)nk * kLP + l] = f2bf(dz);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // dQ[l] += scale sum_nk dZ[l,nk] aL[nk] (+ sum_nk w[l,nk] dA[nk])
+#pragma unroll
+    for (int st = 0; st < KS2; ++st) {
+      const bf16x8 pz = pack8(dl[2 * st] * p.scale, dl[2 * st + 1] * p.scale);
+      pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!LAST) {
+        const bf16x8 pw = pack8(wq[2 * st], wq[2 * st + 1]);
+        pv_step<D, LD>(Vs + 32 * st * LD, pw, o, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+  if (tile_live && live)
+    store_rows_f32<D>(dQp + (row_offset(p, a, l) + qcol) * d, o, 1.0f, g, bp.accumulate != 0);
+}
+
+// ---------------------------------------------------------------------------------------
 // stage L backward, cols kernel, one workgroup per (m, j)
 // ---------------------------------------------------------------------------------------
 template <int D, int NLT, bool LAST>
@@ -585,9 +804,7 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
 
 }  // namespace
 
-bool bwd_bf16_fits(const KParams& kp) {
-  return kp.ntk * kp.b1 <= kBRows && kp.b1 <= kBRows && (kp.d == 64 || kp.d == 128);
-}
+bool bwd_bf16_fits(const KParams& kp) { return kp.b1 <= kBRows && (kp.d == 64 || kp.d == 128); }
 size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total) {
   // the transposed L and dZ arrays: (m, j, nk) rows of kLP bf16 each, two arrays
   return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * kLP * 2 * 2;
@@ -649,8 +866,17 @@ hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, boo
 template <int D, typename TW>
 static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, bool last, u16* Pw, u16* Zw,
                              hipStream_t s) {
-  hipError_t e = last ? launch_rows<D, true, TW>(bp, grid, nkt, Pw, Zw, s)
-                      : launch_rows<D, false, TW>(bp, grid, nkt, Pw, Zw, s);
+  hipError_t e;
+  if (16 * nkt > kBRows) {
+    // key range beyond the resident kernel: streamed, one wave per query tile (six waves always:
+    // the staging loops are laid out for 384 threads)
+    if (last) k_bwdm_l_rows_stream<D, true, TW><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+    else k_bwdm_l_rows_stream<D, false, TW><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+    e = hipGetLastError();
+  } else {
+    e = last ? launch_rows<D, true, TW>(bp, grid, nkt, Pw, Zw, s)
+             : launch_rows<D, false, TW>(bp, grid, nkt, Pw, Zw, s);
+  }
   if (e != hipSuccess) return e;
   return last ? launch_cols<D, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<D, false>(bp, grid, nlt, Pw, Zw, s);
 }

@@ -43,13 +43,19 @@ CASES = {
     "bf16-ragged-T3": small("bf16", head_dim=128, f_q=2, f_kv=2, h=11, w=21, b1=22, b2=21, tile=0, iters=3),
     "bf16-d64-mask": small("bf16", head_dim=64, f_q=2, f_kv=6, h=4, w=12, b1=8, b2=6, tile=1, iters=2,
                            causal_chunk=2, q_frame_offset=2),
+    # key ranges beyond 96 rows: stage L backward streams them in segments of 64.  120 key rows of
+    # which the chunk-causal mask shows 80 (a ragged second segment), ragged query tiles
+    "bf16-stream-mask": small("bf16", head_dim=128, f_q=2, f_kv=6, h=10, w=14, b1=20, b2=7, tile=1, iters=2,
+                              causal_chunk=2, q_frame_offset=2),
+    # 216 key rows, three query tiles (the odd tile count leaves a zero tile), three iterations
+    "bf16-stream-T3": small("bf16", head_dim=64, f_q=2, f_kv=6, h=18, w=16, b1=36, b2=8, tile=1, iters=3),
 }
 
 
 def on_matrix_unit(wl):
     """bf16 storage: stage L backward runs on the bf16 matrix unit (bf16 operands, fp32 accumulation)
-    when the key range has at most 96 rows, stage R backward when b2 <= 64; the rest stays fp32."""
-    return wl.dtype == "bf16" and ((wl.ntk * wl.b1 <= 96 and wl.b1 <= 96) or wl.b2 <= 64)
+    when b1 <= 96, stage R backward when b2 <= 64; the rest stays fp32."""
+    return wl.dtype == "bf16" and (wl.b1 <= 96 or wl.b2 <= 64)
 
 
 def run_case(wl, heads=None, compute=None):
