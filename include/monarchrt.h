@@ -136,9 +136,9 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
  *   head_dim], dK and dV [batch, heads, N_kv, head_dim]: device memory, fp32, contiguous, fully
  *   overwritten.  Arithmetic: with p->dtype = MRT_BF16 and p->compute = MRT_COMPUTE_DEFAULT the
  *   contractions run on the bf16 matrix unit with fp32 accumulation wherever the blocks fit its
- *   kernels (stage L backward: key range of a query tile, tile rows x b1, at most 96 and
- *   head_dim 64 or 128; stage R backward: b2 <= 64; if both hold the forward intermediates are
- *   recomputed by the bf16 forward kernels too) and Q, dO must be 16-byte aligned; everything
+ *   kernels (stage L backward: b1 <= 96 and head_dim 64 or 128, key ranges beyond 96 rows are
+ *   streamed; stage R backward: b2 <= 64; if both hold the forward intermediates are recomputed
+ *   by the bf16 forward kernels too) and Q, dO must be 16-byte aligned; everything
  *   else, and every call with MRT_FP32 storage or MRT_COMPUTE_F32, runs in fp32.  Gradients of
  *   the bf16 kernels differ from exact ones by up to about 2e-2 of the largest gradient entry, of
  *   the fp32 kernels by 1e-4 of it.  The forward intermediates of every iteration are recomputed
