@@ -33,16 +33,16 @@ MEASURED_TRAFFIC = {
     # (workload, kernel): (fetched bytes, written bytes) per launch, from the committed
     # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries (KiB counters x calibration factor x 1024)
     ("C1", "stage_R_first"): (28.9e6, 16.1e6),
-    ("C1", "stage_L_refine"): (30.6e6, 17.7e6),
+    ("C1", "stage_L_refine"): (29.3e6, 14.4e6),
     ("C1", "stage_R_last"): (43.3e6, 30.5e6),
     ("C1", "stage_L_out"): (43.6e6, 14.9e6),
     ("C2", "stage_R_first"): (43.3e6, 32.3e6),
-    ("C2", "stage_L_refine"): (84.0e6, 34.5e6),
-    ("C2", "stage_R_last"): (57.7e6, 61.3e6),
+    ("C2", "stage_L_refine"): (44.0e6, 28.8e6),
+    ("C2", "stage_R_last"): (57.7e6, 61.2e6),
     ("C2", "stage_L_out"): (72.7e6, 14.4e6),
-    ("C3", "stage_R_first"): (103.0e6, 144.3e6),
-    ("C3", "stage_L_refine"): (267.4e6, 127.1e6),
-    ("C3", "stage_R_last"): (254.5e6, 272.4e6),
+    ("C3", "stage_R_first"): (102.9e6, 144.3e6),
+    ("C3", "stage_L_refine"): (267.5e6, 127.2e6),
+    ("C3", "stage_R_last"): (254.5e6, 271.8e6),
     ("C3", "stage_L_out"): (265.5e6, 9.1e6),
 }
 

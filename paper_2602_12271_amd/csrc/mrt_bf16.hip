@@ -531,6 +531,87 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   MRT_STAMP(2);
 }
 
+// Second half of a stage L refinement for PT key tiles (tile0 ...) of one (m, j) column, given
+// z = log2 L[l, nk] for every query tile: weights of the l-average, alpha_R / c_R = sum_l w Q,
+// stored as the next iteration's abar rows.
+template <int D, int NLT, int PT, int LD>
+__device__ inline void refine_finish(const KParams& p, const u16* Qs, f32x4 (&z)[PT][NLT], int npt, int tile0,
+                                     u16* aRout, int NK, int j, int lane, bool stamp) {
+  constexpr int NVT = D / 16;
+  const int g = lane >> 4, c = lane & 15;
+  const int b2 = p.b2;
+  if (stamp) MRT_STAMP(3);
+  // weights of the l-average: L[l, nk] itself; only if a whole column underflows in fp32 is the
+  // column maximum taken out first (the ratio alpha_R / c_R is unchanged by it)
+  float csum[PT], shift[PT];
+  bf16x8 pb[(NLT + 1) / 2][PT];
+  auto weigh = [&]() {
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      csum[pt] = 0.f;
+#pragma unroll
+      for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
+        f32x4 lo, hi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          lo[r] = exp2_fast(z[pt][2 * st2][r] - shift[pt]);
+          csum[pt] += lo[r];
+          if (2 * st2 + 1 < NLT) {
+            hi[r] = exp2_fast(z[pt][2 * st2 + 1 < NLT ? 2 * st2 + 1 : 0][r] - shift[pt]);
+            csum[pt] += hi[r];
+          }
+        }
+        pb[st2][pt] = pack8(lo, hi);
+      }
+      csum[pt] = xsum(csum[pt]);
+    }
+  };
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
+  weigh();
+  bool under = false;
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt) under |= (pt < npt && csum[pt] == 0.f);
+  if (__any(under)) {
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      float cm = -INFINITY;
+#pragma unroll
+      for (int lt = 0; lt < NLT; ++lt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) cm = fmaxf(cm, z[pt][lt][r]);
+      shift[pt] = xmax(cm);
+    }
+    weigh();
+  }
+  if (stamp) MRT_STAMP(4);
+  f32x4 o[PT][NVT];
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
+    pv_step_multi<D, PT, LD>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (stamp) MRT_STAMP(5);
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt) {
+    const int nk = 16 * (tile0 + pt) + c;
+    if (pt < npt && nk < NK) {
+      store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
+      // the backward pass rebuilds the weights as exp(log L - cmx) * cinv
+      if (p.cmx_out != nullptr && g == 0) {
+        const size_t at = (size_t)(aRout - (u16*)p.aR) / D + (size_t)nk * b2 + j;
+        p.cmx_out[at] = shift[pt] * kLn2;
+        p.cinv_out[at] = 1.0f / csum[pt];
+      }
+    }
+  }
+  if (stamp) MRT_STAMP(6);
+}
+
 // Pass 2 of the refine stage for one (m, j): waves stride over groups of PT adjacent 16-wide nk
 // tiles (every LDS read of Q serves all PT tiles).  Qs holds Q[m, :, j, :] row-major (rows >= b1
 // zero), lse the base-2 log-sum-exp of every row l.  When `resident`, alpha_L[m, j] and its
@@ -600,76 +681,7 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
       // keep the scheduler from hoisting every tile's operand reads to the top (register blow-up)
       if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
-    if (grp == wave) MRT_STAMP(3);
-    // weights of the l-average: L[l, nk] itself; only if a whole column underflows in fp32 is the
-    // column maximum taken out first (the ratio alpha_R / c_R is unchanged by it)
-    float csum[PT], shift[PT];
-    bf16x8 pb[(NLT + 1) / 2][PT];
-    auto weigh = [&]() {
-#pragma unroll
-      for (int pt = 0; pt < PT; ++pt) {
-        csum[pt] = 0.f;
-#pragma unroll
-        for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
-          f32x4 lo, hi = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            lo[r] = exp2_fast(z[pt][2 * st2][r] - shift[pt]);
-            csum[pt] += lo[r];
-            if (2 * st2 + 1 < NLT) {
-              hi[r] = exp2_fast(z[pt][2 * st2 + 1 < NLT ? 2 * st2 + 1 : 0][r] - shift[pt]);
-              csum[pt] += hi[r];
-            }
-          }
-          pb[st2][pt] = pack8(lo, hi);
-        }
-        csum[pt] = xsum(csum[pt]);
-      }
-    };
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
-    weigh();
-    bool under = false;
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt) under |= (pt < npt && csum[pt] == 0.f);
-    if (__any(under)) {
-#pragma unroll
-      for (int pt = 0; pt < PT; ++pt) {
-        float cm = -INFINITY;
-#pragma unroll
-        for (int lt = 0; lt < NLT; ++lt)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) cm = fmaxf(cm, z[pt][lt][r]);
-        shift[pt] = xmax(cm);
-      }
-      weigh();
-    }
-    if (grp == wave) MRT_STAMP(4);
-    f32x4 o[PT][NVT];
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-      for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
-      pv_step_multi<D, PT, LD>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (grp == wave) MRT_STAMP(5);
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt) {
-      const int nk = 16 * (PT * grp + pt) + c;
-      if (pt < npt && nk < NK) {
-        store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
-        // the backward pass rebuilds the weights as exp(log L - cmx) * cinv
-        if (p.cmx_out != nullptr && g == 0) {
-          const size_t at = (size_t)(aRout - (u16*)p.aR) / D + (size_t)nk * b2 + j;
-          p.cmx_out[at] = shift[pt] * kLn2;
-          p.cinv_out[at] = 1.0f / csum[pt];
-        }
-      }
-    }
-    if (grp == wave) MRT_STAMP(6);
+    refine_finish<D, NLT, PT, LD>(p, Qs, z, npt, PT * grp, aRout, NK, j, lane, grp == wave);
   }
 }
 
@@ -908,105 +920,142 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   MRT_STAMP(2);
 }
 
-template <int D, int NLT>
-__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_res(KParams p) {
-  constexpr int LD = D + kResPad, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), NTKMAX = kResRows / 16;
-  __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
-  __shared__ __attribute__((aligned(16))) u16 Ks[kResRows * LD];
-  __shared__ __attribute__((aligned(16))) float bias[kResRows];
-  __shared__ __attribute__((aligned(16))) float lse[16 * NLT];
+// Maximum / sum over the 16 lanes that share lane >> 4 (one accumulator row of an MFMA tile):
+// data-parallel-primitive moves (pairs, quads, mirrored halves of 8, mirrored 16), no LDS traffic.
+template <int CTRL>
+__device__ inline float dpp_mov(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+__device__ inline float row16_max(float x) {
+  x = fmaxf(x, dpp_mov<0xB1>(x));    // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp_mov<0x4E>(x));    // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp_mov<0x141>(x));   // row_half_mirror
+  return fmaxf(x, dpp_mov<0x140>(x));  // row_mirror
+}
+__device__ inline float row16_sum(float x) {
+  x += dpp_mov<0xB1>(x);
+  x += dpp_mov<0x4E>(x);
+  x += dpp_mov<0x141>(x);
+  return x + dpp_mov<0x140>(x);
+}
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
-  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
+// Stage L of an earlier iteration for key ranges of at most 64 PT rows, in one pass over the
+// logits: wave w owns key tiles PT w .. PT w + PT - 1 and forms their logits against every query
+// tile once, with queries on the accumulator rows.  The row statistics of the joint softmax over
+// the key range are reduced inside the wave and exchanged between the four waves through LDS;
+// alpha_L goes from global memory straight into the matrix operands, only Q is staged.
+template <int D, int NLT, int PT>
+__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_one(KParams p) {
+  constexpr int LD = D + kResPad, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), LROWS = 16 * NLT;
+  __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
+  __shared__ __attribute__((aligned(16))) float red_m[4][LROWS];
+  __shared__ __attribute__((aligned(16))) float red_s[4][LROWS];
+  __shared__ __attribute__((aligned(16))) float lse[LROWS];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= kResRows
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 64 * PT
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
-  const int nkt = (NK + 15) >> 4;
 
-  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
-  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);
+  const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
   const float* cLp = p.cL + row0;
 
   MRT_STAMP(0);
-  // every global load of the workgroup is issued before the first LDS store
+  const int tile0 = PT * wave;
+  const int ntiles = (NK + 15) >> 4;
+  const int npt = ntiles - tile0 < PT ? (ntiles - tile0 > 0 ? ntiles - tile0 : 0) : PT;
   RowRegs<D, QROWS, 256> rq;
-  RowRegs<D, kResRows, 256> rk;
   rq.load(Qp, qrow, b1, tid);
-  rk.load(aLp, PlainRows{D}, NK, tid);
-  static_assert(kResRows <= 256, "one bias value per thread");
-  const float cl = cLp[tid < NK ? tid : NK - 1];
+  bf16x8 kb[PT][KS1];
+  float cl[PT];
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt) {
+    const int nk = 16 * (tile0 + pt) + c;
+    const int nkc = nk < NK ? nk : NK - 1;
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) kb[pt][ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
+    cl[pt] = cLp[nkc] * kLog2e;
+  }
   rq.template store<LD>(Qs, tid);
-  rk.template store<LD>(Ks, tid);
-  if (tid < kResRows) bias[tid] = tid < NK ? -cl * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
 
-  // ---- pass 1: base-2 log-sum-exp of every query row over the resident keys; a wave takes two
-  // query tiles at a time so that every key operand read from LDS feeds two MFMAs
+  // logits in the base-2 domain: rows 4g + r are queries, column c is key 16 (tile0 + pt) + c
   const float scale2 = p.scale * kLog2e;
-  constexpr int QT = 2, NPAIRS = (NLT + QT - 1) / QT;
-  for (int pair = wave; pair < NPAIRS; pair += nwaves) {
-    const int nq = NLT - QT * pair < QT ? NLT - QT * pair : QT;
-    bf16x8 qv[QT][KS1];
+  f32x4 z[PT][NLT];
 #pragma unroll
-    for (int q = 0; q < QT; ++q) {
-      const int lt = QT * pair + q < NLT ? QT * pair + q : NLT - 1;
+  for (int lt = 0; lt < NLT; ++lt) {
+    bf16x8 av[KS1];
 #pragma unroll
-      for (int ks = 0; ks < KS1; ++ks) qv[q][ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
-    }
-    float mx[QT];
-    f32x4 s[QT][NTKMAX];
+    for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
 #pragma unroll
-    for (int q = 0; q < QT; ++q) mx[q] = -INFINITY;
+    for (int pt = 0; pt < PT; ++pt) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      if (pt < npt) {
 #pragma unroll
-    for (int kt = 0; kt < NTKMAX; ++kt) {
-#pragma unroll
-      for (int q = 0; q < QT; ++q) s[q][kt] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      if (kt < nkt) {
-        bf16x8 av[KS1];
-#pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Ks + (16 * kt + c) * LD + 32 * ks + 8 * g);
-        const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
-#pragma unroll
-        for (int q = 0; q < QT; ++q) {
-          if (q < nq) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], qv[q][ks], acc);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              acc[r] = fmaf(acc[r], scale2, bi[r]);
-              mx[q] = fmaxf(mx[q], acc[r]);
-            }
-            s[q][kt] = acc;
-          }
-        }
+        for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
       }
+      const bool col = 16 * (tile0 + pt) + c < NK;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] = col ? fmaf(acc[r], scale2, -cl[pt]) : -INFINITY;
+      z[pt][lt] = acc;
     }
+    if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+  }
+  // this wave's share of every query row's maximum and sum
 #pragma unroll
-    for (int q = 0; q < QT; ++q) {
-      const float m2 = xmax(mx[q]);
-      float sum = 0.f;
+  for (int lt = 0; lt < NLT; ++lt) {
+    f32x4 mx, sm;
 #pragma unroll
-      for (int kt = 0; kt < NTKMAX; ++kt)
+    for (int r = 0; r < 4; ++r) {
+      float v = z[0][lt][r];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sum += exp2_fast(s[q][kt][r] - m2);
-      sum = xsum(sum);
-      if (q < nq && g == 0) lse[16 * (QT * pair + q) + c] = m2 + log2_fast(sum);
+      for (int pt = 1; pt < PT; ++pt) v = fmaxf(v, z[pt][lt][r]);
+      v = row16_max(v);
+      const float ref = v == -INFINITY ? 0.f : v;
+      float e = 0.f;
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) e += exp2_fast(z[pt][lt][r] - ref);
+      mx[r] = v;
+      sm[r] = row16_sum(e);
+    }
+    if (c == 0) {
+      *(f32x4*)(&red_m[wave][16 * lt + 4 * g]) = mx;
+      *(f32x4*)(&red_s[wave][16 * lt + 4 * g]) = sm;
     }
   }
   __syncthreads();
+  if (tid < LROWS) {
+    float M = red_m[0][tid];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) M = fmaxf(M, red_m[w][tid]);
+    float S = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) S = fmaf(red_s[w][tid], exp2_fast(red_m[w][tid] - M), S);
+    lse[tid] = M + log2_fast(S);
+  }
+  __syncthreads();
   MRT_STAMP(2);
-
+#pragma unroll
+  for (int lt = 0; lt < NLT; ++lt) {
+    const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool ok = 16 * lt + 4 * g + r < b1;
+        z[pt][lt][r] = ok ? z[pt][lt][r] - ls[r] : -INFINITY;
+      }
+  }
   u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
-  refine_pass2<D, NLT, 2, LD>(p, Qs, lse, true, Ks, bias, aLp, cLp, aRout, NK, j, wave, nwaves, lane);
-  MRT_STAMP(6);
+  if (npt > 0) refine_finish<D, NLT, PT, LD>(p, Qs, z, npt, tile0, aRout, NK, j, lane, wave == 0);
 }
 
 // dense baseline: 128 queries per workgroup (4 waves x 2 tiles of 16), flash loop over all
@@ -1372,21 +1421,6 @@ hipError_t launch_l_out_res_d(const KParams& kp, dim3 grid, int nkt, hipStream_t
 }
 
 template <int D>
-hipError_t launch_l_refine_res_d(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
-  const int nthr = 256;
-  switch (nlt) {
-    case 1: k_bf16_stage_l_refine_res<D, 1><<<grid, nthr, 0, s>>>(kp); break;
-    case 2: k_bf16_stage_l_refine_res<D, 2><<<grid, nthr, 0, s>>>(kp); break;
-    case 3: k_bf16_stage_l_refine_res<D, 3><<<grid, nthr, 0, s>>>(kp); break;
-    case 4: k_bf16_stage_l_refine_res<D, 4><<<grid, nthr, 0, s>>>(kp); break;
-    case 5: k_bf16_stage_l_refine_res<D, 5><<<grid, nthr, 0, s>>>(kp); break;
-    case 6: k_bf16_stage_l_refine_res<D, 6><<<grid, nthr, 0, s>>>(kp); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
-}
-
-template <int D>
 hipError_t launch_l_refine_d(const KParams& kp, dim3 grid, int nthr, int nlt, hipStream_t s) {
   switch (nlt) {
     case 1: return launch_l_refine<D, 1>(kp, grid, nthr, s);
@@ -1433,6 +1467,20 @@ hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last
                      : launch_r_d<64>(kp, grid, (int)gs, first, last, s);
 }
 
+template <int D, int PT>
+hipError_t launch_l_refine_one(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
+  switch (nlt) {
+    case 1: k_bf16_stage_l_refine_one<D, 1, PT><<<grid, 256, 0, s>>>(kp); break;
+    case 2: k_bf16_stage_l_refine_one<D, 2, PT><<<grid, 256, 0, s>>>(kp); break;
+    case 3: k_bf16_stage_l_refine_one<D, 3, PT><<<grid, 256, 0, s>>>(kp); break;
+    case 4: k_bf16_stage_l_refine_one<D, 4, PT><<<grid, 256, 0, s>>>(kp); break;
+    case 5: k_bf16_stage_l_refine_one<D, 5, PT><<<grid, 256, 0, s>>>(kp); break;
+    case 6: k_bf16_stage_l_refine_one<D, 6, PT><<<grid, 256, 0, s>>>(kp); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_t s) {
   dim3 grid(kp.b2, kp.ntq, nbh);
   const int nlt = (kp.b1 + 15) / 16;
@@ -1442,11 +1490,17 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   // b1 > 128 needs a fifth and sixth wave.
   // short key ranges: everything resident, three workgroups per compute unit
   const int nk_max = kp.ntk * kp.b1;
+  // earlier iterations, key range of at most 192 rows and b1 <= 96: one pass over the logits
+  if (!last && nk_max <= kMidRows && nlt <= 6) {
+    if (nk_max <= 128) return kp.d == 128 ? launch_l_refine_one<128, 2>(kp, grid, nlt, s)
+                                          : launch_l_refine_one<64, 2>(kp, grid, nlt, s);
+    return kp.d == 128 ? launch_l_refine_one<128, 3>(kp, grid, nlt, s)
+                       : launch_l_refine_one<64, 3>(kp, grid, nlt, s);
+  }
   if (nk_max <= kResRows) {
-    if (last) return kp.d == 128 ? launch_l_out_res_d<128>(kp, grid, (nk_max + 15) / 16, s)
-                                 : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
-    return kp.d == 128 ? launch_l_refine_res_d<128>(kp, grid, nlt, s)
-                       : launch_l_refine_res_d<64>(kp, grid, nlt, s);
+    // (a key range of at most 96 rows means b1 <= 96: the earlier iterations went above)
+    return kp.d == 128 ? launch_l_out_res_d<128>(kp, grid, (nk_max + 15) / 16, s)
+                       : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
   }
   // medium key ranges: one LDS tile used twice, still three workgroups per compute unit
   if (nk_max <= kMidRows && nlt <= 8) {
