@@ -47,6 +47,17 @@ MEASURED_TRAFFIC = {
 }
 
 
+def dense_flops(wl):
+    """4 d per (query, visible key) pair of the dense baseline (both products), all heads."""
+    hw = wl.h * wl.w
+    pairs = 0
+    for fq in range(wl.f_q):
+        seen = wl.f_kv if wl.causal_chunk == 0 else min(
+            wl.f_kv, ((wl.q_frame_offset + fq) // wl.causal_chunk + 1) * wl.causal_chunk)
+        pairs += hw * seen * hw
+    return 4.0 * wl.head_dim * wl.batch * wl.heads * pairs
+
+
 def visible_pairs(wl):
     """sum over query tiles of their visible key tiles (tile-level chunk-causal reading)."""
     if wl.tile == 0:
@@ -368,6 +379,7 @@ def main():
                        "sum_kernel_ms": sum(k["ms_per_call"] for k in kernels)},
         "kernels": kernels,
         "dense_baseline_ms": dense_ms,
+        "dense_frac_mfma": (dense_flops(wl) / (dense_ms / 1e3) / PEAK_MFMA_BF16) if dense_ms else None,
         "speedup_vs_dense": (dense_ms / ms_per_step) if dense_ms else None,
         "parity_max_abs_err_head0": parity,
     }
