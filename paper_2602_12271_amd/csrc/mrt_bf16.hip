@@ -54,12 +54,25 @@ __device__ unsigned long long* g_trace_buf = nullptr;
 // rows are staged in LDS once and every query tile of the group that sees key tile n is then
 // processed against them without further barriers (the next tile's query-side rows are
 // prefetched while the current tile is computed).
+// LDS of the last iteration's variant (keys and values resident): row padding of 8 elements, and
+// the value tile stored bottom-up right after the keys, value row r at LDS row b2 + ROWS - 1 - r.
+// Rows b2 .. ROWS - 1 of both tiles (zeros: the matrix tiles read 16 rows at a time) are then the
+// same LDS rows, so the pair takes ROWS + b2 rows and five workgroups of 256 threads fit a
+// compute unit at b2 = 52 (1080 blocks of the 4680-token chunk are resident at once).
+constexpr int kPadRV = 8;
+template <int NT, int D>
+inline size_t stage_r_last_lds_bytes(int b2) {
+  return (size_t)(32 * ((NT + 1) / 2) + b2) * (D + kPadRV) * 2;
+}
+
 template <int NT, int D, bool FIRST, bool LAST>
-__global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) {
-  constexpr int LD = D + kPad, KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
+__global__ __launch_bounds__(64 * NT, (LAST && NT == 4) ? 5 : 4) void k_bf16_stage_r(KParams p, int gs) {
+  constexpr int LD = D + (LAST ? kPadRV : kPad), KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
   constexpr int NTHR = 64 * NT;
-  __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];
-  __shared__ __attribute__((aligned(16))) u16 Vs[LAST ? ROWS * LD : 8];
+  __shared__ __attribute__((aligned(16))) u16 Ks_static[LAST ? 8 : ROWS * LD];
+  extern __shared__ __attribute__((aligned(16))) u16 r_lds[];     // LAST only
+  u16* Ks = LAST ? r_lds : Ks_static;
+  u16* Vtop = r_lds + (p.b2 + ROWS - 1) * LD;                     // value row 0
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
@@ -107,7 +120,7 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   };
   load_q(ml0);
   rk.template store<LD>(Ks, tid);
-  if (LAST) rv.template store<LD>(Vs, tid);
+  if (LAST) rv.template store_rev<LD>(Vtop, tid);
   __syncthreads();
   MRT_STAMP(1);
 
@@ -192,7 +205,7 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
 #pragma unroll
         for (int st = 0; st < KS2; ++st) {
           pv_step_half<D, LD>(Ks + 32 * st * LD, pb[st], oK, lane, h);
-          pv_step_half<D, LD>(Vs + 32 * st * LD, pb[st], oV, lane, h);
+          pv_step_half<D, LD, -1>(Vtop - 32 * st * LD, pb[st], oV, lane, h);
           __builtin_amdgcn_sched_barrier(0);
         }
         if (j < b2) {
@@ -1114,9 +1127,10 @@ __global__ __launch_bounds__(256, 2) void k_bf16_dense(KParams p) {
 
 template <int NT, int D>
 hipError_t launch_r(const KParams& kp, dim3 grid, int gs, bool first, bool last, hipStream_t s) {
-  if (first && last) k_bf16_stage_r<NT, D, true, true><<<grid, 64 * NT, 0, s>>>(kp, gs);
+  const size_t lds = last ? stage_r_last_lds_bytes<NT, D>(kp.b2) : 0;
+  if (first && last) k_bf16_stage_r<NT, D, true, true><<<grid, 64 * NT, lds, s>>>(kp, gs);
   else if (first) k_bf16_stage_r<NT, D, true, false><<<grid, 64 * NT, 0, s>>>(kp, gs);
-  else if (last) k_bf16_stage_r<NT, D, false, true><<<grid, 64 * NT, 0, s>>>(kp, gs);
+  else if (last) k_bf16_stage_r<NT, D, false, true><<<grid, 64 * NT, lds, s>>>(kp, gs);
   else k_bf16_stage_r<NT, D, false, false><<<grid, 64 * NT, 0, s>>>(kp, gs);
   return hipGetLastError();
 }

@@ -83,18 +83,19 @@ __device__ inline void pv_step(const u16* vals, bf16x8 pb, f32x4* acc, int lane)
 
 // One half of pv_step: tiles h*D/32 .. (h+1)*D/32 - 1 (features 64h' .. of each 32-feature pair
 // group) into acc[0 .. D/32).
-template <int D, int LD = D + kPad>
+// DIR = -1: the tile is stored bottom-up (row r at vals - r * LD).
+template <int D, int LD = D + kPad, int DIR = 1>
 __device__ inline void pv_step_half(const u16* vals, bf16x8 pb, f32x4* acc, int lane, int h) {
   constexpr int HALF = D / 32;
   const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
-  const u16* base = vals + (4 * g + e) * LD + 8 * q;
+  const u16* base = vals + DIR * (4 * g + e) * LD + 8 * q;
   s16x4 lo[HALF], hi[HALF];
 #pragma unroll
   for (int i = 0; i < HALF; ++i) {
     const int vt = h * HALF + i;
     const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
     lo[i] = ld_lds_tr(p0);
-    hi[i] = ld_lds_tr(p0 + 16 * LD);
+    hi[i] = ld_lds_tr(p0 + DIR * 16 * LD);
   }
 #pragma unroll
   for (int i = 0; i < HALF; ++i) {
@@ -217,6 +218,16 @@ struct RowRegs {
       const int idx = tid + i * NTHR;
       const int r = idx / CPR, c = idx - r * CPR;
       if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
+    }
+  }
+  // Bottom-up: row r at dst - r * LD.
+  template <int LD>
+  __device__ inline void store_rev(u16* dst, int tid) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int idx = tid + i * NTHR;
+      const int r = idx / CPR, c = idx - r * CPR;
+      if (idx < TOTAL) *(uint4*)(dst - r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
     }
   }
 };
