@@ -192,23 +192,42 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
   const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
 
   stage_ws<D, LD, ROWS, 256>(Ks, aLp, PlainRows{D}, NK, tid);
-  if (LAST) stage_ws<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
-  else stage_rows_f32<D, LD, ROWS, 256>(Vs, bp.dA, arow, NK, tid);
+  if (LAST) {
+    stage_ws<D, LD, ROWS, 256>(Vs, Yp, PlainRows{D}, NK, tid);
+  } else {
+    // d abar rows (fp32) into LDS as bf16; d abar . abar is formed on the way: the D/8 consecutive
+    // lanes that share a row hold 8 features each
+    constexpr int CPR = D / 8, TOTAL = ROWS * CPR, NI = (TOTAL + 255) / 256;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int idx = tid + i * 256;
+      const bool in = idx < TOTAL;
+      const int r = (in ? idx : TOTAL - 1) / CPR, ch = idx % CPR;
+      const bool ok = in && r < NK;
+      const size_t at = (size_t)arow(ok ? r : 0) + 8 * ch;
+      f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
+      float t = 0.f;
+      if (ok) {
+        lo = *(const f32x4*)(bp.dA + at);
+        hi = *(const f32x4*)(bp.dA + at + 4);
+        const TW* ab = (const TW*)bp.Anext + at;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
+      }
+#pragma unroll
+      for (int sh = 1; sh < CPR; sh *= 2) t += __shfl_xor(t, sh);
+      if (in) {
+        *(uint4*)(Vs + r * LD + 8 * ch) = __builtin_bit_cast(uint4, pack8(lo, hi));
+        if (ch == 0) tcs[r] = t;
+      }
+    }
+  }
   for (int i = tid; i < ROWS; i += 256) {
     bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
     if (!LAST) {
-      float t = 0.f, cm = 0.f, ci = 0.f;
-      if (i < NK) {
-        const float* da = bp.dA + arow(i);
-        const TW* ab = (const TW*)bp.Anext + arow(i);
-        for (int v = 0; v < D; ++v) t = fmaf(da[v], ldw(ab + v), t);
-        const size_t at = arow0 + (size_t)i * b2 + j;
-        cm = bp.cmx[at] * kLog2e;
-        ci = bp.cinv[at];
-      }
-      tcs[i] = t;
-      cms[i] = cm;
-      cis[i] = ci;
+      const size_t at = arow0 + (size_t)(i < NK ? i : 0) * b2 + j;
+      cms[i] = i < NK ? bp.cmx[at] * kLog2e : 0.f;
+      cis[i] = i < NK ? bp.cinv[at] : 0.f;
     }
   }
   __syncthreads();
