@@ -635,9 +635,9 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
                                     const u16* Kres, const float* bres, const u16* aLp,
                                     const float* cLp, u16* aRout, int NK, int j, int wave,
                                     int nwaves, int lane) {
-  constexpr int KS1 = D / 32, NVT = D / 16;
+  constexpr int KS1 = D / 32;
   const int g = lane >> 4, c = lane & 15;
-  const int b1 = p.b1, b2 = p.b2;
+  const int b1 = p.b1;
   const float scale2 = p.scale * kLog2e;
   const int ntiles = (NK + 15) >> 4;
   const int ngroups = (ntiles + PT - 1) / PT;
@@ -726,8 +726,8 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
 
-  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
-  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
+  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow
+  const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   MRT_STAMP(0);
   stage_rows<D>(Qs, Qp, qrow, qrows, b1, tid, nthr);

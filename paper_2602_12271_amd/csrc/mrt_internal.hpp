@@ -37,7 +37,7 @@ struct KParams {
   void* Y;      // Y       [bh][m][j][nk][d]
   void* aR;     // alpha_R / c_R  [bh][m][nk][j][d]
   float* cL;    // c_L     [bh][m][j][nk]
-  float* cmx_out;   // optional outputs of the fp32 stage L (earlier iterations): column maximum of
+  float* cmx_out;   // optional outputs of stage L (earlier iterations, any kernel): column maximum of
   float* cinv_out;  //   log L and inverse column sum behind alpha_R / c_R   [bh][m][nk][j]
   int H;        // heads (to split the flat batch*head index)
   int bh0;      // first flat (batch,head) index of this pass
