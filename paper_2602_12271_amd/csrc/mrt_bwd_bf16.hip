@@ -12,6 +12,8 @@
 //                d cL[nk] = -sum_l dZ[l,nk], d Y[nk] = sum_l L[l,nk] dO[l]
 // so that every contraction has its summation index on the K side of an MFMA.
 #include "mrt_internal.hpp"
+#include <type_traits>
+
 #include "mrt_bf16_tiles.hpp"
 
 namespace mrt {
@@ -95,6 +97,18 @@ __device__ inline void stage_ws(u16* dst, const u16* src, RowFn rowoff, int vali
 }
 __device__ inline float ldw(const float* p) { return *p; }
 __device__ inline float ldw(const u16* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+// Eight consecutive workspace values (16-byte aligned for bf16, 32 for fp32) as two float vectors.
+__device__ inline void ldw8(const float* p, f32x4& lo, f32x4& hi) {
+  lo = *(const f32x4*)p;
+  hi = *(const f32x4*)(p + 4);
+}
+__device__ inline void ldw8(const u16* p, f32x4& lo, f32x4& hi) {
+  const uint4 v = *(const uint4*)p;
+  lo = f32x4{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+             __uint_as_float(v.y & 0xffff0000u)};
+  hi = f32x4{__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u), __uint_as_float(v.w << 16),
+             __uint_as_float(v.w & 0xffff0000u)};
+}
 
 // S^T tiles of one query tile against NTK resident row tiles: out[kt][r] = rows[16kt + 4g + r] . q
 template <int D, int NTK, int LD>
@@ -154,6 +168,19 @@ __device__ inline void store_rows_f32(float* row, const f32x4* acc, float mul, i
   }
 }
 
+// A lane's row of D/16 accumulator tiles into a workspace array of either type (overwriting).
+template <int D>
+__device__ inline void store_ws_row(float* row, const f32x4* acc, float mul, int g) {
+  store_rows_f32<D>(row, acc, mul, g, false);
+}
+template <int D>
+__device__ inline void store_ws_row(u16* row, const f32x4* acc, float mul, int g) {
+  store_rows<D>(row, acc, mul, g);
+}
+
+// The gradient arrays that only travel between the kernels of the sweep (d alpha_L, dY, and d abar
+// of the iterations t >= 2) are stored in the type TW of the forward intermediates: as bf16 they
+// hold exactly the values the consuming kernel would round its matrix operands to anyway.
 // ---------------------------------------------------------------------------------------
 // stage L backward, rows kernel, one workgroup per (m, j)
 // ---------------------------------------------------------------------------------------
@@ -208,8 +235,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
       f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
       float t = 0.f;
       if (ok) {
-        lo = *(const f32x4*)(bp.dA + at);
-        hi = *(const f32x4*)(bp.dA + at + 4);
+        ldw8((const TW*)bp.dA + at, lo, hi);
         const TW* ab = (const TW*)bp.Anext + at;
 #pragma unroll
         for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
@@ -404,8 +430,7 @@ __global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16
         f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
         float t = 0.f;
         if (ok) {
-          lo = *(const f32x4*)(bp.dA + at);
-          hi = *(const f32x4*)(bp.dA + at + 4);
+          ldw8((const TW*)bp.dA + at, lo, hi);
           const TW* ab = (const TW*)bp.Anext + at;
 #pragma unroll
           for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
@@ -565,7 +590,7 @@ __global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16
 // ---------------------------------------------------------------------------------------
 // stage L backward, cols kernel, one workgroup per (m, j)
 // ---------------------------------------------------------------------------------------
-template <int D, int NLT, bool LAST>
+template <int D, int NLT, bool LAST, typename TW>
 __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16* Pw, const u16* Zw) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, NVT = D / 16, KS2 = (NLT + 1) / 2, QROWS = 32 * KS2;
@@ -613,7 +638,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
       pv_step_nat<D, 1, LD>(Qs + 32 * st * LD, one, 1, o, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (nk < NK) store_rows_f32<D>(bp.daL + (row0 + nk) * d, o[0], p.scale, g, false);
+    if (nk < NK) store_ws_row<D>((TW*)bp.daL + (row0 + nk) * d, o[0], p.scale, g);
     if (LAST) {
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) o[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -623,7 +648,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
         pv_step_nat<D, 1, LD>(Xs + 32 * st * LD, one, 1, o, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (nk < NK) store_rows_f32<D>(bp.dY + (row0 + nk) * d, o[0], 1.0f, g, false);
+      if (nk < NK) store_ws_row<D>((TW*)bp.dY + (row0 + nk) * d, o[0], 1.0f, g);
     }
   }
 }
@@ -676,8 +701,8 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
   constexpr bool kF32Ws = sizeof(TW) == 4;
   RowRegs<D, ROWS, NTHR> ra;                          // Q rows, or abar stored as bf16
   RowRegsF32<D, kF32Ws ? ROWS : 1, NTHR> raf;         // abar stored as fp32
-  RowRegsF32<D, ROWS, NTHR> rg;
-  RowRegsF32<D, LAST ? ROWS : 1, NTHR> ry;
+  typename std::conditional<kF32Ws, RowRegsF32<D, ROWS, NTHR>, RowRegs<D, ROWS, NTHR>>::type rg;
+  typename std::conditional<kF32Ws, RowRegsF32<D, LAST ? ROWS : 1, NTHR>, RowRegs<D, LAST ? ROWS : 1, NTHR>>::type ry;
   auto issue = [&](int ml) {
     const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
     const size_t jrow0 = ((size_t)bhl * p.ntq + ml) * b2;
@@ -691,8 +716,8 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
     } else {
       ra.load((const u16*)p.aR + ablk * d, PlainRows{D}, b2, tid);
     }
-    rg.load(bp.daL, jrow, b2, tid);
-    if (LAST) ry.load(bp.dY, jrow, b2, tid);
+    rg.load((const TW*)bp.daL, jrow, b2, tid);
+    if (LAST) ry.load((const TW*)bp.dY, jrow, b2, tid);
   };
   {
     RowRegs<D, ROWS, NTHR> rk;
@@ -795,7 +820,11 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
         pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (live) store_rows_f32<D>(bp.dA + (ablk + j) * d, o, 1.0f, g, false);
+      // d abar of the first iteration is summed into dQ in fp32 by the last kernel of the call
+      if (live) {
+        if (first) store_rows_f32<D>(bp.dA + (ablk + j) * d, o, 1.0f, g, false);
+        else store_ws_row<D>((TW*)bp.dA + (ablk + j) * d, o, 1.0f, g);
+      }
     }
     __syncthreads();                               // RT / ST complete
 
@@ -839,13 +868,13 @@ static hipError_t launch_rows(const BwdParams& bp, dim3 grid, int nkt, u16* Pw, 
   }
   return hipGetLastError();
 }
-template <int D, bool LAST>
+template <int D, bool LAST, typename TW>
 static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16* Pw, const u16* Zw,
                               hipStream_t s) {
   switch (nlt) {
-    case 1: case 2: k_bwdm_l_cols<D, 2, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
-    case 3: case 4: k_bwdm_l_cols<D, 4, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
-    case 5: case 6: k_bwdm_l_cols<D, 6, LAST><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 1: case 2: k_bwdm_l_cols<D, 2, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 3: case 4: k_bwdm_l_cols<D, 4, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 5: case 6: k_bwdm_l_cols<D, 6, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -897,7 +926,8 @@ static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, b
              : launch_rows<D, false, TW>(bp, grid, nkt, Pw, Zw, s);
   }
   if (e != hipSuccess) return e;
-  return last ? launch_cols<D, true>(bp, grid, nlt, Pw, Zw, s) : launch_cols<D, false>(bp, grid, nlt, Pw, Zw, s);
+  return last ? launch_cols<D, true, TW>(bp, grid, nlt, Pw, Zw, s)
+              : launch_cols<D, false, TW>(bp, grid, nlt, Pw, Zw, s);
 }
 
 hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, bool ws_bf16, void* scratch,
