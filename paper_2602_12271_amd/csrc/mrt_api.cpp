@@ -576,6 +576,8 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     bp.dY = (float*)arr(L.off_dY());
     bp.dA = (float*)arr(L.off_dA());
     bp.dQ = dQ; bp.dK = dK; bp.dV = dV;
+    const bool r_mfma = bf16_ops && bwd_bf16_r_fits(bp.k);
+    bp.dq_from_r = (r_mfma && kp.ntk == 1) ? 1 : 0;
     for (int t = T; t >= 1; --t) {
       const bool last = t == T;
       bp.k.aL = arr(L.off_aL(t));
@@ -588,11 +590,12 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
                  : launch_bwd_stage_l(bp, pl.dtype, nbh, last, s);
       if (e != hipSuccess) return hip_fail(e, "backward stage L launch");
       bp.k.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
-      e = (bf16_ops && bwd_bf16_r_fits(bp.k)) ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, ws_bf16, s)
-                                              : launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s);
+      e = r_mfma ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, ws_bf16, s)
+                 : launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s);
       if (e != hipSuccess) return hip_fail(e, "backward stage R launch");
     }
-    if ((e = launch_bwd_q_first(bp, nbh, s)) != hipSuccess) return hip_fail(e, "backward dQ launch");
+    if (!bp.dq_from_r && (e = launch_bwd_q_first(bp, nbh, s)) != hipSuccess)
+      return hip_fail(e, "backward dQ launch");
   }
   return MRT_OK;
 }

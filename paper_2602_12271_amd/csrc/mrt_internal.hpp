@@ -97,6 +97,8 @@ struct BwdParams {
   float* dK;            // [batch*heads][N_kv][d]
   float* dV;
   int accumulate;       // add to dQ (stage L backward) / dK (stage R backward) instead of overwriting
+  int dq_from_r;        // matrix-unit stage R backward of the first iteration adds d abar_1 to dQ itself
+                        // (one key tile per query tile: nothing to sum over), no separate dQ kernel
 };
 
 struct Plan {
