@@ -310,6 +310,22 @@ def main():
         ach = dmodel["flops"] / dom["launches_per_call"] / launch_s / 1e12
         roof = dict(bound="mfma", achieved=ach, peak=PEAK_MFMA_BF16 / 1e12, unit="TFLOP/s",
                     frac=ach / (PEAK_MFMA_BF16 / 1e12))
+    # what a plain device-to-device copy of 256 MB sustains on this machine (read + write bytes per
+    # second): the ceiling a memory-bound kernel can actually reach, next to the published peak
+    csrc = torch.empty(64 * 1000 * 1000, dtype=torch.float32, device=dev).normal_()
+    cdst = torch.empty_like(csrc)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        cdst.copy_(csrc)
+    ev0.record()
+    for _ in range(5):
+        cdst.copy_(csrc)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * csrc.numel() * 4 / (ev0.elapsed_time(ev1) / 1e3) / 1e9
+    del csrc, cdst
+    if roof["bound"] == "hbm":
+        roof.update(copy_gbs=copy_gbs, frac_of_copy=roof["achieved"] / copy_gbs)
     traffic = MEASURED_TRAFFIC.get((wl.name, dom["name"]))
     roof.update(kernel=dom["name"], launch_us=launch_s * 1e6, launch_repeats=reps,
                 traffic=(sum(traffic) / dom["launches_per_call"]) if traffic else None,
