@@ -480,7 +480,11 @@ mrt_status bwd_plan(const mrt_problem* p, int b1, int b2, int tile, int iters, i
                     mrt::Plan* pl) {
   mrt_status st = mrt::make_plan(p, b1, b2, tile, iters, causal_chunk, pl);
   if (st != MRT_OK) return st;
-  if (!mrt::bwd_fits(b1, b2, p->head_dim)) {
+  // the fp32 kernels take blocks whose buffers fit LDS; beyond that only shapes that run on the
+  // bf16 matrix unit in every stage
+  const bool all_mfma = p->dtype == MRT_BF16 && p->compute == MRT_COMPUTE_DEFAULT &&
+                        mrt::bwd_bf16_fits(pl->kp) && mrt::bwd_bf16_r_fits(pl->kp);
+  if (!mrt::bwd_fits(b1, b2, p->head_dim) && !all_mfma) {
     mrt::set_error("backward pass: blocks (%d,%d) at head_dim %d exceed this build's on-chip buffers", b1, b2,
                    p->head_dim);
     return MRT_ERR_UNSUPPORTED;

@@ -22,7 +22,10 @@ namespace {
 
 constexpr int kBRows = 96;     // key rows / query rows held in LDS
 constexpr int kBPad = 8;       // row padding of the LDS tiles (as the forward resident kernels)
-constexpr int kLP = 96;        // row pitch (elements) of the transposed L / dZ arrays
+constexpr int kLP = 96;        // row pitch (elements) of the transposed L / dZ arrays, b1 <= 96
+constexpr int kLPWide = 160;   // the same for 96 < b1 <= 144 (ten query tiles, the last one zeros)
+constexpr int kBRowsWide = 144;
+__host__ __device__ inline int lp_of(int b1) { return b1 <= kBRows ? kLP : kLPWide; }
 
 // fp32 rows -> bf16 LDS tile: row r of the tile comes from src + rowoff(r); rows >= valid are zero.
 template <int D, int LD, int ROWS, int NTHR, typename RowFn>
@@ -379,11 +382,13 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
 // ---------------------------------------------------------------------------------------
 constexpr int kSegTiles = 4, kSeg = 16 * kSegTiles;
 
-template <int D, bool LAST, typename TW>
-__global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16* Pw, u16* Zw) {
+// NW waves: 6 for b1 <= 96, 10 for b1 <= 144 (the pitch of the transposed arrays follows).
+template <int D, bool LAST, typename TW, int NW>
+__global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp, u16* Pw, u16* Zw) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, NTK = kSegTiles, KS2 = NTK / 2;
-  constexpr int CPR = D / 8, TOTAL = kSeg * CPR, NTMAX = 384, NI = (TOTAL + NTMAX - 1) / NTMAX;
+  constexpr int CPR = D / 8, TOTAL = kSeg * CPR, NTMAX = 64 * NW, NI = (TOTAL + NTMAX - 1) / NTMAX;
+  constexpr int LP = NW <= 6 ? kLP : kLPWide;
   __shared__ __attribute__((aligned(16))) u16 Ks[kSeg * LD];    // alpha_L rows of the segment
   __shared__ __attribute__((aligned(16))) u16 Vs[kSeg * LD];    // Y rows (LAST) or d abar rows
   __shared__ __attribute__((aligned(16))) float bias[kSeg];     // -c_L log2(e), -inf beyond NK
@@ -522,8 +527,8 @@ __global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16
 
   // ---- sweep 2: L (or w), dZ, their transposed copies, dQ
   float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
-  u16* Pt = Pw + row0 * kLP;
-  u16* Zt = Zw + row0 * kLP;
+  u16* Pt = Pw + row0 * LP;
+  u16* Zt = Zw + row0 * LP;
   f32x4 o[NVT];
 #pragma unroll
   for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -535,8 +540,8 @@ __global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16
       // the cols kernel reads query rows in steps of 32: an odd tile count leaves one tile of zeros
       if (lt < 2 * ((nlt + 1) / 2))
         for (int nk = k0 + g; nk < NK && nk < k0 + kSeg; nk += 4) {
-          Pt[(size_t)nk * kLP + l] = 0;
-          Zt[(size_t)nk * kLP + l] = 0;
+          Pt[(size_t)nk * LP + l] = 0;
+          Zt[(size_t)nk * LP + l] = 0;
         }
       continue;
     }
@@ -564,8 +569,8 @@ __global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16
         dl[kt][r] = dz;
         const int nk = k0 + 16 * kt + 4 * g + r;
         if (nk < NK) {
-          Pt[(size_t)nk * kLP + l] = f2bf(w);
-          Zt[(size_t)nk * kLP + l] = f2bf(dz);
+          Pt[(size_t)nk * LP + l] = f2bf(w);
+          Zt[(size_t)nk * LP + l] = f2bf(dz);
         }
       }
     }
@@ -591,11 +596,15 @@ __global__ __launch_bounds__(384, 2) void k_bwdm_l_rows_stream(BwdParams bp, u16
 // stage L backward, cols kernel, one workgroup per (m, j)
 // ---------------------------------------------------------------------------------------
 template <int D, int NLT, bool LAST, typename TW>
-__global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16* Pw, const u16* Zw) {
+__global__ __launch_bounds__(256, NLT <= 6 ? 3 : 2) void k_bwdm_l_cols(BwdParams bp, const u16* Pw, const u16* Zw) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, NVT = D / 16, KS2 = (NLT + 1) / 2, QROWS = 32 * KS2;
+  constexpr int LP = NLT <= 6 ? kLP : kLPWide;
+  // up to six query tiles: Q and dO side by side; ten: one tile's worth of LDS, used for Q first
+  // and for dO afterwards
+  constexpr bool kTwoTiles = LAST && NLT <= 6;
   __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
-  __shared__ __attribute__((aligned(16))) u16 Xs[LAST ? QROWS * LD : 8];
+  __shared__ __attribute__((aligned(16))) u16 Xs_two[kTwoTiles ? QROWS * LD : 8];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2, d = D;
@@ -611,11 +620,12 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qcol * p.qs.token;
   const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
   stage_rows_batched<D, LD, QROWS, 256>(Qs, Qp, tile_rows(p, a, p.qs.token), b1, tid);
-  if (LAST) stage_rows_batched<D, LD, QROWS, 256>(Xs, dOp, tile_rows(p, a, p.os.token), b1, tid);
+  if (kTwoTiles) stage_rows_batched<D, LD, QROWS, 256>(Xs_two, dOp, tile_rows(p, a, p.os.token), b1, tid);
   __syncthreads();
 
-  const u16* Pt = Pw + row0 * kLP;
-  const u16* Zt = Zw + row0 * kLP;
+  const u16* Pt = Pw + row0 * LP;
+  const u16* Zt = Zw + row0 * LP;
+  // d alpha_L[nk] = scale sum_l dZ[l, nk] Q[l], d c_L[nk] = -sum_l dZ[l, nk]
   for (int kt = wave; kt < nkt; kt += 4) {
     const int nk = 16 * kt + c;
     const int nkc = nk < NK ? nk : NK - 1;
@@ -623,7 +633,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
     float zsum = 0.f;
 #pragma unroll
     for (int st = 0; st < KS2; ++st) {
-      zb[0][st] = ld_global_16B(Zt + (size_t)nkc * kLP + 32 * st + 8 * g);
+      zb[0][st] = ld_global_16B(Zt + (size_t)nkc * LP + 32 * st + 8 * g);
 #pragma unroll
       for (int e = 0; e < 8; ++e) zsum += (float)zb[0][st][e];
     }
@@ -639,13 +649,33 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_cols(BwdParams bp, const u16*
       __builtin_amdgcn_sched_barrier(0);
     }
     if (nk < NK) store_ws_row<D>((TW*)bp.daL + (row0 + nk) * d, o[0], p.scale, g);
-    if (LAST) {
+    if constexpr (kTwoTiles) {
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) o[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int st = 0; st < KS2; ++st) {
-        const bf16x8 one[1] = {ld_global_16B(Pt + (size_t)nkc * kLP + 32 * st + 8 * g)};
-        pv_step_nat<D, 1, LD>(Xs + 32 * st * LD, one, 1, o, lane);
+        const bf16x8 one[1] = {ld_global_16B(Pt + (size_t)nkc * LP + 32 * st + 8 * g)};
+        pv_step_nat<D, 1, LD>(Xs_two + 32 * st * LD, one, 1, o, lane);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (nk < NK) store_ws_row<D>((TW*)bp.dY + (row0 + nk) * d, o[0], 1.0f, g);
+    }
+  }
+  if constexpr (LAST && !kTwoTiles) {
+    // dY[nk] = sum_l L[l, nk] dO[l], with dO in the tile Q has just left
+    __syncthreads();
+    stage_rows_batched<D, LD, QROWS, 256>(Qs, dOp, tile_rows(p, a, p.os.token), b1, tid);
+    __syncthreads();
+    for (int kt = wave; kt < nkt; kt += 4) {
+      const int nk = 16 * kt + c;
+      const int nkc = nk < NK ? nk : NK - 1;
+      f32x4 o[1][NVT];
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) {
+        const bf16x8 one[1] = {ld_global_16B(Pt + (size_t)nkc * LP + 32 * st + 8 * g)};
+        pv_step_nat<D, 1, LD>(Qs + 32 * st * LD, one, 1, o, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (nk < NK) store_ws_row<D>((TW*)bp.dY + (row0 + nk) * d, o[0], 1.0f, g);
@@ -860,10 +890,10 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
 
 }  // namespace
 
-bool bwd_bf16_fits(const KParams& kp) { return kp.b1 <= kBRows && (kp.d == 64 || kp.d == 128); }
+bool bwd_bf16_fits(const KParams& kp) { return kp.b1 <= kBRowsWide && (kp.d == 64 || kp.d == 128); }
 size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total) {
-  // the transposed L and dZ arrays: (m, j, nk) rows of kLP bf16 each, two arrays
-  return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * kLP * 2 * 2;
+  // the transposed L and dZ arrays: (m, j, nk) rows of 96 or 160 bf16 each, two arrays
+  return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * lp_of(kp.b1) * 2 * 2;
 }
 
 template <int D, bool LAST, typename TW>
@@ -883,6 +913,7 @@ static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16
     case 1: case 2: k_bwdm_l_cols<D, 2, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
     case 3: case 4: k_bwdm_l_cols<D, 4, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
     case 5: case 6: k_bwdm_l_cols<D, 6, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
+    case 7: case 8: case 9: case 10: k_bwdm_l_cols<D, 10, LAST, TW><<<grid, 256, 0, s>>>(bp, Pw, Zw); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -924,10 +955,15 @@ static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, b
                              hipStream_t s) {
   hipError_t e;
   if (16 * nkt > kBRows) {
-    // key range beyond the resident kernel: streamed, one wave per query tile (six waves always:
-    // the staging loops are laid out for 384 threads)
-    if (last) k_bwdm_l_rows_stream<D, true, TW><<<grid, 384, 0, s>>>(bp, Pw, Zw);
-    else k_bwdm_l_rows_stream<D, false, TW><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+    // key range beyond the resident kernel: streamed, one wave per query tile (always six or ten
+    // waves: the staging loops are laid out for the full workgroup)
+    if (nlt <= 6) {
+      if (last) k_bwdm_l_rows_stream<D, true, TW, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+      else k_bwdm_l_rows_stream<D, false, TW, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+    } else {
+      if (last) k_bwdm_l_rows_stream<D, true, TW, 10><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+      else k_bwdm_l_rows_stream<D, false, TW, 10><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+    }
     e = hipGetLastError();
   } else {
     e = last ? launch_rows<D, true, TW>(bp, grid, nkt, Pw, Zw, s)
@@ -944,7 +980,7 @@ hipError_t launch_bwd_bf16_stage_l(const BwdParams& bp, int nbh, bool last, bool
   dim3 grid(kp.b2, kp.ntq, nbh);
   const int nkt = (kp.ntk * kp.b1 + 15) / 16, nlt = (kp.b1 + 15) / 16;
   u16* Pw = (u16*)scratch;
-  u16* Zw = Pw + (size_t)nbh * kp.ntq * kp.b2 * kp.ntk * kp.b1 * kLP;
+  u16* Zw = Pw + (size_t)nbh * kp.ntq * kp.b2 * kp.ntk * kp.b1 * lp_of(kp.b1);
   if (kp.d == 128)
     return ws_bf16 ? launch_l_d<128, u16>(bp, grid, nkt, nlt, last, Pw, Zw, s)
                    : launch_l_d<128, float>(bp, grid, nkt, nlt, last, Pw, Zw, s);

@@ -49,13 +49,17 @@ CASES = {
                               causal_chunk=2, q_frame_offset=2),
     # 216 key rows, three query tiles (the odd tile count leaves a zero tile), three iterations
     "bf16-stream-T3": small("bf16", head_dim=64, f_q=2, f_kv=6, h=18, w=16, b1=36, b2=8, tile=1, iters=3),
+    # nine query tiles (b1 = 135, the 720p tile height): ten waves, the wider transposed arrays,
+    # the cols kernel's single LDS tile; half of the key tiles hidden
+    "bf16-b1-135": small("bf16", head_dim=64, f_q=3, f_kv=6, h=45, w=16, b1=135, b2=8, tile=1, iters=2,
+                         causal_chunk=3, q_frame_offset=0),
 }
 
 
 def on_matrix_unit(wl):
     """bf16 storage: stage L backward runs on the bf16 matrix unit (bf16 operands, fp32 accumulation)
-    when b1 <= 96, stage R backward when b2 <= 64; the rest stays fp32."""
-    return wl.dtype == "bf16" and (wl.b1 <= 96 or wl.b2 <= 64)
+    when b1 <= 144, stage R backward when b2 <= 64; the rest stays fp32."""
+    return wl.dtype == "bf16" and (wl.b1 <= 144 or wl.b2 <= 64)
 
 
 def run_case(wl, heads=None, compute=None):

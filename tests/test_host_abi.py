@@ -184,8 +184,14 @@ def test_backward_entry_checks_on_the_host():
     per_head_f32 = lib.monarch_attn_bwd_workspace_min_bytes(ctypes.byref(pf), 90, 52, 0, T)
     assert want - 2 * n * 96 * 2 <= per_head_f32 <= want - 2 * n * 96 * 2 + 16 * 256
     assert lib.monarch_attn_bwd_workspace_bytes(ref, 90, 52, 0, T) == 12 * per_head
-    # block sizes whose buffers do not fit on chip, and invalid blocks, give 0
+    # b1 = 135 is beyond the fp32 kernels' on-chip buffers: only the bf16 matrix-unit kernels take it
+    # (ten query tiles: transposed arrays of 160 columns); fp32 arithmetic, invalid blocks give 0
     big = problem(heads=40, f_kv=21, h=45, w=80, q_frame_offset=18)
+    nbig = 2 * 40 * 14 * 135                       # (m, j, nk) rows of one head
+    per_head_big = lib.monarch_attn_bwd_workspace_min_bytes(ctypes.byref(big), 135, 40, 1, 3)
+    want_big = (2 * 3 + 3) * nbig * d * 4 + (3 * 3 - 1) * nbig * 4 + 2 * nbig * 160 * 2
+    assert want_big <= per_head_big <= want_big + 32 * 256
+    big = problem(heads=40, f_kv=21, h=45, w=80, q_frame_offset=18, compute=B.MRT_COMPUTE_F32)
     assert lib.monarch_attn_bwd_workspace_bytes(ctypes.byref(big), 135, 40, 1, 3) == 0
     assert "backward" in pkg.last_error()
     assert lib.monarch_attn_bwd_workspace_bytes(ref, 90, 50, 0, T) == 0
