@@ -955,14 +955,14 @@ __device__ inline float row16_sum(float x) {
 // Stage L of an earlier iteration for key ranges of at most 64 PT rows, in one pass over the
 // logits: wave w owns key tiles PT w .. PT w + PT - 1 and forms their logits against every query
 // tile once, with queries on the accumulator rows.  The row statistics of the joint softmax over
-// the key range are reduced inside the wave and exchanged between the four waves through LDS;
+// the key range are reduced inside the wave and exchanged between the NW waves through LDS;
 // alpha_L goes from global memory straight into the matrix operands, only Q is staged.
-template <int D, int NLT, int PT>
-__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_one(KParams p) {
+template <int D, int NLT, int PT, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refine_one(KParams p) {
   constexpr int LD = D + kResPad, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), LROWS = 16 * NLT;
   __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
-  __shared__ __attribute__((aligned(16))) float red_m[4][LROWS];
-  __shared__ __attribute__((aligned(16))) float red_s[4][LROWS];
+  __shared__ __attribute__((aligned(16))) float red_m[NW][LROWS];
+  __shared__ __attribute__((aligned(16))) float red_s[NW][LROWS];
   __shared__ __attribute__((aligned(16))) float lse[LROWS];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
@@ -984,7 +984,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_one(KParams p) {
   const int tile0 = PT * wave;
   const int ntiles = (NK + 15) >> 4;
   const int npt = ntiles - tile0 < PT ? (ntiles - tile0 > 0 ? ntiles - tile0 : 0) : PT;
-  RowRegs<D, QROWS, 256> rq;
+  RowRegs<D, QROWS, 64 * NW> rq;
   rq.load(Qp, qrow, b1, tid);
   bf16x8 kb[PT][KS1];
   float cl[PT];
@@ -1048,10 +1048,10 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_one(KParams p) {
   if (tid < LROWS) {
     float M = red_m[0][tid];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) M = fmaxf(M, red_m[w][tid]);
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, red_m[w][tid]);
     float S = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) S = fmaf(red_s[w][tid], exp2_fast(red_m[w][tid] - M), S);
+    for (int w = 0; w < NW; ++w) S = fmaf(red_s[w][tid], exp2_fast(red_m[w][tid] - M), S);
     lse[tid] = M + log2_fast(S);
   }
   __syncthreads();
@@ -1300,75 +1300,6 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   MRT_STAMP(4);
 }
 
-template <int D, int NLT, int PT>
-__global__ __launch_bounds__(256, 3) void k_bf16_stage_l_refine_mid(KParams p) {
-  constexpr int LD = D + kResPad, KS1 = D / 32, NTK = kMidRows / 16;
-  constexpr int QROWS = 32 * ((NLT + 1) / 2), QT = 2;
-  static_assert(QROWS <= kMidRows, "the Q tile must fit the shared buffer");
-  __shared__ __attribute__((aligned(16))) u16 tile[kMidRows * LD];
-  __shared__ __attribute__((aligned(16))) float bias[kMidRows];
-  __shared__ __attribute__((aligned(16))) float lse[16 * NLT];
-
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
-  const int lane = tid & 63, g = lane >> 4, c = lane & 15;
-  const int b1 = p.b1, b2 = p.b2;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
-  const int a = m / p.c2, bq = m - a * p.c2;
-  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= kMidRows
-  const size_t NKtot = (size_t)p.ntk * b1;
-  const int b = bh / p.H, hd = bh - b * p.H;
-  const WaveTiles<QT> wt(wave, nwaves, NLT);
-
-  const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);
-  const TokRows qrow = tile_rows(p, a, p.qs.token);
-  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
-  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
-  const u16* aLp = (const u16*)p.aL + row0 * D;
-  const float* cLp = p.cL + row0;
-
-  MRT_STAMP(0);
-  bf16x8 qv[QT][KS1];
-#pragma unroll
-  for (int q = 0; q < QT; ++q) {
-    const int l = 16 * wt.lt[q] + c;
-    const int lc = l < b1 ? l : b1 - 1;
-#pragma unroll
-    for (int ks = 0; ks < KS1; ++ks) qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
-  }
-  stage_rows_batched<D, LD, kMidRows, 256>(tile, aLp, PlainRows{D}, NK, tid);
-  for (int i = tid; i < kMidRows; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
-  __syncthreads();
-  MRT_STAMP(1);
-
-  // ---- pass 1: base-2 log-sum-exp of every query row over the resident keys
-  const float scale2 = p.scale * kLog2e;
-#pragma unroll
-  for (int q = 0; q < QT; ++q) {
-    if (q < wt.nq) {
-      f32x4 s[NTK];
-      const float mx = mid_logits<D, NTK, LD>(tile, bias, qv[q], scale2, s, lane);
-      float sm = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < NTK; ++kt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) sm += exp2_fast(s[kt][r] - mx);
-      sm = xsum(sm);
-      if (g == 0) lse[16 * wt.lt[q] + c] = mx + log2_fast(sm);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  __syncthreads();                      // every wave is done with alpha_L in LDS
-  MRT_STAMP(2);
-  stage_rows_batched<D, LD, QROWS, 256>(tile, Qp, qrow, b1, tid);
-  __syncthreads();
-
-  // ---- pass 2: alpha_L streamed from global memory, Q transposed from LDS
-  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
-  refine_pass2<D, NLT, PT, LD>(p, tile, lse, false, nullptr, nullptr, aLp, cLp, aRout, NK, j, wave,
-                               nwaves, lane);
-  MRT_STAMP(6);
-}
-
 template <int D, int NTK>
 hipError_t launch_l_out_mid(const KParams& kp, dim3 grid, hipStream_t s) {
   k_bf16_stage_l_out_mid<D, NTK><<<grid, 256, 0, s>>>(kp);
@@ -1383,22 +1314,6 @@ hipError_t launch_l_out_mid_d(const KParams& kp, dim3 grid, int nkt, hipStream_t
     case 11: case 12: return launch_l_out_mid<D, 12>(kp, grid, s);
   }
   return hipErrorInvalidValue;
-}
-
-template <int D>
-hipError_t launch_l_refine_mid_d(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
-  switch (nlt) {
-    case 1: k_bf16_stage_l_refine_mid<D, 1, 2><<<grid, 256, 0, s>>>(kp); break;
-    case 2: k_bf16_stage_l_refine_mid<D, 2, 2><<<grid, 256, 0, s>>>(kp); break;
-    case 3: k_bf16_stage_l_refine_mid<D, 3, 2><<<grid, 256, 0, s>>>(kp); break;
-    case 4: k_bf16_stage_l_refine_mid<D, 4, 2><<<grid, 256, 0, s>>>(kp); break;
-    case 5: k_bf16_stage_l_refine_mid<D, 5, 2><<<grid, 256, 0, s>>>(kp); break;
-    case 6: k_bf16_stage_l_refine_mid<D, 6, 2><<<grid, 256, 0, s>>>(kp); break;
-    case 7: k_bf16_stage_l_refine_mid<D, 7, 1><<<grid, 256, 0, s>>>(kp); break;
-    case 8: k_bf16_stage_l_refine_mid<D, 8, 1><<<grid, 256, 0, s>>>(kp); break;
-    default: return hipErrorInvalidValue;
-  }
-  return hipGetLastError();
 }
 
 template <int D, int NLT>
@@ -1484,12 +1399,24 @@ hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last
 template <int D, int PT>
 hipError_t launch_l_refine_one(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
   switch (nlt) {
-    case 1: k_bf16_stage_l_refine_one<D, 1, PT><<<grid, 256, 0, s>>>(kp); break;
-    case 2: k_bf16_stage_l_refine_one<D, 2, PT><<<grid, 256, 0, s>>>(kp); break;
-    case 3: k_bf16_stage_l_refine_one<D, 3, PT><<<grid, 256, 0, s>>>(kp); break;
-    case 4: k_bf16_stage_l_refine_one<D, 4, PT><<<grid, 256, 0, s>>>(kp); break;
-    case 5: k_bf16_stage_l_refine_one<D, 5, PT><<<grid, 256, 0, s>>>(kp); break;
-    case 6: k_bf16_stage_l_refine_one<D, 6, PT><<<grid, 256, 0, s>>>(kp); break;
+    case 1: k_bf16_stage_l_refine_one<D, 1, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    case 2: k_bf16_stage_l_refine_one<D, 2, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    case 3: k_bf16_stage_l_refine_one<D, 3, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    case 4: k_bf16_stage_l_refine_one<D, 4, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    case 5: k_bf16_stage_l_refine_one<D, 5, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    case 6: k_bf16_stage_l_refine_one<D, 6, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+// 7 .. 12 query tiles (one key tile per query tile, so as many key tiles): six waves, two key
+// tiles each; an odd tile count runs as the next even one (the extra tile is masked rows)
+template <int D>
+hipError_t launch_l_refine_one_wide(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
+  switch ((nlt + 1) / 2) {
+    case 4: k_bf16_stage_l_refine_one<D, 8, 2, 6><<<grid, 384, 0, s>>>(kp); break;
+    case 5: k_bf16_stage_l_refine_one<D, 10, 2, 6><<<grid, 384, 0, s>>>(kp); break;
+    case 6: k_bf16_stage_l_refine_one<D, 12, 2, 6><<<grid, 384, 0, s>>>(kp); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -1499,30 +1426,31 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   dim3 grid(kp.b2, kp.ntq, nbh);
   const int nlt = (kp.b1 + 15) / 16;
   if (nlt > kMaxLT) return hipErrorInvalidValue;
-  // Workgroups of 4 waves (one per SIMD), each wave owning up to two query tiles, so that two
-  // workgroups fit a compute unit whatever order their waves are dealt to the SIMDs in; only
-  // b1 > 128 needs a fifth and sixth wave.
-  // short key ranges: everything resident, three workgroups per compute unit
   const int nk_max = kp.ntk * kp.b1;
-  // earlier iterations, key range of at most 192 rows and b1 <= 96: one pass over the logits
+  // earlier iterations, key range of at most 192 rows: one pass over the logits (four waves for
+  // b1 <= 96, six beyond)
   if (!last && nk_max <= kMidRows && nlt <= 6) {
     if (nk_max <= 128) return kp.d == 128 ? launch_l_refine_one<128, 2>(kp, grid, nlt, s)
                                           : launch_l_refine_one<64, 2>(kp, grid, nlt, s);
     return kp.d == 128 ? launch_l_refine_one<128, 3>(kp, grid, nlt, s)
                        : launch_l_refine_one<64, 3>(kp, grid, nlt, s);
   }
+  if (!last && nk_max <= kMidRows && nlt <= kMaxLT)
+    return kp.d == 128 ? launch_l_refine_one_wide<128>(kp, grid, nlt, s)
+                       : launch_l_refine_one_wide<64>(kp, grid, nlt, s);
+  // last iteration, short key ranges: everything resident, three workgroups per compute unit
   if (nk_max <= kResRows) {
-    // (a key range of at most 96 rows means b1 <= 96: the earlier iterations went above)
     return kp.d == 128 ? launch_l_out_res_d<128>(kp, grid, (nk_max + 15) / 16, s)
                        : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
   }
-  // medium key ranges: one LDS tile used twice, still three workgroups per compute unit
-  if (nk_max <= kMidRows && nlt <= 8) {
-    if (last) return kp.d == 128 ? launch_l_out_mid_d<128>(kp, grid, (nk_max + 15) / 16, s)
-                                 : launch_l_out_mid_d<64>(kp, grid, (nk_max + 15) / 16, s);
-    return kp.d == 128 ? launch_l_refine_mid_d<128>(kp, grid, nlt, s)
-                       : launch_l_refine_mid_d<64>(kp, grid, nlt, s);
-  }
+  // medium key ranges, last iteration: one LDS tile used twice, still three workgroups per
+  // compute unit (the earlier iterations went above)
+  if (nk_max <= kMidRows && nlt <= 8)
+    return kp.d == 128 ? launch_l_out_mid_d<128>(kp, grid, (nk_max + 15) / 16, s)
+                       : launch_l_out_mid_d<64>(kp, grid, (nk_max + 15) / 16, s);
+  // long key ranges: streamed.  Workgroups of 4 waves (one per SIMD), each wave owning up to two
+  // query tiles, so that two workgroups fit a compute unit whatever order their waves are dealt
+  // to the SIMDs in; only b1 > 128 needs a fifth and sixth wave.
   const int nthr = nlt <= 8 ? 256 : 64 * ((nlt + 1) / 2);
   if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nthr, nlt, s)
                                 : launch_l_refine_d<64>(kp, grid, nthr, nlt, s);
