@@ -23,7 +23,9 @@
 // Stages (App. A.1 / A.2 update equations):
 //   stage R      one workgroup per (m, n, k): Z_R, R = softmax_i, c_L, alpha_L = R K, Y = R V
 //   stage L out  one workgroup per (m, j): flash loop over nk: L = softmax(Z_L), O = L Y
-//   stage L ref  one workgroup per (m, j): log-sum-exp pass over nk, then alpha_R / c_R
+//   stage L ref  one workgroup per (m, j): alpha_R / c_R of the next iteration; one pass over the
+//                logits for key ranges of at most 192 rows (row statistics exchanged between
+//                the waves), else a log-sum-exp pass over nk followed by a second pass
 #include "mrt_internal.hpp"
 #include "mrt_bf16_tiles.hpp"
 

@@ -1,16 +1,17 @@
-// Backward pass on the bf16 matrix unit for short key ranges (NK = visible key tiles * b1 <= 96,
-// b1 <= 96: regular Monarch at the 4680-token chunk, small tiles): bf16 MFMA operands, fp32
-// accumulation and fp32 softmax arithmetic, same register layouts as the forward kernels
-// (mrt_bf16.hip).  The workspace arrays stay fp32 (shared with the fp32 kernels of
-// mrt_bwd_f32.hip, which remain the path for every other shape and for fp32 storage); operands are
-// rounded to bf16 when they are staged into LDS.
+// Backward pass on the bf16 matrix unit (bf16 storage, b1 <= 144 for stage L, b2 <= 64 for stage R,
+// head_dim 64 or 128): bf16 MFMA operands, fp32 accumulation and fp32 softmax arithmetic, same
+// register layouts as the forward kernels (mrt_bf16.hip).  The workspace arrays are typed by TW:
+// fp32 when the fp32 forward kernels recomputed the intermediates (one of the two stages runs the
+// fp32 kernels of mrt_bwd_f32.hip), bf16 when every stage runs here and the bf16 forward kernels
+// did; operands are rounded to bf16 at the latest when they are staged into LDS.
 //
 // Stage L backward is split in two kernels per (m, j):
 //   rows kernel  (lanes own query rows l):  L, dL, delta, dZ;  dQ[l] += scale dZ aL (+ w dA);
 //                writes L (or w) and dZ transposed, as bf16 [nk][l], for the second kernel
 //   cols kernel  (lanes own key rows nk):   d aL[nk] = scale sum_l dZ[l,nk] Q[l],
 //                d cL[nk] = -sum_l dZ[l,nk], d Y[nk] = sum_l L[l,nk] dO[l]
-// so that every contraction has its summation index on the K side of an MFMA.
+// so that every contraction has its summation index on the K side of an MFMA.  The rows kernel
+// holds the key range in LDS when it has at most 96 rows and streams it in segments otherwise.
 #include "mrt_internal.hpp"
 #include <type_traits>
 
