@@ -56,20 +56,20 @@ __device__ unsigned long long* g_trace_buf = nullptr;
 // rows are staged in LDS once and every query tile of the group that sees key tile n is then
 // processed against them without further barriers (the next tile's query-side rows are
 // prefetched while the current tile is computed).
-// LDS of the last iteration's variant (keys and values resident): row padding of 8 elements, and
-// the value tile stored bottom-up right after the keys, value row r at LDS row b2 + ROWS - 1 - r.
-// Rows b2 .. ROWS - 1 of both tiles (zeros: the matrix tiles read 16 rows at a time) are then the
-// same LDS rows, so the pair takes ROWS + b2 rows and five workgroups of 256 threads fit a
-// compute unit at b2 = 52 (1080 blocks of the 4680-token chunk are resident at once).
-constexpr int kPadRV = 8;
+// LDS of the last iteration's variant (keys and values resident): the value tile is stored
+// bottom-up right after the keys, value row r at LDS row b2 + ROWS - 1 - r.  Rows b2 .. ROWS - 1
+// of both tiles (zeros: the matrix tiles read 16 rows at a time) are then the same LDS rows, so the
+// pair takes ROWS + b2 rows.  Row padding: 16 elements as everywhere (measured 0.3 us faster than 8
+// at b2 = 52), 8 for five or six waves, where it lets a third workgroup onto the compute unit.
+template <int NT> constexpr int kPadRV = NT >= 5 ? 8 : kPad;
 template <int NT, int D>
 inline size_t stage_r_last_lds_bytes(int b2) {
-  return (size_t)(32 * ((NT + 1) / 2) + b2) * (D + kPadRV) * 2;
+  return (size_t)(32 * ((NT + 1) / 2) + b2) * (D + kPadRV<NT>) * 2;
 }
 
 template <int NT, int D, bool FIRST, bool LAST>
-__global__ __launch_bounds__(64 * NT, (LAST && NT == 4) ? 5 : 4) void k_bf16_stage_r(KParams p, int gs) {
-  constexpr int LD = D + (LAST ? kPadRV : kPad), KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
+__global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) {
+  constexpr int LD = D + (LAST ? kPadRV<NT> : kPad), KS1 = D / 32, KS2 = (NT + 1) / 2, ROWS = 32 * KS2, NVT = D / 16;
   constexpr int NTHR = 64 * NT;
   __shared__ __attribute__((aligned(16))) u16 Ks_static[LAST ? 8 : ROWS * LD];
   extern __shared__ __attribute__((aligned(16))) u16 r_lds[];     // LAST only
