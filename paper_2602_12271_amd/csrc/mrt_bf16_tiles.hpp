@@ -46,13 +46,32 @@ constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
 __device__ inline float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ inline float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
 
+// Reductions over the four 16-lane rows of a wave, per lane column (lane & 15): the lanes that hold
+// one accumulator column of an MFMA tile.  gfx950's row-swap instructions do the exchange in the
+// vector ALU instead of a ds_bpermute through the LDS crossbar: with a = b = x on entry,
+// v_permlane16_swap leaves the even rows' values in a and the odd rows' in b (in both rows of each
+// pair), v_permlane32_swap the same for the two halves of the wave.  Written as inline assembly (the
+// builtin folds the two results into one when both operands are the same value), with the wait
+// states a VALU producer / consumer of the swapped registers needs.  All 64 lanes must be active.
+__device__ inline void row_swap16(float& a, float& b) {
+  asm("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ inline void row_swap32(float& a, float& b) {
+  asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
 __device__ inline float xmax(float x) {
-  x = fmaxf(x, __shfl_xor(x, 16));
-  return fmaxf(x, __shfl_xor(x, 32));
+  float a = x, b = x;
+  row_swap16(a, b);
+  a = b = fmaxf(a, b);
+  row_swap32(a, b);
+  return fmaxf(a, b);
 }
 __device__ inline float xsum(float x) {
-  x += __shfl_xor(x, 16);
-  return x + __shfl_xor(x, 32);
+  float a = x, b = x;
+  row_swap16(a, b);
+  a = b = a + b;
+  row_swap32(a, b);
+  return a + b;
 }
 
 // Second product for one 32-key step: acc[vt] += Val^T[phi(vt, .), keys] * P.
