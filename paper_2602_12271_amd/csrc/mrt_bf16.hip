@@ -935,25 +935,6 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   MRT_STAMP(2);
 }
 
-// Maximum / sum over the 16 lanes that share lane >> 4 (one accumulator row of an MFMA tile):
-// data-parallel-primitive moves (pairs, quads, mirrored halves of 8, mirrored 16), no LDS traffic.
-template <int CTRL>
-__device__ inline float dpp_mov(float x) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
-}
-__device__ inline float row16_max(float x) {
-  x = fmaxf(x, dpp_mov<0xB1>(x));    // quad_perm [1,0,3,2]
-  x = fmaxf(x, dpp_mov<0x4E>(x));    // quad_perm [2,3,0,1]
-  x = fmaxf(x, dpp_mov<0x141>(x));   // row_half_mirror
-  return fmaxf(x, dpp_mov<0x140>(x));  // row_mirror
-}
-__device__ inline float row16_sum(float x) {
-  x += dpp_mov<0xB1>(x);
-  x += dpp_mov<0x4E>(x);
-  x += dpp_mov<0x141>(x);
-  return x + dpp_mov<0x140>(x);
-}
-
 // Stage L of an earlier iteration for key ranges of at most 64 PT rows, in one pass over the
 // logits: wave w owns key tiles PT w .. PT w + PT - 1 and forms their logits against every query
 // tile once, with queries on the accumulator rows.  The row statistics of the joint softmax over

@@ -74,6 +74,31 @@ __device__ inline float xsum(float x) {
   return a + b;
 }
 
+// Maximum / sum over the 16 lanes that share lane >> 4 (one accumulator row of an MFMA tile):
+// data-parallel-primitive moves (pairs, quads, mirrored halves of 8, mirrored 16), no LDS traffic.
+template <int CTRL>
+__device__ inline float dpp_mov(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+__device__ inline float row16_max(float x) {
+  x = fmaxf(x, dpp_mov<0xB1>(x));    // quad_perm [1,0,3,2]
+  x = fmaxf(x, dpp_mov<0x4E>(x));    // quad_perm [2,3,0,1]
+  x = fmaxf(x, dpp_mov<0x141>(x));   // row_half_mirror
+  return fmaxf(x, dpp_mov<0x140>(x));  // row_mirror
+}
+__device__ inline float row16_sum(float x) {
+  x += dpp_mov<0xB1>(x);
+  x += dpp_mov<0x4E>(x);
+  x += dpp_mov<0x141>(x);
+  return x + dpp_mov<0x140>(x);
+}
+// Sum over aligned groups of 8 lanes (the first three steps of the above).
+__device__ inline float row8_sum(float x) {
+  x += dpp_mov<0xB1>(x);
+  x += dpp_mov<0x4E>(x);
+  return x + dpp_mov<0x141>(x);
+}
+
 // Second product for one 32-key step: acc[vt] += Val^T[phi(vt, .), keys] * P.
 // vals points at LDS row `32*step` of a row-major [rows][D + kPad] tile; output feature of
 // accumulator row (4g + r) of tile vt is phi = 32(vt/2) + 8g + 4(vt%2) + r.

@@ -244,8 +244,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
 #pragma unroll
         for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
       }
-#pragma unroll
-      for (int sh = 1; sh < CPR; sh *= 2) t += __shfl_xor(t, sh);
+      t = CPR == 16 ? row16_sum(t) : row8_sum(t);
       if (in) {
         *(uint4*)(Vs + r * LD + 8 * ch) = __builtin_bit_cast(uint4, pack8(lo, hi));
         if (ch == 0) tcs[r] = t;
@@ -441,8 +440,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
 #pragma unroll
           for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
         }
-#pragma unroll
-        for (int sh = 1; sh < CPR; sh *= 2) t += __shfl_xor(t, sh);
+        t = CPR == 16 ? row16_sum(t) : row8_sum(t);
         if (in) {
           *(uint4*)(Vs + r * LD + 8 * ch) = __builtin_bit_cast(uint4, pack8(lo, hi));
           if (ch == 0) tcs[r] = t;
