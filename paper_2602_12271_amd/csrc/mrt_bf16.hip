@@ -947,6 +947,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
   __shared__ __attribute__((aligned(16))) float red_m[NW][LROWS];
   __shared__ __attribute__((aligned(16))) float red_s[NW][LROWS];
   __shared__ __attribute__((aligned(16))) float lse[LROWS];
+  __shared__ int redo;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
@@ -1005,37 +1006,69 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
     }
     if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
   }
-  // this wave's share of every query row's maximum and sum
+  // this wave's share of every query row's sum of 2^z, relative to a reference the waves then
+  // reconcile.  First with one reference per query tile (the maximum over the tile's 16 rows: six
+  // cross-lane steps per tile instead of four per row); a row whose logits all lie 126 or more
+  // below its tile's maximum would lose its sum to underflow, so if any row's total comes out zero
+  // the statistics are redone with every row's own maximum.
+  auto stats = [&](bool per_row) {
 #pragma unroll
-  for (int lt = 0; lt < NLT; ++lt) {
-    f32x4 mx, sm;
+    for (int lt = 0; lt < NLT; ++lt) {
+      f32x4 vr;
+      float vt = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float v = z[0][lt][r];
+      for (int r = 0; r < 4; ++r) {
+        float v = z[0][lt][r];
 #pragma unroll
-      for (int pt = 1; pt < PT; ++pt) v = fmaxf(v, z[pt][lt][r]);
-      v = row16_max(v);
-      const float ref = v == -INFINITY ? 0.f : v;
-      float e = 0.f;
+        for (int pt = 1; pt < PT; ++pt) v = fmaxf(v, z[pt][lt][r]);
+        vr[r] = v;
+        vt = fmaxf(vt, v);
+      }
+      if (per_row) {
 #pragma unroll
-      for (int pt = 0; pt < PT; ++pt) e += exp2_fast(z[pt][lt][r] - ref);
-      mx[r] = v;
-      sm[r] = row16_sum(e);
+        for (int r = 0; r < 4; ++r) vr[r] = row16_max(vr[r]);
+      } else {
+        vt = xmax(row16_max(vt));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) vr[r] = vt;
+      }
+      f32x4 sm;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float ref = vr[r] == -INFINITY ? 0.f : vr[r];
+        float e = 0.f;
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) e += exp2_fast(z[pt][lt][r] - ref);
+        sm[r] = row16_sum(e);
+      }
+      if (c == 0) {
+        *(f32x4*)(&red_m[wave][16 * lt + 4 * g]) = vr;
+        *(f32x4*)(&red_s[wave][16 * lt + 4 * g]) = sm;
+      }
     }
-    if (c == 0) {
-      *(f32x4*)(&red_m[wave][16 * lt + 4 * g]) = mx;
-      *(f32x4*)(&red_s[wave][16 * lt + 4 * g]) = sm;
+  };
+  auto combine = [&]() {
+    if (tid < LROWS) {
+      float M = red_m[0][tid];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) M = fmaxf(M, red_m[w][tid]);
+      float S = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) S = fmaf(red_s[w][tid], exp2_fast(red_m[w][tid] - M), S);
+      lse[tid] = M + log2_fast(S);
+      if (!(S > 0.f)) redo = 1;
     }
-  }
+  };
+  if (tid == 0) redo = 0;
+  stats(false);
   __syncthreads();
-  if (tid < LROWS) {
-    float M = red_m[0][tid];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) M = fmaxf(M, red_m[w][tid]);
-    float S = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) S = fmaf(red_s[w][tid], exp2_fast(red_m[w][tid] - M), S);
-    lse[tid] = M + log2_fast(S);
+  combine();
+  __syncthreads();
+  if (redo) {            // uniform: read after the barrier
+    stats(true);
+    __syncthreads();
+    combine();
+    __syncthreads();
   }
   __syncthreads();
   MRT_STAMP(2);

@@ -184,6 +184,30 @@ def test_f32_compute_on_bf16_storage_matches_oracle_tighter():
     assert err <= omax * 2 ** -8 + 1e-5
 
 
+def test_rows_far_below_their_tile_maximum_keep_their_weights():
+    """The one-pass stage L kernel first sums 2^(z - reference) with one reference per 16-row query
+    tile; a row whose logits all lie more than 126 (base 2) below the tile's largest logit loses
+    that sum to underflow and the kernel has to redo the statistics with the row's own maximum.
+    All keys equal, one query row of the opposite sign: that row's logits are 200 below the others',
+    every softmax is uniform, so O must be the mean of V for every query (and the oracle agrees)."""
+    wl = small_bf16(heads=1, f_q=2, f_kv=2, h=16, w=16, b1=32, b2=16, tile=0, iters=3,
+                    causal_chunk=0, q_frame_offset=0)
+    rng = np.random.default_rng(5)
+    n, d = wl.n_q, wl.head_dim
+    Q = np.full((1, 1, n, d), 2.5, np.float32)
+    rows = np.arange(n) // wl.w                      # block-grid row (frame, height) of each token
+    Q[0, 0, rows == 3] = -2.5
+    K = np.full((1, 1, n, d), 2.5, np.float32)
+    V = syn.round_to_bf16(rng.standard_normal((1, 1, n, d)).astype(np.float32))
+    # logits: scale log2(e) q.k = +-102 in base 2
+    assert 2 * wl.scale * 1.4427 * 2.5 * 2.5 * d > 126
+    O = run_monarch_gpu(wl, *to_device(wl, (Q, K, V)))
+    assert torch.isfinite(O.float()).all()
+    mean = V[0, 0].astype(np.float64).mean(axis=0)
+    assert np.abs(O[0, 0].float().cpu().numpy() - mean[None, :]).max() <= 2e-2
+    check(wl, (Q, K, V), O, label="row 200 below its tile's maximum")
+
+
 def test_rerun_is_bit_identical():
     wl = syn.variant("C2", heads=2)
     dev = to_device(wl, syn.make_inputs(wl))
