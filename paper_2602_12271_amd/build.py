@@ -22,6 +22,9 @@ FLAGS = [
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
     # packed fp32 instructions are kept out of the generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # max / min / select need no NaN-quieting instructions: a NaN in the inputs gives an
+    # unspecified result either way; infinities are honoured (the masks are -inf)
+    "-fno-honor-nans",
     "-Wno-unused-command-line-argument",
 ]
 
