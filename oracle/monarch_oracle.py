@@ -29,6 +29,15 @@ design document as well):
     tile iff the chunk of the key tile's frames is not later than the chunk of
     the query tile's frames; hidden pairs take no part at all (no R, not in the
     joint softmax of L).  A tile never straddles a chunk boundary.
+  * chunk-causal mask on regular Monarch (one tile, which straddles every chunk):
+    with the frame as the slowest axis of the block row index the mask depends on
+    the row pair (l, k) alone, so the hidden entries of the attention matrix are
+    the hidden entries of L[j, k, l]: L's softmax over k runs over the key rows
+    whose frame's chunk is not later than the query row's.  R, c_L, alpha_R / c_R
+    are unchanged in form (they see L's zeros).  The updates are then still the
+    exact alternating maximisation of the variational objective of Sec. 3 over
+    Monarch matrices with that support.  The diagonal (k = l) is always visible,
+    so the identity initialisation respects the mask.
   * tiles are the contiguous row / column ranges of Alg. 2's rearrange, so any
     b1 dividing the row count is a tiling (also a fraction of a frame: the
     neighbourhood tiles of Sec. 4.2 with n_f = 1).
@@ -181,9 +190,14 @@ def _safe_rows_div(bR: torch.Tensor, cR: torch.Tensor) -> torch.Tensor:
 
 
 def monarch_attention_regular(Q, K, V, T: int, b1: int, b2: int, scale: float = 1.0,
-                              return_factors: bool = False):
+                              return_factors: bool = False,
+                              row_visible: Optional[torch.Tensor] = None):
     """App. A.1 update equations / pseudocode (a).  N = b1*b2, Q,K,V viewed as
-    [b1, b2, d].  Returns O [N, d] (and L[j,k,l], R[k,j,i] on request)."""
+    [b1, b2, d].  Returns O [N, d] (and L[j,k,l], R[k,j,i] on request).
+
+    row_visible[l, k] (bool, optional): key row k is visible to query row l.  A hidden
+    (l, k) is a zero of the attention matrix for every (j, i), i.e. a zero of L[j, k, l]:
+    the softmax of L over k runs over the visible k only (see the module header)."""
     assert T >= 1
     N, d = Q.shape
     assert N == b1 * b2 and K.shape == (N, d) and V.shape[0] == N
@@ -201,7 +215,11 @@ def monarch_attention_regular(Q, K, V, T: int, b1: int, b2: int, scale: float = 
         aL = torch.einsum("kji,kiv->jkv", R, Kv)
         bL = scale * torch.einsum("jkv,ljv->jkl", aL, Qv)
         cL = _xlogx_sum(R, 2).transpose(0, 1)                    # kj -> jk
-        L = torch.softmax(bL - cL[:, :, None], dim=1)            # over k
+        zL = bL - cL[:, :, None]                                 # j k l
+        if row_visible is not None:
+            assert row_visible.shape == (b1, b1) and bool(row_visible.diagonal().all())
+            zL = zL.masked_fill(~row_visible.transpose(0, 1)[None, :, :], -math.inf)
+        L = torch.softmax(zL, dim=1)                             # over k
     Y = torch.einsum("kji,kiv->jkv", R, Vv)
     Z = torch.einsum("jkl,jkv->ljv", L, Y)
     O = Z.reshape(N, -1)
@@ -389,8 +407,12 @@ def monarch_attn(Q, K, V, *, f_q: int, f_kv: int, h: int, w: int, b1: int, b2: i
         return O
     g = geometry_from_grid(f_q, f_kv, h, w, b1, b2, tile)
     if tile == 0:
-        assert causal_chunk == 0
-        return monarch_attention_regular(Q, K, V, iters, b1, b2, scale)
+        vis_rows = None
+        if causal_chunk > 0:
+            assert f_q == f_kv and b1 == f_q * h
+            rows = torch.arange(b1) // h                         # frame of a block row
+            vis_rows = (rows[None, :] // causal_chunk) <= ((rows[:, None] + q_frame_offset) // causal_chunk)
+        return monarch_attention_regular(Q, K, V, iters, b1, b2, scale, row_visible=vis_rows)
     vis = chunk_causal_visibility(g, h, causal_chunk, q_frame_offset)
     return monarch_attention_tiled(Q, K, V, iters, g, scale, vis)
 

@@ -21,6 +21,9 @@ CASES = {
                                q_frame_offset=1),
     "tiled-T1": dict(f_q=2, f_kv=2, h=2, w=6, b1=2, b2=3, tile=1, iters=1),
     "fw_h-T2": dict(f_q=2, f_kv=2, h=3, w=4, b1=8, b2=3, tile=0, iters=2, assign="fw_h"),
+    "regular-mask-T2": dict(f_q=3, f_kv=3, h=2, w=4, b1=6, b2=4, tile=0, iters=2, causal_chunk=1),
+    "regular-mask-offset-T3": dict(f_q=4, f_kv=4, h=2, w=3, b1=8, b2=3, tile=0, iters=3, causal_chunk=2,
+                                   q_frame_offset=1),
 }
 
 
