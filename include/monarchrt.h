@@ -88,16 +88,20 @@ typedef struct {
  * With rows_q x cols and rows_kv x cols the block grids of the query and key side under
  * p->assignment (the column counts must agree: assignments with the frame axis on the column
  * side need f_q == f_kv):
- *   tile = 0  regular Monarch: needs f_q == f_kv, b1 == rows, b2 == cols, causal_chunk == 0.
+ *   tile = 0  regular Monarch: needs f_q == f_kv, b1 == rows, b2 == cols.
  *   tile = 1  tiled: (b1,b2) are tile-local; needs rows_q % b1 == 0, rows_kv % b1 == 0,
  *             cols % b2 == 0.  A tile may be any contiguous row range, e.g. several frames or,
  *             with n_f = 1, n_h = b1 rows of one frame (the neighbourhood tiles of Sec. 4.2).
  *   iters >= 1 (R is undefined before the first update, App. A.1).
- *   causal_chunk = 0: no mask.  > 0: frames per autoregressive chunk; a key tile is visible
- *             to a query tile iff its chunk is not later than the query tile's chunk, hidden
- *             tile pairs take no part at all.  Needs tile = 1, an assignment whose slowest row
- *             axis is the frame (FH_W, FW_H, F_HW), and tiles that do not straddle a chunk:
- *             b1 divides (rows per frame)*causal_chunk and (rows per frame)*q_frame_offset.
+ *   causal_chunk = 0: no mask.  > 0: frames per autoregressive chunk; needs an assignment whose
+ *             slowest row axis is the frame (FH_W, FW_H, F_HW).
+ *             tile = 1: a key tile is visible to a query tile iff its chunk is not later than the
+ *             query tile's chunk, hidden tile pairs take no part at all; tiles must not straddle
+ *             a chunk: b1 divides (rows per frame)*causal_chunk and (rows per frame)*q_frame_offset.
+ *             tile = 0: the one tile straddles every chunk; the mask depends on the block rows
+ *             (l, k) alone, so it is a support constraint on L: L's softmax over k runs over the
+ *             key rows whose frame's chunk is not later than the chunk of query row l's frame
+ *             (+ q_frame_offset), and the iteration is otherwise unchanged.
  *   p->tile_h = n_h > 0 selects neighbourhood tiles (n_f, n_h, n_w) = (b1 / n_h, n_h, b2) of
  *             Sec. 4.2: needs tile = 1, assignment (fh, w), n_h | h, n_h | b1, n_f | f_q, n_f | f_kv,
  *             b2 | w, and for a mask n_f | causal_chunk and n_f | q_frame_offset.  Tile rows are
@@ -148,7 +152,8 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
  *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers of the fp32
  *   kernels fit the 160 KB of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128), or
  *   such that every stage runs on the bf16 matrix unit (b1 <= 144, b2 <= 64); iters <= 16;
- *   otherwise MRT_ERR_UNSUPPORTED. */
+ *   otherwise MRT_ERR_UNSUPPORTED.  Regular Monarch under a mask (tile = 0, causal_chunk > 0)
+ *   runs stage L backward in the fp32 kernels, so the first limit applies to it. */
 size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,

@@ -126,7 +126,6 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
       set_error("regular Monarch needs f_q == f_kv (use tile=1 for a KV cache)");
       return MRT_ERR_UNSUPPORTED;
     }
-    if (causal_chunk != 0) { set_error("regular Monarch with a causal mask is not built"); return MRT_ERR_UNSUPPORTED; }
     if (p->tile_h != 0) { set_error("tile_h needs tile = 1"); return MRT_ERR_SHAPE; }
     if (b1 != rows_q || b2 != cols) {
       set_error("regular Monarch with assignment %s needs (b1,b2) = (%d,%d), got (%d,%d)", aname, rows_q, cols, b1, b2);
@@ -173,8 +172,13 @@ static mrt_status make_plan(const mrt_problem* p, int b1, int b2, int tile, int 
       set_error("a causal mask needs an assignment whose slowest b1 axis is the frame, not %s", aname);
       return MRT_ERR_UNSUPPORTED;
     }
-    long long ct, qt0;
-    if (k.nh > 0) {
+    long long ct = 0, qt0 = 0;
+    if (tile == 0) {
+      // one tile across every chunk: the mask hides key rows of later chunks from a query row
+      // (a support constraint on L); nothing is hidden if query row 0 already sees every row
+      const long long rl = (long long)causal_chunk * rpf, r0 = (long long)p->q_frame_offset * rpf;
+      if ((r0 / rl + 1) * rl < b1) { k.rl = (int)rl; k.rq0 = (int)r0; }   // rl < b1 <= 192 here
+    } else if (k.nh > 0) {
       const int nf = b1 / k.nh;
       if (causal_chunk % nf || p->q_frame_offset % nf) {
         set_error("a tile (%d frames) must not straddle a causal chunk (%d frames, offset %d)", nf,

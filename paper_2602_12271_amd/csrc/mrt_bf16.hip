@@ -488,7 +488,8 @@ struct WaveTiles {
 };
 
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
-template <int D, int QT, int MAXT>
+// RMASK: regular Monarch under the chunk-causal mask (key rows of later chunks hidden per query row)
+template <int D, int QT, int MAXT, bool RMASK>
 __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
@@ -527,13 +528,15 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   int qchunk[QT];
 #pragma unroll
   for (int q = 0; q < QT; ++q) {
-    qchunk[q] = 0;
+    // chunk of this lane's query row (rows beyond b1 take the last row's; they are not stored)
+    const int l = 16 * wt.lt[q] + c;
+    qchunk[q] = RMASK ? ((l < b1 ? l : b1 - 1) + p.rq0) / p.rl : 0;
 #pragma unroll
     for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
   MRT_STAMP(0);
-  auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-  flash_loop<D, QT, true, false>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st, o, tid,
+  auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = RMASK ? key / p.rl : 0; };
+  flash_loop<D, QT, true, RMASK>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st, o, tid,
                                  nthr, lane);
   MRT_STAMP(1);
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
@@ -1006,6 +1009,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
     }
     if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
   }
+  if (p.rl > 0) {
+    // regular Monarch under the chunk-causal mask: key rows of later chunks are zeros of L
+#pragma unroll
+    for (int lt = 0; lt < NLT; ++lt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int lim = visible_key_rows(p, 16 * lt + 4 * g + r);
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+          if (16 * (tile0 + pt) + c >= lim) z[pt][lt][r] = -INFINITY;
+      }
+  }
   // this wave's share of every query row's sum of 2^z, relative to a reference the waves then
   // reconcile.  First with one reference per query tile (the maximum over the tile's 16 rows: six
   // cross-lane steps per tile instead of four per row); a row whose logits all lie 126 or more
@@ -1166,7 +1181,8 @@ hipError_t launch_r_d(const KParams& kp, dim3 grid, int gs, bool first, bool las
 
 template <int D, int QT, int MAXT>
 hipError_t launch_l_out(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
-  k_bf16_stage_l_out<D, QT, MAXT><<<grid, nthr, 0, s>>>(kp);
+  if (kp.rl > 0) k_bf16_stage_l_out<D, QT, MAXT, true><<<grid, nthr, 0, s>>>(kp);
+  else k_bf16_stage_l_out<D, QT, MAXT, false><<<grid, nthr, 0, s>>>(kp);
   return hipGetLastError();
 }
 
@@ -1455,13 +1471,15 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
     return kp.d == 128 ? launch_l_refine_one_wide<128>(kp, grid, nlt, s)
                        : launch_l_refine_one_wide<64>(kp, grid, nlt, s);
   // last iteration, short key ranges: everything resident, three workgroups per compute unit
-  if (nk_max <= kResRows) {
+  // (regular Monarch under the chunk-causal mask takes the streamed kernel, which has the mask)
+  const bool row_mask = kp.rl > 0;
+  if (nk_max <= kResRows && !row_mask) {
     return kp.d == 128 ? launch_l_out_res_d<128>(kp, grid, (nk_max + 15) / 16, s)
                        : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
   }
   // medium key ranges, last iteration: one LDS tile used twice, still three workgroups per
   // compute unit (the earlier iterations went above)
-  if (nk_max <= kMidRows && nlt <= 8)
+  if (nk_max <= kMidRows && nlt <= 8 && !row_mask)
     return kp.d == 128 ? launch_l_out_mid_d<128>(kp, grid, (nk_max + 15) / 16, s)
                        : launch_l_out_mid_d<64>(kp, grid, (nk_max + 15) / 16, s);
   // long key ranges: streamed.  Workgroups of 4 waves (one per SIMD), each wave owning up to two

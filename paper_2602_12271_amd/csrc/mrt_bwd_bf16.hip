@@ -889,7 +889,11 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
 
 }  // namespace
 
-bool bwd_bf16_fits(const KParams& kp) { return kp.b1 <= kBRowsWide && (kp.d == 64 || kp.d == 128); }
+// (regular Monarch under the chunk-causal mask, kp.rl > 0, is differentiated by the fp32 stage L
+// kernel, which has the mask)
+bool bwd_bf16_fits(const KParams& kp) {
+  return kp.b1 <= kBRowsWide && (kp.d == 64 || kp.d == 128) && kp.rl == 0;
+}
 size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total) {
   // the transposed L and dZ arrays: (m, j, nk) rows of 96 or 160 bf16 each, two arrays
   return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * lp_of(kp.b1) * 2 * 2;

@@ -79,6 +79,10 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp, int kCH)
   const size_t arow0 = ((size_t)bhl * p.ntq + ml) * NKtot * b2;
   auto arow = [&](int nk) { return (arow0 + (size_t)nk * b2 + j) * d; };
 
+  // regular Monarch under the chunk-causal mask: hidden (l, nk) are zeros of L (log L = -inf gives
+  // L = w = 0 below, so they drop out of every sum)
+  auto hidden = [&](int l, int nk) { return p.rl > 0 && nk >= visible_key_rows(p, l); };
+
   // ---- pass 0: log-sum-exp of every row l
   float rmax = -INFINITY, rsum = 0.f;
   for (int c0 = 0; c0 < NK; c0 += kCH) {
@@ -92,7 +96,8 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp, int kCH)
     gemm_tiles(b1, cn, d,
                [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
                [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
-               [&](int l, int c, float x) { Lc[l * lz + c] = p.scale * x - cLp[c0 + c]; }, tid);
+               [&](int l, int c, float x) { Lc[l * lz + c] = hidden(l, c0 + c) ? -INFINITY : p.scale * x - cLp[c0 + c]; },
+               tid);
     __syncthreads();
     if (tid < b1) {
       float mx = rmax;
@@ -134,8 +139,9 @@ __global__ __launch_bounds__(kThreads) void k_bwd_stage_l(BwdParams bp, int kCH)
       gemm_tiles(b1, cn, d,
                  [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
                  [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
-                 [&](int l, int c, float x) { Lc[l * lz + c] = p.scale * x - cLp[c0 + c] - lse[l]; },   // log L
-                 tid);
+                 [&](int l, int c, float x) {                                                            // log L
+                   Lc[l * lz + c] = hidden(l, c0 + c) ? -INFINITY : p.scale * x - cLp[c0 + c] - lse[l];
+                 }, tid);
       gemm_tiles(b1, cn, d,
                  [&](int l, int v) { return l < b1 && v < d ? Xrows[l * ld + v] : 0.f; },
                  [&](int v, int c) { return c < cn && v < d ? Wc[c * ld + v] : 0.f; },

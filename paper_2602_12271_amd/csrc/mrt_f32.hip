@@ -150,6 +150,10 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
   const float* Yp = (const float*)p.Y + row0 * d;
   const float* cLp = p.cL + row0;
 
+  // regular Monarch under the chunk-causal mask: key rows of later chunks are zeros of L (the
+  // first chunk of 16 key rows always holds a visible one, so the running maximum is finite)
+  auto hidden = [&](int l, int nk) { return p.rl > 0 && nk >= visible_key_rows(p, l); };
+
   // pass 1: log-sum-exp of every row l over all visible nk
   float rmax = -INFINITY, rsum = 0.f;
   for (int c0 = 0; c0 < NK; c0 += kCH) {
@@ -163,7 +167,8 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
     gemm_tiles(b1, cn, d,
                [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
                [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
-               [&](int l, int c, float x) { Zc[l * lz + c] = p.scale * x - cLp[c0 + c]; }, tid);
+               [&](int l, int c, float x) { Zc[l * lz + c] = hidden(l, c0 + c) ? -INFINITY : p.scale * x - cLp[c0 + c]; },
+               tid);
     __syncthreads();
     if (tid < b1) {
       float mx = rmax;
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(kThreads) void k_f32_stage_l(KParams p) {
                [&](int l, int v) { return l < b1 && v < d ? Qj[l * ld + v] : 0.f; },
                [&](int v, int c) { return c < cn && v < d ? Kc[c * ld + v] : 0.f; },
                [&](int l, int c, float x) {
-                 const float z = p.scale * x - cLp[c0 + c] - lse[l];   // log L[l,nk]
+                 const float z = hidden(l, c0 + c) ? -INFINITY : p.scale * x - cLp[c0 + c] - lse[l];   // log L[l,nk]
                  Zc[l * lz + c] = LAST ? expf(z) : z;
                }, tid);
     __syncthreads();

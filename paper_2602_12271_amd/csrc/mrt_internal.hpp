@@ -56,6 +56,11 @@ struct KParams {
   int th_tok;   // tokens from one row band to the next = nh * w
   int ct;       // tile rows per causal chunk; 0 = no mask
   int qt0;      // tile row (of the key grid) at which query tile row 0 sits (mask only)
+  // regular Monarch under the chunk-causal mask: its one tile straddles every chunk, and the mask
+  // is a support constraint on L.  Block row x holds frame x / (rows per frame), so query row l
+  // sees the key rows k < visible_key_rows(p, l), a prefix.  rl == 0: nothing hidden.
+  int rl;       // block rows per causal chunk
+  int rq0;      // block row at which query row 0 sits on the key side (frame offset * rows per frame)
   int cc;       // frames per causal chunk (dense baseline); 0 = no mask
   int qoff;     // absolute frame of query frame 0 (dense baseline)
   int Nq, Nkv;  // tokens per head on the query / key side
@@ -78,6 +83,13 @@ __host__ __device__ inline int visible_key_tile_rows(int a, int c1k, int ct, int
   if (ct == 0) return c1k;
   const int rows = ((qt0 + a) / ct + 1) * ct;
   return rows < c1k ? rows : c1k;
+}
+
+// Regular Monarch with p.rl > 0: number of leading key rows visible to query row l (the rows of
+// every chunk up to and including the query row's own).  May exceed b1; the diagonal k = l is
+// always below it.
+__host__ __device__ inline int visible_key_rows(const KParams& p, int l) {
+  return ((l + p.rq0) / p.rl + 1) * p.rl;
 }
 
 // Arguments of the backward kernels: the forward geometry plus gradient buffers.

@@ -62,6 +62,10 @@ def test_named_configurations_are_accepted():
     c0 = pkg.make_problem(batch=1, heads=1, head_dim=64, f_q=1, f_kv=1, h=24, w=24,
                           dtype=B.MRT_F32, scale=1.0)
     assert pkg.monarch_attn_check(c0, 24, 24, 0, 1) == B.MRT_OK                        # C0
+    # regular Monarch under a chunk-causal mask (frame-causal here; 3-frame chunks hide nothing)
+    assert pkg.monarch_attn_check(problem(), 90, 52, 0, 2, 1) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(), 90, 52, 0, 2, 3) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(assign="fw_h"), 156, 30, 0, 2, 2) == B.MRT_OK
     # other aligned assignments within the block limits, and tiles that are a row range of a frame
     assert pkg.monarch_attn_check(problem(assign="w_fh"), 52, 90, 0, 2) == B.MRT_OK
     assert pkg.monarch_attn_check(problem(assign="fw_h"), 156, 30, 0, 2) == B.MRT_OK
@@ -78,7 +82,7 @@ def test_named_configurations_are_accepted():
     (dict(), (90, 50, 0, 2, 0), B.MRT_ERR_BLOCK),            # b2 != w for regular
     (dict(), (45, 52, 0, 2, 0), B.MRT_ERR_BLOCK),            # b1 != f*h for regular
     (dict(f_kv=21), (90, 52, 0, 2, 0), B.MRT_ERR_UNSUPPORTED),   # rectangular needs tile=1
-    (dict(), (90, 52, 0, 2, 3), B.MRT_ERR_UNSUPPORTED),      # regular + mask
+    (dict(assign="w_fh"), (52, 90, 0, 2, 1), B.MRT_ERR_UNSUPPORTED),   # regular + mask needs frames on the b1 side
     (dict(), (90, 52, 0, 0, 0), B.MRT_ERR_SHAPE),            # iters < 1
     (dict(), (90, 52, 2, 1, 0), B.MRT_ERR_SHAPE),            # tile flag
     (dict(), (90, 25, 1, 2, 0), B.MRT_ERR_BLOCK),            # 25 does not divide 52
