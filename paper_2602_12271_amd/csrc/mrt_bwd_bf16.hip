@@ -683,13 +683,19 @@ __global__ __launch_bounds__(256, NLT <= 6 ? 3 : 2) void k_bwdm_l_cols(BwdParams
 }
 
 // ---------------------------------------------------------------------------------------
-// stage R backward, one workgroup (NT waves) per key block (n, k), looping over the query tiles m
-// that see it.  Wave w owns query columns j = 16w + c for the softmax side (as the forward stage R)
-// and key rows i = 16w + c for the dK / dV accumulation, whose contraction runs over j: R and
-// scale dS pass through LDS transposed ([i][j], bf16) in between.
+// stage R backward.  Work item = one key block (batch*head, n, k); for each the workgroup (NT waves)
+// loops over the query tiles m that see it.  Wave w owns query columns j = 16w + c for the softmax
+// side (as the forward stage R) and key rows i = 16w + c for the dK / dV accumulation, whose
+// contraction runs over j: R and scale dS pass through LDS transposed ([i][j], bf16) in between.
+//
+// The grid is persistent: workgroup g takes items g, g + gridDim.x, ...  The global loads of the
+// next step (the next query tile, or the next item's K / V and first tile) are issued as soon as
+// the current step's operands have moved from the register stage into LDS, so they are in flight
+// during the whole of the current step's arithmetic and stores; without that every workgroup of
+// the launch alternates between a load burst, arithmetic and a store burst in lockstep.
 // ---------------------------------------------------------------------------------------
 template <int NT, int D, bool LAST, typename TW>
-__global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, int first) {
+__global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, int first, int nitems) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NT + 1) / 2, ROWS = 32 * KS2;
   constexpr int LR = ROWS + 8, NTHR = 64 * NT;
@@ -703,42 +709,60 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2, d = D;
-  const int nk = blockIdx.x, bhl = blockIdx.z, bh = p.bh0 + bhl;
-  const int n = nk / b1, k = nk - n * b1;
-  const int an = n / p.c2, bn = n - an * p.c2;
-  const int b = bh / p.H, hd = bh - b * p.H;
+  const int nkb = p.ntk * b1;                   // key blocks per (batch, head)
   const size_t NKtot = (size_t)p.ntk * b1;
-
-  const long long krow = row_offset(p, an, k);
-  const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + krow * p.ks.token;
-  const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + krow * p.vs.token;
-  const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
   const int j = 16 * wave + c;                  // query column (softmax side) / key row (dK side)
   const float scale2 = p.scale * kLog2e;
-  f32x4 oK[1][NVT], oV[1][NVT];
-#pragma unroll
-  for (int vt = 0; vt < NVT; ++vt) {
-    oK[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
 
-  // the query tiles that do not see this key tile form a prefix (a later chunk sees more)
-  int ml0 = 0;
-  while (ml0 < p.ntq && an >= visible_key_tile_rows((p.m0 + ml0) / p.c2, p.c1k, p.ct, p.qt0)) ++ml0;
+  // one work item: key block nk of (batch, head) slot bhl
+  struct Item {
+    int w, nk, bhl, bh, k, an, bn, ml0;
+    long long krow;
+  };
+  auto decode = [&](int w) {
+    Item it;
+    it.w = w;
+    it.bhl = w / nkb;
+    it.nk = w - it.bhl * nkb;
+    it.bh = p.bh0 + it.bhl;
+    const int n = it.nk / b1;
+    it.k = it.nk - n * b1;
+    it.an = n / p.c2;
+    it.bn = n - it.an * p.c2;
+    it.krow = row_offset(p, it.an, it.k);
+    // the query tiles that do not see this key tile form a prefix (a later chunk sees more)
+    it.ml0 = 0;
+    while (it.ml0 < p.ntq && it.an >= visible_key_tile_rows((p.m0 + it.ml0) / p.c2, p.c1k, p.ct, p.qt0)) ++it.ml0;
+    return it;
+  };
 
-  // register stages: every global load of a tile is issued before the first LDS store
+  // register stages: every global load of a step is issued before the first LDS store
   constexpr bool kF32Ws = sizeof(TW) == 4;
+  RowRegs<D, ROWS, NTHR> rk;                          // K rows
+  RowRegs<D, LAST ? ROWS : 1, NTHR> rv;               // V rows (t = T)
   RowRegs<D, ROWS, NTHR> ra;                          // Q rows, or abar stored as bf16
   RowRegsF32<D, kF32Ws ? ROWS : 1, NTHR> raf;         // abar stored as fp32
   typename std::conditional<kF32Ws, RowRegsF32<D, ROWS, NTHR>, RowRegs<D, ROWS, NTHR>>::type rg;
   typename std::conditional<kF32Ws, RowRegsF32<D, LAST ? ROWS : 1, NTHR>, RowRegs<D, LAST ? ROWS : 1, NTHR>>::type ry;
-  auto issue = [&](int ml) {
+  auto issue_block = [&](const Item& it) {
+    const int b = it.bh / p.H, hd = it.bh - b * p.H;
+    const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + it.krow * p.ks.token;
+    rk.load(Kp, TokRows{0, p.cmap, it.bn * b2, p.ks.token}, b2, tid);
+    if (LAST) {
+      const u16* Vp = (const u16*)p.V + b * p.vs.batch + hd * p.vs.head + it.krow * p.vs.token;
+      rv.load(Vp, TokRows{0, p.cmap, it.bn * b2, p.vs.token}, b2, tid);
+    }
+  };
+  auto issue_tile = [&](const Item& it, int ml) {
     const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
-    const size_t jrow0 = ((size_t)bhl * p.ntq + ml) * b2;
+    const size_t jrow0 = ((size_t)it.bhl * p.ntq + ml) * b2;
+    const int nk = it.nk;
     auto jrow = [&](int jj) { return (long long)(((jrow0 + jj) * NKtot + nk) * d); };
-    const size_t ablk = (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2;
+    const size_t ablk = (((size_t)it.bhl * p.ntq + ml) * NKtot + nk) * b2;
     if (first) {
-      const long long qrow = row_offset(p, a, k);
+      const int b = it.bh / p.H, hd = it.bh - b * p.H;
+      const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
+      const long long qrow = row_offset(p, a, it.k);
       ra.load(Qbase + qrow * p.qs.token, TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
     } else if constexpr (kF32Ws) {
       raf.load((const float*)p.aR + ablk * d, PlainRows{D}, b2, tid);
@@ -748,142 +772,181 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
     rg.load((const TW*)bp.daL, jrow, b2, tid);
     if (LAST) ry.load((const TW*)bp.dY, jrow, b2, tid);
   };
-  {
-    RowRegs<D, ROWS, NTHR> rk;
-    RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
-    rk.load(Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
-    if (LAST) rv.load(Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
-    if (ml0 < p.ntq) issue(ml0);
-    rk.template store<LD>(Ks, tid);
-    if (LAST) rv.template store<LD>(Vs, tid);
-  }
+
+  Item cur = decode(blockIdx.x);          // the host launches at most nitems workgroups
+  int ml = cur.ml0;
+  bool newblk = true;
+  issue_block(cur);
+  if (ml < p.ntq) issue_tile(cur, ml);
   for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
 
-  for (int ml = ml0; ml < p.ntq; ++ml) {
-    // rows (j, nk) of the [m][j][nk][..] arrays and the (m, nk) block of the [m][nk][j][d] arrays
-    const size_t jrow0 = ((size_t)bhl * p.ntq + ml) * b2;
-    const size_t ablk = (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2;
-    if (ml > ml0) {
-      issue(ml);
-      __syncthreads();                             // the previous tile's reads of As / Gs / Ys / RT / ST
+  f32x4 oK[1][NVT], oV[1][NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) {
+    oK[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  while (true) {
+    const bool has_tile = ml < p.ntq;        // an item no query tile sees only writes its zeros
+    __syncthreads();                         // the previous step's reads of the LDS tiles
+    if (newblk) {
+      rk.template store<LD>(Ks, tid);
+      if (LAST) rv.template store<LD>(Vs, tid);
     }
-    if (first || !kF32Ws) ra.template store<LD>(As, tid);
-    else raf.template store<LD>(As, tid);
-    rg.template store<LD>(Gs, tid);
-    if (LAST) ry.template store<LD>(Ys, tid);
+    if (has_tile) {
+      if (first || !kF32Ws) ra.template store<LD>(As, tid);
+      else raf.template store<LD>(As, tid);
+      rg.template store<LD>(Gs, tid);
+      if (LAST) ry.template store<LD>(Ys, tid);
+    }
+    // c_L's gradient of this lane's column: fetched ahead of the next step's loads, which would
+    // otherwise have to land first (loads return in order)
+    float dcl = 0.f;
+    if (has_tile && j < b2) dcl = bp.dcL[(((size_t)cur.bhl * p.ntq + ml) * b2 + j) * NKtot + cur.nk];
+    // the step after this one, and its loads
+    const bool item_done = !has_tile || ml + 1 >= p.ntq;
+    Item nxt = cur;
+    int nml = ml + 1;
+    bool more = true;
+    if (item_done) {
+      const int w2 = cur.w + (int)gridDim.x;
+      more = w2 < nitems;
+      if (more) {
+        nxt = decode(w2);
+        nml = nxt.ml0;
+        issue_block(nxt);
+      }
+    }
+    if (more && nml < p.ntq) issue_tile(nxt, nml);
     __syncthreads();
 
-    // ---- softmax side: lanes own query column j
-    {
-      const bool live = j < b2;
-      bf16x8 qv[KS1], gv[KS1], yv[KS1];
+    if (has_tile) {
+      // rows (j, nk) of the [m][j][nk][..] arrays and the (m, nk) block of the [m][nk][j][d] arrays
+      const int nk = cur.nk, bhl = cur.bhl, bh = cur.bh, k = cur.k;
+      const size_t ablk = (((size_t)bhl * p.ntq + ml) * NKtot + nk) * b2;
+      // ---- softmax side: lanes own query column j
+      {
+        const bool live = j < b2;
+        bf16x8 qv[KS1], gv[KS1], yv[KS1];
 #pragma unroll
-      for (int ks = 0; ks < KS1; ++ks) {
-        qv[ks] = ld_lds_16B(As + j * LD + 32 * ks + 8 * g);
-        gv[ks] = ld_lds_16B(Gs + j * LD + 32 * ks + 8 * g);
-        if (LAST) yv[ks] = ld_lds_16B(Ys + j * LD + 32 * ks + 8 * g);
-      }
-      const float dcl = live ? bp.dcL[(jrow0 + j) * NKtot + nk] : 0.f;
-      f32x4 s[NT], dr[NT];
-      rows_dot<D, NT, LD>(Ks, qv, s, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      rows_dot<D, NT, LD>(Ks, gv, dr, lane);
-      __builtin_amdgcn_sched_barrier(0);
-      if (LAST) {
-        f32x4 dy[NT];
-        rows_dot<D, NT, LD>(Vs, yv, dy, lane);
-#pragma unroll
-        for (int it = 0; it < NT; ++it) dr[it] += dy[it];
+        for (int ks = 0; ks < KS1; ++ks) {
+          qv[ks] = ld_lds_16B(As + j * LD + 32 * ks + 8 * g);
+          gv[ks] = ld_lds_16B(Gs + j * LD + 32 * ks + 8 * g);
+          if (LAST) yv[ks] = ld_lds_16B(Ys + j * LD + 32 * ks + 8 * g);
+        }
+        f32x4 s[NT], dr[NT];
+        rows_dot<D, NT, LD>(Ks, qv, s, lane);
         __builtin_amdgcn_sched_barrier(0);
+        rows_dot<D, NT, LD>(Ks, gv, dr, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        if (LAST) {
+          f32x4 dy[NT];
+          rows_dot<D, NT, LD>(Vs, yv, dy, lane);
+#pragma unroll
+          for (int it = 0; it < NT; ++it) dr[it] += dy[it];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int it = 0; it < NT; ++it)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const bool ok = 16 * it + 4 * g + r < b2;
+            s[it][r] = ok ? s[it][r] * scale2 : -INFINITY;
+            mx = fmaxf(mx, s[it][r]);
+          }
+        mx = xmax(mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int it = 0; it < NT; ++it)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) sum += exp2_fast(s[it][r] - mx);
+        const float lse2 = mx + log2_fast(xsum(sum));
+        // R, dR (with the entropy term), dS
+        float dot = 0.f;
+#pragma unroll
+        for (int it = 0; it < NT; ++it)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const bool ok = live && 16 * it + 4 * g + r < b2;
+            const float logr2 = s[it][r] - lse2;                     // log2 R, -inf beyond b2
+            const float R = ok ? exp2_fast(logr2) : 0.f;
+            const float dR = ok ? dr[it][r] + dcl * fmaf(logr2, kLn2, 1.0f) : 0.f;
+            s[it][r] = R;
+            dr[it][r] = dR;
+            dot = fmaf(R, dR, dot);
+          }
+        dot = xsum(dot);
+#pragma unroll
+        for (int it = 0; it < NT; ++it)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float ds = p.scale * s[it][r] * (dr[it][r] - dot);   // scale dS
+            dr[it][r] = ds;
+            const int i = 16 * it + 4 * g + r;
+            RT[i * LR + j] = f2bf(s[it][r]);
+            ST[i * LR + j] = f2bf(ds);
+          }
+        // d abar[j] = sum_i (scale dS[j, i]) K[i]
+        f32x4 o[NVT];
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < KS2; ++st) {
+          const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+          const bool has = 2 * st + 1 < NT;
+          const bf16x8 pz = pack8(dr[2 * st], has ? dr[has ? 2 * st + 1 : 0] : zero);
+          pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // d abar of the first iteration is summed into dQ in fp32 by the last kernel of the call
+        // (with one key tile per query tile there is nothing to sum: it goes straight into dQ)
+        if (live) {
+          if (first && bp.dq_from_r) {
+            const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
+            const long long tok = row_offset(p, a, k) + axis_offset(p.cmap, bq * b2 + j);
+            store_rows_f32<D>(bp.dQ + ((size_t)bh * p.Nq + tok) * d, o, 1.0f, g, true);
+          } else if (first) {
+            store_rows_f32<D>(bp.dA + (ablk + j) * d, o, 1.0f, g, false);
+          } else {
+            store_ws_row<D>((TW*)bp.dA + (ablk + j) * d, o, 1.0f, g);
+          }
+        }
       }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int it = 0; it < NT; ++it)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool ok = 16 * it + 4 * g + r < b2;
-          s[it][r] = ok ? s[it][r] * scale2 : -INFINITY;
-          mx = fmaxf(mx, s[it][r]);
-        }
-      mx = xmax(mx);
-      float sum = 0.f;
-#pragma unroll
-      for (int it = 0; it < NT; ++it)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) sum += exp2_fast(s[it][r] - mx);
-      const float lse2 = mx + log2_fast(xsum(sum));
-      // R, dR (with the entropy term), dS
-      float dot = 0.f;
-#pragma unroll
-      for (int it = 0; it < NT; ++it)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool ok = live && 16 * it + 4 * g + r < b2;
-          const float logr2 = s[it][r] - lse2;                     // log2 R, -inf beyond b2
-          const float R = ok ? exp2_fast(logr2) : 0.f;
-          const float dR = ok ? dr[it][r] + dcl * fmaf(logr2, kLn2, 1.0f) : 0.f;
-          s[it][r] = R;
-          dr[it][r] = dR;
-          dot = fmaf(R, dR, dot);
-        }
-      dot = xsum(dot);
-#pragma unroll
-      for (int it = 0; it < NT; ++it)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float ds = p.scale * s[it][r] * (dr[it][r] - dot);   // scale dS
-          dr[it][r] = ds;
-          const int i = 16 * it + 4 * g + r;
-          RT[i * LR + j] = f2bf(s[it][r]);
-          ST[i * LR + j] = f2bf(ds);
-        }
-      // d abar[j] = sum_i (scale dS[j, i]) K[i]
-      f32x4 o[NVT];
-#pragma unroll
-      for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      __syncthreads();                               // RT / ST complete
+
+      // ---- accumulation side: lanes own key row i = j
 #pragma unroll
       for (int st = 0; st < KS2; ++st) {
-        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        const bool has = 2 * st + 1 < NT;
-        const bf16x8 pz = pack8(dr[2 * st], has ? dr[has ? 2 * st + 1 : 0] : zero);
-        pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
+        const bf16x8 bR[1] = {ld_lds_16B(RT + j * LR + 32 * st + 8 * g)};
+        const bf16x8 bS[1] = {ld_lds_16B(ST + j * LR + 32 * st + 8 * g)};
+        pv_step_nat<D, 1, LD>(Gs + 32 * st * LD, bR, 1, oK, lane);     // dK += R^T d alpha_L
         __builtin_amdgcn_sched_barrier(0);
-      }
-      // d abar of the first iteration is summed into dQ in fp32 by the last kernel of the call
-      // (with one key tile per query tile there is nothing to sum: it goes straight into dQ)
-      if (live) {
-        if (first && bp.dq_from_r) {
-          const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
-          const long long tok = row_offset(p, a, k) + axis_offset(p.cmap, bq * b2 + j);
-          store_rows_f32<D>(bp.dQ + ((size_t)bh * p.Nq + tok) * d, o, 1.0f, g, true);
-        } else if (first) {
-          store_rows_f32<D>(bp.dA + (ablk + j) * d, o, 1.0f, g, false);
-        } else {
-          store_ws_row<D>((TW*)bp.dA + (ablk + j) * d, o, 1.0f, g);
+        pv_step_nat<D, 1, LD>(As + 32 * st * LD, bS, 1, oK, lane);     // dK += scale dS^T abar
+        __builtin_amdgcn_sched_barrier(0);
+        if (LAST) {
+          pv_step_nat<D, 1, LD>(Ys + 32 * st * LD, bR, 1, oV, lane);   // dV += R^T d Y
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
-    __syncthreads();                               // RT / ST complete
-
-    // ---- accumulation side: lanes own key row i = j
+    if (item_done) {
+      if (j < b2) {
+        const long long tok = cur.krow + axis_offset(p.cmap, cur.bn * b2 + j);
+        store_rows_f32<D>(bp.dK + ((size_t)cur.bh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
+        if (LAST) store_rows_f32<D>(bp.dV + ((size_t)cur.bh * p.Nkv + tok) * d, oV[0], 1.0f, g, false);
+      }
 #pragma unroll
-    for (int st = 0; st < KS2; ++st) {
-      const bf16x8 bR[1] = {ld_lds_16B(RT + j * LR + 32 * st + 8 * g)};
-      const bf16x8 bS[1] = {ld_lds_16B(ST + j * LR + 32 * st + 8 * g)};
-      pv_step_nat<D, 1, LD>(Gs + 32 * st * LD, bR, 1, oK, lane);     // dK += R^T d alpha_L
-      __builtin_amdgcn_sched_barrier(0);
-      pv_step_nat<D, 1, LD>(As + 32 * st * LD, bS, 1, oK, lane);     // dK += scale dS^T abar
-      __builtin_amdgcn_sched_barrier(0);
-      if (LAST) {
-        pv_step_nat<D, 1, LD>(Ys + 32 * st * LD, bR, 1, oV, lane);   // dV += R^T d Y
-        __builtin_amdgcn_sched_barrier(0);
+      for (int vt = 0; vt < NVT; ++vt) {
+        oK[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
     }
-  }
-  if (j < b2) {
-    const long long tok = krow + axis_offset(p.cmap, bn * b2 + j);
-    store_rows_f32<D>(bp.dK + ((size_t)bh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
-    if (LAST) store_rows_f32<D>(bp.dV + ((size_t)bh * p.Nkv + tok) * d, oV[0], 1.0f, g, false);
+    if (!more) break;
+    cur = nxt;
+    ml = nml;
+    newblk = item_done;
   }
 }
 
@@ -924,19 +987,38 @@ static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16
 
 bool bwd_bf16_r_fits(const KParams& kp) { return kp.b2 <= 64 && (kp.d == 64 || kp.d == 128); }
 
+// Workgroups of `kernel` the current device keeps resident at once (its compute units times the
+// workgroups of `threads` threads that fit one): the size of a persistent grid.
+template <typename K>
+static int resident_workgroups(K kernel, int threads) {
+  int per_cu = 0, dev = 0, cus = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1)
+    per_cu = 1;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  return per_cu * cus;
+}
+
 template <int NT, int D, typename TW>
-static hipError_t launch_r_nt(const BwdParams& bp, dim3 grid, bool first, bool last, hipStream_t s) {
-  if (last) k_bwdm_r<NT, D, true, TW><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
-  else k_bwdm_r<NT, D, false, TW><<<grid, 64 * NT, 0, s>>>(bp, first ? 1 : 0);
+static hipError_t launch_r_nt(const BwdParams& bp, int nitems, bool first, bool last, hipStream_t s) {
+  // persistent grid: as many workgroups as stay resident, each striding over the key blocks
+  if (last) {
+    static const int resident = resident_workgroups(k_bwdm_r<NT, D, true, TW>, 64 * NT);
+    k_bwdm_r<NT, D, true, TW><<<dim3(nitems < resident ? nitems : resident), 64 * NT, 0, s>>>(bp, first ? 1 : 0, nitems);
+  } else {
+    static const int resident = resident_workgroups(k_bwdm_r<NT, D, false, TW>, 64 * NT);
+    k_bwdm_r<NT, D, false, TW><<<dim3(nitems < resident ? nitems : resident), 64 * NT, 0, s>>>(bp, first ? 1 : 0, nitems);
+  }
   return hipGetLastError();
 }
 template <int D, typename TW>
-static hipError_t launch_r_d(const BwdParams& bp, dim3 grid, bool first, bool last, hipStream_t s) {
+static hipError_t launch_r_d(const BwdParams& bp, int nitems, bool first, bool last, hipStream_t s) {
   switch ((bp.k.b2 + 15) / 16) {
-    case 1: return launch_r_nt<1, D, TW>(bp, grid, first, last, s);
-    case 2: return launch_r_nt<2, D, TW>(bp, grid, first, last, s);
-    case 3: return launch_r_nt<3, D, TW>(bp, grid, first, last, s);
-    case 4: return launch_r_nt<4, D, TW>(bp, grid, first, last, s);
+    case 1: return launch_r_nt<1, D, TW>(bp, nitems, first, last, s);
+    case 2: return launch_r_nt<2, D, TW>(bp, nitems, first, last, s);
+    case 3: return launch_r_nt<3, D, TW>(bp, nitems, first, last, s);
+    case 4: return launch_r_nt<4, D, TW>(bp, nitems, first, last, s);
   }
   return hipErrorInvalidValue;
 }
@@ -946,10 +1028,14 @@ static hipError_t launch_r_d(const BwdParams& bp, dim3 grid, bool first, bool la
 hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, bool last, bool ws_bf16,
                                    hipStream_t s) {
   const KParams& kp = bp.k;
-  dim3 grid(kp.ntk * kp.b1, 1, nbh);
+  const long long items = (long long)kp.ntk * kp.b1 * nbh;      // key blocks of the pass
+  if (items < 1 || items > 0x7fffffff) return hipErrorInvalidValue;
+  const int nitems = (int)items;
   if (ws_bf16)
-    return kp.d == 128 ? launch_r_d<128, u16>(bp, grid, first, last, s) : launch_r_d<64, u16>(bp, grid, first, last, s);
-  return kp.d == 128 ? launch_r_d<128, float>(bp, grid, first, last, s) : launch_r_d<64, float>(bp, grid, first, last, s);
+    return kp.d == 128 ? launch_r_d<128, u16>(bp, nitems, first, last, s)
+                       : launch_r_d<64, u16>(bp, nitems, first, last, s);
+  return kp.d == 128 ? launch_r_d<128, float>(bp, nitems, first, last, s)
+                     : launch_r_d<64, float>(bp, nitems, first, last, s);
 }
 
 // Stage L backward on the matrix unit; scratch = bwd_bf16_scratch_bytes() of device memory.
