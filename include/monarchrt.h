@@ -168,7 +168,7 @@ mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk);
 mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
                           const mrt_problem* p, int causal_chunk, void* hip_stream);
 
-/* Number of head groups monarch_attn_fwd runs concurrently: 1..4, or 0 (default) to let the library
+/* Number of head groups monarch_attn_fwd and monarch_attn_bwd run concurrently: 1..4, or 0 (default) to let the library
  * choose per call (one group unless the launches are long and their grids small).  With more than one
  * group the library forks helper HIP streams from hip_stream and joins them back before it
  * returns, so the call is still ordered like a single operation on hip_stream (and can be

@@ -547,29 +547,35 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
   // array X of the pass starts at base + off_X * G (every array holds G heads back to back)
   auto arr = [&](size_t off) { return base + off * (size_t)G; };
 
-  for (int bh0 = 0; bh0 < BH; bh0 += G) {
-    const int nbh = BH - bh0 < G ? BH - bh0 : G;
+  // array X of heads [lo, ..) of the pass: every array keeps rowsD (or rowsS, or the scratch
+  // size) bytes per head, and a kernel launched for a group of heads packs them from its base
+  auto arrD = [&](size_t off, int lo) { return arr(off) + L.rowsD * (size_t)lo; };
+  auto arrS = [&](size_t off, int lo) { return arr(off) + L.rowsS * (size_t)lo; };
+
+  // the whole backward pass of heads [bh0 + lo, bh0 + hi) of a pass, on stream gs
+  auto run_heads = [&](int bh0, int lo, int hi, hipStream_t gs) -> mrt_status {
+    const int nbh = hi - lo;
     KParams kp = pl.kp;
     kp.Q = Q; kp.K = K; kp.V = V; kp.O = nullptr;
-    kp.bh0 = bh0; kp.m0 = 0; kp.ntq = pl.ntq_total;
-    kp.Y = arr(L.off_Y());
+    kp.bh0 = bh0 + lo; kp.m0 = 0; kp.ntq = pl.ntq_total;
+    kp.Y = arrD(L.off_Y(), lo);
     hipError_t e;
     // forward intermediates of every iteration (the last iteration's stage L is not needed): by
     // the bf16 forward kernels when every backward stage runs on the matrix unit (the arrays then
     // hold bf16), else by the fp32 kernels
     for (int t = 1; t <= T; ++t) {
-      kp.aL = arr(L.off_aL(t));
-      kp.cL = (float*)arr(L.off_cL(t));
-      kp.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
+      kp.aL = arrD(L.off_aL(t), lo);
+      kp.cL = (float*)arrS(L.off_cL(t), lo);
+      kp.aR = t >= 2 ? arrD(L.off_aR(t), lo) : nullptr;
       kp.cmx_out = nullptr; kp.cinv_out = nullptr;
-      e = ws_bf16 ? launch_bf16_stage_r(kp, nbh, t == 1, t == T, s)
-                  : launch_f32_stage_r(kp, pl.dtype, nbh, t == 1, t == T, s);
+      e = ws_bf16 ? launch_bf16_stage_r(kp, nbh, t == 1, t == T, gs)
+                  : launch_f32_stage_r(kp, pl.dtype, nbh, t == 1, t == T, gs);
       if (e != hipSuccess) return hip_fail(e, "backward: forward stage R launch");
       if (t < T) {
-        kp.aR = arr(L.off_aR(t + 1));
-        kp.cmx_out = (float*)arr(L.off_cmx(t + 1));
-        kp.cinv_out = (float*)arr(L.off_cinv(t + 1));
-        e = ws_bf16 ? launch_bf16_stage_l(kp, nbh, false, s) : launch_f32_stage_l(kp, pl.dtype, nbh, false, s);
+        kp.aR = arrD(L.off_aR(t + 1), lo);
+        kp.cmx_out = (float*)arrS(L.off_cmx(t + 1), lo);
+        kp.cinv_out = (float*)arrS(L.off_cinv(t + 1), lo);
+        e = ws_bf16 ? launch_bf16_stage_l(kp, nbh, false, gs) : launch_f32_stage_l(kp, pl.dtype, nbh, false, gs);
         if (e != hipSuccess) return hip_fail(e, "backward: forward stage L launch");
       }
     }
@@ -579,33 +585,68 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     memset(&bp, 0, sizeof(bp));
     bp.k = kp;
     bp.dO = dO;
-    bp.daL = (float*)arr(L.off_daL());
-    bp.dcL = (float*)arr(L.off_dcL());
-    bp.dY = (float*)arr(L.off_dY());
-    bp.dA = (float*)arr(L.off_dA());
+    bp.daL = (float*)arrD(L.off_daL(), lo);
+    bp.dcL = (float*)arrS(L.off_dcL(), lo);
+    bp.dY = (float*)arrD(L.off_dY(), lo);
+    bp.dA = (float*)arrD(L.off_dA(), lo);
     bp.dQ = dQ; bp.dK = dK; bp.dV = dV;
     const bool r_mfma = bf16_ops && bwd_bf16_r_fits(bp.k);
     bp.dq_from_r = (r_mfma && kp.ntk == 1) ? 1 : 0;
     for (int t = T; t >= 1; --t) {
       const bool last = t == T;
-      bp.k.aL = arr(L.off_aL(t));
-      bp.k.cL = (float*)arr(L.off_cL(t));
-      bp.Anext = last ? nullptr : (const float*)arr(L.off_aR(t + 1));
-      bp.cmx = last ? nullptr : (const float*)arr(L.off_cmx(t + 1));
-      bp.cinv = last ? nullptr : (const float*)arr(L.off_cinv(t + 1));
+      bp.k.aL = arrD(L.off_aL(t), lo);
+      bp.k.cL = (float*)arrS(L.off_cL(t), lo);
+      bp.Anext = last ? nullptr : (const float*)arrD(L.off_aR(t + 1), lo);
+      bp.cmx = last ? nullptr : (const float*)arrS(L.off_cmx(t + 1), lo);
+      bp.cinv = last ? nullptr : (const float*)arrS(L.off_cinv(t + 1), lo);
       bp.accumulate = last ? 0 : 1;
-      e = L.mfma ? launch_bwd_bf16_stage_l(bp, nbh, last, ws_bf16, arr(L.off_scratch()), s)
-                 : launch_bwd_stage_l(bp, pl.dtype, nbh, last, s);
+      e = L.mfma ? launch_bwd_bf16_stage_l(bp, nbh, last, ws_bf16, arr(L.off_scratch()) + L.scratch * (size_t)lo, gs)
+                 : launch_bwd_stage_l(bp, pl.dtype, nbh, last, gs);
       if (e != hipSuccess) return hip_fail(e, "backward stage L launch");
-      bp.k.aR = t >= 2 ? arr(L.off_aR(t)) : nullptr;
-      e = r_mfma ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, ws_bf16, s)
-                 : launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, s);
+      bp.k.aR = t >= 2 ? arrD(L.off_aR(t), lo) : nullptr;
+      e = r_mfma ? launch_bwd_bf16_stage_r(bp, nbh, t == 1, last, ws_bf16, gs)
+                 : launch_bwd_stage_r(bp, pl.dtype, nbh, t == 1, last, gs);
       if (e != hipSuccess) return hip_fail(e, "backward stage R launch");
     }
-    if (!bp.dq_from_r && (e = launch_bwd_q_first(bp, nbh, s)) != hipSuccess)
+    if (!bp.dq_from_r && (e = launch_bwd_q_first(bp, nbh, gs)) != hipSuccess)
       return hip_fail(e, "backward dQ launch");
+    return MRT_OK;
+  };
+
+  // Heads are independent: as in the forward call, a pass may be cut into head groups whose kernel
+  // chains run on helper streams forked from and joined back to the caller's stream, so that the
+  // part-filled last round of one group's launch overlaps another group's kernels.  It pays for
+  // long calls whose stage L launches are a small multiple of what the chip holds (KV-cache
+  // shapes); otherwise the pass runs on the caller's stream.
+  int want_groups = g_max_groups;
+  if (want_groups == 0) {
+    const long long l_wgs = (long long)pl.ntq_total * pl.kp.b2 * G;
+    want_groups = (L.rowsD * (size_t)G >= (size_t(256) << 20) && l_wgs < 2048) ? 2 : 1;
   }
-  return MRT_OK;
+  StreamPool* pool = (g_prof_on || want_groups <= 1) ? nullptr : get_pool();
+  mrt_status status = MRT_OK;
+  for (int bh0 = 0; bh0 < BH && status == MRT_OK; bh0 += G) {
+    const int nbh = BH - bh0 < G ? BH - bh0 : G;
+    int ngroups = pool ? (nbh < want_groups ? nbh : want_groups) : 1;
+    if (ngroups > 1) {
+      if (hipEventRecord(pool->fork, s) != hipSuccess) ngroups = 1;
+      for (int gi = 1; gi < ngroups; ++gi)
+        if (hipStreamWaitEvent(pool->side[gi - 1], pool->fork, 0) != hipSuccess) status = MRT_ERR_HIP;
+      if (status != MRT_OK) { set_error("helper stream fork failed"); break; }
+    }
+    for (int gi = 0; gi < ngroups && status == MRT_OK; ++gi) {
+      const int lo = (int)((long long)nbh * gi / ngroups), hi = (int)((long long)nbh * (gi + 1) / ngroups);
+      status = run_heads(bh0, lo, hi, gi == 0 ? s : pool->side[gi - 1]);
+    }
+    // join even after a failed launch, so that the helper streams never run ahead of the caller
+    for (int gi = 1; gi < ngroups; ++gi) {
+      if (hipEventRecord(pool->join[gi - 1], pool->side[gi - 1]) != hipSuccess ||
+          hipStreamWaitEvent(s, pool->join[gi - 1], 0) != hipSuccess) {
+        if (status == MRT_OK) { set_error("helper stream join failed"); status = MRT_ERR_HIP; }
+      }
+    }
+  }
+  return status;
 }
 
 mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk) {

@@ -1,6 +1,8 @@
 """GPU parity of the backward pass (gradients w.r.t. Q, K, V through every refinement iteration,
 Sec. 4.3) against the fp64 oracle's gradients, through the C ABI.  The kernels compute in fp32
 whatever the storage type, so the bar is the fp32 one, scaled by the size of the gradients."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -165,3 +167,31 @@ def test_backward_rerun_is_bit_identical(name):
     torch.cuda.synchronize()
     for a, b in zip(g1, g2):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name", ["bf16-stream-mask", "tiled-rect-mask", "bf16-ragged-T3"])
+def test_backward_head_groups_do_not_change_the_result(name):
+    """Concurrent head groups on helper streams against one group on the caller's stream: every
+    group owns its heads' slices of the workspace and of the gradients, so the bits are the same."""
+    wl = dataclasses.replace(CASES[name], heads=5)
+    arrays = syn.make_inputs(wl)
+    rng = np.random.default_rng(11)
+    dO = rng.standard_normal(arrays[0].shape).astype(np.float32)
+    if wl.dtype == "bf16":
+        dO = syn.round_to_bf16(dO)
+    Qd, Kd, Vd, dOd = to_device(wl, arrays + (dO,))
+    kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
+              iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+              scale=wl.scale)
+    try:
+        pkg.binding.set_head_groups(1)
+        g1 = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, **kw)
+        torch.cuda.synchronize()
+        for n in (2, 3, 4):
+            pkg.binding.set_head_groups(n)
+            gn = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, **kw)
+            torch.cuda.synchronize()
+            for a, b in zip(g1, gn):
+                assert torch.equal(a, b), f"{n} groups differ"
+    finally:
+        pkg.binding.set_head_groups(0)
