@@ -620,8 +620,11 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
   // shapes); otherwise the pass runs on the caller's stream.
   int want_groups = g_max_groups;
   if (want_groups == 0) {
-    const long long l_wgs = (long long)pl.ntq_total * pl.kp.b2 * G;
-    want_groups = (L.rowsD * (size_t)G >= (size_t(256) << 20) && l_wgs < 2048) ? 2 : 1;
+    // stage L backward keeps two workgroups per compute unit resident for b1 <= 96, one beyond:
+    // groups pay while a launch is fewer than four rounds of them (measured: 12 heads of the 480p
+    // KV-cache step -10 %, 10 heads per pass of the 720p one +5 %)
+    const long long l_wgs = (long long)pl.ntq_total * pl.kp.b2 * G, slots = pl.kp.b1 <= 96 ? 512 : 256;
+    want_groups = (L.rowsD * (size_t)G >= (size_t(256) << 20) && l_wgs < 4 * slots) ? 2 : 1;
   }
   StreamPool* pool = (g_prof_on || want_groups <= 1) ? nullptr : get_pool();
   mrt_status status = MRT_OK;
