@@ -35,14 +35,14 @@ MEASURED_TRAFFIC = {
     ("C1", "stage_R_first"): (28.9e6, 16.1e6),
     ("C1", "stage_L_refine"): (29.3e6, 14.4e6),
     ("C1", "stage_R_last"): (43.3e6, 30.5e6),
-    ("C1", "stage_L_out"): (43.6e6, 14.9e6),
+    ("C1", "stage_L_out"): (43.7e6, 14.4e6),
     ("C2", "stage_R_first"): (43.3e6, 32.3e6),
     ("C2", "stage_L_refine"): (44.0e6, 28.8e6),
     ("C2", "stage_R_last"): (57.7e6, 61.2e6),
     ("C2", "stage_L_out"): (72.7e6, 14.4e6),
     ("C3", "stage_R_first"): (102.9e6, 144.3e6),
     ("C3", "stage_L_refine"): (267.5e6, 127.2e6),
-    ("C3", "stage_R_last"): (254.5e6, 271.8e6),
+    ("C3", "stage_R_last"): (255.2e6, 274.4e6),
     ("C3", "stage_L_out"): (265.5e6, 9.1e6),
 }
 
