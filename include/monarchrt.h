@@ -152,8 +152,7 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
  *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers of the fp32
  *   kernels fit the 160 KB of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128), or
  *   such that every stage runs on the bf16 matrix unit (b1 <= 144, b2 <= 64); iters <= 16;
- *   otherwise MRT_ERR_UNSUPPORTED.  Regular Monarch under a mask (tile = 0, causal_chunk > 0)
- *   runs stage L backward in the fp32 kernels, so the first limit applies to it. */
+ *   otherwise MRT_ERR_UNSUPPORTED. */
 size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,

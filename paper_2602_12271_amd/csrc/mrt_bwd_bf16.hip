@@ -114,6 +114,14 @@ __device__ inline void ldw8(const u16* p, f32x4& lo, f32x4& hi) {
              __uint_as_float(v.w & 0xffff0000u)};
 }
 
+// Bias of keys key0 .. key0 + 3 of a lane whose query row sees the keys below lim (regular Monarch
+// under the chunk-causal mask: a hidden key gets -inf like a key beyond the range).
+__device__ inline f32x4 mask_bias(f32x4 bi, int key0, int lim) {
+#pragma unroll
+  for (int r = 0; r < 4; ++r) bi[r] = key0 + r < lim ? bi[r] : -INFINITY;
+  return bi;
+}
+
 // S^T tiles of one query tile against NTK resident row tiles: out[kt][r] = rows[16kt + 4g + r] . q
 template <int D, int NTK, int LD>
 __device__ inline void rows_dot(const u16* rows, const bf16x8 (&qv)[D / 32], f32x4 (&out)[NTK], int lane) {
@@ -282,6 +290,8 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
       qv[ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
       xv[ks] = LAST ? ld_global_16B(dOp + orow(lc) + 32 * ks + 8 * g) : qv[ks];
     }
+    // regular Monarch under the chunk-causal mask: this lane's query row sees the keys below klim
+    const int klim = p.rl > 0 ? visible_key_rows(p, lc) : 0x7fffffff;
     f32x4 s[NTK], dl[NTK], z[NTK];
     rows_dot<D, NTK, LD>(Ks, qv, s, lane);
 #pragma unroll
@@ -293,7 +303,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
     float mx = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < NTK; ++kt) {
-      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      const f32x4 bi = mask_bias(*(const f32x4*)(bias + 16 * kt + 4 * g), 16 * kt + 4 * g, klim);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
@@ -318,7 +328,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
     f32x4 wq[NTK];
 #pragma unroll
     for (int kt = 0; kt < NTK; ++kt) {
-      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      const f32x4 bi = mask_bias(*(const f32x4*)(bias + 16 * kt + 4 * g), 16 * kt + 4 * g, klim);
       f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {0.f, 0.f, 0.f, 0.f}, tc = {0.f, 0.f, 0.f, 0.f};
       if (!LAST) {
         cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
@@ -470,6 +480,9 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     xv[ks] = LAST ? ld_global_16B(dOp + orow(lc) + 32 * ks + 8 * g) : qv[ks];
   }
   const float scale2 = p.scale * kLog2e;
+  // regular Monarch under the chunk-causal mask: this lane's query row sees the keys below klim
+  // (key 0 is visible to every row, so the running maxima are finite after the first segment)
+  const int klim = p.rl > 0 ? visible_key_rows(p, lc) : 0x7fffffff;
 
   // ---- sweep 1: lse2[l] and delta[l]
   float mz = -INFINITY, sz = 0.f;            // running maximum / sum of 2^(z - mz)
@@ -487,7 +500,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     float mx = -INFINITY, mxw = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < NTK; ++kt) {
-      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      const f32x4 bi = mask_bias(*(const f32x4*)(bias + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
       f32x4 cm = {0.f, 0.f, 0.f, 0.f};
       if (!LAST) cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
 #pragma unroll
@@ -536,8 +549,9 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     stage(k0);
     __syncthreads();
     if (!tile_live) {
-      // the cols kernel reads query rows in steps of 32: an odd tile count leaves one tile of zeros
-      if (lt < 2 * ((nlt + 1) / 2))
+      // the cols kernel reads as many query tiles as its template holds (2, 4, 6, or all ten of
+      // the wide pitch): the tiles beyond the last query tile are zeros
+      if (lt < (NW <= 6 ? 2 * ((nlt + 1) / 2) : NW))
         for (int nk = k0 + g; nk < NK && nk < k0 + kSeg; nk += 4) {
           Pt[(size_t)nk * LP + l] = 0;
           Zt[(size_t)nk * LP + l] = 0;
@@ -551,7 +565,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kt = 0; kt < NTK; ++kt) {
-      const f32x4 bi = *(const f32x4*)(bias + 16 * kt + 4 * g);
+      const f32x4 bi = mask_bias(*(const f32x4*)(bias + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
       f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {0.f, 0.f, 0.f, 0.f}, tc = {0.f, 0.f, 0.f, 0.f};
       if (!LAST) {
         cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
@@ -952,11 +966,7 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
 
 }  // namespace
 
-// (regular Monarch under the chunk-causal mask, kp.rl > 0, is differentiated by the fp32 stage L
-// kernel, which has the mask)
-bool bwd_bf16_fits(const KParams& kp) {
-  return kp.b1 <= kBRowsWide && (kp.d == 64 || kp.d == 128) && kp.rl == 0;
-}
+bool bwd_bf16_fits(const KParams& kp) { return kp.b1 <= kBRowsWide && (kp.d == 64 || kp.d == 128); }
 size_t bwd_bf16_scratch_bytes(const KParams& kp, int ntq_total) {
   // the transposed L and dZ arrays: (m, j, nk) rows of 96 or 160 bf16 each, two arrays
   return (size_t)ntq_total * kp.b2 * kp.ntk * kp.b1 * lp_of(kp.b1) * 2 * 2;

@@ -55,6 +55,9 @@ CASES = {
     # the cols kernel's single LDS tile; half of the key tiles hidden
     "bf16-b1-135": small("bf16", head_dim=64, f_q=3, f_kv=6, h=45, w=16, b1=135, b2=8, tile=1, iters=2,
                          causal_chunk=3, q_frame_offset=0),
+    # eight query tiles: the ten-wave streamed kernel with two waves that only write zero tiles
+    "bf16-b1-120": small("bf16", head_dim=128, heads=1, f_q=4, f_kv=4, h=30, w=12, b1=120, b2=12, tile=0,
+                         iters=2),
 }
 
 
@@ -195,3 +198,35 @@ def test_backward_head_groups_do_not_change_the_result(name):
                 assert torch.equal(a, b), f"{n} groups differ"
     finally:
         pkg.binding.set_head_groups(0)
+
+
+@pytest.mark.parametrize("name", ["bf16-b1-120", "bf16-b1-135", "bf16-stream-mask", "bf16-ragged-T3",
+                                  "tiled-rect-mask", "regular-T3"])
+def test_backward_reads_nothing_it_has_not_written(name):
+    """A workspace full of NaN bit patterns (what a recycled allocation may hold) gives the same bits
+    as a zeroed one: every workspace entry a kernel reads was written earlier in the same call,
+    padding rows and tiles included."""
+    wl = CASES[name]
+    arrays = syn.make_inputs(wl)
+    rng = np.random.default_rng(5)
+    dO = rng.standard_normal(arrays[0].shape).astype(np.float32)
+    if wl.dtype == "bf16":
+        dO = syn.round_to_bf16(dO)
+    Qd, Kd, Vd, dOd = to_device(wl, arrays + (dO,))
+    kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
+              iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+              scale=wl.scale, assign=wl.assign, tile_h=wl.tile_h)
+    prob = pkg.make_problem(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, f_q=wl.f_q, f_kv=wl.f_kv,
+                            h=wl.h, w=wl.w, dtype=pkg.MRT_F32 if wl.dtype == "f32" else pkg.MRT_BF16,
+                            scale=wl.scale, q_frame_offset=wl.q_frame_offset)
+    import ctypes
+    n = pkg.load_library().monarch_attn_bwd_workspace_bytes(ctypes.byref(prob), wl.b1, wl.b2, wl.tile, wl.iters)
+    assert n > 0
+    clean = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    dirty = torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda:0")
+    g0 = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, workspace=clean, **kw)
+    g1 = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, workspace=dirty, **kw)
+    torch.cuda.synchronize()
+    for nm, a, b in zip("QKV", g0, g1):
+        assert torch.isfinite(b).all(), f"d{nm} picked up workspace garbage"
+        assert torch.equal(a, b), f"d{nm} depends on the workspace's previous contents"

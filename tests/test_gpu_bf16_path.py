@@ -315,3 +315,21 @@ def test_bidirectional_480p_one_frame_tiles():
     arrays = syn.make_inputs(wl)
     O = run_monarch_gpu(wl, *to_device(wl, arrays))
     check(wl, arrays, O, heads=[1], label="480p bidirectional (30,52) T=1")
+
+
+@pytest.mark.parametrize("name", ["reg-ragged", "reg-d64", "tiled-rect-mask", "tiled-b2-1", "tiled-self-causal",
+                                  "max-blocks"])
+def test_forward_reads_nothing_it_has_not_written(name):
+    """A workspace full of NaN bit patterns (what a recycled allocation may hold) gives the same bits
+    as a zeroed one: every intermediate a kernel reads was written earlier in the same call."""
+    wl = SMALL[name]
+    dev = to_device(wl, syn.make_inputs(wl))
+    prob = pkg.make_problem(batch=wl.batch, heads=wl.heads, head_dim=wl.head_dim, f_q=wl.f_q, f_kv=wl.f_kv,
+                            h=wl.h, w=wl.w, scale=wl.scale, q_frame_offset=wl.q_frame_offset)
+    n = pkg.monarch_attn_workspace_bytes(prob, wl.b1, wl.b2, wl.tile, wl.iters)
+    clean = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    dirty = torch.full((n,), 0xFF, dtype=torch.uint8, device="cuda:0")
+    O0 = run_monarch_gpu(wl, *dev, workspace=clean)
+    O1 = run_monarch_gpu(wl, *dev, workspace=dirty)
+    assert torch.isfinite(O1.float()).all()
+    assert torch.equal(O0, O1)

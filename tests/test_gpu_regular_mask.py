@@ -125,13 +125,18 @@ BWD_CASES = {
     "f32-offset-T3": case("f32", head_dim=64, f_q=6, h=4, w=9, iters=3, causal_chunk=2, q_frame_offset=1),
     "bf16-T2": case(f_q=4, h=11, w=21, iters=2, causal_chunk=1),
     "bf16-d64-T1": case(head_dim=64, f_q=4, h=6, w=12, iters=1, causal_chunk=2),
+    # b1 = 120: the streamed rows kernel (key range beyond 96 rows), ten waves
+    "bf16-b1-120-T2": case(heads=1, f_q=4, h=30, w=12, iters=2, causal_chunk=1),
+    # offset query frames, three iterations
+    "bf16-offset-T3": case(head_dim=64, f_q=6, h=9, w=13, iters=3, causal_chunk=2, q_frame_offset=1),
 }
 
 
 @pytest.mark.parametrize("name", list(BWD_CASES))
 def test_masked_regular_backward(name):
-    """Stage L of the backward pass runs in fp32 under the mask; with bf16 storage stage R runs on
-    the bf16 matrix unit, so the bar is the bf16 one relative to the largest gradient."""
+    """fp32 storage: the fp32 kernels, whose stage L masks its logits.  bf16 storage: the bf16
+    matrix-unit kernels (hidden keys get a bias of -inf in the rows kernels), bar relative to the
+    largest gradient."""
     wl = BWD_CASES[name]
     print(f"case {name}: {wl}", flush=True)
     arrays = syn.make_inputs(wl)
