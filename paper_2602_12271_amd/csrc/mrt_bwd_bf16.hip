@@ -391,20 +391,26 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
 // dZ and the dQ products with them.
 // ---------------------------------------------------------------------------------------
 constexpr int kSegTiles = 4, kSeg = 16 * kSegTiles;
+// Segments staged per barrier pair: two segments' loads are in flight together and the exposed
+// load latency and the two barriers are paid once per 128 key rows (70 KB of LDS per workgroup,
+// two workgroups per compute unit).
+// (three or four segments at a time, which the ten-wave variant's LDS would allow, measured no
+// faster and slower)
+constexpr int kStageSegs = 2, kStage = kSeg * kStageSegs;
 
 // NW waves: 6 for b1 <= 96, 10 for b1 <= 144 (the pitch of the transposed arrays follows).
 template <int D, bool LAST, typename TW, int NW>
 __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp, u16* Pw, u16* Zw) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, NTK = kSegTiles, KS2 = NTK / 2;
-  constexpr int CPR = D / 8, TOTAL = kSeg * CPR, NTMAX = 64 * NW, NI = (TOTAL + NTMAX - 1) / NTMAX;
+  constexpr int CPR = D / 8, TOTAL = kStage * CPR, NTMAX = 64 * NW, NI = (TOTAL + NTMAX - 1) / NTMAX;
   constexpr int LP = NW <= 6 ? kLP : kLPWide;
-  __shared__ __attribute__((aligned(16))) u16 Ks[kSeg * LD];    // alpha_L rows of the segment
-  __shared__ __attribute__((aligned(16))) u16 Vs[kSeg * LD];    // Y rows (LAST) or d abar rows
-  __shared__ __attribute__((aligned(16))) float bias[kSeg];     // -c_L log2(e), -inf beyond NK
-  __shared__ __attribute__((aligned(16))) float tcs[kSeg];      // d abar . abar                  (not LAST)
-  __shared__ __attribute__((aligned(16))) float cms[kSeg];      // max_l log2 L[l, nk]            (not LAST)
-  __shared__ __attribute__((aligned(16))) float cis[kSeg];      // 1 / sum_l 2^(log2 L - max)     (not LAST)
+  __shared__ __attribute__((aligned(16))) u16 Ks[kStage * LD];    // alpha_L rows of the segment
+  __shared__ __attribute__((aligned(16))) u16 Vs[kStage * LD];    // Y rows (LAST) or d abar rows
+  __shared__ __attribute__((aligned(16))) float bias[kStage];     // -c_L log2(e), -inf beyond NK
+  __shared__ __attribute__((aligned(16))) float tcs[kStage];      // d abar . abar                  (not LAST)
+  __shared__ __attribute__((aligned(16))) float cms[kStage];      // max_l log2 L[l, nk]            (not LAST)
+  __shared__ __attribute__((aligned(16))) float cis[kStage];      // 1 / sum_l 2^(log2 L - max)     (not LAST)
 
   constexpr int nthr = NTMAX;                  // launched with exactly this many threads
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
@@ -429,10 +435,10 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
 
   // one segment of the key side into LDS; d abar . abar is formed on the way from the fp32 rows
   auto stage = [&](int k0) {
-    const int valid = NK - k0 < kSeg ? NK - k0 : kSeg;
-    stage_ws<D, LD, kSeg, NTMAX>(Ks, aLp + (size_t)k0 * d, PlainRows{D}, valid, tid);
+    const int valid = NK - k0 < kStage ? NK - k0 : kStage;
+    stage_ws<D, LD, kStage, NTMAX>(Ks, aLp + (size_t)k0 * d, PlainRows{D}, valid, tid);
     if (LAST) {
-      stage_ws<D, LD, kSeg, NTMAX>(Vs, Yp + (size_t)k0 * d, PlainRows{D}, valid, tid);
+      stage_ws<D, LD, kStage, NTMAX>(Vs, Yp + (size_t)k0 * d, PlainRows{D}, valid, tid);
     } else {
       // D/8 consecutive lanes share a row: 8 features each
 #pragma unroll
@@ -457,7 +463,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
         }
       }
     }
-    if (tid < kSeg) {
+    if (tid < kStage) {
       const int nk = k0 + tid;
       const bool ok = nk < NK;
       bias[tid] = ok ? -cLp[nk] * kLog2e : -INFINITY;
@@ -487,22 +493,27 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
   // ---- sweep 1: lse2[l] and delta[l]
   float mz = -INFINITY, sz = 0.f;            // running maximum / sum of 2^(z - mz)
   float mw = -INFINITY, dw = 0.f;            // the same for the shifted logits, weighted sum of u
-  for (int k0 = 0; k0 < NK; k0 += kSeg) {
+  for (int kb = 0; kb < NK; kb += kStage) {
     __syncthreads();
-    stage(k0);
+    stage(kb);
     __syncthreads();
+    for (int h = 0; h < kStageSegs && kb + h * kSeg < NK; ++h) {
+    const int k0 = kb + h * kSeg;
+    const u16* Ksh = Ks + h * kSeg * LD;
+    const u16* Vsh = Vs + h * kSeg * LD;
+    const float *biash = bias + h * kSeg, *tcsh = tcs + h * kSeg, *cmsh = cms + h * kSeg, *cish = cis + h * kSeg;
     if (!tile_live) continue;
     f32x4 s[NTK], dl[NTK];
-    rows_dot<D, NTK, LD>(Ks, qv, s, lane);
+    rows_dot<D, NTK, LD>(Ksh, qv, s, lane);
     __builtin_amdgcn_sched_barrier(0);
-    rows_dot<D, NTK, LD>(Vs, xv, dl, lane);
+    rows_dot<D, NTK, LD>(Vsh, xv, dl, lane);
     __builtin_amdgcn_sched_barrier(0);
     float mx = -INFINITY, mxw = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < NTK; ++kt) {
-      const f32x4 bi = mask_bias(*(const f32x4*)(bias + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
+      const f32x4 bi = mask_bias(*(const f32x4*)(biash + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
       f32x4 cm = {0.f, 0.f, 0.f, 0.f};
-      if (!LAST) cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
+      if (!LAST) cm = *(const f32x4*)(cmsh + 16 * kt + 4 * g);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
@@ -517,9 +528,9 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     for (int kt = 0; kt < NTK; ++kt) {
       f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {1.f, 1.f, 1.f, 1.f}, tc = {0.f, 0.f, 0.f, 0.f};
       if (!LAST) {
-        cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
-        ci = *(const f32x4*)(cis + 16 * kt + 4 * g);
-        tc = *(const f32x4*)(tcs + 16 * kt + 4 * g);
+        cm = *(const f32x4*)(cmsh + 16 * kt + 4 * g);
+        ci = *(const f32x4*)(cish + 16 * kt + 4 * g);
+        tc = *(const f32x4*)(tcsh + 16 * kt + 4 * g);
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -533,6 +544,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     dw = fmaf(dw, exp2_fast((LAST ? mz : mw) - mwn), xsum(pd));
     mz = mzn;
     mw = mwn;
+    }
   }
   const float lse2 = mz + log2_fast(sz);
   const float delta = dw * exp2_fast((LAST ? mz : mw) - lse2);
@@ -544,10 +556,15 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
   f32x4 o[NVT];
 #pragma unroll
   for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int k0 = 0; k0 < NK; k0 += kSeg) {
+  for (int kb = 0; kb < NK; kb += kStage) {
     __syncthreads();
-    stage(k0);
+    stage(kb);
     __syncthreads();
+    for (int h = 0; h < kStageSegs && kb + h * kSeg < NK; ++h) {
+    const int k0 = kb + h * kSeg;
+    const u16* Ksh = Ks + h * kSeg * LD;
+    const u16* Vsh = Vs + h * kSeg * LD;
+    const float *biash = bias + h * kSeg, *tcsh = tcs + h * kSeg, *cmsh = cms + h * kSeg, *cish = cis + h * kSeg;
     if (!tile_live) {
       // the cols kernel reads as many query tiles as its template holds (2, 4, 6, or all ten of
       // the wide pitch): the tiles beyond the last query tile are zeros
@@ -559,18 +576,18 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
       continue;
     }
     f32x4 s[NTK], dl[NTK], wq[NTK];
-    rows_dot<D, NTK, LD>(Ks, qv, s, lane);
+    rows_dot<D, NTK, LD>(Ksh, qv, s, lane);
     __builtin_amdgcn_sched_barrier(0);
-    rows_dot<D, NTK, LD>(Vs, xv, dl, lane);
+    rows_dot<D, NTK, LD>(Vsh, xv, dl, lane);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kt = 0; kt < NTK; ++kt) {
-      const f32x4 bi = mask_bias(*(const f32x4*)(bias + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
+      const f32x4 bi = mask_bias(*(const f32x4*)(biash + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
       f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {0.f, 0.f, 0.f, 0.f}, tc = {0.f, 0.f, 0.f, 0.f};
       if (!LAST) {
-        cm = *(const f32x4*)(cms + 16 * kt + 4 * g);
-        ci = *(const f32x4*)(cis + 16 * kt + 4 * g);
-        tc = *(const f32x4*)(tcs + 16 * kt + 4 * g);
+        cm = *(const f32x4*)(cmsh + 16 * kt + 4 * g);
+        ci = *(const f32x4*)(cish + 16 * kt + 4 * g);
+        tc = *(const f32x4*)(tcsh + 16 * kt + 4 * g);
       }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -592,13 +609,14 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
 #pragma unroll
     for (int st = 0; st < KS2; ++st) {
       const bf16x8 pz = pack8(dl[2 * st] * p.scale, dl[2 * st + 1] * p.scale);
-      pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
+      pv_step<D, LD>(Ksh + 32 * st * LD, pz, o, lane);
       __builtin_amdgcn_sched_barrier(0);
       if (!LAST) {
         const bf16x8 pw = pack8(wq[2 * st], wq[2 * st + 1]);
-        pv_step<D, LD>(Vs + 32 * st * LD, pw, o, lane);
+        pv_step<D, LD>(Vsh + 32 * st * LD, pw, o, lane);
         __builtin_amdgcn_sched_barrier(0);
       }
+    }
     }
   }
   if (tile_live && live)
