@@ -417,6 +417,26 @@ __global__ __launch_bounds__(kThreads) void k_bwd_q_first(BwdParams bp) {
   const float* dAp = bp.dA + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * d;
   float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
   const long long qrow = row_offset(p, a, k);
+  if (d % 4 == 0) {
+    // four features per lane, four key tiles in flight per step (a pure stream: the loads are all
+    // there is to hide)
+    const f32x4* src = (const f32x4*)(dAp + (size_t)k * b2 * d);
+    const size_t per_n = (size_t)b1 * b2 * d / 4;
+    for (int idx = threadIdx.x; idx < b2 * d / 4; idx += kThreads) {
+      const int jj = (4 * idx) / d, v = 4 * idx - jj * d;
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};
+      int n = 0;
+      for (; n + 4 <= nvis; n += 4) {
+        const f32x4 x0 = src[(size_t)n * per_n + idx], x1 = src[(size_t)(n + 1) * per_n + idx];
+        const f32x4 x2 = src[(size_t)(n + 2) * per_n + idx], x3 = src[(size_t)(n + 3) * per_n + idx];
+        s += (x0 + x1) + (x2 + x3);
+      }
+      for (; n < nvis; ++n) s += src[(size_t)n * per_n + idx];
+      f32x4* dst = (f32x4*)(dQp + (qrow + axis_offset(p.cmap, bq * b2 + jj)) * d + v);
+      *dst += s;
+    }
+    return;
+  }
   for (int idx = threadIdx.x; idx < b2 * d; idx += kThreads) {
     const int jj = idx / d, v = idx - jj * d;
     float s = 0.f;
