@@ -248,9 +248,10 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
       float t = 0.f;
       if (ok) {
         ldw8((const TW*)bp.dA + at, lo, hi);
-        const TW* ab = (const TW*)bp.Anext + at;
+        f32x4 alo, ahi;
+        ldw8((const TW*)bp.Anext + at, alo, ahi);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
+        for (int e = 0; e < 4; ++e) t = fmaf(lo[e], alo[e], fmaf(hi[e], ahi[e], t));
       }
       t = CPR == 16 ? row16_sum(t) : row8_sum(t);
       if (in) {
@@ -452,9 +453,10 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
         float t = 0.f;
         if (ok) {
           ldw8((const TW*)bp.dA + at, lo, hi);
-          const TW* ab = (const TW*)bp.Anext + at;
+          f32x4 alo, ahi;
+          ldw8((const TW*)bp.Anext + at, alo, ahi);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) t = fmaf(lo[e], ldw(ab + e), fmaf(hi[e], ldw(ab + 4 + e), t));
+          for (int e = 0; e < 4; ++e) t = fmaf(lo[e], alo[e], fmaf(hi[e], ahi[e], t));
         }
         t = CPR == 16 ? row16_sum(t) : row8_sum(t);
         if (in) {
