@@ -790,10 +790,12 @@ constexpr int kResPad = 8;      // row padding of the resident tiles (row stride
 // Exact softmax of QT query tiles (nq of them live) against NTK resident key tiles; every key
 // operand read from LDS serves all QT tiles.  On return s holds the exponentials (base-2 logits
 // minus the column maximum) and sum their column sums.
-template <int D, int NTK, int LD, int QT>
+// RMASK (regular Monarch under the chunk-causal mask): the lane's query row of tile q sees the keys
+// below klim[q].
+template <int D, int NTK, int LD, int QT, bool RMASK>
 __device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8 (&qv)[QT][D / 32],
-                                  int nq, float scale2, f32x4 (&s)[QT][NTK], float (&sum)[QT],
-                                  int lane) {
+                                  int nq, float scale2, const int (&klim)[QT], f32x4 (&s)[QT][NTK],
+                                  float (&sum)[QT], int lane) {
   constexpr int KS1 = D / 32;
   const int g = lane >> 4, c = lane & 15;
 #pragma unroll
@@ -832,6 +834,7 @@ __device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         s[q][kt][r] = fmaf(s[q][kt][r], scale2, bi[kt][r]);      // -inf beyond the last key
+        if (RMASK && 16 * kt + 4 * g + r >= klim[q]) s[q][kt][r] = -INFINITY;
         mx = fmaxf(mx, s[q][kt][r]);
       }
     mx = xmax(mx);
@@ -847,7 +850,7 @@ __device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8
   }
 }
 
-template <int D, int NTK>
+template <int D, int NTK, bool RMASK>
 __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   constexpr int LD = D + kResPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
   constexpr int QT = 2;
@@ -908,7 +911,13 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
     const int nq = nlt - QT * pair < QT ? nlt - QT * pair : QT;
     f32x4 s[QT][NTK];
     float sum[QT];
-    res_logits<D, NTK, LD, QT>(Ks, bias, qv, nq, scale2, s, sum, lane);
+    int klim[QT];
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * (QT * pair + q) + c;
+      klim[q] = RMASK ? visible_key_rows(p, l < b1 ? l : b1 - 1) : 0;
+    }
+    res_logits<D, NTK, LD, QT, RMASK>(Ks, bias, qv, nq, scale2, klim, s, sum, lane);
     bf16x8 pb[KS2][QT];
 #pragma unroll
     for (int q = 0; q < QT; ++q)
@@ -1198,9 +1207,9 @@ constexpr int kMidRows = 192;
 
 // Base-2 logits (bias added, -inf beyond the last key) of one query tile against NTK resident key
 // tiles (NTK <= 12), and their column maximum.
-template <int D, int NTK, int LD>
+template <int D, int NTK, int LD, bool RMASK>
 __device__ inline float mid_logits(const u16* Ks, const float* bias, const bf16x8 (&qv)[D / 32],
-                                   float scale2, f32x4 (&s)[2 * ((NTK + 1) / 2)], int lane) {
+                                   float scale2, int klim, f32x4 (&s)[2 * ((NTK + 1) / 2)], int lane) {
   constexpr int KS1 = D / 32, KS2 = (NTK + 1) / 2;
   const int g = lane >> 4, c = lane & 15;
 #pragma unroll
@@ -1232,13 +1241,14 @@ __device__ inline float mid_logits(const u16* Ks, const float* bias, const bf16x
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
+      if (RMASK && 16 * kt + 4 * g + r >= klim) s[kt][r] = -INFINITY;   // hidden from this query row
       mx = fmaxf(mx, s[kt][r]);
     }
   }
   return xmax(mx);
 }
 
-template <int D, int NTK>
+template <int D, int NTK, bool RMASK>
 __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   constexpr int LD = D + kResPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
   constexpr int QT = 2;
@@ -1287,7 +1297,9 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
     sum[q] = 1.f;
     if (q < wt.nq) {
       f32x4 s[2 * KS2];
-      const float mx = mid_logits<D, NTK, LD>(tile, bias, qv[q], scale2, s, lane);
+      const int lq = 16 * wt.lt[q] + c;
+      const int klim = RMASK ? visible_key_rows(p, lq < b1 ? lq : b1 - 1) : 0;
+      const float mx = mid_logits<D, NTK, LD, RMASK>(tile, bias, qv[q], scale2, klim, s, lane);
       float sm = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 2 * KS2; ++kt)
@@ -1334,7 +1346,8 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
 
 template <int D, int NTK>
 hipError_t launch_l_out_mid(const KParams& kp, dim3 grid, hipStream_t s) {
-  k_bf16_stage_l_out_mid<D, NTK><<<grid, 256, 0, s>>>(kp);
+  if (kp.rl > 0) k_bf16_stage_l_out_mid<D, NTK, true><<<grid, 256, 0, s>>>(kp);
+  else k_bf16_stage_l_out_mid<D, NTK, false><<<grid, 256, 0, s>>>(kp);
   return hipGetLastError();
 }
 
@@ -1364,7 +1377,8 @@ hipError_t launch_l_refine(const KParams& kp, dim3 grid, int nthr, hipStream_t s
 
 template <int D, int NTK>
 hipError_t launch_l_out_res(const KParams& kp, dim3 grid, hipStream_t s) {
-  k_bf16_stage_l_out_res<D, NTK><<<grid, 256, 0, s>>>(kp);
+  if (kp.rl > 0) k_bf16_stage_l_out_res<D, NTK, true><<<grid, 256, 0, s>>>(kp);
+  else k_bf16_stage_l_out_res<D, NTK, false><<<grid, 256, 0, s>>>(kp);
   return hipGetLastError();
 }
 
@@ -1471,15 +1485,13 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
     return kp.d == 128 ? launch_l_refine_one_wide<128>(kp, grid, nlt, s)
                        : launch_l_refine_one_wide<64>(kp, grid, nlt, s);
   // last iteration, short key ranges: everything resident, three workgroups per compute unit
-  // (regular Monarch under the chunk-causal mask takes the streamed kernel, which has the mask)
-  const bool row_mask = kp.rl > 0;
-  if (nk_max <= kResRows && !row_mask) {
+  if (nk_max <= kResRows) {
     return kp.d == 128 ? launch_l_out_res_d<128>(kp, grid, (nk_max + 15) / 16, s)
                        : launch_l_out_res_d<64>(kp, grid, (nk_max + 15) / 16, s);
   }
   // medium key ranges, last iteration: one LDS tile used twice, still three workgroups per
   // compute unit (the earlier iterations went above)
-  if (nk_max <= kMidRows && nlt <= 8 && !row_mask)
+  if (nk_max <= kMidRows && nlt <= 8)
     return kp.d == 128 ? launch_l_out_mid_d<128>(kp, grid, (nk_max + 15) / 16, s)
                        : launch_l_out_mid_d<64>(kp, grid, (nk_max + 15) / 16, s);
   // long key ranges: streamed.  Workgroups of 4 waves (one per SIMD), each wave owning up to two
