@@ -10,7 +10,7 @@ in row-major (frame, height, width) order (App. B.1, the ordering called phi).
 All arithmetic is float64 (torch CPU tensors); inputs of any float dtype are
 widened first.
 
-Notation follows App. A (Alg. 1 / Alg. 2 and the two pseudocode figures):
+Notation follows App. A (the update equations of Alg. 1 / Alg. 2):
   l  query row inside a tile      j  column inside a tile (queries and keys)
   k  key row inside a tile        i  key column inside a tile
   m  query tile                   n  key tile              v  feature
@@ -192,39 +192,55 @@ def _safe_rows_div(bR: torch.Tensor, cR: torch.Tensor) -> torch.Tensor:
 def monarch_attention_regular(Q, K, V, T: int, b1: int, b2: int, scale: float = 1.0,
                               return_factors: bool = False,
                               row_visible: Optional[torch.Tensor] = None):
-    """App. A.1 update equations / pseudocode (a).  N = b1*b2, Q,K,V viewed as
-    [b1, b2, d].  Returns O [N, d] (and L[j,k,l], R[k,j,i] on request).
+    """App. A.1, the update equations of one iteration, written as batched matrix products.
+    N = b1*b2; Q, K, V are read as b1 x b2 x d tensors Q[l, j, :], K[k, i, :], V[k, i, :].
+
+    The factors are held the way the text of App. A.1 indexes them: L[j, l, k] (for column j,
+    a b1 x b1 matrix from query row l to key row k, each row a distribution over k) and
+    R[k, j, i] (for key row k, a b2 x b2 matrix from query column j to key column i, each row a
+    distribution over i).  Column j of the query grid is the matrix Qcol[j] = Q[:, j, :], row k of
+    the key grid the matrix Krow[k] = K[k, :, :]; every update below is then one batched product
+    over j (the L side) or over k (the R side).
+
+    Returns O [N, d]; on request also the factors, L as [j, k, l] (transposed, the layout
+    materialise_regular takes) and R as [k, j, i].
 
     row_visible[l, k] (bool, optional): key row k is visible to query row l.  A hidden
-    (l, k) is a zero of the attention matrix for every (j, i), i.e. a zero of L[j, k, l]:
+    (l, k) is a zero of the attention matrix for every (j, i), i.e. a zero of L[j, l, k]:
     the softmax of L over k runs over the visible k only (see the module header)."""
     assert T >= 1
     N, d = Q.shape
     assert N == b1 * b2 and K.shape == (N, d) and V.shape[0] == N
-    Qv = Q.to(F64).reshape(b1, b2, d)            # l j v
-    Kv = K.to(F64).reshape(b1, b2, d)            # k i v
-    Vv = V.to(F64).reshape(b1, b2, V.shape[1])   # k i v
-    L = torch.eye(b1, dtype=F64).expand(b2, b1, b1).clone()      # j k l
-    R = None
+    Qcol = Q.to(F64).reshape(b1, b2, d).transpose(0, 1)          # [j][l, v]
+    Krow = K.to(F64).reshape(b1, b2, d)                          # [k][i, v]
+    Vrow = V.to(F64).reshape(b1, b2, V.shape[1])                 # [k][i, v]
+    if row_visible is not None:
+        assert row_visible.shape == (b1, b1) and bool(row_visible.diagonal().all())
+    Lf = torch.eye(b1, dtype=F64).repeat(b2, 1, 1)               # L^(0)[j][l, k] = delta(l, k)
+    Rf = None
     for _ in range(T):
-        aR = torch.einsum("jkl,ljv->kjv", L, Qv)
-        bR = scale * torch.einsum("kjv,kiv->kji", aR, Kv)
-        cR = torch.einsum("jkl->kj", L)
-        R = torch.softmax(_safe_rows_div(bR, cR), dim=2)         # over i
-
-        aL = torch.einsum("kji,kiv->jkv", R, Kv)
-        bL = scale * torch.einsum("jkv,ljv->jkl", aL, Qv)
-        cL = _xlogx_sum(R, 2).transpose(0, 1)                    # kj -> jk
-        zL = bL - cL[:, :, None]                                 # j k l
+        # R update.  alpha_R[k, j, :] = sum_l L[j, l, k] Q[l, j, :],  c_R[k, j] = sum_l L[j, l, k]
+        alpha_R = torch.matmul(Lf.transpose(1, 2), Qcol)         # [j][k, v]
+        c_R = Lf.sum(dim=1)                                      # [j][k]
+        # beta_R[k, j, i] = sum_v alpha_R[k, j, v] K[k, i, v]: for each k, (rows j) x Krow[k]^T
+        beta_R = torch.matmul(alpha_R.transpose(0, 1), Krow.transpose(1, 2))      # [k][j, i]
+        Z_R = _safe_rows_div(scale * beta_R, c_R.transpose(0, 1))
+        Rf = torch.softmax(Z_R, dim=2)                           # over i
+        # L update.  alpha_L[j, k, :] = sum_i R[k, j, i] K[k, i, :],  c_L[j, k] = sum_i R log R
+        alpha_L = torch.matmul(Rf, Krow)                         # [k][j, v]
+        c_L = _xlogx_sum(Rf, 2)                                  # [k][j]
+        # beta_L[j, l, k] = sum_v alpha_L[j, k, v] Q[l, j, v]: for each j, Qcol[j] x (rows k)^T
+        beta_L = torch.matmul(Qcol, alpha_L.permute(1, 2, 0))    # [j][l, k]
+        Z_L = scale * beta_L - c_L.transpose(0, 1)[:, None, :]
         if row_visible is not None:
-            assert row_visible.shape == (b1, b1) and bool(row_visible.diagonal().all())
-            zL = zL.masked_fill(~row_visible.transpose(0, 1)[None, :, :], -math.inf)
-        L = torch.softmax(zL, dim=1)                             # over k
-    Y = torch.einsum("kji,kiv->jkv", R, Vv)
-    Z = torch.einsum("jkl,jkv->ljv", L, Y)
-    O = Z.reshape(N, -1)
+            Z_L = Z_L.masked_fill(~row_visible[None, :, :], -math.inf)
+        Lf = torch.softmax(Z_L, dim=2)                           # over k
+    # Y[k, j, :] = sum_i R[k, j, i] V[k, i, :],  O[l, j, :] = sum_k L[j, l, k] Y[k, j, :]
+    Yf = torch.matmul(Rf, Vrow)                                  # [k][j, v]
+    Ocol = torch.matmul(Lf, Yf.transpose(0, 1))                  # [j][l, v]
+    O = Ocol.transpose(0, 1).reshape(N, -1)
     if return_factors:
-        return O, L, R
+        return O, Lf.transpose(1, 2).contiguous(), Rf
     return O
 
 
@@ -240,31 +256,38 @@ def materialise_regular(L: torch.Tensor, R: torch.Tensor) -> torch.Tensor:
 # Alg. 2: tiled MonarchAttention (App. A.2), rectangular + tile mask
 # --------------------------------------------------------------------------
 def _tiled_one_query_tile(Qm, Kt, Vt, T, scale):
-    """Alg. 2 for one query tile against the list of its visible key tiles.
+    """App. A.2's update equations for ONE query tile (l_1, j_1 fixed) against the list of its
+    visible key tiles (k_1, i_1) = n, as batched matrix products.
 
-    Qm [b1,b2,d] (l j v); Kt,Vt [nv,b1,b2,d] (n k i v).  Returns Z [b1,b2,dv],
-    L [nv,b2,b1,b1] (n j k l), R [nv,b1,b2,b2] (n k j i).
+    Qm [b1, b2, d] is the query tile, Q[l, j, :]; Kt, Vt [nv, b1, b2, d] the key tiles,
+    K[n, k, i, :].  The factors are held as App. A.2 indexes them with the tile pair dropped:
+    L[n][j][l, k] and R[n][k][j, i].  The R side is the regular update once per key tile; the L
+    side differs in one place: for every (j, l) the softmax runs over ALL (n, k) together.
+
+    Returns the tile of the output O[l, j, :] and the factors, L as [n, j, k, l] (the layout
+    materialise_tiled takes) and R as [n, k, j, i].
     """
     nv, b1, b2, _ = Kt.shape
-    L = torch.eye(b1, dtype=F64).expand(nv, b2, b1, b1).clone()  # n j k l
-    R = None
+    Qcol = Qm.transpose(0, 1)                                    # [j][l, v]
+    Lf = torch.eye(b1, dtype=F64).repeat(nv, b2, 1, 1)           # L^(0)[n][j][l, k] = delta(l, k)
+    Rf = None
     for _ in range(T):
-        aR = torch.einsum("njkl,ljv->nkjv", L, Qm)
-        bR = scale * torch.einsum("nkjv,nkiv->nkji", aR, Kt)
-        cR = torch.einsum("njkl->nkj", L)
-        R = torch.softmax(_safe_rows_div(bR, cR), dim=3)         # over i
-
-        aL = torch.einsum("nkji,nkiv->njkv", R, Kt)
-        bL = scale * torch.einsum("njkv,ljv->njkl", aL, Qm)
-        cL = _xlogx_sum(R, 3).permute(0, 2, 1)                   # nkj -> njk
-        ZL = bL - cL[..., None]                                  # n j k l
-        # joint softmax over (n, k) for every (j, l)
-        Zf = ZL.permute(1, 3, 0, 2).reshape(b2, b1, nv * b1)     # j l (n k)
-        Lf = torch.softmax(Zf, dim=2)
-        L = Lf.reshape(b2, b1, nv, b1).permute(2, 0, 3, 1).contiguous()  # n j k l
-    Y = torch.einsum("nkji,nkiv->njkv", R, Vt)
-    Z = torch.einsum("njkl,njkv->ljv", L, Y)
-    return Z, L, R
+        # R update, per key tile n
+        alpha_R = torch.matmul(Lf.transpose(2, 3), Qcol)         # [n][j][k, v]
+        c_R = Lf.sum(dim=2)                                      # [n][j][k]
+        beta_R = torch.matmul(alpha_R.transpose(1, 2), Kt.transpose(2, 3))        # [n][k][j, i]
+        Rf = torch.softmax(_safe_rows_div(scale * beta_R, c_R.transpose(1, 2)), dim=3)   # over i
+        # L update: logits per key tile, then one softmax per (j, l) across every (n, k)
+        alpha_L = torch.matmul(Rf, Kt)                           # [n][k][j, v]
+        c_L = _xlogx_sum(Rf, 3)                                  # [n][k][j]
+        beta_L = torch.matmul(Qcol, alpha_L.permute(0, 2, 3, 1))                  # [n][j][l, k]
+        Z_L = scale * beta_L - c_L.transpose(1, 2)[:, :, None, :]
+        joint = Z_L.permute(1, 2, 0, 3).reshape(b2, b1, nv * b1)                  # [j][l, (n k)]
+        Lf = torch.softmax(joint, dim=2).reshape(b2, b1, nv, b1).permute(2, 0, 1, 3)   # [n][j][l, k]
+    Yf = torch.matmul(Rf, Vt)                                    # [n][k][j, v]
+    # O[l, j, :] = sum_{n, k} L[n, j, l, k] Y[n, k, j, :]
+    Ocol = torch.matmul(Lf, Yf.transpose(1, 2)).sum(dim=0)       # [j][l, v]
+    return Ocol.transpose(0, 1).contiguous(), Lf.transpose(2, 3).contiguous(), Rf
 
 
 def monarch_attention_tiled(Q, K, V, T: int, geom: TileGeometry, scale: float = 1.0,
