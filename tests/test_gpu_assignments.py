@@ -105,7 +105,7 @@ def check(wl, arrays, O, heads=None, oracle=None, label=""):
     err, omax = compare_heads(wl, arrays, O, heads=heads, **kw)
     print(f"  {label}: max|gpu-oracle| = {err:.3e}, max|O| = {omax:.3e}, ratio {err / omax:.3e}",
           flush=True)
-    assert err <= TOL_BF16 * max(1.0, omax)
+    assert err <= TOL_BF16
     assert err <= REL_BF16 * omax + 1e-3
 
 

@@ -1,12 +1,14 @@
 """GPU parity of the bf16 MFMA path against the fp64 oracle, through the C ABI.
 
-Bar: max-abs <= 2e-2 on bf16 inputs with fp32 accumulation, for outputs of magnitude <= 1.
-bf16 rounding is relative (2^-9 per rounding of P, alpha_L, Y, alpha_R and O, compounding over
-the iterations), so for the stress cases whose outputs exceed 1 the bar scales with the oracle's
-largest output: tol = 2e-2 * max(1, max|O|).  Because the named workloads produce outputs of
-magnitude ~0.05 (their softmaxes average many N(0,1) values), the tests also require the error
-to stay below a fraction of the oracle's largest output, so a wrong result cannot hide under
-the absolute bar.
+Bar: max-abs <= 2e-2 on bf16 inputs with fp32 accumulation, asserted as such for every case.
+One stress case lies outside it and says so (OUTSIDE_STATED_BAR): sharp softmaxes with outputs of
+magnitude 3.5, where bf16 rounding (2^-9 relative per rounding of P, alpha_L, Y, alpha_R and O,
+compounding over the iterations and amplified by the softmaxes) alone exceeds 2e-2; it is held to
+the error a CPU emulation of those rounding points shows, and the fp32 arithmetic mode meets the
+plain bar on it (test_f32_compute_on_bf16_storage_matches_oracle_tighter).  Because the named
+workloads produce outputs of magnitude ~0.05 (their softmaxes average many N(0,1) values), the
+tests also require the error to stay below a fraction of the oracle's largest output, so a wrong
+result cannot hide under the absolute bar.
 """
 import numpy as np
 import pytest
@@ -61,12 +63,16 @@ SMALL = {
 }
 
 
-def check(wl, arrays, O, heads=None, oracle=None, label=""):
+# Cases outside the stated 2e-2 bar, with the bar they are held to instead (max-abs).
+OUTSIDE_STATED_BAR = {"tiled-sharp": 6e-2}
+
+
+def check(wl, arrays, O, heads=None, oracle=None, label="", bar=TOL_BF16):
     kw = {} if oracle is None else {"oracle": oracle}
     err, omax = compare_heads(wl, arrays, O, heads=heads, **kw)
     print(f"  {label}: max|gpu-oracle| = {err:.3e}, max|O| = {omax:.3e}, ratio {err / omax:.3e}",
           flush=True)
-    assert err <= TOL_BF16 * max(1.0, omax)
+    assert err <= bar
     assert err <= REL_BF16 * omax + 1e-3
     return err, omax
 
@@ -77,7 +83,7 @@ def test_monarch_bf16_small(name):
     arrays = syn.make_inputs(wl)
     print(f"case {name}", flush=True)
     O = run_monarch_gpu(wl, *to_device(wl, arrays))
-    check(wl, arrays, O, label=name)
+    check(wl, arrays, O, label=name, bar=OUTSIDE_STATED_BAR.get(name, TOL_BF16))
 
 
 @pytest.mark.parametrize("name", ["reg-ragged", "tiled-rect-mask", "tiled-sharp", "reg-d64"])
@@ -108,14 +114,27 @@ def test_monarch_bf16_c3_hidden_chunks():
     check(wl, arrays, O, heads=[0, 5, 11], label="C3 offset 9")
 
 
-@pytest.mark.timeout(600)
-def test_monarch_bf16_c4_sampled_heads():
-    wl = syn.WORKLOADS["C4"]
+def c4_heads():
+    """First, last and two seeded heads of the 40."""
+    mid = np.random.default_rng(40).choice(np.arange(1, 39), size=2, replace=False)
+    return [0, 39] + sorted(int(x) for x in mid)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("offset", [18, 9])
+def test_monarch_bf16_c4_sampled_heads(offset):
+    """The 720p KV-cache step: 40 heads on the GPU in the launch configuration the benchmark times,
+    four of them through the oracle.  offset 18: the last query chunk, every key chunk visible (the
+    timed workload).  offset 9: the query chunk moved back so that 3 of the 7 key chunks are hidden
+    and the streamed stage L kernels at b1 = 135 see a visible prefix of the key tiles (block-causal
+    decoding, Sec. 5)."""
+    wl = syn.variant("C4", q_frame_offset=offset)
     arrays = syn.make_inputs(wl)
-    print("config C4 (40 heads on the GPU, 2 heads through the oracle)", flush=True)
+    heads = c4_heads()
+    print(f"config C4, q_frame_offset={offset} (40 heads on the GPU, heads {heads} through the oracle)", flush=True)
     O = run_monarch_gpu(wl, *to_device(wl, arrays))
     assert torch.isfinite(O.float()).all()
-    check(wl, arrays, O, heads=[0, 39], label="C4")
+    check(wl, arrays, O, heads=heads, label=f"C4 offset {offset}")
 
 
 @pytest.mark.timeout(600)

@@ -47,6 +47,10 @@ CASES = {
     "f_hw": case(f_q=3, h=6, w=10, b1=3, b2=60, iters=2, causal_chunk=1, assign="f_hw"),
 }
 
+# Outside the stated 2e-2 bar, with the bar it is held to instead: sharp logits (sigma 1.5 per
+# coordinate), outputs of magnitude 3 -- one bf16 rounding of the output alone is 8e-3 there.
+OUTSIDE_STATED_BAR = {"b1-180": 3e-2}
+
 F32_CASES = {
     "f32-frame-causal": case("f32", head_dim=40, f_q=3, h=5, w=13, iters=3, causal_chunk=1),
     "f32-offset": case("f32", head_dim=64, f_q=6, h=4, w=9, iters=2, causal_chunk=2, q_frame_offset=1),
@@ -61,7 +65,7 @@ def test_masked_regular_bf16(name):
     O = run_monarch_gpu(wl, *to_device(wl, arrays))
     err, omax = compare_heads(wl, arrays, O)
     print(f"  max|gpu-oracle| = {err:.3e}, max|O| = {omax:.3e}", flush=True)
-    assert err <= TOL_BF16 * max(1.0, omax) and err <= REL_BF16 * omax + 1e-3
+    assert err <= OUTSIDE_STATED_BAR.get(name, TOL_BF16) and err <= REL_BF16 * omax + 1e-3
     # the mask matters: the unmasked operator differs by far more than the bar
     wl0 = dataclasses.replace(wl, causal_chunk=0)
     O0 = run_monarch_gpu(wl0, *to_device(wl0, arrays))
@@ -106,7 +110,7 @@ def test_position_only_inputs_reproduce_masked_dense_attention(name):
     print(f"  position-only {name}: max|monarch - dense| on GPU = {diff:.3e}", flush=True)
     assert diff <= TOL_BF16
     err, omax = compare_heads(wl, (Q, K, V), Om, heads=[0], oracle=oracle_dense_head)
-    assert err <= TOL_BF16 * max(1.0, omax)
+    assert err <= TOL_BF16
 
 
 def test_a_mask_that_hides_nothing_gives_the_unmasked_bits():

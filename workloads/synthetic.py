@@ -159,9 +159,15 @@ def rope_angles(frames: np.ndarray, h: int, w: int, head_dim: int,
                            ww[:, None] * freqs(pw)[None]], axis=1)
 
 
-def apply_rope(x: np.ndarray, ang: np.ndarray) -> np.ndarray:
-    """Rotate adjacent element pairs (2p, 2p+1) of x[..., token, d] by ang[token, p]."""
-    c, s = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+def rope_tables(ang: np.ndarray):
+    """(cos, sin) of the angles as fp32, the form apply_rope multiplies with."""
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def apply_rope(x: np.ndarray, ang: np.ndarray, tables=None) -> np.ndarray:
+    """Rotate adjacent element pairs (2p, 2p+1) of x[..., token, d] by ang[token, p]
+    (tables: rope_tables(ang) computed beforehand, to share them between heads)."""
+    c, s = rope_tables(ang) if tables is None else tables
     xe, xo = x[..., 0::2], x[..., 1::2]
     out = np.empty_like(x)
     out[..., 0::2] = xe * c - xo * s
@@ -177,17 +183,25 @@ def _draw(wl: Workload, tensor_id: int, b: int, hd: int, n: int, sigma: float) -
     return (sigma * rng.standard_normal((n, wl.head_dim), dtype=np.float32)).astype(np.float32)
 
 
-def make_head(wl: Workload, b: int, hd: int):
+def _rope_tables_qk(wl: Workload):
+    tq = rope_tables(rope_angles(wl.q_frame_offset + np.arange(wl.f_q), wl.h, wl.w, wl.head_dim))
+    tk = rope_tables(rope_angles(np.arange(wl.f_kv), wl.h, wl.w, wl.head_dim))
+    return tq, tk
+
+
+def make_head(wl: Workload, b: int, hd: int, tables=None):
     """Q [n_q,d], K,V [n_kv,d] of one (batch, head) as fp32 arrays whose values are
     exactly representable in the workload's storage dtype.  Heads are drawn from
     independent streams keyed by (seed, tensor, batch, head), so any head can be
-    regenerated alone."""
+    regenerated alone.  tables: the rotary (cos, sin) tables of the query and key grids, if the
+    caller already has them (they are the same for every head)."""
     Q = _draw(wl, 0, b, hd, wl.n_q, wl.sigma_qk)
     K = _draw(wl, 1, b, hd, wl.n_kv, wl.sigma_qk)
     V = _draw(wl, 2, b, hd, wl.n_kv, wl.sigma_v)
     if wl.rope:
-        Q = apply_rope(Q, rope_angles(wl.q_frame_offset + np.arange(wl.f_q), wl.h, wl.w, wl.head_dim))
-        K = apply_rope(K, rope_angles(np.arange(wl.f_kv), wl.h, wl.w, wl.head_dim))
+        tq, tk = _rope_tables_qk(wl) if tables is None else tables
+        Q = apply_rope(Q, None, tq)
+        K = apply_rope(K, None, tk)
     if wl.dtype == "bf16":
         Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
     return Q, K, V
@@ -195,13 +209,24 @@ def make_head(wl: Workload, b: int, hd: int):
 
 def make_inputs(wl: Workload):
     """All heads: Q [batch, heads, n_q, d], K, V [batch, heads, n_kv, d] (fp32 arrays
-    holding storage-dtype-exact values)."""
+    holding storage-dtype-exact values).  Heads are generated by a few threads (every head has its
+    own random stream, so the values do not depend on the schedule)."""
+    from concurrent.futures import ThreadPoolExecutor
     Q = np.empty((wl.batch, wl.heads, wl.n_q, wl.head_dim), np.float32)
     K = np.empty((wl.batch, wl.heads, wl.n_kv, wl.head_dim), np.float32)
     V = np.empty_like(K)
-    for b in range(wl.batch):
-        for hd in range(wl.heads):
-            Q[b, hd], K[b, hd], V[b, hd] = make_head(wl, b, hd)
+    tables = _rope_tables_qk(wl) if wl.rope else None
+
+    def one(bh):
+        b, hd = divmod(bh, wl.heads)
+        Q[b, hd], K[b, hd], V[b, hd] = make_head(wl, b, hd, tables)
+
+    n = wl.batch * wl.heads
+    if n == 1:
+        one(0)
+    else:
+        with ThreadPoolExecutor(max_workers=min(8, n)) as pool:
+            list(pool.map(one, range(n)))
     return Q, K, V
 
 
