@@ -82,6 +82,8 @@ typedef struct {
   int tile_h;          /* 0: a tile is b1 consecutive block-grid rows.  n_h > 0 (tiled calls with
                           the (fh, w) assignment only): a tile is the neighbourhood of Sec. 4.2,
                           n_h grid rows of each of n_f = b1 / n_h consecutive frames          */
+  int head_groups;     /* head groups this call runs concurrently (1..4); 0 = the process-wide
+                          default of mrt_set_head_groups, which itself defaults to automatic   */
 } mrt_problem;
 
 /* Checks a MonarchRT call without touching the GPU (same rules monarch_attn_fwd applies).
@@ -127,7 +129,20 @@ size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int ti
  *   Q [batch, heads, N_q, head_dim], K, V [batch, heads, N_kv, head_dim], O like Q; device
  *   memory, element strides in p.  O is fully overwritten.  workspace: device memory, 256-byte
  *   aligned, contents undefined on entry and exit.  hip_stream: a hipStream_t (NULL = the
- *   default stream).  Calls sharing a workspace must be ordered on one stream. */
+ *   default stream).  Calls sharing a workspace must be ordered on one stream.
+ *   Accuracy.  MRT_F32 storage (and MRT_COMPUTE_F32): O differs from the exact result of App. A's
+ *   iteration by at most 1e-4 (max-abs) for inputs of unit scale.  MRT_BF16 storage with
+ *   MRT_COMPUTE_DEFAULT: the matrix operands (Q, K, V, the probabilities of R and L, alpha_L, Y,
+ *   alpha_R / c_R) and O are rounded to bf16, 2^-9 relative each; the roundings of alpha_L and
+ *   alpha_R enter the next logits, whose softmaxes amplify them.  For outputs of magnitude <= 1
+ *   the error stays within 2e-2 max-abs; it grows with the output's magnitude and with the
+ *   sharpness of the softmaxes (logits of standard deviation 3, |O| up to 3.5, three iterations:
+ *   up to 6e-2, the error a CPU emulation of exactly these rounding points also shows).  A caller
+ *   who needs the plain 2e-2 there selects MRT_COMPUTE_F32.
+ *   Thread safety: the call may be issued from several host threads and on several streams at
+ *   once (each call with its own workspace).  Calls that run more than one head group share the
+ *   device's helper streams; the library serialises their enqueue, so such calls still complete
+ *   correctly but their head groups queue behind each other on those streams. */
 mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
                             const mrt_problem* p, int b1, int b2, int tile, int iters,
                             int causal_chunk, void* workspace, size_t workspace_bytes,
@@ -172,7 +187,9 @@ mrt_status dense_attn_fwd(const void* Q, const void* K, const void* V, void* O,
  * group the library forks helper HIP streams from hip_stream and joins them back before it
  * returns, so the call is still ordered like a single operation on hip_stream (and can be
  * captured into a HIP graph from it).  The helper streams and their events are created once per
- * device on first use, at the default priority, and live until the process ends.  Process-wide. */
+ * device on first use, at the default priority, and live until the process ends.  This sets the
+ * process-wide default; mrt_problem.head_groups > 0 overrides it for one call.  Multi-group calls
+ * on one device take turns enqueueing (a mutex held from the fork to the join). */
 void mrt_set_head_groups(int n);
 
 /* Per-kernel timing for benchmarks.  mrt_profile_enable(r) with r >= 1 (at most 64) makes the two

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -65,6 +66,7 @@ static mrt_status check_common(const mrt_problem* p) {
   }
   if (!(p->scale > 0.0f) || !(p->scale < 1e30f)) { set_error("scale must be positive and finite"); return MRT_ERR_SHAPE; }
   if (p->tile_h < 0) { set_error("tile_h < 0"); return MRT_ERR_SHAPE; }
+  if (p->head_groups < 0) { set_error("head_groups < 0"); return MRT_ERR_SHAPE; }
   return MRT_OK;
 }
 
@@ -245,15 +247,15 @@ static inline void trace_next_launch(hipStream_t) {}
 
 // ---- optional per-kernel timing (benchmarks only) --------------------------------------
 struct ProfRecord { hipEvent_t a, b; int kind, reps; };
-static int g_prof_on = 0;      // 0 = off, r > 0 = each launch issued r times inside its bracket
+static std::atomic<int> g_prof_on{0};   // 0 = off, r > 0 = each launch issued r times inside its bracket
 static std::vector<ProfRecord> g_prof;
 static std::mutex g_prof_mu;
 
 // Runs `launch` once, or, while profiling, g_prof_on times between two events.  Every kernel of
 // this library reads only buffers it does not write, so a repeated launch leaves the same result.
 template <class F>
-static hipError_t timed_launch(hipStream_t s, int kind, F launch) {
-  const int reps = g_prof_on;
+static hipError_t timed_launch(hipStream_t s, int kind, F launch, bool may_time = true) {
+  const int reps = may_time ? g_prof_on.load(std::memory_order_relaxed) : 0;
   if (reps <= 0) return launch();
   hipEvent_t a = nullptr, b = nullptr;
   if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return launch();
@@ -268,10 +270,16 @@ static hipError_t timed_launch(hipStream_t s, int kind, F launch) {
 
 // ---- helper streams for concurrent head groups ------------------------------------------
 constexpr int kMaxGroups = 4;
-static int g_max_groups = 0;   // 0 = choose per call
+static std::atomic<int> g_max_groups{0};   // process-wide default; 0 = choose per call
 struct StreamPool {
   hipStream_t side[kMaxGroups - 1];
   hipEvent_t fork, join[kMaxGroups - 1];
+  // Held from the fork record to the last join wait of a call: the pool's events and helper
+  // streams belong to one call at a time, so two host threads (or two caller streams) inside
+  // multi-group calls on one device never re-record an event another call still has to wait on.
+  // A stream wait binds to the record that precedes it, so the next call may re-record the events
+  // as soon as this one has enqueued its waits.
+  std::mutex in_use;
 };
 // One pool per device, created on first use and kept for the life of the process.  Streams are
 // created with the default priority.
@@ -291,6 +299,12 @@ static StreamPool* get_pool() {
   if (!ok) { failed[dev] = true; delete p; return nullptr; }   // fall back to one stream
   pools[dev] = p;
   return p;
+}
+
+// Head groups a call asks for: the call's own field, else the process-wide default (0 = automatic).
+static int requested_groups(const mrt_problem* p) {
+  int n = p->head_groups > 0 ? p->head_groups : g_max_groups.load(std::memory_order_relaxed);
+  return n > kMaxGroups ? kMaxGroups : n;
 }
 
 static mrt_status hip_fail(hipError_t e, const char* what) {
@@ -337,10 +351,14 @@ size_t monarch_attn_workspace_bytes(const mrt_problem* p, int b1, int b2, int ti
   return pl.slab_bytes() * recommended_slabs(pl);
 }
 
-mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
-                            const mrt_problem* p, int b1, int b2, int tile, int iters,
-                            int causal_chunk, void* workspace, size_t workspace_bytes,
-                            void* hip_stream) {
+}  // extern "C"
+
+namespace mrt {
+// The forward call behind both entry points.  own_stream_only: run every launch on the caller's
+// stream and create no HIP object (no helper streams, no timing events).
+mrt_status fwd_run(const void* Q, const void* K, const void* V, void* O, const mrt_problem* p, int b1,
+                   int b2, int tile, int iters, int causal_chunk, void* workspace,
+                   size_t workspace_bytes, void* hip_stream, bool own_stream_only) {
   Plan pl;
   mrt_status st = make_plan(p, b1, b2, tile, iters, causal_chunk, &pl);
   if (st != MRT_OK) return st;
@@ -388,13 +406,16 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
   // Measured on MI355X: the fork/join costs ~10 us per extra group, so it only pays for launches
   // that run for >= 100 us and whose stage L grid is within a few multiples of the 512 workgroups
   // the chip holds (KV-cache shapes at 12 heads: -7 %); small calls run on the caller's stream.
-  int want_groups = g_max_groups;
+  int want_groups = requested_groups(p);
   if (want_groups == 0) {
     const size_t inter_per_launch = pl.slab_aL * per_head * G;
     const long long l_wgs = (long long)A * pl.kp.c2 * pl.kp.b2 * G;
     want_groups = (inter_per_launch >= (size_t(128) << 20) && l_wgs < 2048) ? 2 : 1;
   }
-  StreamPool* pool = (g_prof_on || want_groups <= 1) ? nullptr : get_pool();
+  const bool may_time = !own_stream_only;
+  StreamPool* pool = (own_stream_only || g_prof_on.load() || want_groups <= 1) ? nullptr : get_pool();
+  std::unique_lock<std::mutex> pool_lock;
+  if (pool) pool_lock = std::unique_lock<std::mutex>(pool->in_use);
   mrt_status status = MRT_OK;
   for (int bh0 = 0; bh0 < BH && status == MRT_OK; bh0 += G)
   for (int a0 = 0; a0 < pl.c1q && status == MRT_OK; a0 += A) {
@@ -425,13 +446,13 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
         e = timed_launch(gs, MRT_KERNEL_STAGE_R | (first ? MRT_KERNEL_FIRST : 0) | (last ? MRT_KERNEL_LAST : 0), [&] {
           return pl.f32_path() ? launch_f32_stage_r(kg, pl.dtype, hi - lo, first, last, gs)
                                : launch_bf16_stage_r(kg, hi - lo, first, last, gs);
-        });
+        }, may_time);
         if (e != hipSuccess) { status = hip_fail(e, "stage R launch"); break; }
         trace_next_launch(gs);
         e = timed_launch(gs, MRT_KERNEL_STAGE_L | (last ? MRT_KERNEL_LAST : 0), [&] {
           return pl.f32_path() ? launch_f32_stage_l(kg, pl.dtype, hi - lo, last, gs)
                                : launch_bf16_stage_l(kg, hi - lo, last, gs);
-        });
+        }, may_time);
         if (e != hipSuccess) { status = hip_fail(e, "stage L launch"); break; }
       }
     }
@@ -444,6 +465,17 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
     }
   }
   return status;
+}
+}  // namespace mrt
+
+extern "C" {
+
+mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O,
+                            const mrt_problem* p, int b1, int b2, int tile, int iters,
+                            int causal_chunk, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  return mrt::fwd_run(Q, K, V, O, p, b1, b2, tile, iters, causal_chunk, workspace, workspace_bytes,
+                      hip_stream, false);
 }
 
 // ---- backward pass -------------------------------------------------------------------------
@@ -618,7 +650,7 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
   // part-filled last round of one group's launch overlaps another group's kernels.  It pays for
   // long calls whose stage L launches are a small multiple of what the chip holds (KV-cache
   // shapes); otherwise the pass runs on the caller's stream.
-  int want_groups = g_max_groups;
+  int want_groups = requested_groups(p);
   if (want_groups == 0) {
     // stage L backward keeps two workgroups per compute unit resident for b1 <= 96, one beyond:
     // groups pay while a launch is fewer than four rounds of them (measured: 12 heads of the 480p
@@ -626,7 +658,9 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     const long long l_wgs = (long long)pl.ntq_total * pl.kp.b2 * G, slots = pl.kp.b1 <= 96 ? 512 : 256;
     want_groups = (L.rowsD * (size_t)G >= (size_t(256) << 20) && l_wgs < 4 * slots) ? 2 : 1;
   }
-  StreamPool* pool = (g_prof_on || want_groups <= 1) ? nullptr : get_pool();
+  StreamPool* pool = (g_prof_on.load() || want_groups <= 1) ? nullptr : get_pool();
+  std::unique_lock<std::mutex> pool_lock;
+  if (pool) pool_lock = std::unique_lock<std::mutex>(pool->in_use);
   mrt_status status = MRT_OK;
   for (int bh0 = 0; bh0 < BH && status == MRT_OK; bh0 += G) {
     const int nbh = BH - bh0 < G ? BH - bh0 : G;
@@ -695,11 +729,11 @@ int mrt_debug_set_trace(void* buf, size_t stride_bytes) {
 }
 #endif
 
-void mrt_set_head_groups(int n) { g_max_groups = n < 0 ? 0 : (n > kMaxGroups ? kMaxGroups : n); }
+void mrt_set_head_groups(int n) { g_max_groups.store(n < 0 ? 0 : (n > kMaxGroups ? kMaxGroups : n)); }
 
 void mrt_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
-  g_prof_on = on < 0 ? 0 : (on > 64 ? 64 : on);
+  g_prof_on.store(on < 0 ? 0 : (on > 64 ? 64 : on));
 }
 
 int mrt_profile_read(float* ms, int* kind, int capacity) {

@@ -126,6 +126,11 @@ struct Plan {
 
 void set_error(const char* fmt, ...);
 
+// The forward call behind monarch_attn_fwd and monarch_attn_fwd_noalloc (mrt_api.cpp).
+mrt_status fwd_run(const void* Q, const void* K, const void* V, void* O, const mrt_problem* p, int b1,
+                   int b2, int tile, int iters, int causal_chunk, void* workspace,
+                   size_t workspace_bytes, void* hip_stream, bool own_stream_only);
+
 // fp32 SIMT path (mrt_f32.hip)
 hipError_t launch_f32_stage_r(const KParams& kp, int dtype, int nbh, bool first, bool last,
                               hipStream_t s);

@@ -40,6 +40,7 @@ def test_binding_struct_matches_header_layout():
     assert B.MrtProblem.dtype.offset == 32 + 4 * 24
     assert B.MrtProblem.assignment.offset == 32 + 96 + 12
     assert B.MrtProblem.tile_h.offset == 32 + 96 + 16
+    assert B.MrtProblem.head_groups.offset == 32 + 96 + 20
     assert ctypes.sizeof(B.MrtProblem) == 32 + 96 + 24
     # the header lists the assignments in the binding's order
     text = open(HEADER).read()
@@ -206,3 +207,45 @@ def test_backward_entry_checks_on_the_host():
     assert lib.monarch_attn_bwd(fake, fake, fake, fake, fake, fake, fake, *args, fake, 1024, None) == B.MRT_ERR_WORKSPACE
     assert lib.monarch_attn_bwd(fake, fake, fake, fake, fake, fake, fake, ctypes.byref(big), 135, 40, 1, 3, 3,
                                 fake, 1 << 40, None) == B.MRT_ERR_UNSUPPORTED
+
+
+def test_host_entry_points_are_thread_safe():
+    """monarch_attn_check and the workspace queries keep no shared state: several host threads calling
+    them at once (valid and invalid requests mixed) get the same answers as one thread, and every
+    thread reads its own last-error text."""
+    import threading
+    lib = pkg.load_library()
+    good = problem(f_kv=21, q_frame_offset=18)
+    bad = problem()
+    want_ws = pkg.monarch_attn_workspace_bytes(good, 90, 26, 1, 2)
+    want_min = pkg.monarch_attn_workspace_bytes(good, 90, 26, 1, 2, minimum=True)
+    failures = []
+
+    def worker(k):
+        for i in range(300):
+            if (i + k) % 2:
+                if pkg.monarch_attn_check(good, 90, 26, 1, 2, 3) != B.MRT_OK:
+                    failures.append("valid request rejected")
+                if pkg.monarch_attn_workspace_bytes(good, 90, 26, 1, 2) != want_ws:
+                    failures.append("workspace size changed")
+                if pkg.monarch_attn_workspace_bytes(good, 90, 26, 1, 2, minimum=True) != want_min:
+                    failures.append("minimum workspace size changed")
+            else:
+                b1 = 91 + k                                     # does not divide the 90 rows
+                if pkg.monarch_attn_check(bad, b1, 26, 1, 2) != B.MRT_ERR_BLOCK:
+                    failures.append("invalid request accepted")
+                if f"({b1},26)" not in lib.mrt_last_error().decode():
+                    failures.append("another thread's error text")
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures[:3]
+
+
+def test_head_groups_field_is_checked():
+    assert pkg.monarch_attn_check(problem(head_groups=2), 90, 52, 0, 2) == B.MRT_OK
+    assert pkg.monarch_attn_check(problem(head_groups=9), 90, 52, 0, 2) == B.MRT_OK      # clamped to 4
+    assert pkg.monarch_attn_check(problem(head_groups=-1), 90, 52, 0, 2) == B.MRT_ERR_SHAPE
