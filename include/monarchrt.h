@@ -148,6 +148,22 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
                             int causal_chunk, void* workspace, size_t workspace_bytes,
                             void* hip_stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, serving loops, harnesses that
+ * forbid hipMalloc): monarch_attn_fwd with the library's own scratch memory in place of the
+ * workspace argument.  The scratch is a 128 MiB array in the library's device image, one copy per
+ * GPU, held until the process ends.  The call allocates nothing, creates no stream or event, runs
+ * every kernel on hip_stream (one head group) and is otherwise identical to monarch_attn_fwd with
+ * a 128 MiB workspace: as many heads, or query tile rows of one head, per pass as fit.  It returns
+ * MRT_ERR_WORKSPACE if one query tile row of one (batch, head) needs more than that
+ * (monarch_attn_workspace_min_bytes > 134217728).  Nothing has to be cleared between calls: every
+ * kernel reads only what an earlier kernel of the same call wrote.  All calls on one GPU share the
+ * array, so calls that overlap in time on one GPU (different streams or threads) race; order them
+ * on one stream.  The first call on a device looks up the array's address; make that call
+ * outside a graph capture. */
+mrt_status monarch_attn_fwd_noalloc(const void* Q, const void* K, const void* V, void* O,
+                                    const mrt_problem* p, int b1, int b2, int tile, int iters,
+                                    int causal_chunk, void* hip_stream);
+
 /* Backward pass: gradients of  sum(O * dO)  with respect to Q, K and V for the O of
  * monarch_attn_fwd with the same arguments, differentiating through every refinement iteration
  * (this is what Monarch finetuning trains through, Sec. 4.3).

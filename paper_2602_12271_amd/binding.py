@@ -23,7 +23,9 @@ EXPORTED = [
     "monarch_attn_fwd", "dense_attn_check", "dense_attn_fwd", "mrt_status_string", "mrt_last_error",
     "mrt_profile_enable", "mrt_profile_read", "mrt_set_head_groups",
     "monarch_attn_bwd", "monarch_attn_bwd_workspace_bytes", "monarch_attn_bwd_workspace_min_bytes",
+    "monarch_attn_fwd_noalloc",
 ]
+NOALLOC_SCRATCH_BYTES = 128 << 20
 ASSIGNMENTS = {"fh_w": 0, "w_fh": 1, "fw_h": 2, "h_fw": 3, "f_hw": 4, "hw_f": 5}
 KERNEL_STAGE_R, KERNEL_STAGE_L, KERNEL_DENSE, KERNEL_FIRST, KERNEL_LAST = 1, 2, 4, 16, 32
 
@@ -71,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.monarch_attn_workspace_bytes.restype = sz
     lib.monarch_attn_fwd.argtypes = [vp, vp, vp, vp, P, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.monarch_attn_fwd.restype = ci
+    lib.monarch_attn_fwd_noalloc.argtypes = [vp, vp, vp, vp, P, ci, ci, ci, ci, ci, vp]
+    lib.monarch_attn_fwd_noalloc.restype = ci
     fp = ctypes.c_void_p
     lib.monarch_attn_bwd_workspace_min_bytes.argtypes = [P, ci, ci, ci, ci]
     lib.monarch_attn_bwd_workspace_min_bytes.restype = sz
@@ -194,6 +198,22 @@ def monarch_attn_fwd(Q, K, V, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_ch
     if st != MRT_OK:
         _raise(lib, st)
     return O
+
+
+def monarch_attn_fwd_noalloc(Q, K, V, out, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,
+                             q_frame_offset=0, scale=1.0, compute=MRT_COMPUTE_DEFAULT, stream=None,
+                             assign="fh_w", tile_h=0):
+    """monarch_attn_fwd on the library's built-in scratch memory: the call allocates nothing, so the
+    output tensor must be passed in."""
+    import torch
+    lib = load_library()
+    prob = _torch_problem(Q, K, V, out, f_q, f_kv, h, w, q_frame_offset, scale, compute, assign, tile_h)
+    s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+    st = lib.monarch_attn_fwd_noalloc(Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(),
+                                      ctypes.byref(prob), b1, b2, tile, iters, causal_chunk, s)
+    if st != MRT_OK:
+        _raise(lib, st)
+    return out
 
 
 def monarch_attn_bwd(Q, K, V, dO, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,

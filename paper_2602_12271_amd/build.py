@@ -14,7 +14,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-SOURCES = ["mrt_api.cpp", "mrt_f32.hip", "mrt_bf16.hip", "mrt_bwd_f32.hip", "mrt_bwd_bf16.hip"]
+SOURCES = ["mrt_api.cpp", "mrt_static.hip", "mrt_f32.hip", "mrt_bf16.hip", "mrt_bwd_f32.hip", "mrt_bwd_bf16.hip"]
 OUT = os.path.join(HERE, "libmonarchrt.so")
 
 FLAGS = [

@@ -249,3 +249,19 @@ def test_head_groups_field_is_checked():
     assert pkg.monarch_attn_check(problem(head_groups=2), 90, 52, 0, 2) == B.MRT_OK
     assert pkg.monarch_attn_check(problem(head_groups=9), 90, 52, 0, 2) == B.MRT_OK      # clamped to 4
     assert pkg.monarch_attn_check(problem(head_groups=-1), 90, 52, 0, 2) == B.MRT_ERR_SHAPE
+
+
+def test_noalloc_entry_point_rejects_what_its_scratch_cannot_hold():
+    """Host-side checks of monarch_attn_fwd_noalloc run before any GPU call: an invalid request gets
+    the same status as from monarch_attn_fwd's checks, and a request whose smallest pass needs more
+    than the built-in scratch (a 21-frame full sequence with 3-frame tiles of 135 x 96 at fp32:
+    135 x 96 x 7 key tiles x 128 features x 4 bytes x 3 arrays per query tile row = 139 MB) is refused."""
+    lib = pkg.load_library()
+    p = problem()
+    assert lib.monarch_attn_fwd_noalloc(None, None, None, None, ctypes.byref(p), 91, 52, 0, 2, 0, None) == B.MRT_ERR_BLOCK
+    big = problem(heads=1, f_q=21, f_kv=21, h=45, w=96, dtype=B.MRT_F32)
+    assert pkg.monarch_attn_workspace_bytes(big, 135, 96, 1, 2, minimum=True) > B.NOALLOC_SCRATCH_BYTES
+    assert lib.monarch_attn_fwd_noalloc(None, None, None, None, ctypes.byref(big), 135, 96, 1, 2, 0, None) == B.MRT_ERR_WORKSPACE
+    assert "built-in scratch" in lib.mrt_last_error().decode()
+    # a request that fits but has no tensors is refused before any launch
+    assert lib.monarch_attn_fwd_noalloc(None, None, None, None, ctypes.byref(p), 90, 52, 0, 2, 0, None) == B.MRT_ERR_NULL
