@@ -227,6 +227,33 @@ def test_rows_far_below_their_tile_maximum_keep_their_weights():
     check(wl, (Q, K, V), O, label="row 200 below its tile's maximum")
 
 
+@pytest.mark.parametrize("shape", ["regular-one-pass", "tiled-streamed"])
+def test_key_rows_far_below_every_query_keep_a_finite_average(shape):
+    """alpha_R / c_R is an average of query rows weighted by L[l, nk]; a key row whose logits lie more
+    than 126 (base 2) below every query's largest logit has all its weights underflow in fp32, and the
+    kernels must then form the same ratio from log L relative to the column's maximum instead of
+    dividing 0 by 0.  One key row of the opposite sign against otherwise equal keys and queries:
+    its logits are 204 below the others', V is random, and the oracle (fp64 does not underflow at
+    2^-204) gives the reference."""
+    if shape == "regular-one-pass":
+        wl = small_bf16(heads=1, f_q=2, f_kv=2, h=16, w=16, b1=32, b2=16, tile=0, iters=3,
+                        causal_chunk=0, q_frame_offset=0)
+    else:   # 4 key tiles of 64 rows: the streamed two-pass refine kernel
+        wl = small_bf16(heads=1, f_q=1, f_kv=4, h=64, w=16, b1=64, b2=16, tile=1, iters=3,
+                        causal_chunk=0, q_frame_offset=0)
+    rng = np.random.default_rng(6)
+    d = wl.head_dim
+    Q = np.full((1, 1, wl.n_q, d), 2.5, np.float32)
+    K = np.full((1, 1, wl.n_kv, d), 2.5, np.float32)
+    krow = np.arange(wl.n_kv) // wl.w
+    K[0, 0, krow == 5] = -2.5
+    V = syn.round_to_bf16(rng.standard_normal((1, 1, wl.n_kv, d)).astype(np.float32))
+    assert 2 * wl.scale * 1.4427 * 2.5 * 2.5 * d > 126
+    O = run_monarch_gpu(wl, *to_device(wl, (Q, K, V)))
+    assert torch.isfinite(O.float()).all()
+    check(wl, (Q, K, V), O, label=f"key row 204 below the others ({shape})")
+
+
 def test_rerun_is_bit_identical():
     wl = syn.variant("C2", heads=2)
     dev = to_device(wl, syn.make_inputs(wl))
