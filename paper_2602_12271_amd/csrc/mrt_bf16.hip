@@ -102,7 +102,6 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   RowRegs<D, ROWS, NTHR> rk;
   RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
   rk.load(Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
-  if (LAST) rv.load(Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
 
   // query-side rows of this wave (row j = 16*wave + c) go straight to registers: Q[m, k, j, :] in
   // the first iteration (L is the identity), alpha_R / c_R afterwards
@@ -121,8 +120,8 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
     for (int ks = 0; ks < KS1; ++ks) qn[ks] = ld_global_16B(arow + 32 * ks + 8 * g);
   };
   load_q(ml0);
+  if (LAST) rv.load(Vp, TokRows{0, p.cmap, bn * b2, p.vs.token}, b2, tid);
   rk.template store<LD>(Ks, tid);
-  if (LAST) rv.template store_rev<LD>(Vtop, tid);
   __syncthreads();
   MRT_STAMP(1);
 
@@ -174,6 +173,12 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
     if (g == 0 && j < b2) p.cL[row] = kLn2 * (ent * inv - log2_fast(sum));
 
     __builtin_amdgcn_sched_barrier(0);
+    if (LAST && ml == ml0) {
+      // the values, requested with the keys, were still arriving during the first tile's logits and
+      // softmax; they are needed from here on
+      rv.template store_rev<LD>(Vtop, tid);
+      __syncthreads();
+    }
     // alpha_L = R K (and Y = R V)
     bf16x8 pb[KS2];
 #pragma unroll
@@ -225,6 +230,8 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
 // flash loop shared by stage L (out), stage L (refine, pass 1) and the dense baseline
 // ---------------------------------------------------------------------------------------
 constexpr int kCK = 64;   // keys per LDS chunk (two 32-key steps)
+constexpr int kPadF = kPad;   // row padding of the chunk buffers and of the streamed refine kernel's Q tile
+                              // (8 measured 1 % slower at the KV-cache shapes)
 constexpr int kMinThreads = 256;   // the chunk copy below assumes at least this many threads
 
 template <int QT>
@@ -258,7 +265,7 @@ struct ChunkRegs {
     }
   }
   __device__ inline void commit(u16* dst, int tid, int nthr) const {
-    constexpr int LD = D + kPad;
+    constexpr int LD = D + kPadF;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int idx = tid + i * nthr;
@@ -278,7 +285,7 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
                                    const int* kchunk, const int (&qchunk)[QT],
                                    const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
                                    FlashState<QT>& st, f32x4 (&o)[QT][D / 16], int lane) {
-  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16, HALF = NVT / 2;
+  constexpr int LD = D + kPadF, KS1 = D / 32, NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, c = lane & 15;
   f32x4 s[QT][4];
 #pragma unroll
@@ -388,7 +395,7 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
 // LDS layout of the double-buffered chunk pipeline
 template <int D, bool WITH_V>
 struct FlashLds {
-  static constexpr int LD = D + kPad;
+  static constexpr int LD = D + kPadF;
   static constexpr size_t kBytes = (size_t)2 * kCK * LD * 2 * (WITH_V ? 2 : 1) + 2 * kCK * 8;
   u16* k0;
   u16* v0;
@@ -715,7 +722,7 @@ constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
 // the scheduler can overlap one tile's LDS reads with another's MFMAs).
 template <int D, int QT, int MAXT, int NLT, int PT>
 __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
-  constexpr int LD = D + kPad, KS1 = D / 32, NVT = D / 16;
+  constexpr int LD = D + kPadF, KS1 = D / 32, NVT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   FlashLds<D, false> lds(smem);
   u16* Qs = (u16*)(smem + FlashLds<D, false>::kBytes);   // [qrows][LD], rows >= b1 zero
@@ -735,7 +742,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   MRT_STAMP(0);
-  stage_rows<D>(Qs, Qp, qrow, qrows, b1, tid, nthr);
+  stage_rows<D, LD>(Qs, Qp, qrow, qrows, b1, tid, nthr);
 
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
@@ -890,27 +897,29 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
         qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
     }
   };
-  const int npairs = (nlt + QT - 1) / QT;
+  const int npairs = (nlt + QT - 1) / QT;      // <= 3 (b1 <= 96): at most one pair per wave
   // every global load of the workgroup is issued before the first LDS store: one memory round
-  // trip instead of one per tile (the query rows, needed last, are requested last)
+  // trip instead of one per tile.  The loads return in order: alpha_L, c_L and the query rows, which
+  // the logits need, are requested first; the values follow and are still arriving while the
+  // logits and the softmax are formed (they are committed to LDS only before the second product).
   RowRegs<D, ROWS, 256> rk, rv;
   rk.load(aLp, PlainRows{D}, NK, tid);
-  rv.load(Yp, PlainRows{D}, NK, tid);
   static_assert(ROWS <= 256, "one bias value per thread");
   const float cl = cLp[tid < NK ? tid : NK - 1];
   if (wave < npairs) load_q(wave);
+  rv.load(Yp, PlainRows{D}, NK, tid);
   rk.template store<LD>(Ks, tid);
-  rv.template store<LD>(Vs, tid);
   if (tid < ROWS) bias[tid] = tid < NK ? -cl * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
 
   const float scale2 = p.scale * kLog2e;
-  for (int pair = wave; pair < npairs; pair += nwaves) {
-    if (pair != wave) load_q(pair);
-    const int nq = nlt - QT * pair < QT ? nlt - QT * pair : QT;
+  const int pair = wave;
+  const int nq = pair < npairs ? (nlt - QT * pair < QT ? nlt - QT * pair : QT) : 0;
+  bf16x8 pb[KS2][QT];
+  float sum[QT];
+  if (nq > 0) {
     f32x4 s[QT][NTK];
-    float sum[QT];
     int klim[QT];
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
@@ -918,7 +927,6 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
       klim[q] = RMASK ? visible_key_rows(p, l < b1 ? l : b1 - 1) : 0;
     }
     res_logits<D, NTK, LD, QT, RMASK>(Ks, bias, qv, nq, scale2, klim, s, sum, lane);
-    bf16x8 pb[KS2][QT];
 #pragma unroll
     for (int q = 0; q < QT; ++q)
 #pragma unroll
@@ -927,7 +935,12 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
         const f32x4 hi = (2 * st + 1 < NTK) ? s[q][(2 * st + 1 < NTK) ? 2 * st + 1 : 0] : zero;
         pb[st][q] = pack8(s[q][2 * st], hi);
       }
-    __builtin_amdgcn_sched_barrier(0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  rv.template store<LD>(Vs, tid);
+  __syncthreads();
+  MRT_STAMP(2);
+  if (nq > 0) {
     f32x4 o[QT][NVT];
 #pragma unroll
     for (int q = 0; q < QT; ++q)
@@ -938,13 +951,14 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
       pv_step_multi<D, QT, LD>(Vs + 32 * st * LD, pb[st], nq, o, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
+    const TokRows orow = tile_rows(p, a, p.os.token);
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
       const int l = 16 * (QT * pair + q) + c;
-      if (q < nq && l < b1) store_rows<D>(Op + tile_rows(p, a, p.os.token)(l), o[q], 1.0f / sum[q], g);
+      if (q < nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
     }
   }
-  MRT_STAMP(2);
+  MRT_STAMP(3);
 }
 
 // Stage L of an earlier iteration for key ranges of at most 64 PT rows, in one pass over the
@@ -997,44 +1011,52 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
   MRT_STAMP(1);
 
   // logits in the base-2 domain: rows 4g + r are queries, column c is key 16 (tile0 + pt) + c
+  // (a lambda: the two rare underflow paths below form them a second time)
   const float scale2 = p.scale * kLog2e;
   f32x4 z[PT][NLT];
+  auto logits = [&]() {
 #pragma unroll
-  for (int lt = 0; lt < NLT; ++lt) {
-    bf16x8 av[KS1];
+    for (int lt = 0; lt < NLT; ++lt) {
+      bf16x8 av[KS1];
 #pragma unroll
-    for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
+      for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
 #pragma unroll
-    for (int pt = 0; pt < PT; ++pt) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      if (pt < npt) {
+      for (int pt = 0; pt < PT; ++pt) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (pt < npt) {
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
+          for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
+        }
+        const bool col = 16 * (tile0 + pt) + c < NK;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[r] = col ? fmaf(acc[r], scale2, -cl[pt]) : -INFINITY;
+        z[pt][lt] = acc;
       }
-      const bool col = 16 * (tile0 + pt) + c < NK;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) acc[r] = col ? fmaf(acc[r], scale2, -cl[pt]) : -INFINITY;
-      z[pt][lt] = acc;
+      if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
-    if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
-  }
-  if (p.rl > 0) {
-    // regular Monarch under the chunk-causal mask: key rows of later chunks are zeros of L
+    if (p.rl > 0) {
+      // regular Monarch under the chunk-causal mask: key rows of later chunks are zeros of L
 #pragma unroll
-    for (int lt = 0; lt < NLT; ++lt)
+      for (int lt = 0; lt < NLT; ++lt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int lim = visible_key_rows(p, 16 * lt + 4 * g + r);
+        for (int r = 0; r < 4; ++r) {
+          const int lim = visible_key_rows(p, 16 * lt + 4 * g + r);
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt)
-          if (16 * (tile0 + pt) + c >= lim) z[pt][lt][r] = -INFINITY;
-      }
-  }
-  // this wave's share of every query row's sum of 2^z, relative to a reference the waves then
-  // reconcile.  First with one reference per query tile (the maximum over the tile's 16 rows: six
-  // cross-lane steps per tile instead of four per row); a row whose logits all lie 126 or more
-  // below its tile's maximum would lose its sum to underflow, so if any row's total comes out zero
-  // the statistics are redone with every row's own maximum.
+          for (int pt = 0; pt < PT; ++pt)
+            if (16 * (tile0 + pt) + c >= lim) z[pt][lt][r] = -INFINITY;
+        }
+    }
+  };
+  logits();
+  // This wave's share of every query row's sum of 2^z, relative to a reference the waves then
+  // reconcile; the exponentials e = 2^(z - reference) are kept in place of the logits, and a weight
+  // is L = 2^(z - lse) = e * 2^(reference - M) / S with M the largest reference of the row and S
+  // the row's total relative to it: one exponential per logit.  First with one reference per query
+  // tile (the maximum over the tile's 16 rows: six cross-lane steps per tile instead of four per
+  // row).  A row whose largest logit lies far below its tile's maximum would lose weights to
+  // underflow (e is flushed below 2^-126), so if any row's total comes out below 2^-64 the logits
+  // are formed again and the statistics redone with every row's own maximum; with S >= 2^-64 a
+  // flushed e stands for a weight below 2^-62.
   auto stats = [&](bool per_row) {
 #pragma unroll
     for (int lt = 0; lt < NLT; ++lt) {
@@ -1062,7 +1084,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
         const float ref = vr[r] == -INFINITY ? 0.f : vr[r];
         float e = 0.f;
 #pragma unroll
-        for (int pt = 0; pt < PT; ++pt) e += exp2_fast(z[pt][lt][r] - ref);
+        for (int pt = 0; pt < PT; ++pt) {
+          z[pt][lt][r] = exp2_fast(z[pt][lt][r] - ref);
+          e += z[pt][lt][r];
+        }
         sm[r] = row16_sum(e);
       }
       if (c == 0) {
@@ -1071,16 +1096,25 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
       }
     }
   };
+  // per row: log-sum-exp (base 2) and, in place of every wave's partial sum, the factor that turns
+  // that wave's exponentials into weights (zero for the padding rows beyond b1)
   auto combine = [&]() {
     if (tid < LROWS) {
       float M = red_m[0][tid];
 #pragma unroll
       for (int w = 1; w < NW; ++w) M = fmaxf(M, red_m[w][tid]);
-      float S = 0.f;
+      const float Ms = M == -INFINITY ? 0.f : M;
+      float f[NW], S = 0.f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) S = fmaf(red_s[w][tid], exp2_fast(red_m[w][tid] - M), S);
-      lse[tid] = M + log2_fast(S);
-      if (!(S > 0.f)) redo = 1;
+      for (int w = 0; w < NW; ++w) {
+        f[w] = exp2_fast(red_m[w][tid] - Ms);
+        S = fmaf(red_s[w][tid], f[w], S);
+      }
+      lse[tid] = Ms + log2_fast(S);
+      const float inv = tid < b1 ? 1.0f / S : 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) red_s[w][tid] = f[w] * inv;
+      if (!(S > 0x1p-64f) && tid < b1) redo = 1;
     }
   };
   if (tid == 0) redo = 0;
@@ -1089,26 +1123,106 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
   combine();
   __syncthreads();
   if (redo) {            // uniform: read after the barrier
+    logits();
     stats(true);
     __syncthreads();
     combine();
     __syncthreads();
   }
-  __syncthreads();
   MRT_STAMP(2);
+  // weights L[l, nk] as packed bf16 operands, and their column sums c_R
+  constexpr int NVT = D / 16, NS2 = (NLT + 1) / 2;
+  float csum[PT];
+  bf16x8 pb[NS2][PT];
 #pragma unroll
-  for (int lt = 0; lt < NLT; ++lt) {
-    const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
+  for (int pt = 0; pt < PT; ++pt) csum[pt] = 0.f;
+#pragma unroll
+  for (int st2 = 0; st2 < NS2; ++st2) {
+    const f32x4 f0 = *(const f32x4*)(&red_s[wave][32 * st2 + 4 * g]);
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    const f32x4 f1 = 2 * st2 + 1 < NLT ? *(const f32x4*)(&red_s[wave][32 * st2 + 16 + 4 * g]) : zero;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      const f32x4 lo = z[pt][2 * st2] * f0;
+      const f32x4 hi = 2 * st2 + 1 < NLT ? z[pt][2 * st2 + 1 < NLT ? 2 * st2 + 1 : 0] * f1 : zero;
+      csum[pt] += (lo[0] + lo[1]) + (lo[2] + lo[3]) + (hi[0] + hi[1]) + (hi[2] + hi[3]);
+      pb[st2][pt] = pack8(lo, hi);
+    }
+  }
+  bool under = false;
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt) {
+    csum[pt] = xsum(csum[pt]);
+    under |= (pt < npt && 16 * (tile0 + pt) + c < NK && csum[pt] == 0.f);
+  }
+  float shift[PT];
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
+  if (__any(under)) {
+    // a whole column of weights underflowed: the ratio alpha_R / c_R is formed from log2 L relative
+    // to the column's maximum instead (logits formed again; rare)
+    logits();
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      float cm = -INFINITY;
+#pragma unroll
+      for (int lt = 0; lt < NLT; ++lt) {
+        const f32x4 ls = *(const f32x4*)(lse + 16 * lt + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          z[pt][lt][r] = 16 * lt + 4 * g + r < b1 ? z[pt][lt][r] - ls[r] : -INFINITY;
+          cm = fmaxf(cm, z[pt][lt][r]);
+        }
+      }
+      cm = xmax(cm);
+      shift[pt] = cm == -INFINITY ? 0.f : cm;
+      csum[pt] = 0.f;
+#pragma unroll
+      for (int st2 = 0; st2 < NS2; ++st2) {
+        f32x4 lo, hi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          lo[r] = exp2_fast(z[pt][2 * st2][r] - shift[pt]);
+          csum[pt] += lo[r];
+          if (2 * st2 + 1 < NLT) {
+            hi[r] = exp2_fast(z[pt][2 * st2 + 1 < NLT ? 2 * st2 + 1 : 0][r] - shift[pt]);
+            csum[pt] += hi[r];
+          }
+        }
+        pb[st2][pt] = pack8(lo, hi);
+      }
+      csum[pt] = xsum(csum[pt]);
+    }
+  }
+  MRT_STAMP(4);
+  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
+  if (npt > 0) {
+    f32x4 o[PT][NVT];
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const bool ok = 16 * lt + 4 * g + r < b1;
-        z[pt][lt][r] = ok ? z[pt][lt][r] - ls[r] : -INFINITY;
+      for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st2 = 0; st2 < NS2; ++st2) {
+      pv_step_multi<D, PT, LD>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    MRT_STAMP(5);
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      const int nk = 16 * (tile0 + pt) + c;
+      if (pt < npt && nk < NK) {
+        store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
+        // the backward pass rebuilds the weights as exp(log L - cmx) * cinv
+        if (p.cmx_out != nullptr && g == 0) {
+          const size_t at = (size_t)(aRout - (u16*)p.aR) / D + (size_t)nk * b2 + j;
+          p.cmx_out[at] = shift[pt] * kLn2;
+          p.cinv_out[at] = 1.0f / csum[pt];
+        }
       }
+    }
   }
-  u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
-  if (npt > 0) refine_finish<D, NLT, PT, LD>(p, Qs, z, npt, tile0, aRout, NK, j, lane, wave == 0);
+  MRT_STAMP(6);
 }
 
 // dense baseline: 128 queries per workgroup (4 waves x 2 tiles of 16), flash loop over all
@@ -1365,7 +1479,7 @@ template <int D, int NLT>
 hipError_t launch_l_refine(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
   constexpr int QT = NLT <= 4 ? 1 : 2, MAXT = NLT <= 8 ? 256 : 384, PT = NLT <= 8 ? 2 : 1;
   const int qrows = 32 * ((NLT + 1) / 2);
-  const size_t lds = FlashLds<D, false>::kBytes + (size_t)qrows * (D + kPad) * 2 + 16 * kMaxLT * 4;
+  const size_t lds = FlashLds<D, false>::kBytes + (size_t)qrows * (D + kPadF) * 2 + 16 * kMaxLT * 4;
   hipError_t e;
   if (lds > 64 * 1024 &&
       (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT>,
