@@ -58,6 +58,11 @@ static mrt_status check_common(const mrt_problem* p) {
       set_error("stride set %d: bf16 path needs strides that are multiples of 8 elements", t);
       return MRT_ERR_SHAPE;
     }
+    // the bf16 kernels address the tokens of one (batch, head) with 32-bit element offsets
+    if (!f32 && (t < 1 || t > 2 ? nq : nkv) * st[t]->token >= (1ll << 31)) {
+      set_error("stride set %d: tokens x token stride must stay below 2^31 elements on the bf16 path", t);
+      return MRT_ERR_UNSUPPORTED;
+    }
   }
   if (p->q_frame_offset < 0) { set_error("q_frame_offset < 0"); return MRT_ERR_SHAPE; }
   if ((int)p->assignment < 0 || (int)p->assignment > (int)MRT_ASSIGN_HW_F) {

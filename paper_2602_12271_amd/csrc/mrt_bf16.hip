@@ -76,7 +76,7 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   u16* Ks = LAST ? r_lds : Ks_static;
   u16* Vtop = r_lds + (p.b2 + ROWS - 1) * LD;                     // value row 0
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int nk = blockIdx.x, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int n = nk / b1, k = nk - n * b1;
@@ -254,14 +254,16 @@ struct ChunkRegs {
   // has to wait for them before the commit; the commit zero-fills the rows that do not exist.
   __device__ inline void load(const u16* src, long long stride, int nvalid, int tid, int nthr) {
     valid = nvalid;
+    // thread t fetches chunk t % CPR of rows t / CPR + i * (nthr / CPR) (nthr is a multiple of 64):
+    // a 32-bit offset from the uniform chunk base, one multiply and then a uniform increment per
+    // load; rows beyond the last valid one re-read it
+    const u16* base = src + 8 * (tid % CPR);
+    const unsigned S = (unsigned)stride, last = (unsigned)(nvalid - 1) * S, inc = (unsigned)(nthr / CPR) * S;
+    unsigned off = (unsigned)(tid / CPR) * S;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      int idx = tid + i * nthr;
-      idx = idx < TOTAL ? idx : TOTAL - 1;
-      int r = idx / CPR;
-      const int c = idx - r * CPR;
-      r = r < nvalid ? r : nvalid - 1;
-      v[i] = *(const uint4*)(src + (long long)r * stride + 8 * c);
+      v[i] = *(const uint4*)(base + (off < last ? off : last));
+      off += inc;
     }
   }
   __device__ inline void commit(u16* dst, int tid, int nthr) const {
@@ -502,7 +504,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
   FlashLds<D, true> lds(smem);
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
@@ -728,7 +730,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   u16* Qs = (u16*)(smem + FlashLds<D, false>::kBytes);   // [qrows][LD], rows >= b1 zero
   float* lse = (float*)(Qs + (size_t)qrows * LD);        // [16 * kMaxLT]
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   constexpr int nlt = NLT;
@@ -865,7 +867,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   __shared__ __attribute__((aligned(16))) u16 Vs[ROWS * LD];
   __shared__ __attribute__((aligned(16))) float bias[ROWS];
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
@@ -966,7 +968,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
 // tile once, with queries on the accumulator rows.  The row statistics of the joint softmax over
 // the key range are reduced inside the wave and exchanged between the NW waves through LDS;
 // alpha_L goes from global memory straight into the matrix operands, only Q is staged.
-template <int D, int NLT, int PT, int NW>
+template <int D, int NLT, int PT, int NW, bool RMASK>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refine_one(KParams p) {
   constexpr int LD = D + kResPad, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), LROWS = 16 * NLT;
   __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
@@ -975,7 +977,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
   __shared__ __attribute__((aligned(16))) float lse[LROWS];
   __shared__ int redo;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
@@ -1034,7 +1036,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
       }
       if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
-    if (p.rl > 0) {
+    if constexpr (RMASK) {
       // regular Monarch under the chunk-causal mask: key rows of later chunks are zeros of L
 #pragma unroll
       for (int lt = 0; lt < NLT; ++lt)
@@ -1122,7 +1124,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
   __syncthreads();
   combine();
   __syncthreads();
-  if (redo) {            // uniform: read after the barrier
+  if (__builtin_expect(redo, 0)) {            // uniform: read after the barrier
     logits();
     stats(true);
     __syncthreads();
@@ -1158,7 +1160,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
   float shift[PT];
 #pragma unroll
   for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
-  if (__any(under)) {
+  if (__builtin_expect(__any(under), 0)) {
     // a whole column of weights underflowed: the ratio alpha_R / c_R is formed from log2 L relative
     // to the column's maximum instead (logits formed again; rare)
     logits();
@@ -1234,7 +1236,7 @@ __global__ __launch_bounds__(256, 2) void k_bf16_dense(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16, QT = kDenseQT;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
   FlashLds<D, true> lds(smem);
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int q0 = blockIdx.x * kDenseQ, bh = blockIdx.y;
   const int b = bh / p.H, hd = bh - b * p.H;
   const int qtiles = (p.Nq - q0 + 15) >> 4;
@@ -1369,7 +1371,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   __shared__ __attribute__((aligned(16))) u16 tile[ROWS * LD];
   __shared__ __attribute__((aligned(16))) float bias[ROWS];
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = tid >> 6, nwaves = nthr >> 6;
+  const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
@@ -1556,15 +1558,23 @@ hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last
                      : launch_r_d<64>(kp, grid, (int)gs, first, last, s);
 }
 
+// RMASK: regular Monarch under the chunk-causal mask (a variant of its own, so that the unmasked
+// kernel carries neither the mask code nor its registers)
+template <int D, int NLT, int PT, int NW>
+void launch_refine_one_k(const KParams& kp, dim3 grid, hipStream_t s) {
+  if (kp.rl > 0) k_bf16_stage_l_refine_one<D, NLT, PT, NW, true><<<grid, 64 * NW, 0, s>>>(kp);
+  else k_bf16_stage_l_refine_one<D, NLT, PT, NW, false><<<grid, 64 * NW, 0, s>>>(kp);
+}
+
 template <int D, int PT>
 hipError_t launch_l_refine_one(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
   switch (nlt) {
-    case 1: k_bf16_stage_l_refine_one<D, 1, PT, 4><<<grid, 256, 0, s>>>(kp); break;
-    case 2: k_bf16_stage_l_refine_one<D, 2, PT, 4><<<grid, 256, 0, s>>>(kp); break;
-    case 3: k_bf16_stage_l_refine_one<D, 3, PT, 4><<<grid, 256, 0, s>>>(kp); break;
-    case 4: k_bf16_stage_l_refine_one<D, 4, PT, 4><<<grid, 256, 0, s>>>(kp); break;
-    case 5: k_bf16_stage_l_refine_one<D, 5, PT, 4><<<grid, 256, 0, s>>>(kp); break;
-    case 6: k_bf16_stage_l_refine_one<D, 6, PT, 4><<<grid, 256, 0, s>>>(kp); break;
+    case 1: launch_refine_one_k<D, 1, PT, 4>(kp, grid, s); break;
+    case 2: launch_refine_one_k<D, 2, PT, 4>(kp, grid, s); break;
+    case 3: launch_refine_one_k<D, 3, PT, 4>(kp, grid, s); break;
+    case 4: launch_refine_one_k<D, 4, PT, 4>(kp, grid, s); break;
+    case 5: launch_refine_one_k<D, 5, PT, 4>(kp, grid, s); break;
+    case 6: launch_refine_one_k<D, 6, PT, 4>(kp, grid, s); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -1574,9 +1584,9 @@ hipError_t launch_l_refine_one(const KParams& kp, dim3 grid, int nlt, hipStream_
 template <int D>
 hipError_t launch_l_refine_one_wide(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
   switch ((nlt + 1) / 2) {
-    case 4: k_bf16_stage_l_refine_one<D, 8, 2, 6><<<grid, 384, 0, s>>>(kp); break;
-    case 5: k_bf16_stage_l_refine_one<D, 10, 2, 6><<<grid, 384, 0, s>>>(kp); break;
-    case 6: k_bf16_stage_l_refine_one<D, 12, 2, 6><<<grid, 384, 0, s>>>(kp); break;
+    case 4: launch_refine_one_k<D, 8, 2, 6>(kp, grid, s); break;
+    case 5: launch_refine_one_k<D, 10, 2, 6>(kp, grid, s); break;
+    case 6: launch_refine_one_k<D, 12, 2, 6>(kp, grid, s); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

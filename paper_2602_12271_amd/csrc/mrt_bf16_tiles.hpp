@@ -2,6 +2,9 @@
 // access helpers, the transposed LDS read, the second-product step and tile staging.
 // See the head of mrt_bf16.hip for the register layouts these assume.
 #pragma once
+#include <type_traits>
+#include <utility>
+
 #include "mrt_internal.hpp"
 
 namespace mrt {
@@ -199,12 +202,19 @@ __device__ inline void store_rows_half(u16* row, const f32x4* acc, float mul, in
 
 // Element offset of row r of a tile of a token-indexed tensor (Q, K, V, O): the tile's rows are
 // the block-grid indices x0 + r along one side of the block grid.
+// A row map is "linear" when consecutive rows are a fixed number of elements apart (one-level axis
+// maps; always for the workspace arrays): row r then sits at first() + r * step(), and the host's
+// checks keep every offset inside one (batch, head) below 2^31 elements, so that the per-lane part
+// of an address is a 32-bit offset from a wave-uniform base.
 struct TokRows {
   long long base;      // tokens
   AxisMap m;
   int x0;
   long long tstride;   // elements per token
   __device__ inline long long operator()(int r) const { return (base + axis_offset(m, x0 + r)) * tstride; }
+  __device__ inline bool linear() const { return m.div == 0; }
+  __device__ inline long long first() const { return (base + (long long)x0 * m.lo) * tstride; }
+  __device__ inline unsigned step() const { return (unsigned)m.lo * (unsigned)tstride; }
 };
 // Rows of tile row a: contiguous block-grid rows, or nh rows of each of the tile's frames.
 __device__ inline TokRows tile_rows(const KParams& p, int a, long long tstride) {
@@ -217,7 +227,17 @@ __device__ inline TokRows tile_rows(const KParams& p, int a, long long tstride) 
 struct PlainRows {
   long long stride;
   __device__ inline long long operator()(int r) const { return (long long)r * stride; }
+  __device__ inline bool linear() const { return true; }
+  __device__ inline long long first() const { return 0; }
+  __device__ inline unsigned step() const { return (unsigned)stride; }
 };
+
+// Row maps that can say whether their rows are evenly spaced (TokRows, PlainRows); any other
+// callable taking a row index is treated as a general map.
+template <typename T, typename = void>
+struct HasLinear : std::false_type {};
+template <typename T>
+struct HasLinear<T, std::void_t<decltype(std::declval<const T&>().linear())>> : std::true_type {};
 
 // Cooperative copy of `rows` rows of D bf16 (row r at src + rowoff(r)) into a row-major LDS tile,
 // zero-filling rows >= valid.
@@ -245,6 +265,20 @@ struct RowRegs {
   template <typename RowFn>
   __device__ inline void load(const u16* src, RowFn rowoff, int nvalid, int tid) {
     valid = nvalid;
+    static_assert(NTHR % CPR == 0, "a thread keeps its column chunk from load to load");
+    if constexpr (HasLinear<RowFn>::value) if (rowoff.linear()) {
+      // thread t fetches chunk t % CPR of rows t / CPR + i * (NTHR / CPR): one multiply, then a
+      // uniform increment per load; rows beyond the last valid one re-read it (clamped offset)
+      const u16* base = src + rowoff.first() + 8 * (tid % CPR);
+      const unsigned S = rowoff.step(), last = (unsigned)(nvalid - 1) * S, inc = (unsigned)(NTHR / CPR) * S;
+      unsigned off = (unsigned)(tid / CPR) * S;
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        v[i] = *(const uint4*)(base + (off < last ? off : last));
+        off += inc;
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       int idx = tid + i * NTHR;
