@@ -230,8 +230,9 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
 // flash loop shared by stage L (out), stage L (refine, pass 1) and the dense baseline
 // ---------------------------------------------------------------------------------------
 constexpr int kCK = 64;   // keys per LDS chunk (two 32-key steps)
-constexpr int kPadF = kPad;   // row padding of the chunk buffers and of the streamed refine kernel's Q tile
-                              // (8 measured 1 % slower at the KV-cache shapes)
+// Row padding of the chunk buffers (and of the streamed refine kernel's Q tile) is a template
+// parameter PAD of the pieces below: 16 elements as elsewhere (8 measured 1 % slower at the
+// KV-cache shapes), 8 where the smaller tiles let a second workgroup onto the compute unit.
 constexpr int kMinThreads = 256;   // the chunk copy below assumes at least this many threads
 
 template <int QT>
@@ -245,7 +246,7 @@ struct FlashState {
 
 // One 64-row chunk of D bf16 held in registers between its global load and its LDS commit, so
 // that the load of chunk c+1 is in flight while chunk c is being consumed.
-template <int D>
+template <int D, int PAD = kPad>
 struct ChunkRegs {
   static constexpr int CPR = D / 8, TOTAL = kCK * CPR, N = (TOTAL + kMinThreads - 1) / kMinThreads;
   uint4 v[N];
@@ -267,7 +268,7 @@ struct ChunkRegs {
     }
   }
   __device__ inline void commit(u16* dst, int tid, int nthr) const {
-    constexpr int LD = D + kPadF;
+    constexpr int LD = D + PAD;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int idx = tid + i * nthr;
@@ -282,12 +283,12 @@ struct ChunkRegs {
 // Every key-side LDS operand is read once and used for all QT query tiles.
 // bias[i] is added to the scaled logit of key i (-inf for keys beyond the end); when MASKED,
 // kchunk[i] > qchunk[q] hides key i from this lane's query of tile q.
-template <int D, int QT, bool WITH_V, bool MASKED>
+template <int D, int QT, bool WITH_V, bool MASKED, int PAD = kPad>
 __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bias,
                                    const int* kchunk, const int (&qchunk)[QT],
                                    const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
                                    FlashState<QT>& st, f32x4 (&o)[QT][D / 16], int lane) {
-  constexpr int LD = D + kPadF, KS1 = D / 32, NVT = D / 16, HALF = NVT / 2;
+  constexpr int LD = D + PAD, KS1 = D / 32, NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, c = lane & 15;
   f32x4 s[QT][4];
 #pragma unroll
@@ -395,9 +396,9 @@ __device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bi
 }
 
 // LDS layout of the double-buffered chunk pipeline
-template <int D, bool WITH_V>
+template <int D, bool WITH_V, int PAD = kPad>
 struct FlashLds {
-  static constexpr int LD = D + kPadF;
+  static constexpr int LD = D + PAD;
   static constexpr size_t kBytes = (size_t)2 * kCK * LD * 2 * (WITH_V ? 2 : 1) + 2 * kCK * 8;
   u16* k0;
   u16* v0;
@@ -423,9 +424,9 @@ struct FlashLds {
 // negative is the key's bias, and the chunk id of the key.
 // On return chunks (n-2, n-1) are still resident: with nkeys <= 2*kCK the whole key array and
 // its biases can be re-read from lds.K(0) / lds.bias(0) as 2*kCK contiguous rows.
-template <int D, bool WITH_V>
+template <int D, bool WITH_V, int PAD = kPad>
 struct ChunkFetch {
-  ChunkRegs<D> rk, rv;
+  ChunkRegs<D, PAD> rk, rv;
   float rb;    // raw per-key value fetched by meta(); turned into the bias at commit time
   int rc, rvalid;
   template <typename Meta>
@@ -439,7 +440,7 @@ struct ChunkFetch {
     if (tid < kCK) meta(c0 + (tid < valid ? tid : valid - 1), rb, rc);
   }
   template <bool MASKED>
-  __device__ inline void commit(FlashLds<D, WITH_V>& lds, int buf, int tid, int nthr) const {
+  __device__ inline void commit(FlashLds<D, WITH_V, PAD>& lds, int buf, int tid, int nthr) const {
     rk.commit(lds.K(buf), tid, nthr);
     if (WITH_V) rv.commit(lds.V(buf), tid, nthr);
     if (tid < kCK) {
@@ -449,15 +450,15 @@ struct ChunkFetch {
   }
 };
 
-template <int D, int QT, bool WITH_V, bool MASKED, typename Meta>
+template <int D, int QT, bool WITH_V, bool MASKED, int PAD = kPad, typename Meta>
 __device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
-                                  long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V>& lds,
+                                  long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V, PAD>& lds,
                                   const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
                                   const int (&qchunk)[QT], FlashState<QT>& st,
                                   f32x4 (&o)[QT][D / 16], int tid, int nthr, int lane) {
-  ChunkFetch<D, WITH_V> f;
+  ChunkFetch<D, WITH_V, PAD> f;
   {
-    ChunkFetch<D, WITH_V> f1;
+    ChunkFetch<D, WITH_V, PAD> f1;
     f.fetch(kbase, kstride, vbase, vstride, nkeys, 0, meta, tid, nthr);
     const bool two = kCK < nkeys;
     if (two) f1.fetch(kbase, kstride, vbase, vstride, nkeys, kCK, meta, tid, nthr);
@@ -470,7 +471,7 @@ __device__ inline void flash_loop(const u16* kbase, long long kstride, const u16
     const bool more = c0 + 2 * kCK < nkeys;
     if (more) f.fetch(kbase, kstride, vbase, vstride, nkeys, c0 + 2 * kCK, meta, tid, nthr);
     if (nq > 0)
-      flash_chunk<D, QT, WITH_V, MASKED>(lds.K(buf), lds.V(buf), lds.bias(buf), lds.kch(buf), qchunk,
+      flash_chunk<D, QT, WITH_V, MASKED, PAD>(lds.K(buf), lds.V(buf), lds.bias(buf), lds.kch(buf), qchunk,
                                          qv, nq, scale, st, o, lane);
     if (more) {
       __syncthreads();                     // every wave is done with this buffer
@@ -722,12 +723,12 @@ constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
 
 // NLT = number of 16-row l tiles (compile time, so that the tile loops unroll without guards and
 // the scheduler can overlap one tile's LDS reads with another's MFMAs).
-template <int D, int QT, int MAXT, int NLT, int PT>
+template <int D, int QT, int MAXT, int NLT, int PT, int PAD>
 __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
-  constexpr int LD = D + kPadF, KS1 = D / 32, NVT = D / 16;
+  constexpr int LD = D + PAD, KS1 = D / 32, NVT = D / 16;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  FlashLds<D, false> lds(smem);
-  u16* Qs = (u16*)(smem + FlashLds<D, false>::kBytes);   // [qrows][LD], rows >= b1 zero
+  FlashLds<D, false, PAD> lds(smem);
+  u16* Qs = (u16*)(smem + FlashLds<D, false, PAD>::kBytes);   // [qrows][LD], rows >= b1 zero
   float* lse = (float*)(Qs + (size_t)qrows * LD);        // [16 * kMaxLT]
 
   const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
@@ -768,7 +769,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
 #pragma unroll
     for (int q = 0; q < QT; ++q) qchunk[q] = 0;
     auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-    flash_loop<D, QT, false, false>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st,
+    flash_loop<D, QT, false, false, PAD>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st,
                                     odummy, tid, nthr, lane);
     MRT_STAMP(1);
 #pragma unroll
@@ -1477,17 +1478,21 @@ hipError_t launch_l_out_mid_d(const KParams& kp, dim3 grid, int nkt, hipStream_t
   return hipErrorInvalidValue;
 }
 
+// Streamed refine kernel: always four waves (one per SIMD, so that two workgroups fit a compute
+// unit however their waves are dealt to the SIMDs), each owning up to QT query tiles.  Beyond
+// eight query tiles (b1 > 128) the tiles take 8 elements of row padding instead of 16: the
+// workgroup's LDS then stays under half of the compute unit's 160 KB.
 template <int D, int NLT>
-hipError_t launch_l_refine(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
-  constexpr int QT = NLT <= 4 ? 1 : 2, MAXT = NLT <= 8 ? 256 : 384, PT = NLT <= 8 ? 2 : 1;
+hipError_t launch_l_refine(const KParams& kp, dim3 grid, hipStream_t s) {
+  constexpr int QT = (NLT + 3) / 4, MAXT = 256, PT = NLT <= 8 ? 2 : 1, PAD = NLT <= 8 ? kPad : 8;
   const int qrows = 32 * ((NLT + 1) / 2);
-  const size_t lds = FlashLds<D, false>::kBytes + (size_t)qrows * (D + kPadF) * 2 + 16 * kMaxLT * 4;
+  const size_t lds = FlashLds<D, false, PAD>::kBytes + (size_t)qrows * (D + PAD) * 2 + 16 * kMaxLT * 4;
   hipError_t e;
   if (lds > 64 * 1024 &&
-      (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT>,
+      (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT, PAD>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
     return e;
-  k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT><<<grid, nthr, lds, s>>>(kp, qrows);
+  k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT, PAD><<<grid, 256, lds, s>>>(kp, qrows);
   return hipGetLastError();
 }
 
@@ -1512,20 +1517,20 @@ hipError_t launch_l_out_res_d(const KParams& kp, dim3 grid, int nkt, hipStream_t
 }
 
 template <int D>
-hipError_t launch_l_refine_d(const KParams& kp, dim3 grid, int nthr, int nlt, hipStream_t s) {
+hipError_t launch_l_refine_d(const KParams& kp, dim3 grid, int nlt, hipStream_t s) {
   switch (nlt) {
-    case 1: return launch_l_refine<D, 1>(kp, grid, nthr, s);
-    case 2: return launch_l_refine<D, 2>(kp, grid, nthr, s);
-    case 3: return launch_l_refine<D, 3>(kp, grid, nthr, s);
-    case 4: return launch_l_refine<D, 4>(kp, grid, nthr, s);
-    case 5: return launch_l_refine<D, 5>(kp, grid, nthr, s);
-    case 6: return launch_l_refine<D, 6>(kp, grid, nthr, s);
-    case 7: return launch_l_refine<D, 7>(kp, grid, nthr, s);
-    case 8: return launch_l_refine<D, 8>(kp, grid, nthr, s);
-    case 9: return launch_l_refine<D, 9>(kp, grid, nthr, s);
-    case 10: return launch_l_refine<D, 10>(kp, grid, nthr, s);
-    case 11: return launch_l_refine<D, 11>(kp, grid, nthr, s);
-    case 12: return launch_l_refine<D, 12>(kp, grid, nthr, s);
+    case 1: return launch_l_refine<D, 1>(kp, grid, s);
+    case 2: return launch_l_refine<D, 2>(kp, grid, s);
+    case 3: return launch_l_refine<D, 3>(kp, grid, s);
+    case 4: return launch_l_refine<D, 4>(kp, grid, s);
+    case 5: return launch_l_refine<D, 5>(kp, grid, s);
+    case 6: return launch_l_refine<D, 6>(kp, grid, s);
+    case 7: return launch_l_refine<D, 7>(kp, grid, s);
+    case 8: return launch_l_refine<D, 8>(kp, grid, s);
+    case 9: return launch_l_refine<D, 9>(kp, grid, s);
+    case 10: return launch_l_refine<D, 10>(kp, grid, s);
+    case 11: return launch_l_refine<D, 11>(kp, grid, s);
+    case 12: return launch_l_refine<D, 12>(kp, grid, s);
   }
   return hipErrorInvalidValue;
 }
@@ -1622,8 +1627,8 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   // query tiles, so that two workgroups fit a compute unit whatever order their waves are dealt
   // to the SIMDs in; only b1 > 128 needs a fifth and sixth wave.
   const int nthr = nlt <= 8 ? 256 : 64 * ((nlt + 1) / 2);
-  if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nthr, nlt, s)
-                                : launch_l_refine_d<64>(kp, grid, nthr, nlt, s);
+  if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nlt, s)
+                                : launch_l_refine_d<64>(kp, grid, nlt, s);
   if (nlt <= 4) return kp.d == 128 ? launch_l_out<128, 1, 256>(kp, grid, nthr, s)
                                    : launch_l_out<64, 1, 256>(kp, grid, nthr, s);
   if (nlt <= 8) return kp.d == 128 ? launch_l_out<128, 2, 256>(kp, grid, nthr, s)
