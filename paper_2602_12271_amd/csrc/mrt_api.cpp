@@ -288,6 +288,10 @@ struct StreamPool {
 };
 // One pool per device, created on first use and kept for the life of the process.  Streams are
 // created with the default priority.
+// The fork / join events order streams of one device only: no timing, and no system-scope fence
+// (cache write-back to the host's view) when they are recorded; the kernels' own device-scope
+// release at their end is what the other stream's kernels need.
+constexpr unsigned kForkJoinFlags = hipEventDisableTiming | hipEventDisableSystemFence;
 static StreamPool* get_pool() {
   static std::mutex mu;
   static StreamPool* pools[64] = {nullptr};
@@ -297,10 +301,10 @@ static StreamPool* get_pool() {
   std::lock_guard<std::mutex> lk(mu);
   if (pools[dev] || failed[dev]) return pools[dev];
   StreamPool* p = new StreamPool();
-  bool ok = hipEventCreateWithFlags(&p->fork, hipEventDisableTiming) == hipSuccess;
+  bool ok = hipEventCreateWithFlags(&p->fork, kForkJoinFlags) == hipSuccess;
   for (int i = 0; ok && i < kMaxGroups - 1; ++i)
     ok = hipStreamCreateWithFlags(&p->side[i], hipStreamNonBlocking) == hipSuccess &&
-         hipEventCreateWithFlags(&p->join[i], hipEventDisableTiming) == hipSuccess;
+         hipEventCreateWithFlags(&p->join[i], kForkJoinFlags) == hipSuccess;
   if (!ok) { failed[dev] = true; delete p; return nullptr; }   // fall back to one stream
   pools[dev] = p;
   return p;
