@@ -229,257 +229,351 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
 // ---------------------------------------------------------------------------------------
 // flash loop shared by stage L (out), stage L (refine, pass 1) and the dense baseline
 // ---------------------------------------------------------------------------------------
-constexpr int kCK = 64;   // keys per LDS chunk (two 32-key steps)
+constexpr int kHK = 32;    // keys per pipeline step (one register set, one LDS slot)
+constexpr int kRing = 4;   // LDS slots
 // Row padding of the chunk buffers (and of the streamed refine kernel's Q tile) is a template
 // parameter PAD of the pieces below: 16 elements as elsewhere (8 measured 1 % slower at the
 // KV-cache shapes), 8 where the smaller tiles let a second workgroup onto the compute unit.
-constexpr int kMinThreads = 256;   // the chunk copy below assumes at least this many threads
 
+// Online softmax state of a wave's query tiles.  mrun is the reference the exponentials are taken
+// against (the same in the four lanes that share a query): not the running maximum itself but a
+// value within kGrow (base-2) of it, raised only when a chunk brings a logit more than kGrow above
+// it.  Every probability is then at most 2^kGrow, the ratio sum(p v) / sum(p) does not depend on the
+// reference, and the common case of a chunk is free of cross-lane reductions and of rescaling.
+constexpr float kGrow = 8.0f;
 template <int QT>
 struct FlashState {
-  float mrun[QT], lrun[QT];   // running max (reduced over the column), this lane's partial sum
+  float mrun[QT], lrun[QT];   // reference (see above), this lane's partial sum of 2^(z - mrun)
   __device__ inline FlashState() {
 #pragma unroll
     for (int q = 0; q < QT; ++q) { mrun[q] = -INFINITY; lrun[q] = 0.f; }
   }
 };
 
-// One 64-row chunk of D bf16 held in registers between its global load and its LDS commit, so
-// that the load of chunk c+1 is in flight while chunk c is being consumed.
-template <int D, int PAD = kPad>
+// One 32-row chunk of D bf16 held in registers between its global load and its LDS commit, so
+// that its load is in flight while earlier chunks are being consumed.  NT = threads of the
+// workgroup; the loads are unconditional: rows beyond the last valid one are copies of it (the
+// consumer hides them through their bias), and when the pieces do not divide evenly over the
+// threads the surplus loads of the last round re-read the last row and are not committed.
+template <int D, int NT, int PAD = kPad>
 struct ChunkRegs {
-  static constexpr int CPR = D / 8, TOTAL = kCK * CPR, N = (TOTAL + kMinThreads - 1) / kMinThreads;
-  uint4 v[N];
-  int valid;
-  // Loads are unconditional (rows beyond `nvalid` re-read the last valid row) so that nothing
-  // has to wait for them before the commit; the commit zero-fills the rows that do not exist.
-  __device__ inline void load(const u16* src, long long stride, int nvalid, int tid, int nthr) {
-    valid = nvalid;
-    // thread t fetches chunk t % CPR of rows t / CPR + i * (nthr / CPR) (nthr is a multiple of 64):
-    // a 32-bit offset from the uniform chunk base, one multiply and then a uniform increment per
-    // load; rows beyond the last valid one re-read it
+  static constexpr int CPR = D / 8, TOTAL = kHK * CPR, N = (TOTAL + NT - 1) / NT;
+  static constexpr bool RAGGED = TOTAL % NT != 0;
+  s16x8 v[N];
+  // nvalid >= 1 rows exist at src
+  __device__ inline void load(const u16* src, long long stride, int nvalid, int tid) {
+    // thread t fetches piece t % CPR of rows t / CPR + i * (NT / CPR): a 32-bit offset from the
+    // uniform chunk base, one multiply and then a uniform increment per load
     const u16* base = src + 8 * (tid % CPR);
-    const unsigned S = (unsigned)stride, last = (unsigned)(nvalid - 1) * S, inc = (unsigned)(nthr / CPR) * S;
+    const unsigned S = (unsigned)stride, last = (unsigned)(nvalid - 1) * S, inc = (unsigned)(NT / CPR) * S;
     unsigned off = (unsigned)(tid / CPR) * S;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      v[i] = *(const uint4*)(base + (off < last ? off : last));
+      v[i] = *(const s16x8*)(base + (off < last ? off : last));
       off += inc;
     }
   }
-  __device__ inline void commit(u16* dst, int tid, int nthr) const {
+  __device__ inline void commit(u16* dst, int tid) const {
     constexpr int LD = D + PAD;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      const int idx = tid + i * nthr;
+      const int idx = tid + i * NT;
       const int r = idx / CPR, c = idx - r * CPR;
-      if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
+      if (!RAGGED || i + 1 < N || idx < TOTAL) *(s16x8*)(dst + r * LD + 8 * c) = v[i];
     }
   }
 };
 
-// One 64-key chunk against the wave's QT query tiles (16 queries each; tiles q >= nq are idle):
-// logits, online softmax update and, when WITH_V, rescale + accumulate of the output tiles.
-// Every key-side LDS operand is read once and used for all QT query tiles.
-// bias[i] is added to the scaled logit of key i (-inf for keys beyond the end); when MASKED,
-// kchunk[i] > qchunk[q] hides key i from this lane's query of tile q.
-template <int D, int QT, bool WITH_V, bool MASKED, int PAD = kPad>
-__device__ inline void flash_chunk(const u16* Kc, const u16* Vc, const float* bias,
-                                   const int* kchunk, const int (&qchunk)[QT],
-                                   const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
-                                   FlashState<QT>& st, f32x4 (&o)[QT][D / 16], int lane) {
-  constexpr int LD = D + PAD, KS1 = D / 32, NVT = D / 16, HALF = NVT / 2;
+// One 32-key chunk against the wave's QT query tiles (16 queries each), in three stages that the
+// streaming loop interleaves across chunks: the logits (MFMA), the online softmax update
+// (vector ALU) and, when WITH_V, the rescale + accumulate of the output tiles (MFMA).  NQ, the
+// number of tiles the wave owns (the first NQ of its QT), is a compile-time value: a chunk is
+// then straight code in which the scheduler can overlap one stage's MFMAs with another's
+// softmax arithmetic.
+// Every key-side LDS operand is read once and used for all NQ query tiles.
+
+// raw logits: s[q][t] = K tile t (16 keys) x Q tile q, summed over D
+template <int D, int QT, int NQ, int PAD>
+__device__ inline void flash_qk(const u16* Kc, const bf16x8 (&qv)[QT][D / 32], f32x4 (&s)[QT][2], int lane) {
+  constexpr int LD = D + PAD, KS1 = D / 32;
   const int g = lane >> 4, c = lane & 15;
-  f32x4 s[QT][4];
+  // both key tiles' operand reads are issued before the first MFMA, and consecutive MFMAs
+  // alternate between independent accumulators
+  bf16x8 a[2][KS1];
 #pragma unroll
-  for (int q = 0; q < QT; ++q)
+  for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int it = 0; it < 4; ++it) s[q][it] = f32x4{0.f, 0.f, 0.f, 0.f};
-  // two key tiles at a time: their operand reads are issued before the first MFMA, and
-  // consecutive MFMAs alternate between independent accumulators
+    for (int ks = 0; ks < KS1; ++ks)
+      a[t][ks] = ld_lds_16B(Kc + (16 * t + c) * LD + 32 * ks + 8 * g);
 #pragma unroll
-  for (int ip = 0; ip < 2; ++ip) {
-    bf16x8 a[2][KS1];
+  for (int q = 0; q < NQ; ++q)
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t) s[q][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < KS1; ++ks)
-        a[t][ks] = ld_lds_16B(Kc + (16 * (2 * ip + t) + c) * LD + 32 * ks + 8 * g);
+  for (int q = 0; q < NQ; ++q)
 #pragma unroll
-    for (int q = 0; q < QT; ++q) {
-      if (q < nq) {
+    for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks)
+      for (int t = 0; t < 2; ++t) s[q][t] = mfma(a[t][ks], qv[q][ks], s[q][t]);
+}
+
+// base-2 logits of the chunk in place of the raw products: z = scale * s + bias.  bias[i] is
+// added to the scaled logit of key i (-inf for keys beyond the end); when MASKED,
+// kchunk[i] > qchunk[q] hides key i from this lane's query of tile q.  Returns whether one of this
+// lane's logits lies more than kGrow above its query's reference.
+template <int QT, int NQ, bool MASKED>
+__device__ inline bool flash_logits(f32x4 (&s)[QT][2], const float* bias, const int* kchunk,
+                                    const int (&qchunk)[QT], float scale, const FlashState<QT>& st, int lane) {
+  const int g = lane >> 4;
+  f32x4 bi[2];
+  int4 kc[2];
 #pragma unroll
-          for (int t = 0; t < 2; ++t) s[q][2 * ip + t] = mfma(a[t][ks], qv[q][ks], s[q][2 * ip + t]);
-      }
-    }
-  }
-  f32x4 bi[4];
-  int4 kc[4];
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  for (int it = 0; it < 2; ++it) {
     bi[it] = *(const f32x4*)(bias + 16 * it + 4 * g);
     if (MASKED) kc[it] = *(const int4*)(kchunk + 16 * it + 4 * g);
   }
-  bf16x8 pb[QT][2];
+  bool grow = false;
 #pragma unroll
-  for (int q = 0; q < QT; ++q) {
-    if (q < nq) {
-      float cm = -INFINITY;
+  for (int q = 0; q < NQ; ++q) {
+    float zm = -INFINITY;
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int kcs[4] = {MASKED ? kc[it].x : 0, MASKED ? kc[it].y : 0, MASKED ? kc[it].z : 0,
-                            MASKED ? kc[it].w : 0};
+    for (int it = 0; it < 2; ++it) {
+      const int kcs[4] = {MASKED ? kc[it].x : 0, MASKED ? kc[it].y : 0, MASKED ? kc[it].z : 0,
+                          MASKED ? kc[it].w : 0};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float z = fmaf(s[q][it][r], scale, bi[it][r]);
-          if (MASKED && kcs[r] > qchunk[q]) z = -INFINITY;
-          s[q][it][r] = z;
-          cm = fmaxf(cm, z);
-        }
-      }
-      cm = xmax(cm);
-      const float mnew = fmaxf(st.mrun[q], cm);
-      // mnew == -inf only if every key so far is hidden from this query: keep the state empty
-      const float msafe = (MASKED && mnew == -INFINITY) ? 0.f : mnew;
-      const float alpha = exp2_fast(st.mrun[q] - msafe);   // mrun = -inf -> 0
-      float ps = 0.f;
-#pragma unroll
-      for (int it = 0; it < 4; ++it)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float e = exp2_fast(s[q][it][r] - msafe);
-          s[q][it][r] = e;
-          ps += e;
-        }
-      st.lrun[q] = fmaf(st.lrun[q], alpha, ps);
-      st.mrun[q] = mnew;
-      if (WITH_V) {
-        pb[q][0] = pack8(s[q][0], s[q][1]);
-        pb[q][1] = pack8(s[q][2], s[q][3]);
-        // once the running maxima have settled (after the first few chunks) alpha is 1 in every
-        // lane and the rescaling of the accumulators can be skipped for the whole wave
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-          for (int vt = 0; vt < NVT; ++vt) o[q][vt] = o[q][vt] * alpha;
-        }
+      for (int r = 0; r < 4; ++r) {
+        float z = fmaf(s[q][it][r], scale, bi[it][r]);
+        if (MASKED && kcs[r] > qchunk[q]) z = -INFINITY;
+        s[q][it][r] = z;
+        zm = fmaxf(zm, z);
       }
     }
+    grow |= zm > st.mrun[q] + kGrow;    // also the first finite logit after mrun = -inf
   }
-  if (WITH_V) {
-    const int sl = lane & 15, e = sl >> 2, qq = sl & 3;
+  return grow;
+}
+
+// The rare step: raise every query's reference to its running maximum (the old reference or the
+// chunk's largest logit) and rescale its sum and, when WITH_V, its accumulators.
+template <int D, int QT, int NQ, bool WITH_V>
+__device__ inline void flash_grow(const f32x4 (&s)[QT][2], FlashState<QT>& st, f32x4 (&o)[QT][D / 16]) {
 #pragma unroll
-    for (int step = 0; step < 2; ++step) {
-      const u16* base = Vc + (32 * step + 4 * g + e) * LD + 8 * qq;
+  for (int q = 0; q < NQ; ++q) {
+    float zm = -INFINITY;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        s16x4 lo[HALF], hi[HALF];
+    for (int it = 0; it < 2; ++it)
 #pragma unroll
-        for (int i = 0; i < HALF; ++i) {
-          const int vt = h * HALF + i;
-          const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
-          lo[i] = ld_lds_tr(p0);
-          hi[i] = ld_lds_tr(p0 + 16 * LD);
-        }
+      for (int r = 0; r < 4; ++r) zm = fmaxf(zm, s[q][it][r]);
+    const float mnew = fmaxf(st.mrun[q], xmax(zm));
+    // mnew == -inf only if every key so far is hidden from this query: the state stays empty
+    const float alpha = mnew == -INFINITY ? 1.0f : exp2_fast(st.mrun[q] - mnew);   // mrun = -inf -> 0
+    st.lrun[q] *= alpha;
+    st.mrun[q] = mnew;
+    if (WITH_V) {
 #pragma unroll
-        for (int i = 0; i < HALF; ++i) {
-          const bf16x8 av =
-              __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7));
-#pragma unroll
-          for (int q = 0; q < QT; ++q)
-            if (q < nq) o[q][h * HALF + i] = mfma(av, pb[q][step], o[q][h * HALF + i]);
-        }
-      }
+      for (int vt = 0; vt < D / 16; ++vt) o[q][vt] = o[q][vt] * alpha;
     }
   }
 }
 
-// LDS layout of the double-buffered chunk pipeline
+// probabilities 2^(z - mrun) of the chunk: added to the running sums and, when WITH_V, packed
+// to bf16 for the second product
+template <int QT, int NQ, bool WITH_V, bool MASKED>
+__device__ inline void flash_exp(f32x4 (&s)[QT][2], FlashState<QT>& st, bf16x8 (&pb)[QT]) {
+#pragma unroll
+  for (int q = 0; q < NQ; ++q) {
+    // a reference of -inf (possible only when MASKED: every key so far hidden) gives 2^(-inf - 0) = 0
+    const float m = (MASKED && st.mrun[q] == -INFINITY) ? 0.f : st.mrun[q];
+    float ps = 0.f;
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float e = exp2_fast(s[q][it][r] - m);
+        s[q][it][r] = e;
+        ps += e;
+      }
+    st.lrun[q] += ps;
+    if (WITH_V) pb[q] = pack8(s[q][0], s[q][1]);
+  }
+}
+
+// o[q] += P[q] V
+template <int D, int QT, int NQ, int PAD>
+__device__ inline void flash_pv(const u16* Vc, const bf16x8 (&pb)[QT], f32x4 (&o)[QT][D / 16], int lane) {
+  constexpr int LD = D + PAD, NVT = D / 16, HALF = NVT / 2;
+  const int g = lane >> 4;
+  const int sl = lane & 15, e = sl >> 2, qq = sl & 3;
+  const u16* base = Vc + (4 * g + e) * LD + 8 * qq;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    s16x4 lo[HALF], hi[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const int vt = h * HALF + i;
+      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+      lo[i] = ld_lds_tr(p0);
+      hi[i] = ld_lds_tr(p0 + 16 * LD);
+    }
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const bf16x8 av =
+          __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo[i], hi[i], 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) o[q][h * HALF + i] = mfma(av, pb[q], o[q][h * HALF + i]);
+    }
+  }
+}
+
+// LDS layout of the chunk pipeline: a ring of kRing slots of kHK rows each (contiguous, so that
+// the ring is also one array of kRing * kHK rows)
 template <int D, bool WITH_V, int PAD = kPad>
 struct FlashLds {
-  static constexpr int LD = D + PAD;
-  static constexpr size_t kBytes = (size_t)2 * kCK * LD * 2 * (WITH_V ? 2 : 1) + 2 * kCK * 8;
+  static constexpr int LD = D + PAD, ROWS = kRing * kHK;
+  static constexpr size_t kBytes = (size_t)ROWS * LD * 2 * (WITH_V ? 2 : 1) + ROWS * 8;
   u16* k0;
   u16* v0;
   float* b0;
   int* c0;
   __device__ inline explicit FlashLds(unsigned char* base) {
     u16* p = (u16*)base;
-    k0 = p; p += 2 * kCK * LD;
-    v0 = p; if (WITH_V) p += 2 * kCK * LD;
+    k0 = p; p += ROWS * LD;
+    v0 = p; if (WITH_V) p += ROWS * LD;
     b0 = (float*)p;
-    c0 = (int*)(b0 + 2 * kCK);
+    c0 = (int*)(b0 + ROWS);
   }
-  __device__ inline u16* K(int buf) const { return k0 + buf * (kCK * LD); }
-  __device__ inline u16* V(int buf) const { return v0 + buf * (kCK * LD); }
-  __device__ inline float* bias(int buf) const { return b0 + buf * kCK; }
-  __device__ inline int* kch(int buf) const { return c0 + buf * kCK; }
+  __device__ inline u16* K(int slot) const { return k0 + slot * (kHK * LD); }
+  __device__ inline u16* V(int slot) const { return v0 + slot * (kHK * LD); }
+  __device__ inline float* bias(int slot) const { return b0 + slot * kHK; }
+  __device__ inline int* kch(int slot) const { return c0 + slot * kHK; }
 };
 
-// The streaming loop: keys [0, nkeys) of a row-major key array (and value array), 64 at a time,
-// over two LDS buffers with one barrier per chunk.  Both buffers are filled before the first
-// barrier (their loads are in flight together), and while chunk c is consumed the loads of
-// chunk c+2 are in flight and chunk c+1 already sits in LDS.  meta(key) fetches the value whose
-// negative is the key's bias, and the chunk id of the key.
-// On return chunks (n-2, n-1) are still resident: with nkeys <= 2*kCK the whole key array and
-// its biases can be re-read from lds.K(0) / lds.bias(0) as 2*kCK contiguous rows.
-template <int D, bool WITH_V, int PAD = kPad>
+// One register set of the pipeline: a chunk of keys (and values) between its global load and its
+// LDS commit.  meta(key) fetches the value whose negative is the key's bias, and the chunk id of
+// the key.  Nothing here is conditional (a chunk beyond the end of the keys is fetched as copies
+// of key 0 and committed with a bias of -inf): the pipeline below then runs as straight code in
+// which the compiler's wait counts for one register set leave the other set's loads in flight.
+template <int D, bool WITH_V, int NT, int PAD = kPad>
 struct ChunkFetch {
-  ChunkRegs<D, PAD> rk, rv;
+  ChunkRegs<D, NT, PAD> rk, rv;
   float rb;    // raw per-key value fetched by meta(); turned into the bias at commit time
   int rc, rvalid;
   template <typename Meta>
   __device__ inline void fetch(const u16* kbase, long long kstride, const u16* vbase,
-                               long long vstride, int nkeys, int c0, Meta& meta, int tid, int nthr) {
-    const int valid = nkeys - c0 < kCK ? nkeys - c0 : kCK;
-    rk.load(kbase + (long long)c0 * kstride, kstride, valid, tid, nthr);
-    if (WITH_V) rv.load(vbase + (long long)c0 * vstride, vstride, valid, tid, nthr);
+                               long long vstride, int nkeys, int c0, Meta& meta, int tid) {
+    const int left = nkeys - c0;                       // <= 0 beyond the end
+    const int valid = left < kHK ? left : kHK;
+    const int first = left > 0 ? c0 : 0, rows = valid > 0 ? valid : 1;
+    rk.load(kbase + (long long)first * kstride, kstride, rows, tid);
+    if (WITH_V) rv.load(vbase + (long long)first * vstride, vstride, rows, tid);
     rvalid = valid;
-    rb = 0.f; rc = 0;
-    if (tid < kCK) meta(c0 + (tid < valid ? tid : valid - 1), rb, rc);
+    const int k = tid & (kHK - 1);
+    meta(first + (k < rows ? k : rows - 1), rb, rc);
   }
   template <bool MASKED>
-  __device__ inline void commit(FlashLds<D, WITH_V, PAD>& lds, int buf, int tid, int nthr) const {
-    rk.commit(lds.K(buf), tid, nthr);
-    if (WITH_V) rv.commit(lds.V(buf), tid, nthr);
-    if (tid < kCK) {
-      lds.bias(buf)[tid] = tid < rvalid ? -rb * kLog2e : -INFINITY;
-      if (MASKED) lds.kch(buf)[tid] = rc;
-    }
+  __device__ inline void commit(FlashLds<D, WITH_V, PAD>& lds, int slot, int tid) const {
+    rk.commit(lds.K(slot), tid);
+    if (WITH_V) rv.commit(lds.V(slot), tid);
+    // every thread writes key (tid mod kHK)'s entry: the copies agree
+    const int k = tid & (kHK - 1);
+    lds.bias(slot)[k] = k < rvalid ? -rb * kLog2e : -INFINITY;
+    if (MASKED) lds.kch(slot)[k] = rc;
   }
 };
 
-template <int D, int QT, bool WITH_V, bool MASKED, int PAD = kPad, typename Meta>
+// The streaming loop: keys [0, nkeys) of a row-major key array (and value array), kHK at a time,
+// through two register sets and a ring of four LDS slots, one barrier per pair of chunks.  While
+// chunks c and c+1 are consumed, chunks c+2 and c+3 sit in (or are being written to) the other
+// two slots and the loads of chunks c+4 and c+5 are in flight: each register set is committed
+// one pair after its loads were issued and reloaded at once, so that a workgroup always has
+// loads outstanding.  The slot a commit overwrites was last read in the previous pair, before
+// that pair's barrier; the chunk it writes is first read after this pair's barrier.
+// The loop body is one run of straight code (chunks are consumed in pairs, an odd last chunk is
+// followed by an empty one) for a wave that owns NQ query tiles.
+template <int D, int QT, int NQ, bool WITH_V, bool MASKED, int NT, int PAD, typename Meta>
+__device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u16* vbase,
+                                    long long vstride, int nkeys, Meta& meta, FlashLds<D, WITH_V, PAD>& lds,
+                                    const bf16x8 (&qv)[QT][D / 32], float scale,
+                                    const int (&qchunk)[QT], FlashState<QT>& st,
+                                    f32x4 (&o)[QT][D / 16], int tid, int lane) {
+  const int npairs = (nkeys + 2 * kHK - 1) / (2 * kHK);
+  using Fetch = ChunkFetch<D, WITH_V, NT, PAD>;
+  Fetch fa, fb;
+  auto fetch = [&](Fetch& f, int chunk) {
+    f.fetch(kbase, kstride, vbase, vstride, nkeys, chunk * kHK, meta, tid);
+  };
+  fetch(fa, 0);
+  fetch(fb, 1);
+  fa.template commit<MASKED>(lds, 0, tid);
+  fetch(fa, 2);
+  fb.template commit<MASKED>(lds, 1, tid);
+  fetch(fb, 3);
+  __syncthreads();
+  for (int pr = 0; pr < npairs; ++pr) {
+    const int s0 = 2 * (pr & 1), s1 = s0 ^ 2;    // slots of this pair's chunks / of the next pair's
+    // Stages of the two chunks, interleaved so that the matrix unit works under the vector ALU:
+    // the second chunk's first product runs under the first chunk's exponentials, the first
+    // chunk's second product under the second chunk's logits (the scheduler is told to issue
+    // each MFMA between a few vector instructions).  Only the rare raise of a reference branches.
+    constexpr int kStageMfma = NQ * (D / 16);   // MFMAs of one stage
+    f32x4 sa[QT][2], sb[QT][2];
+    bf16x8 pa[QT], pbb[QT];
+    if (NQ > 0) {
+      flash_qk<D, QT, NQ, PAD>(lds.K(s0), qv, sa, lane);
+      const bool ga = flash_logits<QT, NQ, MASKED>(sa, lds.bias(s0), lds.kch(s0), qchunk, scale, st, lane);
+      if (__builtin_amdgcn_ballot_w64(ga) != 0) flash_grow<D, QT, NQ, WITH_V>(sa, st, o);
+      flash_qk<D, QT, NQ, PAD>(lds.K(s0 + 1), qv, sb, lane);
+      flash_exp<QT, NQ, WITH_V, MASKED>(sa, st, pa);
+#ifndef MRT_NO_SGB
+#pragma unroll
+      for (int i = 0; i < kStageMfma; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+      }
+#endif
+      if (WITH_V) flash_pv<D, QT, NQ, PAD>(lds.V(s0), pa, o, lane);
+      const bool gb = flash_logits<QT, NQ, MASKED>(sb, lds.bias(s0 + 1), lds.kch(s0 + 1), qchunk, scale, st, lane);
+#ifndef MRT_NO_SGB
+      if (WITH_V) {
+#pragma unroll
+        for (int i = 0; i < kStageMfma; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+        }
+      }
+#endif
+      if (__builtin_amdgcn_ballot_w64(gb) != 0) flash_grow<D, QT, NQ, WITH_V>(sb, st, o);
+    }
+    fa.template commit<MASKED>(lds, s1, tid);
+    fetch(fa, 2 * pr + 4);
+    if (NQ > 0) {
+      flash_exp<QT, NQ, WITH_V, MASKED>(sb, st, pbb);
+      if (WITH_V) flash_pv<D, QT, NQ, PAD>(lds.V(s0 + 1), pbb, o, lane);
+    }
+    fb.template commit<MASKED>(lds, s1 + 1, tid);
+    fetch(fb, 2 * pr + 5);
+    __syncthreads();
+  }
+}
+
+// nq = query tiles the wave owns (uniform over the wave): QT, QT - 1 or none; every path runs
+// the same fetches, commits and barriers.
+template <int D, int QT, bool WITH_V, bool MASKED, int NT, int PAD = kPad, typename Meta>
 __device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
                                   long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V, PAD>& lds,
                                   const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
                                   const int (&qchunk)[QT], FlashState<QT>& st,
-                                  f32x4 (&o)[QT][D / 16], int tid, int nthr, int lane) {
-  ChunkFetch<D, WITH_V, PAD> f;
-  {
-    ChunkFetch<D, WITH_V, PAD> f1;
-    f.fetch(kbase, kstride, vbase, vstride, nkeys, 0, meta, tid, nthr);
-    const bool two = kCK < nkeys;
-    if (two) f1.fetch(kbase, kstride, vbase, vstride, nkeys, kCK, meta, tid, nthr);
-    f.template commit<MASKED>(lds, 0, tid, nthr);
-    if (two) f1.template commit<MASKED>(lds, 1, tid, nthr);
-  }
-  __syncthreads();
-  int buf = 0;
-  for (int c0 = 0; c0 < nkeys; c0 += kCK, buf ^= 1) {
-    const bool more = c0 + 2 * kCK < nkeys;
-    if (more) f.fetch(kbase, kstride, vbase, vstride, nkeys, c0 + 2 * kCK, meta, tid, nthr);
-    if (nq > 0)
-      flash_chunk<D, QT, WITH_V, MASKED, PAD>(lds.K(buf), lds.V(buf), lds.bias(buf), lds.kch(buf), qchunk,
-                                         qv, nq, scale, st, o, lane);
-    if (more) {
-      __syncthreads();                     // every wave is done with this buffer
-      f.template commit<MASKED>(lds, buf, tid, nthr);
-    } else if (c0 + kCK < nkeys) {
-      __syncthreads();                     // the next chunk was committed by other waves
-    }
-  }
+                                  f32x4 (&o)[QT][D / 16], int tid, int lane) {
+  if (nq == QT)
+    flash_loop_n<D, QT, QT, WITH_V, MASKED, NT, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
+                                                     qchunk, st, o, tid, lane);
+  else if (QT > 1 && nq == QT - 1)
+    flash_loop_n<D, QT, (QT > 1 ? QT - 1 : 0), WITH_V, MASKED, NT, PAD>(kbase, kstride, vbase, vstride, nkeys, meta,
+                                                                       lds, qv, scale, qchunk, st, o, tid, lane);
+  else
+    flash_loop_n<D, QT, 0, WITH_V, MASKED, NT, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
+                                                    qchunk, st, o, tid, lane);
 }
 
 // Query tiles of a wave: tile q of wave w is l tile (q * nwaves + w); nq of them exist.
@@ -497,15 +591,31 @@ struct WaveTiles {
   }
 };
 
+// Which of two orientations a workgroup deals its query tiles to its waves in.  Waves are dealt to
+// the four SIMDs in the same order for every workgroup, so when the tiles do not divide evenly
+// over the waves (6 tiles on 4 waves: 2, 2, 1, 1) two workgroups that share a compute unit would
+// both put their fuller waves on the same SIMDs.  The wave slot the hardware gave wave 0 on its
+// SIMD (the low bits of the HW_ID register) differs between the workgroups resident on a compute
+// unit at any one time: its parity flips the order for one of them (wave w takes the tiles of wave
+// nwaves - 1 - w), which evens out the load of the SIMDs.  Only speed depends on it.
+__device__ inline int tile_order_flip(int* slot, int tid) {
+  if (tid == 0) *slot = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (3 << 11)) & 1;   // HW_ID, WAVE_ID bits
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane(*slot);
+}
+
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
 // RMASK: regular Monarch under the chunk-causal mask (key rows of later chunks hidden per query row)
-template <int D, int QT, int MAXT, bool RMASK>
-__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
+template <int D, int QT, int NT, bool RMASK>
+__global__ __launch_bounds__(NT, 2) void k_bf16_stage_l_out(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
+  __shared__ int flip_slot;
   FlashLds<D, true> lds(smem);
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int hwave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave = tile_order_flip(&flip_slot, tid) ? NT / 64 - 1 - hwave : hwave;   // tile owner index
   const int g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
@@ -513,7 +623,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
   const int b = bh / p.H, hd = bh - b * p.H;
-  const WaveTiles<QT> wt(wave, nthr >> 6, (b1 + 15) >> 4);
+  const WaveTiles<QT> wt(wave, NT / 64, (b1 + 15) >> 4);
 
   const long long qtok0 = axis_offset(p.cmap, bq * b2 + j);   // column j of the tile; rows via qrow / orow
   const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
@@ -546,8 +656,8 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   }
   MRT_STAMP(0);
   auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = RMASK ? key / p.rl : 0; };
-  flash_loop<D, QT, true, RMASK>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st, o, tid,
-                                 nthr, lane);
+  flash_loop<D, QT, true, RMASK, NT>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st, o,
+                                     tid, lane);
   MRT_STAMP(1);
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
 #pragma unroll
@@ -559,100 +669,24 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_out(KParams p) {
   MRT_STAMP(2);
 }
 
-// Second half of a stage L refinement for PT key tiles (tile0 ...) of one (m, j) column, given
-// z = log2 L[l, nk] for every query tile: weights of the l-average, alpha_R / c_R = sum_l w Q,
-// stored as the next iteration's abar rows.
-template <int D, int NLT, int PT, int LD>
-__device__ inline void refine_finish(const KParams& p, const u16* Qs, f32x4 (&z)[PT][NLT], int npt, int tile0,
-                                     u16* aRout, int NK, int j, int lane, bool stamp) {
-  constexpr int NVT = D / 16;
-  const int g = lane >> 4, c = lane & 15;
-  const int b2 = p.b2;
-  if (stamp) MRT_STAMP(3);
-  // weights of the l-average: L[l, nk] itself; only if a whole column underflows in fp32 is the
-  // column maximum taken out first (the ratio alpha_R / c_R is unchanged by it)
-  float csum[PT], shift[PT];
-  bf16x8 pb[(NLT + 1) / 2][PT];
-  auto weigh = [&]() {
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt) {
-      csum[pt] = 0.f;
-#pragma unroll
-      for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
-        f32x4 lo, hi = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          lo[r] = exp2_fast(z[pt][2 * st2][r] - shift[pt]);
-          csum[pt] += lo[r];
-          if (2 * st2 + 1 < NLT) {
-            hi[r] = exp2_fast(z[pt][2 * st2 + 1 < NLT ? 2 * st2 + 1 : 0][r] - shift[pt]);
-            csum[pt] += hi[r];
-          }
-        }
-        pb[st2][pt] = pack8(lo, hi);
-      }
-      csum[pt] = xsum(csum[pt]);
-    }
-  };
-#pragma unroll
-  for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
-  weigh();
-  bool under = false;
-#pragma unroll
-  for (int pt = 0; pt < PT; ++pt) under |= (pt < npt && csum[pt] == 0.f);
-  if (__any(under)) {
-#pragma unroll
-    for (int pt = 0; pt < PT; ++pt) {
-      float cm = -INFINITY;
-#pragma unroll
-      for (int lt = 0; lt < NLT; ++lt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) cm = fmaxf(cm, z[pt][lt][r]);
-      shift[pt] = xmax(cm);
-    }
-    weigh();
-  }
-  if (stamp) MRT_STAMP(4);
-  f32x4 o[PT][NVT];
-#pragma unroll
-  for (int pt = 0; pt < PT; ++pt)
-#pragma unroll
-    for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int st2 = 0; st2 < (NLT + 1) / 2; ++st2) {
-    pv_step_multi<D, PT, LD>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  if (stamp) MRT_STAMP(5);
-#pragma unroll
-  for (int pt = 0; pt < PT; ++pt) {
-    const int nk = 16 * (tile0 + pt) + c;
-    if (pt < npt && nk < NK) {
-      store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
-      // the backward pass rebuilds the weights as exp(log L - cmx) * cinv
-      if (p.cmx_out != nullptr && g == 0) {
-        const size_t at = (size_t)(aRout - (u16*)p.aR) / D + (size_t)nk * b2 + j;
-        p.cmx_out[at] = shift[pt] * kLn2;
-        p.cinv_out[at] = 1.0f / csum[pt];
-      }
-    }
-  }
-  if (stamp) MRT_STAMP(6);
-}
-
 // Pass 2 of the refine stage for one (m, j): waves stride over groups of PT adjacent 16-wide nk
 // tiles (every LDS read of Q serves all PT tiles).  Qs holds Q[m, :, j, :] row-major (rows >= b1
-// zero), lse the base-2 log-sum-exp of every row l.  When `resident`, alpha_L[m, j] and its
-// -c_L*log2(e) biases are read from LDS (Kres / bres, rows of LD elements), else from global
-// memory with the next group's operands in flight while the current one is processed.
+// zero), lse the base-2 log-sum-exp of every row l.  alpha_L[m, j] and c_L are read from global
+// memory (the cache: pass 1 has just streamed them), with the next group's operands in flight
+// while the current one is processed.  The result
+//   alpha_R[m, nk, j, :] / c_R[m, nk, j] = sum_l w Q[m, l, j, :] / sum_l w,   w = L[l, nk] = 2^z,
+// is stored as the next iteration's abar rows.  It is computed one PAIR of l tiles at a time: the
+// weights are L[l, nk] itself (no maximum is taken out), so a pair's logits can be turned into
+// weights, summed and contracted with its 32 rows of Q at once, and only two tiles of logits per
+// key tile are ever live.  A key whose whole column underflows in fp32 (sum of weights 0) is redone
+// with the column maximum taken out first (the ratio is unchanged by it).
 template <int D, int NLT, int PT, int LD>
-__device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float* lse, bool resident,
-                                    const u16* Kres, const float* bres, const u16* aLp,
-                                    const float* cLp, u16* aRout, int NK, int j, int wave,
-                                    int nwaves, int lane) {
-  constexpr int KS1 = D / 32;
+__device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float* lse, const u16* aLp,
+                                          const float* cLp, u16* aRout, int NK, int j, int wave,
+                                          int nwaves, int lane) {
+  constexpr int KS1 = D / 32, NVT = D / 16, NP = (NLT + 1) / 2;
   const int g = lane >> 4, c = lane & 15;
-  const int b1 = p.b1;
+  const int b1 = p.b1, b2 = p.b2;
   const float scale2 = p.scale * kLog2e;
   const int ntiles = (NK + 15) >> 4;
   const int ngroups = (ntiles + PT - 1) / PT;
@@ -663,16 +697,10 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
     for (int pt = 0; pt < PT; ++pt) {
       const int nk = 16 * (PT * grp + pt) + c;
       const int nkc = nk < NK ? nk : NK - 1;
-      if (resident) {
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) dst[pt][ks] = ld_lds_16B(Kres + nkc * LD + 32 * ks + 8 * g);
-        cdst[pt] = -bres[nkc];
-      } else {
-#pragma unroll
-        for (int ks = 0; ks < KS1; ++ks)
-          dst[pt][ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
-        cdst[pt] = cLp[nkc];
-      }
+      for (int ks = 0; ks < KS1; ++ks)
+        dst[pt][ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
+      cdst[pt] = cLp[nkc];
     }
   };
   if (wave < ngroups) fetch(wave, kbn, cln);
@@ -681,13 +709,13 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
     for (int pt = 0; pt < PT; ++pt) {
 #pragma unroll
       for (int ks = 0; ks < KS1; ++ks) kb[pt][ks] = kbn[pt][ks];
-      cl[pt] = resident ? cln[pt] : cln[pt] * kLog2e;    // c_L in the base-2 domain
+      cl[pt] = cln[pt] * kLog2e;    // c_L in the base-2 domain
     }
     if (grp + nwaves < ngroups) fetch(grp + nwaves, kbn, cln);
     const int npt = ntiles - PT * grp < PT ? ntiles - PT * grp : PT;   // tiles of this group
-    f32x4 z[PT][NLT];     // log2 L[l, nk]
-#pragma unroll
-    for (int lt = 0; lt < NLT; ++lt) {
+
+    // log2 L[l, nk] of l tile lt for the group's key tiles (rows beyond b1: -inf)
+    auto logits = [&](int lt, f32x4 (&z)[PT]) {
       bf16x8 av[KS1];
 #pragma unroll
       for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
@@ -695,21 +723,105 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
 #pragma unroll
       for (int pt = 0; pt < PT; ++pt) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (pt < npt) {
 #pragma unroll
-          for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
-        }
+        for (int ks = 0; ks < KS1; ++ks) acc = mfma(av[ks], kb[pt][ks], acc);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const bool ok = 16 * lt + 4 * g + r < b1;
           acc[r] = ok ? fmaf(acc[r], scale2, -cl[pt]) - ls[r] : -INFINITY;
         }
-        z[pt][lt] = acc;
+        z[pt] = acc;
       }
-      // keep the scheduler from hoisting every tile's operand reads to the top (register blow-up)
-      if (lt % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+    };
+    float csum[PT], shift[PT];
+    f32x4 o[PT][NVT];
+    // pairs in a software pipeline: the next pair's logits (MFMA) are issued ahead of this pair's
+    // exponentials (vector ALU), so that the matrix unit works under them
+    auto pair_logits = [&](int pr, f32x4 (&zlo)[PT], f32x4 (&zhi)[PT]) {
+      logits(2 * pr, zlo);
+      if (2 * pr + 1 < NLT) logits(2 * pr + 1, zhi);
+    };
+    auto run = [&]() {
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) {
+        csum[pt] = 0.f;
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+      f32x4 zlo[PT], zhi[PT], nlo[PT], nhi[PT];
+      pair_logits(0, zlo, zhi);
+#pragma unroll
+      for (int pr = 0; pr < NP; ++pr) {
+        if (pr + 1 < NP) pair_logits(pr + 1, nlo, nhi);
+        bf16x8 pb[PT];
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+          f32x4 lo, hi = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            lo[r] = exp2_fast(zlo[pt][r] - shift[pt]);
+            csum[pt] += lo[r];
+            if (2 * pr + 1 < NLT) {
+              hi[r] = exp2_fast(zhi[pt][r] - shift[pt]);
+              csum[pt] += hi[r];
+            }
+          }
+          pb[pt] = pack8(lo, hi);
+        }
+#ifndef MRT_NO_SGB
+        if (pr + 1 < NP) {
+#pragma unroll
+          for (int i = 0; i < 2 * PT * KS1; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
+          }
+        }
+#endif
+        pv_step_multi<D, PT, LD>(Qs + 32 * pr * LD, pb, PT, o, lane);
+        // keep the scheduler from hoisting every pair's operand reads to the top (register blow-up)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) { zlo[pt] = nlo[pt]; zhi[pt] = nhi[pt]; }
+      }
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) csum[pt] = xsum(csum[pt]);
+    };
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) shift[pt] = 0.f;
+    run();
+    bool under = false;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) under |= (pt < npt && csum[pt] == 0.f);
+    if (__builtin_expect(__any(under), 0)) {
+      float cm[PT];
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) cm[pt] = -INFINITY;
+      for (int lt = 0; lt < NLT; ++lt) {
+        f32x4 z[PT];
+        logits(lt, z);
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) cm[pt] = fmaxf(cm[pt], z[pt][r]);
+      }
+#pragma unroll
+      for (int pt = 0; pt < PT; ++pt) shift[pt] = xmax(cm[pt]);
+      run();
     }
-    refine_finish<D, NLT, PT, LD>(p, Qs, z, npt, PT * grp, aRout, NK, j, lane, grp == wave);
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+      const int nk = 16 * (PT * grp + pt) + c;
+      if (pt < npt && nk < NK) {
+        store_rows<D>(aRout + ((size_t)nk * b2 + j) * D, o[pt], 1.0f / csum[pt], g);
+        // the backward pass rebuilds the weights as exp(log L - cmx) * cinv
+        if (p.cmx_out != nullptr && g == 0) {
+          const size_t at = (size_t)(aRout - (u16*)p.aR) / D + (size_t)nk * b2 + j;
+          p.cmx_out[at] = shift[pt] * kLn2;
+          p.cinv_out[at] = 1.0f / csum[pt];
+        }
+      }
+    }
   }
 }
 
@@ -720,18 +832,22 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
 // softmax over l of log L[l, nk] (the same ratio, safe against underflow) and contracts with Q
 // read transposed from LDS.
 constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
+constexpr int kRefineHead = 16 * kMaxLT * 4 + 16;   // bytes of LDS ahead of the shared region
 
 // NLT = number of 16-row l tiles (compile time, so that the tile loops unroll without guards and
 // the scheduler can overlap one tile's LDS reads with another's MFMAs).
 template <int D, int QT, int MAXT, int NLT, int PT, int PAD>
-__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int qrows) {
+__global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p) {
   constexpr int LD = D + PAD, KS1 = D / 32, NVT = D / 16;
+  // LDS: the row log-sum-exps, then one region that holds the chunk ring during pass 1 and the
+  // Q tile during pass 2 (pass 1 takes its Q operands straight from global memory)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  FlashLds<D, false, PAD> lds(smem);
-  u16* Qs = (u16*)(smem + FlashLds<D, false, PAD>::kBytes);   // [qrows][LD], rows >= b1 zero
-  float* lse = (float*)(Qs + (size_t)qrows * LD);        // [16 * kMaxLT]
+  float* lse = (float*)smem;                             // [16 * kMaxLT], then the tile order flag
+  FlashLds<D, false, PAD> lds(smem + kRefineHead);
+  u16* Qs = (u16*)(smem + kRefineHead);                  // [32 * ceil(NLT / 2)][LD], rows >= b1 zero
 
-  const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
+  constexpr int nwaves = MAXT / 64;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   constexpr int nlt = NLT;
@@ -745,7 +861,8 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
   const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   MRT_STAMP(0);
-  stage_rows<D, LD>(Qs, Qp, qrow, qrows, b1, tid, nthr);
+  // pass 1's tile owner index of this wave
+  const int owner = tile_order_flip((int*)(smem + 16 * kMaxLT * 4), tid) ? nwaves - 1 - wave : wave;
 
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
@@ -753,7 +870,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
 
   // ---- pass 1
   {
-    const WaveTiles<QT> wt(wave, nwaves, nlt);
+    const WaveTiles<QT> wt(owner, nwaves, nlt);
     bf16x8 qv[QT][KS1];
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
@@ -769,8 +886,8 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
 #pragma unroll
     for (int q = 0; q < QT; ++q) qchunk[q] = 0;
     auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = 0; };
-    flash_loop<D, QT, false, false, PAD>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st,
-                                    odummy, tid, nthr, lane);
+    flash_loop<D, QT, false, false, MAXT, PAD>(aLp, D, nullptr, 0, NK, meta, lds, qv, wt.nq, p.scale * kLog2e,
+                                               qchunk, st, odummy, tid, lane);
     MRT_STAMP(1);
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
@@ -778,13 +895,14 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p, int 
       if (q < wt.nq && g == 0) lse[16 * wt.lt[q] + c] = st.mrun[q] + log2_fast(lsum);   // base 2
     }
   }
+  __syncthreads();                 // every wave is done with the chunk ring
+  stage_rows_batched<D, LD, 32 * ((NLT + 1) / 2), MAXT>(Qs, Qp, qrow, b1, tid);
   __syncthreads();
   MRT_STAMP(2);
 
-  // ---- pass 2 (alpha_L[m, j] is still resident in the two chunk buffers when it fits them)
+  // ---- pass 2 (alpha_L[m, j] is streamed again, from the cache)
   u16* aRout = (u16*)p.aR + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * D;
-  refine_pass2<D, NLT, PT, LD>(p, Qs, lse, NK <= 2 * kCK, lds.K(0), lds.bias(0), aLp, cLp, aRout, NK,
-                               j, wave, nwaves, lane);
+  refine_pass2<D, NLT, PT, LD>(p, Qs, lse, aLp, cLp, aRout, NK, j, wave, nwaves, lane);
   MRT_STAMP(6);
 }
 
@@ -1270,8 +1388,8 @@ __global__ __launch_bounds__(256, 2) void k_bf16_dense(KParams p) {
     for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int cc = p.cc, hw = p.hw;
   auto meta = [&](int key, float& raw, int& chunk) { raw = 0.f; chunk = cc > 0 ? (key / hw) / cc : 0; };
-  flash_loop<D, QT, true, true>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, wt.nq, p.scale * kLog2e,
-                                qchunk, st, o, tid, 256, lane);
+  flash_loop<D, QT, true, true, 256>(Kp, p.ks.token, Vp, p.vs.token, nkeys, meta, lds, qv, wt.nq,
+                                     p.scale * kLog2e, qchunk, st, o, tid, lane);
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head;
 #pragma unroll
   for (int q = 0; q < QT; ++q) {
@@ -1305,10 +1423,10 @@ hipError_t launch_r_d(const KParams& kp, dim3 grid, int gs, bool first, bool las
   return hipErrorInvalidValue;
 }
 
-template <int D, int QT, int MAXT>
-hipError_t launch_l_out(const KParams& kp, dim3 grid, int nthr, hipStream_t s) {
-  if (kp.rl > 0) k_bf16_stage_l_out<D, QT, MAXT, true><<<grid, nthr, 0, s>>>(kp);
-  else k_bf16_stage_l_out<D, QT, MAXT, false><<<grid, nthr, 0, s>>>(kp);
+template <int D, int QT, int NT>
+hipError_t launch_l_out(const KParams& kp, dim3 grid, hipStream_t s) {
+  if (kp.rl > 0) k_bf16_stage_l_out<D, QT, NT, true><<<grid, NT, 0, s>>>(kp);
+  else k_bf16_stage_l_out<D, QT, NT, false><<<grid, NT, 0, s>>>(kp);
   return hipGetLastError();
 }
 
@@ -1479,20 +1597,19 @@ hipError_t launch_l_out_mid_d(const KParams& kp, dim3 grid, int nkt, hipStream_t
 }
 
 // Streamed refine kernel: always four waves (one per SIMD, so that two workgroups fit a compute
-// unit however their waves are dealt to the SIMDs), each owning up to QT query tiles.  Beyond
-// eight query tiles (b1 > 128) the tiles take 8 elements of row padding instead of 16: the
-// workgroup's LDS then stays under half of the compute unit's 160 KB.
+// unit however their waves are dealt to the SIMDs), each owning up to QT query tiles.  The chunk
+// ring of pass 1 and the Q tile of pass 2 share one LDS region (at most 56 KB for b1 = 192).
 template <int D, int NLT>
 hipError_t launch_l_refine(const KParams& kp, dim3 grid, hipStream_t s) {
-  constexpr int QT = (NLT + 3) / 4, MAXT = 256, PT = NLT <= 8 ? 2 : 1, PAD = NLT <= 8 ? kPad : 8;
-  const int qrows = 32 * ((NLT + 1) / 2);
-  const size_t lds = FlashLds<D, false, PAD>::kBytes + (size_t)qrows * (D + PAD) * 2 + 16 * kMaxLT * 4;
+  constexpr int QT = (NLT + 3) / 4, MAXT = 256, PT = 2, PAD = kPad;
+  const size_t tile = (size_t)32 * ((NLT + 1) / 2) * (D + PAD) * 2, ring = FlashLds<D, false, PAD>::kBytes;
+  const size_t lds = kRefineHead + (tile > ring ? tile : ring);
   hipError_t e;
   if (lds > 64 * 1024 &&
       (e = hipFuncSetAttribute((const void*)k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT, PAD>,
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
     return e;
-  k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT, PAD><<<grid, 256, lds, s>>>(kp, qrows);
+  k_bf16_stage_l_refine<D, QT, MAXT, NLT, PT, PAD><<<grid, 256, lds, s>>>(kp);
   return hipGetLastError();
 }
 
@@ -1626,15 +1743,16 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
   // long key ranges: streamed.  Workgroups of 4 waves (one per SIMD), each wave owning up to two
   // query tiles, so that two workgroups fit a compute unit whatever order their waves are dealt
   // to the SIMDs in; only b1 > 128 needs a fifth and sixth wave.
-  const int nthr = nlt <= 8 ? 256 : 64 * ((nlt + 1) / 2);
   if (!last) return kp.d == 128 ? launch_l_refine_d<128>(kp, grid, nlt, s)
                                 : launch_l_refine_d<64>(kp, grid, nlt, s);
-  if (nlt <= 4) return kp.d == 128 ? launch_l_out<128, 1, 256>(kp, grid, nthr, s)
-                                   : launch_l_out<64, 1, 256>(kp, grid, nthr, s);
-  if (nlt <= 8) return kp.d == 128 ? launch_l_out<128, 2, 256>(kp, grid, nthr, s)
-                                   : launch_l_out<64, 2, 256>(kp, grid, nthr, s);
-  return kp.d == 128 ? launch_l_out<128, 2, 384>(kp, grid, nthr, s)
-                     : launch_l_out<64, 2, 384>(kp, grid, nthr, s);
+  if (nlt <= 4) return kp.d == 128 ? launch_l_out<128, 1, 256>(kp, grid, s)
+                                   : launch_l_out<64, 1, 256>(kp, grid, s);
+  if (nlt <= 8) return kp.d == 128 ? launch_l_out<128, 2, 256>(kp, grid, s)
+                                   : launch_l_out<64, 2, 256>(kp, grid, s);
+  if (nlt <= 10) return kp.d == 128 ? launch_l_out<128, 2, 320>(kp, grid, s)
+                                    : launch_l_out<64, 2, 320>(kp, grid, s);
+  return kp.d == 128 ? launch_l_out<128, 2, 384>(kp, grid, s)
+                     : launch_l_out<64, 2, 384>(kp, grid, s);
 }
 
 hipError_t launch_bf16_dense(const KParams& kp, int nbh, hipStream_t s) {
