@@ -490,26 +490,25 @@ struct ChunkFetch {
 // that pair's barrier; the chunk it writes is first read after this pair's barrier.
 // The loop body is one run of straight code (chunks are consumed in pairs, an odd last chunk is
 // followed by an empty one) for a wave that owns NQ query tiles.
-template <int D, int QT, int NQ, bool WITH_V, bool MASKED, int NT, int PAD, typename Meta>
+// NSET = 4 keeps four register sets in flight (two pairs ahead), for workgroups that have a compute
+// unit to themselves and few registers per set (512 threads): with one workgroup per compute unit
+// two chunks in flight do not cover the memory latency at the streaming rate.
+template <int D, int QT, int NQ, bool WITH_V, bool MASKED, int NT, int NSET, int PAD, typename Meta>
 __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u16* vbase,
                                     long long vstride, int nkeys, Meta& meta, FlashLds<D, WITH_V, PAD>& lds,
                                     const bf16x8 (&qv)[QT][D / 32], float scale,
                                     const int (&qchunk)[QT], FlashState<QT>& st,
                                     f32x4 (&o)[QT][D / 16], int tid, int lane) {
   const int npairs = (nkeys + 2 * kHK - 1) / (2 * kHK);
+  static_assert(NSET == 2 || NSET == 4, "two or four register sets");
   using Fetch = ChunkFetch<D, WITH_V, NT, PAD>;
   Fetch fa, fb;
   auto fetch = [&](Fetch& f, int chunk) {
     f.fetch(kbase, kstride, vbase, vstride, nkeys, chunk * kHK, meta, tid);
   };
-  fetch(fa, 0);
-  fetch(fb, 1);
-  fa.template commit<MASKED>(lds, 0, tid);
-  fetch(fa, 2);
-  fb.template commit<MASKED>(lds, 1, tid);
-  fetch(fb, 3);
-  __syncthreads();
-  for (int pr = 0; pr < npairs; ++pr) {
+  // one pair of chunks (2 pr, 2 pr + 1); fx and fy hold the next pair's chunks, are committed and
+  // then reloaded with the chunks NSET + 2 and NSET + 3 ahead
+  auto pair = [&](int pr, Fetch& fx, Fetch& fy) {
     const int s0 = 2 * (pr & 1), s1 = s0 ^ 2;    // slots of this pair's chunks / of the next pair's
     // Stages of the two chunks, interleaved so that the matrix unit works under the vector ALU:
     // the second chunk's first product runs under the first chunk's exponentials, the first
@@ -545,34 +544,54 @@ __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u
 #endif
       if (__builtin_amdgcn_ballot_w64(gb) != 0) flash_grow<D, QT, NQ, WITH_V>(sb, st, o);
     }
-    fa.template commit<MASKED>(lds, s1, tid);
-    fetch(fa, 2 * pr + 4);
+    fx.template commit<MASKED>(lds, s1, tid);
+    fetch(fx, 2 * pr + NSET + 2);
     if (NQ > 0) {
       flash_exp<QT, NQ, WITH_V, MASKED>(sb, st, pbb);
       if (WITH_V) flash_pv<D, QT, NQ, PAD>(lds.V(s0 + 1), pbb, o, lane);
     }
-    fb.template commit<MASKED>(lds, s1 + 1, tid);
-    fetch(fb, 2 * pr + 5);
+    fy.template commit<MASKED>(lds, s1 + 1, tid);
+    fetch(fy, 2 * pr + NSET + 3);
     __syncthreads();
+  };
+  fetch(fa, 0);
+  fetch(fb, 1);
+  fa.template commit<MASKED>(lds, 0, tid);
+  fetch(fa, 2);
+  fb.template commit<MASKED>(lds, 1, tid);
+  fetch(fb, 3);
+  if (NSET == 2) {
+    __syncthreads();
+    for (int pr = 0; pr < npairs; ++pr) pair(pr, fa, fb);
+  } else {
+    Fetch fc, fd;
+    fetch(fc, 4);
+    fetch(fd, 5);
+    __syncthreads();
+    // (an odd number of pairs ends with an empty pair: its chunks lie beyond the keys)
+    for (int pr = 0; pr < npairs; pr += 2) {
+      pair(pr, fa, fb);
+      pair(pr + 1, fc, fd);
+    }
   }
 }
 
 // nq = query tiles the wave owns (uniform over the wave): QT, QT - 1 or none; every path runs
 // the same fetches, commits and barriers.
-template <int D, int QT, bool WITH_V, bool MASKED, int NT, int PAD = kPad, typename Meta>
+template <int D, int QT, bool WITH_V, bool MASKED, int NT, int PAD = kPad, int NSET = 2, typename Meta>
 __device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
                                   long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V, PAD>& lds,
                                   const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
                                   const int (&qchunk)[QT], FlashState<QT>& st,
                                   f32x4 (&o)[QT][D / 16], int tid, int lane) {
   if (nq == QT)
-    flash_loop_n<D, QT, QT, WITH_V, MASKED, NT, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
+    flash_loop_n<D, QT, QT, WITH_V, MASKED, NT, NSET, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
                                                      qchunk, st, o, tid, lane);
   else if (QT > 1 && nq == QT - 1)
-    flash_loop_n<D, QT, (QT > 1 ? QT - 1 : 0), WITH_V, MASKED, NT, PAD>(kbase, kstride, vbase, vstride, nkeys, meta,
+    flash_loop_n<D, QT, (QT > 1 ? QT - 1 : 0), WITH_V, MASKED, NT, NSET, PAD>(kbase, kstride, vbase, vstride, nkeys, meta,
                                                                        lds, qv, scale, qchunk, st, o, tid, lane);
   else
-    flash_loop_n<D, QT, 0, WITH_V, MASKED, NT, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
+    flash_loop_n<D, QT, 0, WITH_V, MASKED, NT, NSET, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
                                                     qchunk, st, o, tid, lane);
 }
 
@@ -607,7 +626,7 @@ __device__ inline int tile_order_flip(int* slot, int tid) {
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
 // RMASK: regular Monarch under the chunk-causal mask (key rows of later chunks hidden per query row)
 template <int D, int QT, int NT, bool RMASK>
-__global__ __launch_bounds__(NT, 2) void k_bf16_stage_l_out(KParams p) {
+__global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
   __shared__ int flip_slot;
@@ -656,7 +675,8 @@ __global__ __launch_bounds__(NT, 2) void k_bf16_stage_l_out(KParams p) {
   }
   MRT_STAMP(0);
   auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = RMASK ? key / p.rl : 0; };
-  flash_loop<D, QT, true, RMASK, NT>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq, p.scale * kLog2e, qchunk, st, o,
+  flash_loop<D, QT, true, RMASK, NT, kPad, (NT == 512 ? 4 : 2)>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq,
+                                                                 p.scale * kLog2e, qchunk, st, o,
                                      tid, lane);
   MRT_STAMP(1);
   u16* Op = (u16*)p.O + b * p.os.batch + hd * p.os.head + qtok0 * p.os.token;
@@ -1749,10 +1769,8 @@ hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_
                                    : launch_l_out<64, 1, 256>(kp, grid, s);
   if (nlt <= 8) return kp.d == 128 ? launch_l_out<128, 2, 256>(kp, grid, s)
                                    : launch_l_out<64, 2, 256>(kp, grid, s);
-  if (nlt <= 10) return kp.d == 128 ? launch_l_out<128, 2, 320>(kp, grid, s)
-                                    : launch_l_out<64, 2, 320>(kp, grid, s);
-  return kp.d == 128 ? launch_l_out<128, 2, 384>(kp, grid, s)
-                     : launch_l_out<64, 2, 384>(kp, grid, s);
+  return kp.d == 128 ? launch_l_out<128, 2, 512>(kp, grid, s)
+                     : launch_l_out<64, 2, 512>(kp, grid, s);
 }
 
 hipError_t launch_bf16_dense(const KParams& kp, int nbh, hipStream_t s) {
