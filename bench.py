@@ -215,7 +215,7 @@ def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
     }))
 
 
-def measure_forward(wl, env, steps, warmup, *, head_groups=0, with_dense=True, with_oracle=True,
+def measure_forward(wl, env, steps, warmup, *, head_groups=0, settle_s=0.0, with_dense=True, with_oracle=True,
                     oracle_budget_s=0.0, calibration_copy_mb=0, copy_gbs=None):
     """One workload through monarch_attn_fwd: whole-call time (default launch configuration),
     per-launch durations (HIP events recorded by the library around every launch, one head group so
@@ -253,6 +253,19 @@ def measure_forward(wl, env, steps, warmup, *, head_groups=0, with_dense=True, w
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if settle_s > 0:
+        # the other named configurations follow CPU-side work (parity check of the previous one)
+        # during which the GPU idled: run untimed calls until the clocks have settled, then time
+        # about settle_s seconds of calls (at least `steps`)
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < settle_s:
+            step()
+            n += 1
+            if n % 8 == 0:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        steps = max(steps, int(n * 1.0))
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
@@ -463,7 +476,8 @@ def main():
         # oracle, no oracle timing
         w2 = syn.WORKLOADS[name]
         r = measure_forward(w2, env, max(5, min(args.steps, 20)), max(2, min(args.warmup, 5)),
-                            head_groups=args.head_groups, with_dense=not args.no_dense and name != "C4",
+                            head_groups=args.head_groups, settle_s=0.1,
+                            with_dense=not args.no_dense and name != "C4",
                             with_oracle=not args.no_cpu_baseline, copy_gbs=copy_gbs)
         others.append({"workload": r["config"]["workload"], "ms_per_call": r["ms"],
                        "dominant_kernel": r["roofline"]["kernel"], "bound": r["roofline"]["bound"],
