@@ -933,14 +933,19 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p) {
 // share a compute unit: the 52*heads workgroups of the 4680-token chunk run in a single round.
 // ---------------------------------------------------------------------------------------
 constexpr int kResRows = 96;    // key rows held resident
-constexpr int kResPad = 8;      // row padding of the resident tiles (row stride = 4 banks mod 64)
+constexpr int kResPad = 8;      // row padding of the resident tiles of 64 features (128: swizzled, no padding)
+// layout of a resident tile: swizzled rows for 128 features, padded rows for 64
+template <int D> struct ResTile {
+  static constexpr bool SWZ = D == 128;
+  static constexpr int LD = SWZ ? D : D + kResPad;
+};
 
 // Exact softmax of QT query tiles (nq of them live) against NTK resident key tiles; every key
 // operand read from LDS serves all QT tiles.  On return s holds the exponentials (base-2 logits
 // minus the column maximum) and sum their column sums.
 // RMASK (regular Monarch under the chunk-causal mask): the lane's query row of tile q sees the keys
 // below klim[q].
-template <int D, int NTK, int LD, int QT, bool RMASK>
+template <int D, int NTK, int LD, bool SWZ, int QT, bool RMASK>
 __device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8 (&qv)[QT][D / 32],
                                   int nq, float scale2, const int (&klim)[QT], f32x4 (&s)[QT][NTK],
                                   float (&sum)[QT], int lane) {
@@ -958,7 +963,7 @@ __device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8
       if (2 * kp + t < NTK) {
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks)
-          a[t][ks] = ld_lds_16B(Ks + (16 * (2 * kp + t) + c) * LD + 32 * ks + 8 * g);
+          a[t][ks] = ld_lds_16B(Ks + tile_off<LD, SWZ>(16 * (2 * kp + t) + c, 4 * ks + g));
       }
 #pragma unroll
     for (int q = 0; q < QT; ++q)
@@ -1000,7 +1005,8 @@ __device__ inline void res_logits(const u16* Ks, const float* bias, const bf16x8
 
 template <int D, int NTK, bool RMASK>
 __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
-  constexpr int LD = D + kResPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  constexpr int LD = ResTile<D>::LD, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  constexpr bool SWZ = ResTile<D>::SWZ;
   constexpr int QT = 2;
   __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];
   __shared__ __attribute__((aligned(16))) u16 Vs[ROWS * LD];
@@ -1049,7 +1055,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   const float cl = cLp[tid < NK ? tid : NK - 1];
   if (wave < npairs) load_q(wave);
   rv.load(Yp, PlainRows{D}, NK, tid);
-  rk.template store<LD>(Ks, tid);
+  rk.template store<LD, SWZ>(Ks, tid);
   if (tid < ROWS) bias[tid] = tid < NK ? -cl * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
@@ -1067,7 +1073,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
       const int l = 16 * (QT * pair + q) + c;
       klim[q] = RMASK ? visible_key_rows(p, l < b1 ? l : b1 - 1) : 0;
     }
-    res_logits<D, NTK, LD, QT, RMASK>(Ks, bias, qv, nq, scale2, klim, s, sum, lane);
+    res_logits<D, NTK, LD, SWZ, QT, RMASK>(Ks, bias, qv, nq, scale2, klim, s, sum, lane);
 #pragma unroll
     for (int q = 0; q < QT; ++q)
 #pragma unroll
@@ -1078,7 +1084,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
       }
   }
   __builtin_amdgcn_sched_barrier(0);
-  rv.template store<LD>(Vs, tid);
+  rv.template store<LD, SWZ>(Vs, tid);
   __syncthreads();
   MRT_STAMP(2);
   if (nq > 0) {
@@ -1089,7 +1095,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
       for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st = 0; st < KS2; ++st) {
-      pv_step_multi<D, QT, LD>(Vs + 32 * st * LD, pb[st], nq, o, lane);
+      pv_step_multi<D, QT, LD, SWZ>(Vs + 32 * st * LD, pb[st], nq, o, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
     const TokRows orow = tile_rows(p, a, p.os.token);
@@ -1109,7 +1115,8 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
 // alpha_L goes from global memory straight into the matrix operands, only Q is staged.
 template <int D, int NLT, int PT, int NW, bool RMASK>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refine_one(KParams p) {
-  constexpr int LD = D + kResPad, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), LROWS = 16 * NLT;
+  constexpr int LD = ResTile<D>::LD, KS1 = D / 32, QROWS = 32 * ((NLT + 1) / 2), LROWS = 16 * NLT;
+  constexpr bool SWZ = ResTile<D>::SWZ;
   __shared__ __attribute__((aligned(16))) u16 Qs[QROWS * LD];
   __shared__ __attribute__((aligned(16))) float red_m[NW][LROWS];
   __shared__ __attribute__((aligned(16))) float red_s[NW][LROWS];
@@ -1147,7 +1154,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
     for (int ks = 0; ks < KS1; ++ks) kb[pt][ks] = ld_global_16B(aLp + (size_t)nkc * D + 32 * ks + 8 * g);
     cl[pt] = cLp[nkc] * kLog2e;
   }
-  rq.template store<LD>(Qs, tid);
+  rq.template store<LD, SWZ>(Qs, tid);
   __syncthreads();
   MRT_STAMP(1);
 
@@ -1160,7 +1167,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
     for (int lt = 0; lt < NLT; ++lt) {
       bf16x8 av[KS1];
 #pragma unroll
-      for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + (16 * lt + c) * LD + 32 * ks + 8 * g);
+      for (int ks = 0; ks < KS1; ++ks) av[ks] = ld_lds_16B(Qs + tile_off<LD, SWZ>(16 * lt + c, 4 * ks + g));
 #pragma unroll
       for (int pt = 0; pt < PT; ++pt) {
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -1345,7 +1352,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
       for (int vt = 0; vt < NVT; ++vt) o[pt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st2 = 0; st2 < NS2; ++st2) {
-      pv_step_multi<D, PT, LD>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
+      pv_step_multi<D, PT, LD, SWZ>(Qs + 32 * st2 * LD, pb[st2], npt, o, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
     MRT_STAMP(5);
@@ -1462,7 +1469,7 @@ constexpr int kMidRows = 192;
 
 // Base-2 logits (bias added, -inf beyond the last key) of one query tile against NTK resident key
 // tiles (NTK <= 12), and their column maximum.
-template <int D, int NTK, int LD, bool RMASK>
+template <int D, int NTK, int LD, bool SWZ, bool RMASK>
 __device__ inline float mid_logits(const u16* Ks, const float* bias, const bf16x8 (&qv)[D / 32],
                                    float scale2, int klim, f32x4 (&s)[2 * ((NTK + 1) / 2)], int lane) {
   constexpr int KS1 = D / 32, KS2 = (NTK + 1) / 2;
@@ -1475,7 +1482,7 @@ __device__ inline float mid_logits(const u16* Ks, const float* bias, const bf16x
       if (2 * kp + t < NTK) {
 #pragma unroll
         for (int ks = 0; ks < KS1; ++ks)
-          a[t][ks] = ld_lds_16B(Ks + (16 * (2 * kp + t) + c) * LD + 32 * ks + 8 * g);
+          a[t][ks] = ld_lds_16B(Ks + tile_off<LD, SWZ>(16 * (2 * kp + t) + c, 4 * ks + g));
       }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -1505,7 +1512,8 @@ __device__ inline float mid_logits(const u16* Ks, const float* bias, const bf16x
 
 template <int D, int NTK, bool RMASK>
 __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
-  constexpr int LD = D + kResPad, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  constexpr int LD = ResTile<D>::LD, KS1 = D / 32, NVT = D / 16, KS2 = (NTK + 1) / 2, ROWS = 32 * KS2;
+  constexpr bool SWZ = ResTile<D>::SWZ;
   constexpr int QT = 2;
   __shared__ __attribute__((aligned(16))) u16 tile[ROWS * LD];
   __shared__ __attribute__((aligned(16))) float bias[ROWS];
@@ -1538,7 +1546,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
 #pragma unroll
     for (int ks = 0; ks < KS1; ++ks) qv[q][ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
   }
-  stage_rows_batched<D, LD, ROWS, 256>(tile, aLp, PlainRows{D}, NK, tid);
+  stage_rows_batched<D, LD, ROWS, 256, SWZ>(tile, aLp, PlainRows{D}, NK, tid);
   for (int i = tid; i < ROWS; i += nthr) bias[i] = i < NK ? -cLp[i] * kLog2e : -INFINITY;
   __syncthreads();
   MRT_STAMP(1);
@@ -1554,7 +1562,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
       f32x4 s[2 * KS2];
       const int lq = 16 * wt.lt[q] + c;
       const int klim = RMASK ? visible_key_rows(p, lq < b1 ? lq : b1 - 1) : 0;
-      const float mx = mid_logits<D, NTK, LD, RMASK>(tile, bias, qv[q], scale2, klim, s, lane);
+      const float mx = mid_logits<D, NTK, LD, SWZ, RMASK>(tile, bias, qv[q], scale2, klim, s, lane);
       float sm = 0.f;
 #pragma unroll
       for (int kt = 0; kt < 2 * KS2; ++kt)
@@ -1574,7 +1582,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   }
   __syncthreads();                      // every wave is done with alpha_L
   MRT_STAMP(2);
-  stage_rows_batched<D, LD, ROWS, 256>(tile, Yp, PlainRows{D}, NK, tid);
+  stage_rows_batched<D, LD, ROWS, 256, SWZ>(tile, Yp, PlainRows{D}, NK, tid);
   __syncthreads();
   MRT_STAMP(3);
 
@@ -1587,7 +1595,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
       for (int vt = 0; vt < NVT; ++vt) o[q][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int st = 0; st < KS2; ++st) {
-      pv_step_multi<D, QT, LD>(tile + 32 * st * LD, pb[st], wt.nq, o, lane);
+      pv_step_multi<D, QT, LD, SWZ>(tile + 32 * st * LD, pb[st], wt.nq, o, lane);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll

@@ -102,6 +102,19 @@ __device__ inline float row8_sum(float x) {
   return x + dpp_mov<0x141>(x);
 }
 
+// Swizzled LDS tiles (SWZ = true; rows of 128 bf16 = 256 bytes = all 64 banks, NOT padded): the
+// 16-byte piece p of row r sits at piece index p ^ swz16(r), swz16(r) = 4 (r mod 4) ^ (r / 4 mod 4).
+// Both ways a tile is read are then free of bank conflicts: a matrix operand read of one piece
+// column from 8 consecutive rows (ds_read_b128: 8 lanes per clock; swz16 takes 8 different values
+// on rows 8a .. 8a + 7) and a transposed read (ds_read_b64_tr_b16: 16 lanes per clock on rows
+// 4g .. 4g + 3, four pieces q + 4k each: (q + 4k) ^ swz16 = (q ^ g) + 4 (k ^ e) covers all 16
+// pieces).  With padded rows one of the two always conflicts (two- to four-fold).
+__device__ inline int swz16(int row) { return ((row & 3) << 2) ^ ((row >> 2) & 3); }
+template <int LD, bool SWZ>
+__device__ inline int tile_off(int row, int piece) {
+  return row * LD + 8 * (SWZ ? piece ^ swz16(row) : piece);
+}
+
 // Second product for one 32-key step: acc[vt] += Val^T[phi(vt, .), keys] * P.
 // vals points at LDS row `32*step` of a row-major [rows][D + kPad] tile; output feature of
 // accumulator row (4g + r) of tile vt is phi = 32(vt/2) + 8g + 4(vt%2) + r.
@@ -152,19 +165,20 @@ __device__ inline void pv_step_half(const u16* vals, bf16x8 pb, f32x4* acc, int 
 }
 
 // Same for NB probability operands sharing every value-side LDS read (operands >= nb idle).
-template <int D, int NB, int LD = D + kPad>
+// vals must be a multiple of 16 rows into its tile when SWZ.
+template <int D, int NB, int LD = D + kPad, bool SWZ = false>
 __device__ inline void pv_step_multi(const u16* vals, const bf16x8 (&pb)[NB], int nb,
                                      f32x4 (&acc)[NB][D / 16], int lane) {
   constexpr int NVT = D / 16, HALF = NVT / 2;
   const int g = lane >> 4, s = lane & 15, e = s >> 2, q = s & 3;
-  const u16* base = vals + (4 * g + e) * LD + 8 * q;
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     s16x4 lo[HALF], hi[HALF];
 #pragma unroll
     for (int i = 0; i < HALF; ++i) {
       const int vt = h * HALF + i;
-      const u16* p0 = base + 32 * (vt >> 1) + 4 * (vt & 1);
+      // rows 4g + e and 16 + 4g + e (the same swizzle), piece q + 4 (vt / 2), half vt % 2
+      const u16* p0 = vals + tile_off<LD, SWZ>(4 * g + e, q + 4 * (vt >> 1)) + 4 * (vt & 1);
       lo[i] = ld_lds_tr(p0);
       hi[i] = ld_lds_tr(p0 + 16 * LD);
     }
@@ -289,13 +303,13 @@ struct RowRegs {
       v[i] = *(const uint4*)(src + rowoff(r) + 8 * c);
     }
   }
-  template <int LD>
+  template <int LD, bool SWZ = false>
   __device__ inline void store(u16* dst, int tid) const {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int idx = tid + i * NTHR;
       const int r = idx / CPR, c = idx - r * CPR;
-      if (idx < TOTAL) *(uint4*)(dst + r * LD + 8 * c) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
+      if (idx < TOTAL) *(uint4*)(dst + tile_off<LD, SWZ>(r, c)) = r < valid ? v[i] : uint4{0u, 0u, 0u, 0u};
     }
   }
   // Bottom-up: row r at dst - r * LD.
@@ -310,11 +324,11 @@ struct RowRegs {
   }
 };
 
-template <int D, int LD, int ROWS, int NTHR, typename RowFn>
+template <int D, int LD, int ROWS, int NTHR, bool SWZ = false, typename RowFn>
 __device__ inline void stage_rows_batched(u16* dst, const u16* src, RowFn rowoff, int valid, int tid) {
   RowRegs<D, ROWS, NTHR> r;
   r.load(src, rowoff, valid, tid);
-  r.template store<LD>(dst, tid);
+  r.template store<LD, SWZ>(dst, tid);
 }
 
 
