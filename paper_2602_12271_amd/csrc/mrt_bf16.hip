@@ -510,11 +510,10 @@ __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u
   // then reloaded with the chunks NSET + 2 and NSET + 3 ahead
   auto pair = [&](int pr, Fetch& fx, Fetch& fy) {
     const int s0 = 2 * (pr & 1), s1 = s0 ^ 2;    // slots of this pair's chunks / of the next pair's
-    // Stages of the two chunks, interleaved so that the matrix unit works under the vector ALU:
-    // the second chunk's first product runs under the first chunk's exponentials, the first
-    // chunk's second product under the second chunk's logits (the scheduler is told to issue
-    // each MFMA between a few vector instructions).  Only the rare raise of a reference branches.
-    constexpr int kStageMfma = NQ * (D / 16);   // MFMAs of one stage
+    // Stages of the two chunks in an order that leaves the scheduler independent work to put
+    // under each other: the second chunk's first product next to the first chunk's exponentials,
+    // the first chunk's second product next to the second chunk's logits.  Only the rare raise of
+    // a reference branches.
     f32x4 sa[QT][2], sb[QT][2];
     bf16x8 pa[QT], pbb[QT];
     if (NQ > 0) {
@@ -523,25 +522,8 @@ __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u
       if (__builtin_amdgcn_ballot_w64(ga) != 0) flash_grow<D, QT, NQ, WITH_V>(sa, st, o);
       flash_qk<D, QT, NQ, PAD>(lds.K(s0 + 1), qv, sb, lane);
       flash_exp<QT, NQ, WITH_V, MASKED>(sa, st, pa);
-#ifndef MRT_NO_SGB
-#pragma unroll
-      for (int i = 0; i < kStageMfma; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-        __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
-      }
-#endif
       if (WITH_V) flash_pv<D, QT, NQ, PAD>(lds.V(s0), pa, o, lane);
       const bool gb = flash_logits<QT, NQ, MASKED>(sb, lds.bias(s0 + 1), lds.kch(s0 + 1), qchunk, scale, st, lane);
-#ifndef MRT_NO_SGB
-      if (WITH_V) {
-#pragma unroll
-        for (int i = 0; i < kStageMfma; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-        }
-      }
-#endif
       if (__builtin_amdgcn_ballot_w64(gb) != 0) flash_grow<D, QT, NQ, WITH_V>(sb, st, o);
     }
     fx.template commit<MASKED>(lds, s1, tid);
@@ -610,31 +592,15 @@ struct WaveTiles {
   }
 };
 
-// Which of two orientations a workgroup deals its query tiles to its waves in.  Waves are dealt to
-// the four SIMDs in the same order for every workgroup, so when the tiles do not divide evenly
-// over the waves (6 tiles on 4 waves: 2, 2, 1, 1) two workgroups that share a compute unit would
-// both put their fuller waves on the same SIMDs.  The wave slot the hardware gave wave 0 on its
-// SIMD (the low bits of the HW_ID register) differs between the workgroups resident on a compute
-// unit at any one time: its parity flips the order for one of them (wave w takes the tiles of wave
-// nwaves - 1 - w), which evens out the load of the SIMDs.  Only speed depends on it.
-__device__ inline int tile_order_flip(int* slot, int tid) {
-  if (tid == 0) *slot = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (3 << 11)) & 1;   // HW_ID, WAVE_ID bits
-  __syncthreads();
-  return __builtin_amdgcn_readfirstlane(*slot);
-}
-
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
 // RMASK: regular Monarch under the chunk-causal mask (key rows of later chunks hidden per query row)
 template <int D, int QT, int NT, bool RMASK>
 __global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
-  __shared__ int flip_slot;
   FlashLds<D, true> lds(smem);
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int hwave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wave = tile_order_flip(&flip_slot, tid) ? NT / 64 - 1 - hwave : hwave;   // tile owner index
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
@@ -788,16 +754,6 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
           }
           pb[pt] = pack8(lo, hi);
         }
-#ifndef MRT_NO_SGB
-        if (pr + 1 < NP) {
-#pragma unroll
-          for (int i = 0; i < 2 * PT * KS1; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);
-          }
-        }
-#endif
         pv_step_multi<D, PT, LD>(Qs + 32 * pr * LD, pb, PT, o, lane);
         // keep the scheduler from hoisting every pair's operand reads to the top (register blow-up)
         __builtin_amdgcn_sched_barrier(0);
@@ -852,7 +808,7 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
 // softmax over l of log L[l, nk] (the same ratio, safe against underflow) and contracts with Q
 // read transposed from LDS.
 constexpr int kMaxLT = 12;   // l tiles of 16 (b1 <= 192)
-constexpr int kRefineHead = 16 * kMaxLT * 4 + 16;   // bytes of LDS ahead of the shared region
+constexpr int kRefineHead = 16 * kMaxLT * 4;   // bytes of LDS ahead of the shared region
 
 // NLT = number of 16-row l tiles (compile time, so that the tile loops unroll without guards and
 // the scheduler can overlap one tile's LDS reads with another's MFMAs).
@@ -862,7 +818,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p) {
   // LDS: the row log-sum-exps, then one region that holds the chunk ring during pass 1 and the
   // Q tile during pass 2 (pass 1 takes its Q operands straight from global memory)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* lse = (float*)smem;                             // [16 * kMaxLT], then the tile order flag
+  float* lse = (float*)smem;                             // [16 * kMaxLT]
   FlashLds<D, false, PAD> lds(smem + kRefineHead);
   u16* Qs = (u16*)(smem + kRefineHead);                  // [32 * ceil(NLT / 2)][LD], rows >= b1 zero
 
@@ -881,8 +837,6 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p) {
   const TokRows qrow = tile_rows(p, a, p.qs.token);
   const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qtok0 * p.qs.token;
   MRT_STAMP(0);
-  // pass 1's tile owner index of this wave
-  const int owner = tile_order_flip((int*)(smem + 16 * kMaxLT * 4), tid) ? nwaves - 1 - wave : wave;
 
   const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
   const u16* aLp = (const u16*)p.aL + row0 * D;
@@ -890,7 +844,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p) {
 
   // ---- pass 1
   {
-    const WaveTiles<QT> wt(owner, nwaves, nlt);
+    const WaveTiles<QT> wt(wave, nwaves, nlt);
     bf16x8 qv[QT][KS1];
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
