@@ -577,6 +577,14 @@ __device__ inline void flash_loop(const u16* kbase, long long kstride, const u16
                                                     qchunk, st, o, tid, lane);
 }
 
+// Head of a stage L workgroup.  Stage R, which ran just before, worked through the heads in
+// ascending order; stage L takes them in DESCENDING order, so that its first workgroups read what
+// was written last and is still in the memory-side cache (and stage L's own results for head 0,
+// written last, are what the next stage R reads first).  With intermediates of a few hundred MB
+// per launch a forward order would find nothing of them left (KV-cache step at 480p, one head
+// group: 498 -> 478 us per call).
+__device__ inline int last_head_first() { return (int)gridDim.z - 1 - (int)blockIdx.z; }
+
 // Query tiles of a wave: tile q of wave w is l tile (q * nwaves + w); nq of them exist.
 template <int QT>
 struct WaveTiles {
@@ -603,7 +611,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KPar
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = last_head_first(), bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -689,15 +697,17 @@ __device__ inline void refine_pass2(const KParams& p, const u16* Qs, const float
       cdst[pt] = cLp[nkc];
     }
   };
-  if (wave < ngroups) fetch(wave, kbn, cln);
-  for (int grp = wave; grp < ngroups; grp += nwaves) {
+  // the groups are taken from the END of the key range backwards: pass 1 has just streamed the
+  // range front to back, so its tail is what the caches still hold
+  if (wave < ngroups) fetch(ngroups - 1 - wave, kbn, cln);
+  for (int grp = ngroups - 1 - wave; grp >= 0; grp -= nwaves) {
 #pragma unroll
     for (int pt = 0; pt < PT; ++pt) {
 #pragma unroll
       for (int ks = 0; ks < KS1; ++ks) kb[pt][ks] = kbn[pt][ks];
       cl[pt] = cln[pt] * kLog2e;    // c_L in the base-2 domain
     }
-    if (grp + nwaves < ngroups) fetch(grp + nwaves, kbn, cln);
+    if (grp - nwaves >= 0) fetch(grp - nwaves, kbn, cln);
     const int npt = ntiles - PT * grp < PT ? ntiles - PT * grp : PT;   // tiles of this group
 
     // log2 L[l, nk] of l tile lt for the group's key tiles (rows beyond b1: -inf)
@@ -827,7 +837,7 @@ __global__ __launch_bounds__(MAXT, 2) void k_bf16_stage_l_refine(KParams p) {
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
   constexpr int nlt = NLT;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = last_head_first(), bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -969,7 +979,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
   const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = last_head_first(), bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 16*NTK
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -1079,7 +1089,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 3 : 2) void k_bf16_stage_l_refin
 
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = last_head_first(), bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 64 * PT
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -1475,7 +1485,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
   const int tid = threadIdx.x, nthr = blockDim.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthr >> 6;
   const int lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2;
-  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = last_head_first(), bh = p.bh0 + bhl;
   const int a = m / p.c2, bq = m - a * p.c2;
   const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;   // <= 16*NTK
   const size_t NKtot = (size_t)p.ntk * b1;
