@@ -413,13 +413,13 @@ mrt_status fwd_run(const void* Q, const void* K, const void* V, void* O, const m
   // one group's launch (workgroup counts are rarely a multiple of what the chip holds) overlaps
   // the next kernel of another group.  Per-kernel timing needs launches that do not overlap.
   // Measured on MI355X: the fork/join costs ~10 us per extra group, so it only pays for launches
-  // that run for >= 100 us and whose stage L grid is within a few multiples of the 512 workgroups
-  // the chip holds (KV-cache shapes at 12 heads: -7 %); small calls run on the caller's stream.
+  // that run for >= 100 us, and only when a group's chain has several kernels to interleave with
+  // the other group's (T >= 2: KV-cache steps -1 ... -4 %; the two-kernel chains of T = 1 lose
+  // 1 ... 5 %); small calls run on the caller's stream.
   int want_groups = requested_groups(p);
   if (want_groups == 0) {
     const size_t inter_per_launch = pl.slab_aL * per_head * G;
-    const long long l_wgs = (long long)A * pl.kp.c2 * pl.kp.b2 * G;
-    want_groups = (inter_per_launch >= (size_t(128) << 20) && l_wgs < 2048) ? 2 : 1;
+    want_groups = (inter_per_launch >= (size_t(128) << 20) && pl.T >= 2) ? 2 : 1;
   }
   const bool may_time = !own_stream_only;
   StreamPool* pool = (own_stream_only || g_prof_on.load() || want_groups <= 1) ? nullptr : get_pool();
