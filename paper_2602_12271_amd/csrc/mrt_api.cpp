@@ -310,6 +310,18 @@ static StreamPool* get_pool() {
   return p;
 }
 
+// Compute units of the current device (256 on MI355X); queried once per process.
+static int compute_units() {
+  static const int n = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+      cus = 256;
+    return cus;
+  }();
+  return n;
+}
+
 // Head groups a call asks for: the call's own field, else the process-wide default (0 = automatic).
 static int requested_groups(const mrt_problem* p) {
   int n = p->head_groups > 0 ? p->head_groups : g_max_groups.load(std::memory_order_relaxed);
@@ -439,8 +451,20 @@ mrt_status fwd_run(const void* Q, const void* K, const void* V, void* O, const m
         if (hipStreamWaitEvent(pool->side[gi - 1], pool->fork, 0) != hipSuccess) status = MRT_ERR_HIP;
       if (status != MRT_OK) { set_error("helper stream fork failed"); break; }
     }
+    // Two groups: when the heads whose stage L workgroups fill the chip exactly once (two
+    // workgroups per compute unit) are at least half of the pass, the first group takes that many
+    // and the second the rest, so that the larger group's stage L launches have no part-filled
+    // second round (12 heads of 52 columns: 9 + 3, 467 -> 456 us on the 480p KV-cache step);
+    // otherwise the heads are split evenly.
+    int first_group = 0;
+    if (ngroups == 2) {
+      const long long wgs_per_head = (long long)na * pl.kp.c2 * pl.kp.b2;
+      const int per_round = (int)(2LL * compute_units() / (wgs_per_head > 0 ? wgs_per_head : 1));
+      if (per_round < nbh && 2 * per_round >= nbh) first_group = per_round;
+    }
     for (int gi = 0; gi < ngroups; ++gi) {
-      const int lo = (int)((long long)nbh * gi / ngroups), hi = (int)((long long)nbh * (gi + 1) / ngroups);
+      int lo = (int)((long long)nbh * gi / ngroups), hi = (int)((long long)nbh * (gi + 1) / ngroups);
+      if (first_group > 0) { lo = gi == 0 ? 0 : first_group; hi = gi == 0 ? first_group : nbh; }
       hipStream_t gs = gi == 0 ? s : pool->side[gi - 1];
       KParams kg = kp;
       kg.bh0 = bh0 + lo;
