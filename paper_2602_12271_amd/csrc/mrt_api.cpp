@@ -704,8 +704,18 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
         if (hipStreamWaitEvent(pool->side[gi - 1], pool->fork, 0) != hipSuccess) status = MRT_ERR_HIP;
       if (status != MRT_OK) { set_error("helper stream fork failed"); break; }
     }
+    // two groups: as in the forward call, the first takes the heads whose stage L workgroups fill
+    // the chip exactly once when those are at least half of the pass
+    int first_group = 0;
+    if (ngroups == 2) {
+      const long long wgs_per_head = (long long)pl.ntq_total * pl.kp.b2;
+      const long long slots = (pl.kp.b1 <= 96 ? 2LL : 1LL) * compute_units();
+      const int per_round = (int)(slots / (wgs_per_head > 0 ? wgs_per_head : 1));
+      if (per_round < nbh && 2 * per_round >= nbh) first_group = per_round;
+    }
     for (int gi = 0; gi < ngroups && status == MRT_OK; ++gi) {
-      const int lo = (int)((long long)nbh * gi / ngroups), hi = (int)((long long)nbh * (gi + 1) / ngroups);
+      int lo = (int)((long long)nbh * gi / ngroups), hi = (int)((long long)nbh * (gi + 1) / ngroups);
+      if (first_group > 0) { lo = gi == 0 ? 0 : first_group; hi = gi == 0 ? first_group : nbh; }
       status = run_heads(bh0, lo, hi, gi == 0 ? s : pool->side[gi - 1]);
     }
     // join even after a failed launch, so that the helper streams never run ahead of the caller
