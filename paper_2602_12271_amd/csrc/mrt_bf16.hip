@@ -231,9 +231,9 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
 // ---------------------------------------------------------------------------------------
 constexpr int kHK = 32;    // keys per pipeline step (one register set, one LDS slot)
 constexpr int kRing = 4;   // LDS slots
-// Row padding of the chunk buffers (and of the streamed refine kernel's Q tile) is a template
+// Row padding of the chunk slots (and of the streamed refine kernel's Q tile) is a template
 // parameter PAD of the pieces below: 16 elements as elsewhere (8 measured 1 % slower at the
-// KV-cache shapes), 8 where the smaller tiles let a second workgroup onto the compute unit.
+// KV-cache shapes, and so did unpadded rows with the resident kernels' XOR swizzle).
 
 // Online softmax state of a wave's query tiles.  mrun is the reference the exponentials are taken
 // against (the same in the four lanes that share a query): not the running maximum itself but a
