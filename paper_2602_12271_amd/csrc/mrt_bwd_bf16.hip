@@ -625,6 +625,263 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
     store_rows_f32<D>(dQp + (row_offset(p, a, l) + qcol) * d, o, 1.0f, g, bp.accumulate != 0);
 }
 
+// Sum of the products of the eight bf16 pairs of two 16-byte pieces.
+__device__ inline float dot8_bf16(uint4 a, uint4 b) {
+  const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+  float t = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    t = fmaf(__uint_as_float(aw[e] << 16), __uint_as_float(bw[e] << 16), t);
+    t = fmaf(__uint_as_float(aw[e] & 0xffff0000u), __uint_as_float(bw[e] & 0xffff0000u), t);
+  }
+  return t;
+}
+
+// ---------------------------------------------------------------------------------------
+// The streamed rows kernel for a bf16 workspace, software-pipelined.  Same two sweeps over the key
+// range and the same arithmetic as k_bwdm_l_rows_stream, but the segments of 64 key rows travel
+// through a ring of two LDS slots behind one set of registers: while the waves work on segment s
+// (slot s mod 2), the global loads of segment s + 1 are in flight; they are written to the other
+// slot when the wave is done with s, the loads of s + 2 are issued, and one barrier ends the step.
+// The loop body has no branch around a load, so the waits count exactly (the transposed stores of
+// a step are never waited for), and a step past the end of the range reloads the last segment into
+// the slot nobody reads.  d abar . abar, which the first sweep forms on the way from the two rows,
+// is kept for the second sweep in this (m, j)'s row of d c_L, which the cols kernel overwrites
+// afterwards, so the second sweep does not read abar again.
+// ---------------------------------------------------------------------------------------
+template <int D, bool LAST, int NW>
+__global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u16* Pw, u16* Zw) {
+  const KParams& p = bp.k;
+  constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, NTK = kSegTiles, KS2 = NTK / 2;
+  constexpr int NTHR = 64 * NW, CPR = D / 8, TOTAL = kSeg * CPR;
+  constexpr int LP = NW <= 6 ? kLP : kLPWide;
+  __shared__ __attribute__((aligned(16))) u16 Ks[2][kSeg * LD];    // alpha_L rows of a segment
+  __shared__ __attribute__((aligned(16))) u16 Vs[2][kSeg * LD];    // Y rows (LAST) or d abar rows
+  // per slot: -c_L log2(e) (-inf beyond NK) | d abar . abar | max_l log2 L[l, nk] | 1 / sum_l 2^(log2 L - max)
+  __shared__ __attribute__((aligned(16))) float side[2][4][kSeg];
+
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int g = lane >> 4, c = lane & 15;
+  const int b1 = p.b1, b2 = p.b2, d = D;
+  const int j = blockIdx.x, ml = blockIdx.y, m = p.m0 + ml, bhl = blockIdx.z, bh = p.bh0 + bhl;
+  const int a = m / p.c2, bq = m - a * p.c2;
+  const int NK = visible_key_tile_rows(a, p.c1k, p.ct, p.qt0) * p.c2 * b1;
+  const int nseg = (NK + kSeg - 1) / kSeg;
+  const size_t NKtot = (size_t)p.ntk * b1;
+  const int b = bh / p.H, hd = bh - b * p.H;
+
+  const size_t row0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * NKtot;
+  const u16* aLp = (const u16*)p.aL + row0 * d;
+  const u16* Yp = (const u16*)p.Y + row0 * d;
+  const float* cLp = p.cL + row0;
+  float* tcp = bp.dcL + row0;                  // d abar . abar between the sweeps
+  // rows (nk, j) of the [m][nk][j][d] arrays
+  const size_t arow0 = ((size_t)bhl * p.ntq + ml) * NKtot * b2;
+  const long long qcol = axis_offset(p.cmap, bq * b2 + j);
+  const u16* Qp = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head + qcol * p.qs.token;
+  const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
+  const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
+
+  // the register set behind the ring
+  RowRegs<D, kSeg, NTHR> rA, rB, rC;
+  float sc = 0.f;
+  // SWEEP 1 also fetches abar (for d abar . abar); SWEEP 2 reads that product back instead
+  auto issue = [&](auto sweep, int seg) {
+    constexpr int SWEEP = decltype(sweep)::value;
+    const int k0 = kSeg * (seg < nseg ? seg : nseg - 1);
+    const int valid = NK - k0 < kSeg ? NK - k0 : kSeg;
+    rA.load(aLp + (size_t)k0 * d, PlainRows{D}, valid, tid);
+    if (LAST) {
+      rB.load(Yp + (size_t)k0 * d, PlainRows{D}, valid, tid);
+    } else {
+      const size_t at0 = (arow0 + (size_t)k0 * b2 + j) * d;
+      rB.load((const u16*)bp.dA + at0, PlainRows{(long long)b2 * D}, valid, tid);
+      if (SWEEP == 1) rC.load((const u16*)bp.Anext + at0, PlainRows{(long long)b2 * D}, valid, tid);
+    }
+    // one side value per thread: wave 0 fetches c_L, and for the earlier iterations wave 1 the
+    // column maximum, wave 2 the inverse column sum, wave 3 (second sweep) d abar . abar
+    const int r = tid & 63;
+    const int nkc = k0 + r < NK ? k0 + r : NK - 1;
+    const float* sp = cLp + nkc;
+    if (!LAST) {
+      const size_t at = arow0 + (size_t)nkc * b2 + j;
+      sp = wave == 1 ? bp.cmx + at : wave == 2 ? bp.cinv + at : (wave == 3 && SWEEP == 2) ? tcp + nkc : sp;
+    }
+    sc = *sp;
+  };
+  auto commit = [&](auto sweep, int seg, int slot) {
+    constexpr int SWEEP = decltype(sweep)::value;
+    const int k0 = kSeg * (seg < nseg ? seg : nseg - 1);
+    const int valid = NK - k0 < kSeg ? NK - k0 : kSeg;
+    rA.template store<LD>(Ks[slot], tid);
+    rB.template store<LD>(Vs[slot], tid);
+    if (!LAST && SWEEP == 1) {
+      // the D/8 consecutive lanes that share a row hold 8 features each
+#pragma unroll
+      for (int i = 0; i < RowRegs<D, kSeg, NTHR>::N; ++i) {
+        const int idx = tid + i * NTHR;
+        const int r = idx / CPR, ch = idx - r * CPR;
+        float t = dot8_bf16(rB.v[i], rC.v[i]);
+        t = CPR == 16 ? row16_sum(t) : row8_sum(t);
+        if (idx < TOTAL && ch == 0) {
+          side[slot][1][r] = r < valid ? t : 0.f;
+          if (r < valid) tcp[k0 + r] = t;
+        }
+      }
+    }
+    const int r = tid & 63;
+    const bool ok = k0 + r < NK;
+    const float v = wave == 0 ? (ok ? -sc * kLog2e : -INFINITY) : wave == 1 ? (ok ? sc * kLog2e : 0.f) : (ok ? sc : 0.f);
+    const int which = wave == 0 ? 0 : wave == 1 ? 2 : wave == 2 ? 3 : 1;
+    const bool wr = wave == 0 || (!LAST && (wave < 3 || (wave == 3 && SWEEP == 2)));
+    if (wr) side[slot][which][r] = v;
+  };
+
+  const int lt = wave, l = 16 * lt + c;
+  const bool live = l < b1;                  // a query tile beyond the last one, or its ragged end: zeros
+  const int lc = l < b1 ? l : b1 - 1;
+  bf16x8 qv[KS1], xv[KS1];
+#pragma unroll
+  for (int ks = 0; ks < KS1; ++ks) {
+    qv[ks] = ld_global_16B(Qp + qrow(lc) + 32 * ks + 8 * g);
+    xv[ks] = LAST ? ld_global_16B(dOp + orow(lc) + 32 * ks + 8 * g) : qv[ks];
+  }
+  const float scale2 = p.scale * kLog2e;
+  // regular Monarch under the chunk-causal mask: this lane's query row sees the keys below klim
+  // (key 0 is visible to every row, so the running maxima are finite after the first segment)
+  const int klim = p.rl > 0 ? visible_key_rows(p, lc) : 0x7fffffff;
+
+  // ---- sweep 1: lse2[l] and delta[l]
+  float mz = -INFINITY, sz = 0.f;            // running maximum / sum of 2^(z - mz)
+  float mw = -INFINITY, dw = 0.f;            // the same for the shifted logits, weighted sum of u
+  {
+    const std::integral_constant<int, 1> sw;
+    issue(sw, 0);
+    commit(sw, 0, 0);
+    issue(sw, 1);
+    __syncthreads();
+    for (int sg = 0; sg < nseg; ++sg) {
+      const int slot = sg & 1, k0 = kSeg * sg;
+      const u16* Ksh = Ks[slot];
+      const u16* Vsh = Vs[slot];
+      const float *biash = side[slot][0], *tcsh = side[slot][1], *cmsh = side[slot][2], *cish = side[slot][3];
+      f32x4 s[NTK], dl[NTK];
+      rows_dot<D, NTK, LD>(Ksh, qv, s, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      rows_dot<D, NTK, LD>(Vsh, xv, dl, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      float mx = -INFINITY, mxw = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < NTK; ++kt) {
+        const f32x4 bi = mask_bias(*(const f32x4*)(biash + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
+        f32x4 cm = {0.f, 0.f, 0.f, 0.f};
+        if (!LAST) cm = *(const f32x4*)(cmsh + 16 * kt + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          s[kt][r] = fmaf(s[kt][r], scale2, bi[r]);
+          mx = fmaxf(mx, s[kt][r]);
+          if (!LAST) mxw = fmaxf(mxw, s[kt][r] - cm[r]);
+        }
+      }
+      const float mzn = fmaxf(mz, xmax(mx));
+      const float mwn = LAST ? mzn : fmaxf(mw, xmax(mxw));
+      float ps = 0.f, pd = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < NTK; ++kt) {
+        f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {1.f, 1.f, 1.f, 1.f}, tc = {0.f, 0.f, 0.f, 0.f};
+        if (!LAST) {
+          cm = *(const f32x4*)(cmsh + 16 * kt + 4 * g);
+          ci = *(const f32x4*)(cish + 16 * kt + 4 * g);
+          tc = *(const f32x4*)(tcsh + 16 * kt + 4 * g);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float e = exp2_fast(s[kt][r] - mzn);
+          ps += e;
+          const float ew = LAST ? e : exp2_fast(s[kt][r] - cm[r] - mwn) * ci[r];
+          pd = fmaf(ew, dl[kt][r] - tc[r], pd);
+        }
+      }
+      sz = fmaf(sz, exp2_fast(mz - mzn), xsum(ps));
+      dw = fmaf(dw, exp2_fast((LAST ? mz : mw) - mwn), xsum(pd));
+      mz = mzn;
+      mw = mwn;
+      commit(sw, sg + 1, slot ^ 1);
+      issue(sw, sg + 2);
+      __syncthreads();
+    }
+  }
+  const float lse2 = mz + log2_fast(sz);
+  const float delta = dw * exp2_fast((LAST ? mz : mw) - lse2);
+
+  // ---- sweep 2: L (or w), dZ, their transposed copies, dQ
+  float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
+  u16* Pt = Pw + row0 * LP;
+  u16* Zt = Zw + row0 * LP;
+  f32x4 o[NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) o[vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  {
+    const std::integral_constant<int, 2> sw;
+    issue(sw, 0);
+    commit(sw, 0, 0);
+    issue(sw, 1);
+    __syncthreads();
+    for (int sg = 0; sg < nseg; ++sg) {
+      const int slot = sg & 1, k0 = kSeg * sg;
+      const u16* Ksh = Ks[slot];
+      const u16* Vsh = Vs[slot];
+      const float *biash = side[slot][0], *tcsh = side[slot][1], *cmsh = side[slot][2], *cish = side[slot][3];
+      f32x4 s[NTK], dl[NTK], wq[NTK];
+      rows_dot<D, NTK, LD>(Ksh, qv, s, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      rows_dot<D, NTK, LD>(Vsh, xv, dl, lane);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kt = 0; kt < NTK; ++kt) {
+        const f32x4 bi = mask_bias(*(const f32x4*)(biash + 16 * kt + 4 * g), k0 + 16 * kt + 4 * g, klim);
+        f32x4 cm = {0.f, 0.f, 0.f, 0.f}, ci = {0.f, 0.f, 0.f, 0.f}, tc = {0.f, 0.f, 0.f, 0.f};
+        if (!LAST) {
+          cm = *(const f32x4*)(cmsh + 16 * kt + 4 * g);
+          ci = *(const f32x4*)(cish + 16 * kt + 4 * g);
+          tc = *(const f32x4*)(tcsh + 16 * kt + 4 * g);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float logl = fmaf(s[kt][r], scale2, bi[r]) - lse2;           // log2 L, -inf beyond NK
+          const float L = live ? exp2_fast(logl) : 0.f;
+          const float w = LAST ? L : (live ? exp2_fast(logl - cm[r]) * ci[r] : 0.f);
+          const float dz = w * (dl[kt][r] - tc[r]) - L * delta;
+          wq[kt][r] = w;
+          dl[kt][r] = dz;
+          const int nk = k0 + 16 * kt + 4 * g + r;
+          if (nk < NK) {
+            Pt[(size_t)nk * LP + l] = f2bf(w);
+            Zt[(size_t)nk * LP + l] = f2bf(dz);
+          }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // dQ[l] += scale sum_nk dZ[l,nk] aL[nk] (+ sum_nk w[l,nk] dA[nk])
+#pragma unroll
+      for (int st = 0; st < KS2; ++st) {
+        const bf16x8 pz = pack8(dl[2 * st] * p.scale, dl[2 * st + 1] * p.scale);
+        pv_step<D, LD>(Ksh + 32 * st * LD, pz, o, lane);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!LAST) {
+          const bf16x8 pw = pack8(wq[2 * st], wq[2 * st + 1]);
+          pv_step<D, LD>(Vsh + 32 * st * LD, pw, o, lane);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      commit(sw, sg + 1, slot ^ 1);
+      issue(sw, sg + 2);
+      __syncthreads();
+    }
+  }
+  if (live) store_rows_f32<D>(dQp + (row_offset(p, a, l) + qcol) * d, o, 1.0f, g, bp.accumulate != 0);
+}
+
 // ---------------------------------------------------------------------------------------
 // stage L backward, cols kernel, one workgroup per (m, j)
 // ---------------------------------------------------------------------------------------
@@ -1076,7 +1333,16 @@ static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, b
   if (16 * nkt > kBRows) {
     // key range beyond the resident kernel: streamed, one wave per query tile (always six or ten
     // waves: the staging loops are laid out for the full workgroup)
-    if (nlt <= 6) {
+    if constexpr (sizeof(TW) == 2) {
+      // bf16 workspace: the pipelined kernel
+      if (nlt <= 6) {
+        if (last) k_bwdm_l_rows_ring<D, true, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+        else k_bwdm_l_rows_ring<D, false, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+      } else {
+        if (last) k_bwdm_l_rows_ring<D, true, 10><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+        else k_bwdm_l_rows_ring<D, false, 10><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+      }
+    } else if (nlt <= 6) {
       if (last) k_bwdm_l_rows_stream<D, true, TW, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
       else k_bwdm_l_rows_stream<D, false, TW, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
     } else {

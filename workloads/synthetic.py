@@ -98,6 +98,10 @@ WORKLOADS: Dict[str, Workload] = {
     "T5-480-hw": Workload("T5-480-hw", 1, 12, 128, 21, 21, 30, 52, 30, 52, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
     "T5-720-3hw": Workload("T5-720-3hw", 1, 12, 128, 21, 21, 45, 80, 135, 80, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
     "T5-720-hw": Workload("T5-720-hw", 1, 12, 128, 21, 21, 45, 80, 45, 80, 1, 1, 0, 0, "bf16", _INV_SQRT128, True),
+    # The whole 21-frame sequence under the block-causal mask (chunks of 3 frames), the shape a
+    # training step of the autoregressive model runs (forward and backward): query tile row a sees
+    # the key tile rows of chunks 0 .. a, so the stage L problems differ sevenfold in length.
+    "BC-480-3hw": Workload("BC-480-3hw", 1, 12, 128, 21, 21, 30, 52, 90, 52, 1, 1, 3, 0, "bf16", _INV_SQRT128, True),
     # C1's tensors under the other aligned block assignments that fit the kernels' block limits
     # (Sec. 4.1): (w, fh) = (52, 90) and (fw, h) = (156, 30), regular Monarch, T = 2
     "C1-w_fh": Workload("C1-w_fh", 1, 12, 128, 3, 3, 30, 52, 52, 90, 0, 2, 0, 0, "bf16", _INV_SQRT128, True,
