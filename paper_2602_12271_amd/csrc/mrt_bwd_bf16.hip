@@ -648,17 +648,30 @@ __device__ inline float dot8_bf16(uint4 a, uint4 b) {
 // the slot nobody reads.  d abar . abar, which the first sweep forms on the way from the two rows,
 // is kept for the second sweep in this (m, j)'s row of d c_L, which the cols kernel overwrites
 // afterwards, so the second sweep does not read abar again.
+//
+// NQT query tiles (6 for b1 <= 96, 10 for b1 <= 144).  A workgroup of more than four waves has a
+// compute unit to itself (its waves do not spread evenly over the SIMDs, so a second one does not
+// fit beside it), and six waves leave half of the unit's wave slots empty: with KSPLIT = 2 every
+// query tile is owned by two waves, each taking half of a segment's key tiles, twelve waves in
+// all.  The two halves' row statistics are merged after the first sweep and their partial dQ rows
+// after the second, through LDS.  (KSPLIT = 2 needs every row to see key 32 of the range, which
+// holds unless regular Monarch runs under the chunk-causal mask: the host picks KSPLIT = 1 then.)
 // ---------------------------------------------------------------------------------------
-template <int D, bool LAST, int NW>
-__global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u16* Pw, u16* Zw) {
+template <int D, bool LAST, int NQT, int KSPLIT>
+__global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdParams bp, u16* Pw, u16* Zw) {
   const KParams& p = bp.k;
-  constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, NTK = kSegTiles, KS2 = NTK / 2;
+  constexpr int NW = NQT * KSPLIT;
+  constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, NTK = kSegTiles / KSPLIT, KS2 = NTK / 2;
   constexpr int NTHR = 64 * NW, CPR = D / 8, TOTAL = kSeg * CPR;
-  constexpr int LP = NW <= 6 ? kLP : kLPWide;
-  __shared__ __attribute__((aligned(16))) u16 Ks[2][kSeg * LD];    // alpha_L rows of a segment
-  __shared__ __attribute__((aligned(16))) u16 Vs[2][kSeg * LD];    // Y rows (LAST) or d abar rows
+  constexpr int LP = NQT <= 6 ? kLP : kLPWide;
+  static_assert(NTK % 2 == 0 && 4 * kSeg * LD * 2 >= (KSPLIT - 1) * NQT * NVT * 64 * 16, "LDS reuse");
+  // per slot: alpha_L rows of a segment (Ks), Y rows (LAST) or d abar rows (Vs)
+  __shared__ __attribute__((aligned(16))) u16 ring[4 * kSeg * LD];
+  u16 (*Ks)[kSeg * LD] = (u16 (*)[kSeg * LD])ring;
+  u16 (*Vs)[kSeg * LD] = (u16 (*)[kSeg * LD])(ring + 2 * kSeg * LD);
   // per slot: -c_L log2(e) (-inf beyond NK) | d abar . abar | max_l log2 L[l, nk] | 1 / sum_l 2^(log2 L - max)
   __shared__ __attribute__((aligned(16))) float side[2][4][kSeg];
+  __shared__ __attribute__((aligned(16))) f32x4 halves[KSPLIT][NQT][16];   // row statistics of the key halves
 
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
@@ -737,7 +750,9 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u
     if (wr) side[slot][which][r] = v;
   };
 
-  const int lt = wave, l = 16 * lt + c;
+  // wave -> query tile lt and key half kh: key tiles NTK kh .. NTK kh + NTK - 1 of every segment
+  const int kh = wave / NQT, lt = wave - kh * NQT, l = 16 * lt + c;
+  const int koff = 16 * NTK * kh;
   const bool live = l < b1;                  // a query tile beyond the last one, or its ragged end: zeros
   const int lc = l < b1 ? l : b1 - 1;
   bf16x8 qv[KS1], xv[KS1];
@@ -761,10 +776,11 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u
     issue(sw, 1);
     __syncthreads();
     for (int sg = 0; sg < nseg; ++sg) {
-      const int slot = sg & 1, k0 = kSeg * sg;
-      const u16* Ksh = Ks[slot];
-      const u16* Vsh = Vs[slot];
-      const float *biash = side[slot][0], *tcsh = side[slot][1], *cmsh = side[slot][2], *cish = side[slot][3];
+      const int slot = sg & 1, k0 = kSeg * sg + koff;
+      const u16* Ksh = Ks[slot] + koff * LD;
+      const u16* Vsh = Vs[slot] + koff * LD;
+      const float *biash = side[slot][0] + koff, *tcsh = side[slot][1] + koff, *cmsh = side[slot][2] + koff,
+                  *cish = side[slot][3] + koff;
       f32x4 s[NTK], dl[NTK];
       rows_dot<D, NTK, LD>(Ksh, qv, s, lane);
       __builtin_amdgcn_sched_barrier(0);
@@ -811,6 +827,23 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u
       __syncthreads();
     }
   }
+  if constexpr (KSPLIT > 1) {
+    // the halves' statistics, merged in the same order by every wave of a tile
+    if (g == 0) halves[kh][lt][c] = f32x4{mz, sz, mw, dw};
+    __syncthreads();
+    f32x4 h = halves[0][lt][c];
+    mz = h[0]; sz = h[1]; mw = h[2]; dw = h[3];
+#pragma unroll
+    for (int q = 1; q < KSPLIT; ++q) {
+      h = halves[q][lt][c];
+      const float mzn = fmaxf(mz, h[0]), mwn = fmaxf(mw, h[2]);
+      sz = fmaf(sz, exp2_fast(mz - mzn), h[1] * exp2_fast(h[0] - mzn));
+      dw = fmaf(dw, exp2_fast((LAST ? mz : mw) - (LAST ? mzn : mwn)),
+                h[3] * exp2_fast((LAST ? h[0] : h[2]) - (LAST ? mzn : mwn)));
+      mz = mzn;
+      mw = mwn;
+    }
+  }
   const float lse2 = mz + log2_fast(sz);
   const float delta = dw * exp2_fast((LAST ? mz : mw) - lse2);
 
@@ -828,10 +861,11 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u
     issue(sw, 1);
     __syncthreads();
     for (int sg = 0; sg < nseg; ++sg) {
-      const int slot = sg & 1, k0 = kSeg * sg;
-      const u16* Ksh = Ks[slot];
-      const u16* Vsh = Vs[slot];
-      const float *biash = side[slot][0], *tcsh = side[slot][1], *cmsh = side[slot][2], *cish = side[slot][3];
+      const int slot = sg & 1, k0 = kSeg * sg + koff;
+      const u16* Ksh = Ks[slot] + koff * LD;
+      const u16* Vsh = Vs[slot] + koff * LD;
+      const float *biash = side[slot][0] + koff, *tcsh = side[slot][1] + koff, *cmsh = side[slot][2] + koff,
+                  *cish = side[slot][3] + koff;
       f32x4 s[NTK], dl[NTK], wq[NTK];
       rows_dot<D, NTK, LD>(Ksh, qv, s, lane);
       __builtin_amdgcn_sched_barrier(0);
@@ -878,6 +912,20 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_ring(BwdParams bp, u
       issue(sw, sg + 2);
       __syncthreads();
     }
+  }
+  if constexpr (KSPLIT > 1) {
+    // partial dQ rows of the upper key halves, through the ring's LDS (no longer in use)
+    f32x4* part = (f32x4*)ring;
+    if (kh > 0) {
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) part[(((kh - 1) * NQT + lt) * NVT + vt) * 64 + lane] = o[vt];
+    }
+    __syncthreads();
+    if (kh > 0) return;
+#pragma unroll
+    for (int q = 1; q < KSPLIT; ++q)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) o[vt] += part[(((q - 1) * NQT + lt) * NVT + vt) * 64 + lane];
   }
   if (live) store_rows_f32<D>(dQp + (row_offset(p, a, l) + qcol) * d, o, 1.0f, g, bp.accumulate != 0);
 }
@@ -1335,12 +1383,15 @@ static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, b
     // waves: the staging loops are laid out for the full workgroup)
     if constexpr (sizeof(TW) == 2) {
       // bf16 workspace: the pipelined kernel
-      if (nlt <= 6) {
-        if (last) k_bwdm_l_rows_ring<D, true, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
-        else k_bwdm_l_rows_ring<D, false, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+      if (nlt <= 6 && bp.k.rl == 0) {
+        if (last) k_bwdm_l_rows_ring<D, true, 6, 2><<<grid, 768, 0, s>>>(bp, Pw, Zw);
+        else k_bwdm_l_rows_ring<D, false, 6, 2><<<grid, 768, 0, s>>>(bp, Pw, Zw);
+      } else if (nlt <= 6) {
+        if (last) k_bwdm_l_rows_ring<D, true, 6, 1><<<grid, 384, 0, s>>>(bp, Pw, Zw);
+        else k_bwdm_l_rows_ring<D, false, 6, 1><<<grid, 384, 0, s>>>(bp, Pw, Zw);
       } else {
-        if (last) k_bwdm_l_rows_ring<D, true, 10><<<grid, 640, 0, s>>>(bp, Pw, Zw);
-        else k_bwdm_l_rows_ring<D, false, 10><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+        if (last) k_bwdm_l_rows_ring<D, true, 10, 1><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+        else k_bwdm_l_rows_ring<D, false, 10, 1><<<grid, 640, 0, s>>>(bp, Pw, Zw);
       }
     } else if (nlt <= 6) {
       if (last) k_bwdm_l_rows_stream<D, true, TW, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
