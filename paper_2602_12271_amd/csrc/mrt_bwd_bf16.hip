@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
     const int l = 16 * lt + c;
     if (lt >= nlt) {
       for (int nk = g; nk < NK; nk += 4) {
-        Pt[(size_t)nk * kLP + l] = 0;
+        if (LAST) Pt[(size_t)nk * kLP + l] = 0;
         Zt[(size_t)nk * kLP + l] = 0;
       }
       continue;
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
         dl[kt][r] = dz;
         const int nk = 16 * kt + 4 * g + r;
         if (nk < NK) {
-          Pt[(size_t)nk * kLP + l] = f2bf(wq[kt][r]);
+          if (LAST) Pt[(size_t)nk * kLP + l] = f2bf(wq[kt][r]);   // only dY, at t = T, is formed from it
           Zt[(size_t)nk * kLP + l] = f2bf(dz);
         }
       }
@@ -572,7 +572,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
       // the wide pitch): the tiles beyond the last query tile are zeros
       if (lt < (NW <= 6 ? 2 * ((nlt + 1) / 2) : NW))
         for (int nk = k0 + g; nk < NK && nk < k0 + kSeg; nk += 4) {
-          Pt[(size_t)nk * LP + l] = 0;
+          if (LAST) Pt[(size_t)nk * LP + l] = 0;
           Zt[(size_t)nk * LP + l] = 0;
         }
       continue;
@@ -601,7 +601,7 @@ __global__ __launch_bounds__(64 * NW, 3) void k_bwdm_l_rows_stream(BwdParams bp,
         dl[kt][r] = dz;
         const int nk = k0 + 16 * kt + 4 * g + r;
         if (nk < NK) {
-          Pt[(size_t)nk * LP + l] = f2bf(w);
+          if (LAST) Pt[(size_t)nk * LP + l] = f2bf(w);       // only dY, at t = T, is formed from it
           Zt[(size_t)nk * LP + l] = f2bf(dz);
         }
       }
@@ -890,7 +890,7 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
           dl[kt][r] = dz;
           const int nk = k0 + 16 * kt + 4 * g + r;
           if (nk < NK) {
-            Pt[(size_t)nk * LP + l] = f2bf(w);
+            if (LAST) Pt[(size_t)nk * LP + l] = f2bf(w);       // only dY, at t = T, is formed from it
             Zt[(size_t)nk * LP + l] = f2bf(dz);
           }
         }
