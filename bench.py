@@ -175,6 +175,39 @@ def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
+    # the same training step as two calls that hand the intermediates over (forward that saves them,
+    # reverse sweep from them), when the workspace of all heads fits half of the device memory
+    saved = None
+    nsv = lib.monarch_attn_bwd_saved_workspace_bytes(pref, wl.b1, wl.b2, wl.tile, wl.iters)
+    if 0 < nsv < torch.cuda.get_device_properties(Q.device).total_memory // 2:
+        ws = None                       # release the per-pass workspace first
+        wsv = torch.empty(nsv, dtype=torch.uint8, device=Q.device)
+        O = torch.empty_like(Q)
+
+        def fwd_save():
+            st = lib.monarch_attn_fwd_save(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), pref, wl.b1,
+                                           wl.b2, wl.tile, wl.iters, wl.causal_chunk, wsv.data_ptr(), nsv, stream)
+            if st != 0:
+                raise RuntimeError(f"monarch_attn_fwd_save failed: {pkg.last_error()}")
+
+        def bwd_saved():
+            st = lib.monarch_attn_bwd_saved(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(),
+                                            dQ.data_ptr(), dK.data_ptr(), dV.data_ptr(), pref, wl.b1, wl.b2,
+                                            wl.tile, wl.iters, wl.causal_chunk, wsv.data_ptr(), nsv, stream)
+            if st != 0:
+                raise RuntimeError(f"monarch_attn_bwd_saved failed: {pkg.last_error()}")
+
+        times = []
+        for fn in (fwd_save, bwd_saved):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) * 1e3 / steps)
+        saved = {"fwd_save_ms": times[0], "bwd_saved_ms": times[1], "workspace_mb": nsv / 1e6}
     flops = backward_flops(wl)
     ach = flops / (ms / 1e3) / 1e12
     # the library's rule for running every stage on the bf16 matrix unit
@@ -212,6 +245,7 @@ def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
                              + ", whole call: forward recomputation + reverse sweep; blocks of this size keep "
                                "the call latency-bound, far below either roofline"},
         "cpu_baseline": cpu, "parity_max_abs_err_head0": parity,
+        "saved_intermediates": saved,
     }))
 
 

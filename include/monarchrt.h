@@ -191,6 +191,27 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
                             int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
                             void* hip_stream);
 
+/* The same training step in two calls that hand the intermediates over instead of forming them
+ * twice (Sec. 4.3: finetuning runs the operator forward and backward on the same inputs):
+ * monarch_attn_fwd_save computes O as monarch_attn_fwd does, with the arithmetic the backward pass
+ * uses (bf16 matrix unit where monarch_attn_bwd would use it, fp32 otherwise), and leaves the
+ * intermediates of every iteration in `workspace`; monarch_attn_bwd_saved, given the same Q, K, V,
+ * arguments and workspace, runs only the reverse sweep and returns exactly the gradients
+ * monarch_attn_bwd returns.  Arguments, layouts, limits and error behaviour as for
+ * monarch_attn_fwd and monarch_attn_bwd, except that the workspace holds every (batch, head) at
+ * once: at least monarch_attn_bwd_saved_workspace_bytes() bytes (0: unsupported problem), else
+ * MRT_ERR_WORKSPACE.  The caller keeps the workspace untouched between the two calls and orders
+ * them (same stream, or an event); monarch_attn_bwd_saved leaves the saved intermediates intact,
+ * so it may be called again (another dO) without a new forward call. */
+size_t monarch_attn_bwd_saved_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
+mrt_status monarch_attn_fwd_save(const void* Q, const void* K, const void* V, void* O, const mrt_problem* p,
+                                 int b1, int b2, int tile, int iters, int causal_chunk, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream);
+mrt_status monarch_attn_bwd_saved(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
+                                  float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
+                                  int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream);
+
 /* Dense baseline  O = softmax(scale * Q K^T + mask) V  (Sec. 2.2), flash-style, no workspace.
  * causal_chunk > 0 masks, per token, keys whose frame's chunk is later than the query frame's
  * chunk (query frames offset by q_frame_offset). */

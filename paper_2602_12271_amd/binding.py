@@ -24,6 +24,7 @@ EXPORTED = [
     "mrt_profile_enable", "mrt_profile_read", "mrt_set_head_groups",
     "monarch_attn_bwd", "monarch_attn_bwd_workspace_bytes", "monarch_attn_bwd_workspace_min_bytes",
     "monarch_attn_fwd_noalloc",
+    "monarch_attn_bwd_saved_workspace_bytes", "monarch_attn_fwd_save", "monarch_attn_bwd_saved",
 ]
 NOALLOC_SCRATCH_BYTES = 128 << 20
 ASSIGNMENTS = {"fh_w": 0, "w_fh": 1, "fw_h": 2, "h_fw": 3, "f_hw": 4, "hw_f": 5}
@@ -82,6 +83,12 @@ def load_library() -> ctypes.CDLL:
     lib.monarch_attn_bwd_workspace_bytes.restype = sz
     lib.monarch_attn_bwd.argtypes = [vp, vp, vp, vp, fp, fp, fp, P, ci, ci, ci, ci, ci, vp, sz, vp]
     lib.monarch_attn_bwd.restype = ci
+    lib.monarch_attn_bwd_saved_workspace_bytes.argtypes = [P, ci, ci, ci, ci]
+    lib.monarch_attn_bwd_saved_workspace_bytes.restype = sz
+    lib.monarch_attn_fwd_save.argtypes = [vp, vp, vp, vp, P, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.monarch_attn_fwd_save.restype = ci
+    lib.monarch_attn_bwd_saved.argtypes = [vp, vp, vp, vp, fp, fp, fp, P, ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.monarch_attn_bwd_saved.restype = ci
     lib.dense_attn_check.argtypes = [P, ci]
     lib.dense_attn_check.restype = ci
     lib.dense_attn_fwd.argtypes = [vp, vp, vp, vp, P, ci, vp]
@@ -240,6 +247,52 @@ def monarch_attn_bwd(Q, K, V, dO, *, f_q, f_kv, h, w, b1, b2, tile, iters, causa
                               dK.data_ptr(), dV.data_ptr(), ctypes.byref(prob), b1, b2, tile, iters,
                               causal_chunk, workspace.data_ptr(),
                               workspace.numel() * workspace.element_size(), s)
+    if st != MRT_OK:
+        _raise(lib, st)
+    return dQ, dK, dV
+
+
+def monarch_attn_fwd_save(Q, K, V, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,
+                          q_frame_offset=0, scale=1.0, workspace=None, out=None, stream=None, assign="fh_w",
+                          tile_h=0, compute=MRT_COMPUTE_DEFAULT):
+    """Forward call of a training step: returns (O, workspace); the workspace holds the intermediates of
+    every iteration for monarch_attn_bwd_saved."""
+    import torch
+    lib = load_library()
+    O = torch.empty_like(Q) if out is None else out
+    prob = _torch_problem(Q, K, V, O, f_q, f_kv, h, w, q_frame_offset, scale, compute, assign, tile_h)
+    if workspace is None:
+        nbytes = lib.monarch_attn_bwd_saved_workspace_bytes(ctypes.byref(prob), b1, b2, tile, iters)
+        if nbytes == 0:
+            st = lib.monarch_attn_check(ctypes.byref(prob), b1, b2, tile, iters, causal_chunk)
+            _raise(lib, st if st != MRT_OK else MRT_ERR_UNSUPPORTED)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=Q.device)
+    s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+    st = lib.monarch_attn_fwd_save(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), ctypes.byref(prob),
+                                   b1, b2, tile, iters, causal_chunk, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), s)
+    if st != MRT_OK:
+        _raise(lib, st)
+    return O, workspace
+
+
+def monarch_attn_bwd_saved(Q, K, V, dO, workspace, *, f_q, f_kv, h, w, b1, b2, tile, iters, causal_chunk=0,
+                           q_frame_offset=0, scale=1.0, stream=None, assign="fh_w", tile_h=0,
+                           compute=MRT_COMPUTE_DEFAULT):
+    """Gradients (dQ, dK, dV) from the intermediates monarch_attn_fwd_save left in `workspace` (same
+    Q, K, V and arguments): only the reverse sweep runs."""
+    import torch
+    lib = load_library()
+    assert dO.shape == Q.shape and dO.dtype == Q.dtype and dO.is_cuda
+    prob = _torch_problem(Q, K, V, dO, f_q, f_kv, h, w, q_frame_offset, scale, compute, assign, tile_h)
+    dQ = torch.empty(Q.shape, dtype=torch.float32, device=Q.device)
+    dK = torch.empty(K.shape, dtype=torch.float32, device=Q.device)
+    dV = torch.empty(V.shape, dtype=torch.float32, device=Q.device)
+    s = torch.cuda.current_stream(Q.device).cuda_stream if stream is None else stream
+    st = lib.monarch_attn_bwd_saved(Q.data_ptr(), K.data_ptr(), V.data_ptr(), dO.data_ptr(), dQ.data_ptr(),
+                                    dK.data_ptr(), dV.data_ptr(), ctypes.byref(prob), b1, b2, tile, iters,
+                                    causal_chunk, workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), s)
     if st != MRT_OK:
         _raise(lib, st)
     return dQ, dK, dV

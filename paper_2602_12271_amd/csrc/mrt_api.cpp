@@ -578,28 +578,41 @@ size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, in
   return per * heads;
 }
 
-mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
-                            float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
-                            int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
-                            void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// What a call of the backward machinery does: everything (monarch_attn_bwd), only the forward
+// intermediates plus O (monarch_attn_fwd_save), or only the reverse sweep over intermediates a
+// monarch_attn_fwd_save call left in the workspace (monarch_attn_bwd_saved).
+enum BwdMode { kBwdAll, kBwdForwardOnly, kBwdSweepOnly };
+
+mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, void* O, const void* dO,
+                   float* dQ, float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
+                   int iters, int causal_chunk, void* workspace, size_t workspace_bytes, void* hip_stream) {
   using namespace mrt;
   Plan pl;
   mrt_status st = bwd_plan(p, b1, b2, tile, iters, causal_chunk, &pl);
   if (st != MRT_OK) return st;
-  if (!Q || !K || !V || !dO || !dQ || !dK || !dV || !workspace) {
-    set_error("Q, K, V, dO, dQ, dK, dV and workspace must be non-NULL");
+  if (!Q || !K || !V || !workspace) { set_error("Q, K, V and workspace must be non-NULL"); return MRT_ERR_NULL; }
+  if (mode == kBwdForwardOnly ? !O : (!dO || !dQ || !dK || !dV)) {
+    set_error(mode == kBwdForwardOnly ? "O must be non-NULL" : "dO, dQ, dK and dV must be non-NULL");
     return MRT_ERR_NULL;
   }
   if ((uintptr_t)workspace % 256) { set_error("workspace must be 256-byte aligned"); return MRT_ERR_WORKSPACE; }
   const BwdLayout L = bwd_layout(pl, p);
   if (L.mfma) {
-    const void* ptrs[2] = {Q, dO};
+    const void* ptrs[2] = {Q, mode == kBwdForwardOnly ? (const void*)O : dO};
     for (const void* q : ptrs)
       if ((uintptr_t)q % 16) { set_error("bf16 path needs 16-byte aligned tensors"); return MRT_ERR_SHAPE; }
   }
-  if (workspace_bytes < L.per_head) {
-    set_error("workspace has %zu bytes, the backward pass of one (batch,head) needs %zu", workspace_bytes,
-              L.per_head);
+  // intermediates handed from one call to the next: every (batch, head) stays in the workspace
+  const size_t need = mode == kBwdAll ? L.per_head : L.per_head * (size_t)pl.B * pl.kp.H;
+  if (workspace_bytes < need) {
+    if (mode == kBwdAll)
+      set_error("workspace has %zu bytes, the backward pass of one (batch,head) needs %zu", workspace_bytes, need);
+    else
+      set_error("workspace has %zu bytes, keeping the intermediates of every (batch,head) needs %zu",
+                workspace_bytes, need);
     return MRT_ERR_WORKSPACE;
   }
   const int BH = pl.B * pl.kp.H, T = pl.T;
@@ -621,14 +634,14 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
   auto run_heads = [&](int bh0, int lo, int hi, hipStream_t gs) -> mrt_status {
     const int nbh = hi - lo;
     KParams kp = pl.kp;
-    kp.Q = Q; kp.K = K; kp.V = V; kp.O = nullptr;
+    kp.Q = Q; kp.K = K; kp.V = V; kp.O = mode == kBwdForwardOnly ? O : nullptr;
     kp.bh0 = bh0 + lo; kp.m0 = 0; kp.ntq = pl.ntq_total;
     kp.Y = arrD(L.off_Y(), lo);
     hipError_t e;
-    // forward intermediates of every iteration (the last iteration's stage L is not needed): by
-    // the bf16 forward kernels when every backward stage runs on the matrix unit (the arrays then
-    // hold bf16), else by the fp32 kernels
-    for (int t = 1; t <= T; ++t) {
+    // forward intermediates of every iteration (the last iteration's stage L only when O is asked
+    // for): by the bf16 forward kernels when every backward stage runs on the matrix unit (the
+    // arrays then hold bf16), else by the fp32 kernels
+    for (int t = 1; t <= T && mode != kBwdSweepOnly; ++t) {
       kp.aL = arrD(L.off_aL(t), lo);
       kp.cL = (float*)arrS(L.off_cL(t), lo);
       kp.aR = t >= 2 ? arrD(L.off_aR(t), lo) : nullptr;
@@ -642,8 +655,16 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
         kp.cinv_out = (float*)arrS(L.off_cinv(t + 1), lo);
         e = ws_bf16 ? launch_bf16_stage_l(kp, nbh, false, gs) : launch_f32_stage_l(kp, pl.dtype, nbh, false, gs);
         if (e != hipSuccess) return hip_fail(e, "backward: forward stage L launch");
+      } else if (mode == kBwdForwardOnly) {
+        kp.cmx_out = nullptr; kp.cinv_out = nullptr;
+        e = ws_bf16 ? launch_bf16_stage_l(kp, nbh, true, gs) : launch_f32_stage_l(kp, pl.dtype, nbh, true, gs);
+        if (e != hipSuccess) return hip_fail(e, "forward stage L launch");
       }
     }
+    if (mode == kBwdForwardOnly) return MRT_OK;
+    kp.aL = arrD(L.off_aL(T), lo);
+    kp.cL = (float*)arrS(L.off_cL(T), lo);
+    kp.aR = T >= 2 ? arrD(L.off_aR(T), lo) : nullptr;
     kp.cmx_out = nullptr; kp.cinv_out = nullptr;
     // reverse sweep
     BwdParams bp;
@@ -727,6 +748,38 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
     }
   }
   return status;
+}
+}  // namespace
+
+extern "C" {
+
+mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
+                            float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
+                            int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  return bwd_run(kBwdAll, Q, K, V, nullptr, dO, dQ, dK, dV, p, b1, b2, tile, iters, causal_chunk, workspace,
+                 workspace_bytes, hip_stream);
+}
+
+size_t monarch_attn_bwd_saved_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters) {
+  mrt::Plan pl;
+  if (bwd_plan(p, b1, b2, tile, iters, 0, &pl) != MRT_OK) return 0;
+  return bwd_layout(pl, p).per_head * (size_t)pl.B * pl.kp.H;
+}
+
+mrt_status monarch_attn_fwd_save(const void* Q, const void* K, const void* V, void* O, const mrt_problem* p,
+                                 int b1, int b2, int tile, int iters, int causal_chunk, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+  return bwd_run(kBwdForwardOnly, Q, K, V, O, nullptr, nullptr, nullptr, nullptr, p, b1, b2, tile, iters,
+                 causal_chunk, workspace, workspace_bytes, hip_stream);
+}
+
+mrt_status monarch_attn_bwd_saved(const void* Q, const void* K, const void* V, const void* dO, float* dQ,
+                                  float* dK, float* dV, const mrt_problem* p, int b1, int b2, int tile,
+                                  int iters, int causal_chunk, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  return bwd_run(kBwdSweepOnly, Q, K, V, nullptr, dO, dQ, dK, dV, p, b1, b2, tile, iters, causal_chunk,
+                 workspace, workspace_bytes, hip_stream);
 }
 
 mrt_status dense_attn_check(const mrt_problem* p, int causal_chunk) {

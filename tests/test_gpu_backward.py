@@ -200,6 +200,48 @@ def test_backward_head_groups_do_not_change_the_result(name):
         pkg.binding.set_head_groups(0)
 
 
+@pytest.mark.parametrize("name", ["bf16-stream-mask", "bf16-ragged-T3", "bf16-ragged-T1", "tiled-rect-mask",
+                                  "bf16-b1-135", "regular-T2"])
+def test_forward_that_saves_and_backward_from_saved_intermediates(name):
+    """The training-step pair: monarch_attn_fwd_save gives the forward output (bit for bit where the
+    bf16 forward kernels run it, to the forward tolerance where the fp32 ones do) and leaves the
+    intermediates in a workspace filled with NaNs beforehand; monarch_attn_bwd_saved then returns the
+    very bits monarch_attn_bwd returns, twice in a row (a second dO reuses the saved intermediates)."""
+    wl = dataclasses.replace(CASES[name], heads=3) if CASES[name].heads < 3 else CASES[name]
+    arrays = syn.make_inputs(wl)
+    rng = np.random.default_rng(5)
+    dOs = [rng.standard_normal(arrays[0].shape).astype(np.float32) for _ in range(2)]
+    if wl.dtype == "bf16":
+        dOs = [syn.round_to_bf16(x) for x in dOs]
+    Qd, Kd, Vd, dO1, dO2 = to_device(wl, arrays + tuple(dOs))
+    kw = dict(f_q=wl.f_q, f_kv=wl.f_kv, h=wl.h, w=wl.w, b1=wl.b1, b2=wl.b2, tile=wl.tile,
+              iters=wl.iters, causal_chunk=wl.causal_chunk, q_frame_offset=wl.q_frame_offset,
+              scale=wl.scale, assign=wl.assign, tile_h=wl.tile_h)
+    import ctypes
+    lib = pkg.load_library()
+    prob = pkg.binding._torch_problem(Qd, Kd, Vd, dO1, wl.f_q, wl.f_kv, wl.h, wl.w, wl.q_frame_offset, wl.scale,
+                                      pkg.MRT_COMPUTE_DEFAULT, wl.assign, wl.tile_h)
+    nbytes = lib.monarch_attn_bwd_saved_workspace_bytes(ctypes.byref(prob), wl.b1, wl.b2, wl.tile, wl.iters)
+    assert nbytes > 0
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda:0").view(torch.uint8)
+    O, ws = pkg.monarch_attn_fwd_save(Qd, Kd, Vd, workspace=ws, **kw)
+    O_ref = pkg.monarch_attn_fwd(Qd, Kd, Vd, **kw)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all()
+    every_stage_bf16 = wl.dtype == "bf16" and wl.head_dim in (64, 128) and wl.b1 <= 144 and wl.b2 <= 64
+    if every_stage_bf16 or wl.dtype != "bf16":
+        assert torch.equal(O, O_ref)                 # the same kernels ran
+    else:
+        assert (O.float() - O_ref.float()).abs().max().item() <= 2e-2
+    for dOd in (dO1, dO2):
+        got = pkg.monarch_attn_bwd_saved(Qd, Kd, Vd, dOd, ws, **kw)
+        want = pkg.monarch_attn_bwd(Qd, Kd, Vd, dOd, **kw)
+        torch.cuda.synchronize()
+        for name_g, a, b in zip("QKV", got, want):
+            assert torch.isfinite(a).all(), f"non-finite d{name_g}"
+            assert torch.equal(a, b), f"d{name_g} differs from monarch_attn_bwd"
+
+
 @pytest.mark.parametrize("name", ["bf16-b1-120", "bf16-b1-135", "bf16-stream-mask", "bf16-ragged-T3",
                                   "tiled-rect-mask", "regular-T3"])
 def test_backward_reads_nothing_it_has_not_written(name):

@@ -209,6 +209,32 @@ def test_backward_entry_checks_on_the_host():
                                 fake, 1 << 40, None) == B.MRT_ERR_UNSUPPORTED
 
 
+def test_saved_intermediates_entry_checks_on_the_host():
+    """The training-step pair keeps every (batch, head) in the workspace: its size is the backward
+    pass's size of one head times batch * heads, and both calls refuse anything smaller before any
+    launch."""
+    lib = pkg.load_library()
+    p = problem()
+    ref = ctypes.byref(p)
+    T = 2
+    per_head = lib.monarch_attn_bwd_workspace_min_bytes(ref, 90, 52, 0, T)
+    total = lib.monarch_attn_bwd_saved_workspace_bytes(ref, 90, 52, 0, T)
+    assert total == 12 * per_head
+    assert lib.monarch_attn_bwd_saved_workspace_bytes(ref, 90, 50, 0, T) == 0      # invalid blocks
+    fake = ctypes.c_void_p(4096)
+    args = (ref, 90, 52, 0, T, 0)
+    # room for eleven heads only
+    assert lib.monarch_attn_fwd_save(fake, fake, fake, fake, *args, fake, total - 1, None) == B.MRT_ERR_WORKSPACE
+    assert "every (batch,head)" in pkg.last_error()
+    assert lib.monarch_attn_bwd_saved(fake, fake, fake, fake, fake, fake, fake, *args, fake, total - 1,
+                                      None) == B.MRT_ERR_WORKSPACE
+    assert lib.monarch_attn_fwd_save(fake, fake, fake, None, *args, fake, total, None) == B.MRT_ERR_NULL
+    assert lib.monarch_attn_bwd_saved(fake, fake, fake, None, fake, fake, fake, *args, fake, total,
+                                      None) == B.MRT_ERR_NULL
+    assert lib.monarch_attn_fwd_save(fake, fake, fake, fake, *args, ctypes.c_void_p(4100), total,
+                                     None) == B.MRT_ERR_WORKSPACE                  # misaligned workspace
+
+
 def test_host_entry_points_are_thread_safe():
     """monarch_attn_check and the workspace queries keep no shared state: several host threads calling
     them at once (valid and invalid requests mixed) get the same answers as one thread, and every
