@@ -801,6 +801,9 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
       }
       const float mzn = fmaxf(mz, xmax(mx));
       const float mwn = LAST ? mzn : fmaxf(mw, xmax(mxw));
+      // a wave whose key half has been empty so far (a visible range of fewer than 33 keys under the
+      // mask) still has -inf maxima: its exponents are taken against 0 and come out as zeros
+      const float mzs = mzn == -INFINITY ? 0.f : mzn, mws = mwn == -INFINITY ? 0.f : mwn;
       float ps = 0.f, pd = 0.f;
 #pragma unroll
       for (int kt = 0; kt < NTK; ++kt) {
@@ -812,14 +815,14 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float e = exp2_fast(s[kt][r] - mzn);
+          const float e = exp2_fast(s[kt][r] - mzs);
           ps += e;
-          const float ew = LAST ? e : exp2_fast(s[kt][r] - cm[r] - mwn) * ci[r];
+          const float ew = LAST ? e : exp2_fast(s[kt][r] - cm[r] - mws) * ci[r];
           pd = fmaf(ew, dl[kt][r] - tc[r], pd);
         }
       }
-      sz = fmaf(sz, exp2_fast(mz - mzn), xsum(ps));
-      dw = fmaf(dw, exp2_fast((LAST ? mz : mw) - mwn), xsum(pd));
+      sz = fmaf(sz, exp2_fast(mz - mzs), xsum(ps));
+      dw = fmaf(dw, exp2_fast((LAST ? mz : mw) - mws), xsum(pd));
       mz = mzn;
       mw = mwn;
       commit(sw, sg + 1, slot ^ 1);

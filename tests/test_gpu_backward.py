@@ -49,6 +49,12 @@ CASES = {
     # which the chunk-causal mask shows 80 (a ragged second segment), ragged query tiles
     "bf16-stream-mask": small("bf16", head_dim=128, f_q=2, f_kv=6, h=10, w=14, b1=20, b2=7, tile=1, iters=2,
                               causal_chunk=2, q_frame_offset=2),
+    # streamed key range (156 rows) of which the first query tile row sees 26 under the mask: the waves
+    # that own the upper half of every 64-key segment never meet a visible key there
+    "bf16-stream-short-visible": small("bf16", head_dim=128, f_q=4, f_kv=12, h=13, w=39, b1=26, b2=39, tile=1,
+                                       iters=1, causal_chunk=2, q_frame_offset=0),
+    "bf16-stream-short-visible-T2": small("bf16", head_dim=64, f_q=4, f_kv=12, h=13, w=16, b1=26, b2=8, tile=1,
+                                          iters=2, causal_chunk=2, q_frame_offset=0),
     # 216 key rows, three query tiles (the odd tile count leaves a zero tile), three iterations
     "bf16-stream-T3": small("bf16", head_dim=64, f_q=2, f_kv=6, h=18, w=16, b1=36, b2=8, tile=1, iters=3),
     # nine query tiles (b1 = 135, the 720p tile height): ten waves, the wider transposed arrays,
@@ -243,7 +249,7 @@ def test_forward_that_saves_and_backward_from_saved_intermediates(name):
 
 
 @pytest.mark.parametrize("name", ["bf16-b1-120", "bf16-b1-135", "bf16-stream-mask", "bf16-ragged-T3",
-                                  "tiled-rect-mask", "regular-T3"])
+                                  "tiled-rect-mask", "regular-T3", "bf16-stream-short-visible-T2"])
 def test_backward_reads_nothing_it_has_not_written(name):
     """A workspace full of NaN bit patterns (what a recycled allocation may hold) gives the same bits
     as a zeroed one: every workspace entry a kernel reads was written earlier in the same call,
