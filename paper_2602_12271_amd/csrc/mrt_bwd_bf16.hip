@@ -1080,12 +1080,15 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
 
   // register stages: every global load of a step is issued before the first LDS store
   constexpr bool kF32Ws = sizeof(TW) == 4;
-  RowRegs<D, ROWS, NTHR> rk;                          // K rows
-  RowRegs<D, LAST ? ROWS : 1, NTHR> rv;               // V rows (t = T)
-  RowRegs<D, ROWS, NTHR> ra;                          // Q rows, or abar stored as bf16
-  RowRegsF32<D, kF32Ws ? ROWS : 1, NTHR> raf;         // abar stored as fp32
-  typename std::conditional<kF32Ws, RowRegsF32<D, ROWS, NTHR>, RowRegs<D, ROWS, NTHR>>::type rg;
-  typename std::conditional<kF32Ws, RowRegsF32<D, LAST ? ROWS : 1, NTHR>, RowRegs<D, LAST ? ROWS : 1, NTHR>>::type ry;
+  // (the stages cover the 16 NT rows the waves own; an odd NT leaves 16 more tile rows, which the
+  // 32-row steps of the second products read: zeroed once below and never written again)
+  constexpr int SROWS = 16 * NT;
+  RowRegs<D, SROWS, NTHR> rk;                          // K rows
+  RowRegs<D, LAST ? SROWS : 1, NTHR> rv;               // V rows (t = T)
+  RowRegs<D, SROWS, NTHR> ra;                          // Q rows, or abar stored as bf16
+  RowRegsF32<D, kF32Ws ? SROWS : 1, NTHR> raf;         // abar stored as fp32
+  typename std::conditional<kF32Ws, RowRegsF32<D, SROWS, NTHR>, RowRegs<D, SROWS, NTHR>>::type rg;
+  typename std::conditional<kF32Ws, RowRegsF32<D, LAST ? SROWS : 1, NTHR>, RowRegs<D, LAST ? SROWS : 1, NTHR>>::type ry;
   auto issue_block = [&](const Item& it) {
     const int b = it.bh / p.H, hd = it.bh - b * p.H;
     const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + it.krow * p.ks.token;
@@ -1121,6 +1124,12 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
   issue_block(cur);
   if (ml < p.ntq) issue_tile(cur, ml);
   for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
+  if constexpr (ROWS > SROWS) {
+    for (int idx = SROWS * LD + tid; idx < ROWS * LD; idx += NTHR) {
+      Ks[idx] = 0; As[idx] = 0; Gs[idx] = 0;
+      if (LAST) { Vs[idx] = 0; Ys[idx] = 0; }
+    }
+  }
 
   f32x4 oK[1][NVT], oV[1][NVT];
 #pragma unroll
