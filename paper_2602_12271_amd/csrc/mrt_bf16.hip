@@ -99,9 +99,16 @@ __global__ __launch_bounds__(64 * NT, 4) void k_bf16_stage_r(KParams p, int gs) 
   MRT_STAMP(0);
   // all loads of the block (keys, values, the first tile's query-side rows) are issued before
   // the first LDS store
-  RowRegs<D, ROWS, NTHR> rk;
-  RowRegs<D, LAST ? ROWS : 1, NTHR> rv;
+  // (the register stages cover the 16 NT rows the waves own; with an odd NT the 32-row steps of the
+  // second products read 16 rows more, zeros that no store touches: written once here)
+  constexpr int SROWS = 16 * NT;
+  RowRegs<D, SROWS, NTHR> rk;
+  RowRegs<D, LAST ? SROWS : 1, NTHR> rv;
   rk.load(Kp, TokRows{0, p.cmap, bn * b2, p.ks.token}, b2, tid);
+  if constexpr (ROWS > SROWS) {
+    for (int idx = tid; idx < (ROWS - SROWS) * LD / 8; idx += NTHR)
+      *(uint4*)(Ks + SROWS * LD + 8 * idx) = uint4{0u, 0u, 0u, 0u};
+  }
 
   // query-side rows of this wave (row j = 16*wave + c) go straight to registers: Q[m, k, j, :] in
   // the first iteration (L is the identity), alpha_R / c_R afterwards
