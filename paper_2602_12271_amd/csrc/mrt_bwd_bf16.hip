@@ -138,6 +138,39 @@ __device__ inline void rows_dot(const u16* rows, const bf16x8 (&qv)[D / 32], f32
   }
 }
 
+// The same with the LDS reads of the next pair of row tiles issued ahead of the current pair's
+// MFMAs (two sets of operand registers).  For kernels that run one wave per SIMD: there nothing else
+// hides the latency of an LDS read, and the compiler's own schedule waits for every read right
+// before the MFMA that uses it.
+template <int D, int NTK, int LD>
+__device__ inline void rows_dot_ahead(const u16* rows, const bf16x8 (&qv)[D / 32], f32x4 (&out)[NTK], int lane) {
+  constexpr int KS1 = D / 32, NP = (NTK + 1) / 2;
+  const int g = lane >> 4, c = lane & 15;
+  bf16x8 a[2][2][KS1];
+  auto fetch = [&](int kp, bf16x8 (&dst)[2][KS1]) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (2 * kp + t < NTK) {
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) dst[t][ks] = ld_lds_16B(rows + (16 * (2 * kp + t) + c) * LD + 32 * ks + 8 * g);
+      }
+  };
+#pragma unroll
+  for (int kt = 0; kt < NTK; ++kt) out[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  fetch(0, a[0]);
+#pragma unroll
+  for (int kp = 0; kp < NP; ++kp) {
+    if (kp + 1 < NP) fetch(kp + 1, a[(kp + 1) & 1]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        if (2 * kp + t < NTK) out[2 * kp + t] = mfma(a[kp & 1][t][ks], qv[ks], out[2 * kp + t]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // Second-product step with the contraction slots in natural order (slot (g, e) <-> row 8g + e of
 // the 32-row step), for B operands that come from memory rather than from accumulator registers.
 template <int D, int NB, int LD>
@@ -1187,13 +1220,16 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
           if (LAST) yv[ks] = ld_lds_16B(Ys + j * LD + 32 * ks + 8 * g);
         }
         f32x4 s[NT], dr[NT];
-        rows_dot<D, NT, LD>(Ks, qv, s, lane);
+        // (t = T: one workgroup per compute unit, one wave per SIMD: LDS reads issued ahead)
+        if constexpr (LAST) rows_dot_ahead<D, NT, LD>(Ks, qv, s, lane);
+        else rows_dot<D, NT, LD>(Ks, qv, s, lane);
         __builtin_amdgcn_sched_barrier(0);
-        rows_dot<D, NT, LD>(Ks, gv, dr, lane);
+        if constexpr (LAST) rows_dot_ahead<D, NT, LD>(Ks, gv, dr, lane);
+        else rows_dot<D, NT, LD>(Ks, gv, dr, lane);
         __builtin_amdgcn_sched_barrier(0);
         if (LAST) {
           f32x4 dy[NT];
-          rows_dot<D, NT, LD>(Vs, yv, dy, lane);
+          rows_dot_ahead<D, NT, LD>(Vs, yv, dy, lane);
 #pragma unroll
           for (int it = 0; it < NT; ++it) dr[it] += dy[it];
           __builtin_amdgcn_sched_barrier(0);
