@@ -705,6 +705,16 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
   // per slot: -c_L log2(e) (-inf beyond NK) | d abar . abar | max_l log2 L[l, nk] | 1 / sum_l 2^(log2 L - max)
   __shared__ __attribute__((aligned(16))) float side[2][4][kSeg];
   __shared__ __attribute__((aligned(16))) f32x4 halves[KSPLIT][NQT][16];   // row statistics of the key halves
+  // kFuse: the column side of the stage (d alpha_L, d c_L, dY: k_bwdm_l_cols otherwise) is formed
+  // here, from the segment's dZ (and L) left transposed in LDS instead of in global scratch
+  constexpr bool kFuse = KSPLIT == 2 && NQT == 6;
+  constexpr int QROWS = 16 * NQT, LPZ = QROWS + 8, KSC = NQT / 2;
+  __shared__ __attribute__((aligned(16))) u16 Qs[kFuse ? QROWS * LD : 8];             // Q[m, :, j, :]
+  __shared__ __attribute__((aligned(16))) u16 dOs[kFuse && LAST ? QROWS * LD : 8];    // dO[m, :, j, :]
+  // dZ as [nk][l] of a segment: two buffers at t < T (the column side of a step then runs beside the
+  // next step's row side), one at t = T, where L needs one too
+  __shared__ __attribute__((aligned(16))) u16 Zs[kFuse ? (LAST ? 1 : 2) * kSeg * LPZ : 8];
+  __shared__ __attribute__((aligned(16))) u16 Ws[kFuse && LAST ? kSeg * LPZ : 8];
 
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
@@ -728,6 +738,10 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
   const u16* dOp = (const u16*)bp.dO + b * p.os.batch + hd * p.os.head + qcol * p.os.token;
   const TokRows qrow = tile_rows(p, a, p.qs.token), orow = tile_rows(p, a, p.os.token);
 
+  if constexpr (kFuse) {
+    stage_rows_batched<D, LD, QROWS, NTHR>(Qs, Qp, qrow, b1, tid);
+    if (LAST) stage_rows_batched<D, LD, QROWS, NTHR>(dOs, dOp, orow, b1, tid);
+  }
   // the register set behind the ring
   RowRegs<D, kSeg, NTHR> rA, rB, rC;
   float sc = 0.f;
@@ -924,10 +938,16 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
           const float dz = w * (dl[kt][r] - tc[r]) - L * delta;
           wq[kt][r] = w;
           dl[kt][r] = dz;
-          const int nk = k0 + 16 * kt + 4 * g + r;
-          if (nk < NK) {
-            if (LAST) Pt[(size_t)nk * LP + l] = f2bf(w);       // only dY, at t = T, is formed from it
-            Zt[(size_t)nk * LP + l] = f2bf(dz);
+          if constexpr (kFuse) {
+            const int at = (koff + 16 * kt + 4 * g + r) * LPZ + l;
+            Zs[(LAST ? 0 : (sg & 1) * kSeg * LPZ) + at] = f2bf(dz);
+            if (LAST) Ws[at] = f2bf(w);
+          } else {
+            const int nk = k0 + 16 * kt + 4 * g + r;
+            if (nk < NK) {
+              if (LAST) Pt[(size_t)nk * LP + l] = f2bf(w);       // only dY, at t = T, is formed from it
+              Zt[(size_t)nk * LP + l] = f2bf(dz);
+            }
           }
         }
       }
@@ -947,6 +967,42 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
       commit(sw, sg + 1, slot ^ 1);
       issue(sw, sg + 2);
       __syncthreads();
+      if constexpr (kFuse) {
+        // column side of the segment: d alpha_L[nk] = scale sum_l dZ[l, nk] Q[l], d c_L[nk] =
+        // -sum_l dZ[l, nk], and at t = T dY[nk] = sum_l L[l, nk] dO[l]; one 16-row nk tile per wave,
+        // the duty moving on by four waves every step
+        const int duty = (wave + NW - (4 * sg) % NW) % NW;
+        if (duty < (LAST ? 8 : 4)) {
+          const bool second = duty >= 4;                 // dY
+          const int t = duty & 3, nk = kSeg * sg + 16 * t + c;
+          const u16* src = (second ? Ws : Zs + (LAST ? 0 : (sg & 1) * kSeg * LPZ)) + (16 * t + c) * LPZ;
+          bf16x8 zb[KSC];
+          float zsum = 0.f;
+#pragma unroll
+          for (int st = 0; st < KSC; ++st) {
+            zb[st] = ld_lds_16B(src + 32 * st + 8 * g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) zsum += (float)zb[st][e];
+          }
+          zsum = xsum(zsum);
+          if (!second && g == 0 && nk < NK) bp.dcL[row0 + nk] = -zsum;
+          f32x4 oc[1][NVT];
+#pragma unroll
+          for (int vt = 0; vt < NVT; ++vt) oc[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          const u16* tile = second ? dOs : Qs;
+#pragma unroll
+          for (int st = 0; st < KSC; ++st) {
+            const bf16x8 one[1] = {zb[st]};
+            pv_step_nat<D, 1, LD>(tile + 32 * st * LD, one, 1, oc, lane);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (nk < NK) {
+            if (second) store_ws_row<D>((u16*)bp.dY + (row0 + nk) * d, oc[0], 1.0f, g);
+            else store_ws_row<D>((u16*)bp.daL + (row0 + nk) * d, oc[0], p.scale, g);
+          }
+        }
+        if (LAST) __syncthreads();        // one buffer: the next step's row side writes it again
+      }
     }
   }
   if constexpr (KSPLIT > 1) {
@@ -1432,8 +1488,10 @@ static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, b
     if constexpr (sizeof(TW) == 2) {
       // bf16 workspace: the pipelined kernel
       if (nlt <= 6 && bp.k.rl == 0) {
+        // twelve waves, and the column side of the stage in the same kernel: no cols launch
         if (last) k_bwdm_l_rows_ring<D, true, 6, 2><<<grid, 768, 0, s>>>(bp, Pw, Zw);
         else k_bwdm_l_rows_ring<D, false, 6, 2><<<grid, 768, 0, s>>>(bp, Pw, Zw);
+        return hipGetLastError();
       } else if (nlt <= 6) {
         if (last) k_bwdm_l_rows_ring<D, true, 6, 1><<<grid, 384, 0, s>>>(bp, Pw, Zw);
         else k_bwdm_l_rows_ring<D, false, 6, 1><<<grid, 384, 0, s>>>(bp, Pw, Zw);
