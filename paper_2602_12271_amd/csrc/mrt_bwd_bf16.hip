@@ -707,7 +707,8 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
   __shared__ __attribute__((aligned(16))) f32x4 halves[KSPLIT][NQT][16];   // row statistics of the key halves
   // kFuse: the column side of the stage (d alpha_L, d c_L, dY: k_bwdm_l_cols otherwise) is formed
   // here, from the segment's dZ (and L) left transposed in LDS instead of in global scratch
-  constexpr bool kFuse = KSPLIT == 2 && NQT == 6;
+  // (ten query tiles: only at t < T, where one transposed array and the Q tile fit beside the ring)
+  constexpr bool kFuse = (KSPLIT == 2 && NQT == 6) || (NQT == 10 && KSPLIT == 1 && !LAST);
   constexpr int QROWS = 16 * NQT, LPZ = QROWS + 8, KSC = NQT / 2;
   __shared__ __attribute__((aligned(16))) u16 Qs[kFuse ? QROWS * LD : 8];             // Q[m, :, j, :]
   __shared__ __attribute__((aligned(16))) u16 dOs[kFuse && LAST ? QROWS * LD : 8];    // dO[m, :, j, :]
@@ -1497,7 +1498,11 @@ static hipError_t launch_l_d(const BwdParams& bp, dim3 grid, int nkt, int nlt, b
         else k_bwdm_l_rows_ring<D, false, 6, 1><<<grid, 384, 0, s>>>(bp, Pw, Zw);
       } else {
         if (last) k_bwdm_l_rows_ring<D, true, 10, 1><<<grid, 640, 0, s>>>(bp, Pw, Zw);
-        else k_bwdm_l_rows_ring<D, false, 10, 1><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+        else {
+          // t < T: column side in the same kernel
+          k_bwdm_l_rows_ring<D, false, 10, 1><<<grid, 640, 0, s>>>(bp, Pw, Zw);
+          return hipGetLastError();
+        }
       }
     } else if (nlt <= 6) {
       if (last) k_bwdm_l_rows_stream<D, true, TW, 6><<<grid, 384, 0, s>>>(bp, Pw, Zw);
