@@ -223,6 +223,26 @@ __device__ inline void store_ws_row(u16* row, const f32x4* acc, float mul, int g
   store_rows<D>(row, acc, mul, g);
 }
 
+// Transposed store of one accumulator tile: lane (c, g) holds v[r] for query row l = l16 + c and
+// keys nk0 + 4g + r.  The four lanes of a quad (four consecutive query rows) exchange their values
+// (two DPP steps on packed bf16 pairs) so that lane c ends up with key nk0 + 4g + (c mod 4) for
+// the quad's four rows, and stores them as one 8-byte piece of row nk of the [nk][l] array:
+// four store instructions per tile instead of sixteen 2-byte ones.
+__device__ inline void store_tile_transposed(u16* arr, int pitch, int nk0, int NK, int l16, f32x4 v, int c, int g) {
+  const uint32_t P0 = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+  const uint32_t P1 = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+  const uint32_t X0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)P0, 0xB1, 0xf, 0xf, true);   // lane ^ 1
+  const uint32_t X1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)P1, 0xB1, 0xf, 0xf, true);
+  const bool odd = c & 1, up = c & 2;
+  // keys (c mod 2) and 2 + (c mod 2), rows of the lane pair
+  const uint32_t A = odd ? ((X0 >> 16) | (P0 & 0xffff0000u)) : ((P0 & 0xffffu) | (X0 << 16));
+  const uint32_t B = odd ? ((X1 >> 16) | (P1 & 0xffff0000u)) : ((P1 & 0xffffu) | (X1 << 16));
+  const uint32_t recv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(up ? A : B), 0x4E, 0xf, 0xf, true);   // lane ^ 2
+  const uint2 out = up ? uint2{recv, B} : uint2{A, recv};
+  const int nk = nk0 + 4 * g + (c & 3);
+  if (nk < NK) *(uint2*)(arr + (size_t)nk * pitch + l16 + (c & ~3)) = out;
+}
+
 // The gradient arrays that only travel between the kernels of the sweep (d alpha_L, dY, and d abar
 // of the iterations t >= 2) are stored in the type TW of the forward intermediates: as bf16 they
 // hold exactly the values the consuming kernel would round its matrix operands to anyway.
@@ -383,17 +403,12 @@ __global__ __launch_bounds__(256, 3) void k_bwdm_l_rows(BwdParams bp, u16* Pw, u
     delta = xsum(delta);
     // dZ, and the transposed copies for the cols kernel
 #pragma unroll
-    for (int kt = 0; kt < NTK; ++kt)
+    for (int kt = 0; kt < NTK; ++kt) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float dz = dl[kt][r] - s[kt][r] * delta;
-        dl[kt][r] = dz;
-        const int nk = 16 * kt + 4 * g + r;
-        if (nk < NK) {
-          if (LAST) Pt[(size_t)nk * kLP + l] = f2bf(wq[kt][r]);   // only dY, at t = T, is formed from it
-          Zt[(size_t)nk * kLP + l] = f2bf(dz);
-        }
-      }
+      for (int r = 0; r < 4; ++r) dl[kt][r] = dl[kt][r] - s[kt][r] * delta;
+      if (LAST) store_tile_transposed(Pt, kLP, 16 * kt, NK, 16 * lt, wq[kt], c, g);   // only dY, at t = T, is formed from it
+      store_tile_transposed(Zt, kLP, 16 * kt, NK, 16 * lt, dl[kt], c, g);
+    }
     __builtin_amdgcn_sched_barrier(0);
     // dQ[l] = scale sum_nk dZ[l,nk] aL[nk] (+ sum_nk w[l,nk] dA[nk])
     f32x4 o[NVT];
@@ -943,13 +958,11 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
             const int at = (koff + 16 * kt + 4 * g + r) * LPZ + l;
             Zs[(LAST ? 0 : (sg & 1) * kSeg * LPZ) + at] = f2bf(dz);
             if (LAST) Ws[at] = f2bf(w);
-          } else {
-            const int nk = k0 + 16 * kt + 4 * g + r;
-            if (nk < NK) {
-              if (LAST) Pt[(size_t)nk * LP + l] = f2bf(w);       // only dY, at t = T, is formed from it
-              Zt[(size_t)nk * LP + l] = f2bf(dz);
-            }
           }
+        }
+        if constexpr (!kFuse) {
+          if (LAST) store_tile_transposed(Pt, LP, k0 + 16 * kt, NK, 16 * lt, wq[kt], c, g);   // only dY is formed from it
+          store_tile_transposed(Zt, LP, k0 + 16 * kt, NK, 16 * lt, dl[kt], c, g);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
