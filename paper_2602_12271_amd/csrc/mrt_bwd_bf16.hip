@@ -1138,9 +1138,17 @@ __global__ __launch_bounds__(256, NLT <= 6 ? 3 : 2) void k_bwdm_l_cols(BwdParams
 // the current step's operands have moved from the register stage into LDS, so they are in flight
 // during the whole of the current step's arithmetic and stores; without that every workgroup of
 // the launch alternates between a load burst, arithmetic and a store burst in lockstep.
+//
+// LW (loader waves; for the shapes whose tiles leave one workgroup per compute unit): the workgroup
+// has NT more waves that do nothing but the memory side of the pipeline, i.e. hold the register
+// stage, write it to LDS between the step's first two barriers and issue the next step's loads.
+// A wave that issues a step's 66 KB of loads sits in the issue for about their transfer time; on
+// the arithmetic waves that time is lost (nothing else runs on their SIMDs), on waves of their own
+// it overlaps the arithmetic.  Both kinds of waves run the same step sequence and meet at the
+// same three barriers per step.
 // ---------------------------------------------------------------------------------------
-template <int NT, int D, bool LAST, typename TW>
-__global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, int first, int nitems) {
+template <int NT, int D, bool LAST, typename TW, bool LW = false>
+__global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) void k_bwdm_r(BwdParams bp, int first, int nitems) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NT + 1) / 2, ROWS = 32 * KS2;
   constexpr int LR = ROWS + 8, NTHR = 64 * NT;
@@ -1151,8 +1159,12 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
   __shared__ __attribute__((aligned(16))) u16 Ys[LAST ? ROWS * LD : 8];   // d Y[m, n, j, k, :]
   __shared__ __attribute__((aligned(16))) u16 RT[ROWS * LR];              // R[j, i] as [i][j]
   __shared__ __attribute__((aligned(16))) u16 ST[ROWS * LR];              // scale dS[j, i] as [i][j]
+  __shared__ float dcls[LW ? 64 : 1];                                     // d c_L of the step's columns (LW)
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  // LW: threads NTHR .. 2 NTHR - 1 are the loader waves; tid is a thread's index within its kind
+  const bool loader = LW && (int)threadIdx.x >= NTHR;
+  const int tid = loader ? (int)threadIdx.x - NTHR : (int)threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b1 = p.b1, b2 = p.b2, d = D;
   const int nkb = p.ntk * b1;                   // key blocks per (batch, head)
   const size_t NKtot = (size_t)p.ntk * b1;
@@ -1201,31 +1213,94 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
       rv.load(Vp, TokRows{0, p.cmap, it.bn * b2, p.vs.token}, b2, tid);
     }
   };
-  auto issue_tile = [&](const Item& it, int ml) {
+  // part 0: abar (or Q) only, part 1: the gradients only, -1: both
+  auto issue_tile = [&](const Item& it, int ml, int part = -1) {
     const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
     const size_t jrow0 = ((size_t)it.bhl * p.ntq + ml) * b2;
     const int nk = it.nk;
     auto jrow = [&](int jj) { return (long long)(((jrow0 + jj) * NKtot + nk) * d); };
     const size_t ablk = (((size_t)it.bhl * p.ntq + ml) * NKtot + nk) * b2;
-    if (first) {
-      const int b = it.bh / p.H, hd = it.bh - b * p.H;
-      const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
-      const long long qrow = row_offset(p, a, it.k);
-      ra.load(Qbase + qrow * p.qs.token, TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
-    } else if constexpr (kF32Ws) {
-      raf.load((const float*)p.aR + ablk * d, PlainRows{D}, b2, tid);
-    } else {
-      ra.load((const u16*)p.aR + ablk * d, PlainRows{D}, b2, tid);
+    if (part != 1) {
+      if (first) {
+        const int b = it.bh / p.H, hd = it.bh - b * p.H;
+        const u16* Qbase = (const u16*)p.Q + b * p.qs.batch + hd * p.qs.head;
+        const long long qrow = row_offset(p, a, it.k);
+        ra.load(Qbase + qrow * p.qs.token, TokRows{0, p.cmap, bq * b2, p.qs.token}, b2, tid);
+      } else if constexpr (kF32Ws) {
+        raf.load((const float*)p.aR + ablk * d, PlainRows{D}, b2, tid);
+      } else {
+        ra.load((const u16*)p.aR + ablk * d, PlainRows{D}, b2, tid);
+      }
     }
-    rg.load((const TW*)bp.daL, jrow, b2, tid);
-    if (LAST) ry.load((const TW*)bp.dY, jrow, b2, tid);
+    if (part != 0) {
+      rg.load((const TW*)bp.daL, jrow, b2, tid);
+      if (LAST) ry.load((const TW*)bp.dY, jrow, b2, tid);
+    }
   };
 
   Item cur = decode(blockIdx.x);          // the host launches at most nitems workgroups
   int ml = cur.ml0;
   bool newblk = true;
-  issue_block(cur);
-  if (ml < p.ntq) issue_tile(cur, ml);
+  if constexpr (LW) {
+    if (loader) {
+      // ---- loader waves: the memory side of every step, the same sequence of steps and barriers
+      auto dcl_of = [&](const Item& it, int mlx) {
+        return bp.dcL[(((size_t)it.bhl * p.ntq + mlx) * b2 + (tid < b2 ? tid : b2 - 1)) * NKtot + it.nk];
+      };
+      float dcl_r = 0.f;
+      issue_block(cur);
+      if (ml < p.ntq) {
+        if (tid < 64) dcl_r = dcl_of(cur, ml);
+        issue_tile(cur, ml);
+      }
+      while (true) {
+        const bool has_tile = ml < p.ntq;
+        __syncthreads();                       // the arithmetic waves are done with the tiles
+        if (newblk) {
+          rk.template store<LD>(Ks, tid);
+          if (LAST) rv.template store<LD>(Vs, tid);
+        }
+        if (has_tile) {
+          if (first || !kF32Ws) ra.template store<LD>(As, tid);
+          else raf.template store<LD>(As, tid);
+          rg.template store<LD>(Gs, tid);
+          if (LAST) ry.template store<LD>(Ys, tid);
+          if (tid < 64) dcls[tid] = dcl_r;
+        }
+        const bool item_done = !has_tile || ml + 1 >= p.ntq;
+        Item nxt = cur;
+        int nml = ml + 1;
+        bool more = true;
+        if (item_done) {
+          const int w2 = cur.w + (int)gridDim.x;
+          more = w2 < nitems;
+          if (more) {
+            nxt = decode(w2);
+            nml = nxt.ml0;
+          }
+        }
+        __syncthreads();                       // the tiles are in LDS
+        // the next step's loads, in two halves around the arithmetic waves' middle barrier: the
+        // wave sits in the issue of each half while the arithmetic waves work
+        const bool nxt_tile = more && nml < p.ntq;
+        if (item_done && more) issue_block(nxt);
+        if (nxt_tile) {
+          if (tid < 64) dcl_r = dcl_of(nxt, nml);
+          issue_tile(nxt, nml, 0);
+        }
+        if (has_tile) __syncthreads();         // (the arithmetic waves' barrier between their two halves)
+        if (nxt_tile) issue_tile(nxt, nml, 1);
+        if (!more) break;
+        cur = nxt;
+        ml = nml;
+        newblk = item_done;
+      }
+      return;
+    }
+  } else {
+    issue_block(cur);
+    if (ml < p.ntq) issue_tile(cur, ml);
+  }
   for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
   if constexpr (ROWS > SROWS) {
     for (int idx = SROWS * LD + tid; idx < ROWS * LD; idx += NTHR) {
@@ -1244,20 +1319,22 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
   while (true) {
     const bool has_tile = ml < p.ntq;        // an item no query tile sees only writes its zeros
     __syncthreads();                         // the previous step's reads of the LDS tiles
-    if (newblk) {
-      rk.template store<LD>(Ks, tid);
-      if (LAST) rv.template store<LD>(Vs, tid);
-    }
-    if (has_tile) {
-      if (first || !kF32Ws) ra.template store<LD>(As, tid);
-      else raf.template store<LD>(As, tid);
-      rg.template store<LD>(Gs, tid);
-      if (LAST) ry.template store<LD>(Ys, tid);
-    }
-    // c_L's gradient of this lane's column: fetched ahead of the next step's loads, which would
-    // otherwise have to land first (loads return in order)
     float dcl = 0.f;
-    if (has_tile && j < b2) dcl = bp.dcL[(((size_t)cur.bhl * p.ntq + ml) * b2 + j) * NKtot + cur.nk];
+    if constexpr (!LW) {
+      if (newblk) {
+        rk.template store<LD>(Ks, tid);
+        if (LAST) rv.template store<LD>(Vs, tid);
+      }
+      if (has_tile) {
+        if (first || !kF32Ws) ra.template store<LD>(As, tid);
+        else raf.template store<LD>(As, tid);
+        rg.template store<LD>(Gs, tid);
+        if (LAST) ry.template store<LD>(Ys, tid);
+      }
+      // c_L's gradient of this lane's column: fetched ahead of the next step's loads, which would
+      // otherwise have to land first (loads return in order)
+      if (has_tile && j < b2) dcl = bp.dcL[(((size_t)cur.bhl * p.ntq + ml) * b2 + j) * NKtot + cur.nk];
+    }
     // the step after this one, and its loads
     const bool item_done = !has_tile || ml + 1 >= p.ntq;
     Item nxt = cur;
@@ -1269,11 +1346,16 @@ __global__ __launch_bounds__(64 * NT, LAST ? 1 : 2) void k_bwdm_r(BwdParams bp, 
       if (more) {
         nxt = decode(w2);
         nml = nxt.ml0;
-        issue_block(nxt);
+        if constexpr (!LW) issue_block(nxt);
       }
     }
-    if (more && nml < p.ntq) issue_tile(nxt, nml);
+    if constexpr (!LW) {
+      if (more && nml < p.ntq) issue_tile(nxt, nml);
+    }
     __syncthreads();
+    if constexpr (LW) {
+      if (has_tile) dcl = dcls[j & 63];       // written by the loader waves before the barrier
+    }
 
     if (has_tile) {
       // rows (j, nk) of the [m][j][nk][..] arrays and the (m, nk) block of the [m][nk][j][d] arrays
@@ -1457,9 +1539,17 @@ template <int NT, int D, typename TW>
 static hipError_t launch_r_nt(const BwdParams& bp, int nitems, bool first, bool last, hipStream_t s) {
   // persistent grid: as many workgroups as stay resident, each striding over the key blocks
   if (last) {
-    static const int resident = resident_workgroups(k_bwdm_r<NT, D, true, TW>, 64 * NT);
-    k_bwdm_r<NT, D, true, TW><<<dim3(nitems < resident ? nitems : resident), 64 * NT, 0, s>>>(bp, first ? 1 : 0, nitems);
+    if constexpr (D == 128 && NT >= 3) {
+      // five tiles and the two transposed arrays leave one workgroup per compute unit: loader waves
+      static const int resident = resident_workgroups(k_bwdm_r<NT, D, true, TW, true>, 128 * NT);
+      k_bwdm_r<NT, D, true, TW, true><<<dim3(nitems < resident ? nitems : resident), 128 * NT, 0, s>>>(bp, first ? 1 : 0, nitems);
+    } else {
+      static const int resident = resident_workgroups(k_bwdm_r<NT, D, true, TW>, 64 * NT);
+      k_bwdm_r<NT, D, true, TW><<<dim3(nitems < resident ? nitems : resident), 64 * NT, 0, s>>>(bp, first ? 1 : 0, nitems);
+    }
   } else {
+    // (t < T keeps two workgroups per compute unit without loader waves: one workgroup with them
+    // measured 8 % slower at b2 = 52 and 45 % slower at b2 = 40)
     static const int resident = resident_workgroups(k_bwdm_r<NT, D, false, TW>, 64 * NT);
     k_bwdm_r<NT, D, false, TW><<<dim3(nitems < resident ? nitems : resident), 64 * NT, 0, s>>>(bp, first ? 1 : 0, nitems);
   }
