@@ -1316,9 +1316,32 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
     oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // dK / dV of a finished item.  With loader waves they are stored after the next step's first
+  // barrier, while the loader waves write that step's tiles to LDS (the stores need registers only,
+  // and a wave sits in their issue for about their transfer time); otherwise right away.
+  bool pend_kv = false;
+  int pbh = 0, pbn = 0;
+  long long pkrow = 0;
+  auto store_kv = [&]() {
+    if (j < b2) {
+      const long long tok = pkrow + axis_offset(p.cmap, pbn * b2 + j);
+      store_rows_f32<D>(bp.dK + ((size_t)pbh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
+      if (LAST) store_rows_f32<D>(bp.dV + ((size_t)pbh * p.Nkv + tok) * d, oV[0], 1.0f, g, false);
+    }
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) {
+      oK[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    pend_kv = false;
+  };
+
   while (true) {
     const bool has_tile = ml < p.ntq;        // an item no query tile sees only writes its zeros
     __syncthreads();                         // the previous step's reads of the LDS tiles
+    if constexpr (LW) {
+      if (pend_kv) store_kv();
+    }
     float dcl = 0.f;
     if constexpr (!LW) {
       if (newblk) {
@@ -1471,22 +1494,18 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
       }
     }
     if (item_done) {
-      if (j < b2) {
-        const long long tok = cur.krow + axis_offset(p.cmap, cur.bn * b2 + j);
-        store_rows_f32<D>(bp.dK + ((size_t)cur.bh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
-        if (LAST) store_rows_f32<D>(bp.dV + ((size_t)cur.bh * p.Nkv + tok) * d, oV[0], 1.0f, g, false);
-      }
-#pragma unroll
-      for (int vt = 0; vt < NVT; ++vt) {
-        oK[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        oV[0][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-      }
+      pend_kv = true;
+      pbh = cur.bh;
+      pbn = cur.bn;
+      pkrow = cur.krow;
+      if constexpr (!LW) store_kv();
     }
     if (!more) break;
     cur = nxt;
     ml = nml;
     newblk = item_done;
   }
+  if (pend_kv) store_kv();
 }
 
 }  // namespace
