@@ -211,7 +211,7 @@ def bench_backward(args, wl, lib, pkg, syn, torch, np, host, dev, prob, stream):
     flops = backward_flops(wl)
     ach = flops / (ms / 1e3) / 1e12
     # the library's rule for running every stage on the bf16 matrix unit
-    on_mfma = wl.dtype == "bf16" and wl.head_dim in (64, 128) and wl.b2 <= 64 and wl.b1 <= 144
+    on_mfma = wl.dtype == "bf16" and wl.head_dim in (64, 128) and wl.b2 <= 96 and wl.b1 <= 144
     peak = 2500.0 if on_mfma else 157.3
     cpu = parity = None
     if not args.no_cpu_baseline:

@@ -172,17 +172,19 @@ mrt_status monarch_attn_fwd_noalloc(const void* Q, const void* K, const void* V,
  *   overwritten.  Arithmetic: with p->dtype = MRT_BF16 and p->compute = MRT_COMPUTE_DEFAULT the
  *   contractions run on the bf16 matrix unit with fp32 accumulation wherever the blocks fit its
  *   kernels (stage L backward: b1 <= 144 and head_dim 64 or 128, key ranges beyond 96 rows are
- *   streamed; stage R backward: b2 <= 64; if both hold the forward intermediates are recomputed
+ *   streamed; stage R backward: b2 <= 96; if both hold the forward intermediates are recomputed
  *   by the bf16 forward kernels too) and Q, dO must be 16-byte aligned; everything
  *   else, and every call with MRT_FP32 storage or MRT_COMPUTE_F32, runs in fp32.  Gradients of
- *   the bf16 kernels differ from exact ones by up to about 2e-2 of the largest gradient entry, of
- *   the fp32 kernels by 1e-4 of it.  The forward intermediates of every iteration are recomputed
+ *   the bf16 kernels differ from exact ones by up to about 2e-2 of the largest gradient entry
+ *   (typically 5e-3; ill-conditioned inputs, where several iterations pass through nearly tied
+ *   softmaxes, amplify the rounding of the intermediates beyond that), of the fp32 kernels by
+ *   1e-4 of it.  The forward intermediates of every iteration are recomputed
  *   into the workspace first, so nothing has to be kept from the forward call; the workspace
  *   holds whole (batch, head) entries and the library runs as many of them per pass as fit
  *   (workspace rules as for monarch_attn_fwd).
  *   Limits of this build: b1, b2 and head_dim such that the per-workgroup buffers of the fp32
  *   kernels fit the 160 KB of on-chip memory (e.g. b1 <= 96 and b2 <= 80 at head_dim 128), or
- *   such that every stage runs on the bf16 matrix unit (b1 <= 144, b2 <= 64); iters <= 16;
+ *   such that every stage runs on the bf16 matrix unit (b1 <= 144, b2 <= 96); iters <= 16;
  *   otherwise MRT_ERR_UNSUPPORTED. */
 size_t monarch_attn_bwd_workspace_min_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);
 size_t monarch_attn_bwd_workspace_bytes(const mrt_problem* p, int b1, int b2, int tile, int iters);

@@ -676,7 +676,8 @@ mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, vo
     bp.dY = (float*)arrD(L.off_dY(), lo);
     bp.dA = (float*)arrD(L.off_dA(), lo);
     bp.dQ = dQ; bp.dK = dK; bp.dV = dV;
-    const bool r_mfma = bf16_ops && bwd_bf16_r_fits(bp.k);
+    // (64 < b2 <= 96 runs on the matrix unit only with a bf16 workspace, i.e. when stage L does too)
+    const bool r_mfma = bf16_ops && bwd_bf16_r_fits(bp.k) && (bp.k.b2 <= 64 || ws_bf16);
     bp.dq_from_r = (r_mfma && kp.ntk == 1) ? 1 : 0;
     for (int t = T; t >= 1; --t) {
       const bool last = t == T;

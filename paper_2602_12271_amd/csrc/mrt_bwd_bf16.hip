@@ -1147,19 +1147,27 @@ __global__ __launch_bounds__(256, NLT <= 6 ? 3 : 2) void k_bwdm_l_cols(BwdParams
 // it overlaps the arithmetic.  Both kinds of waves run the same step sequence and meet at the
 // same three barriers per step.
 // ---------------------------------------------------------------------------------------
+// Five and six waves (64 < b2 <= 96) always run with loader waves, three and two of them (eight
+// waves in all: a third wave on a SIMD would leave 168 registers each); at t = T and head_dim 128 their five tiles and two transposed
+// arrays exceed LDS, so scale dS^T takes the place of the V tile once V's logit products are done
+// (one more barrier per step; the loader waves write V again every step).
+template <int NT> constexpr int kLoaderThreads = NT == 5 ? 192 : NT == 6 ? 128 : 64 * NT;
 template <int NT, int D, bool LAST, typename TW, bool LW = false>
-__global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) void k_bwdm_r(BwdParams bp, int first, int nitems) {
+__global__ __launch_bounds__(64 * NT + (LW ? kLoaderThreads<NT> : 0), LW ? 2 : (LAST ? 1 : 2)) void k_bwdm_r(BwdParams bp, int first, int nitems) {
   const KParams& p = bp.k;
   constexpr int LD = D + kBPad, KS1 = D / 32, NVT = D / 16, KS2 = (NT + 1) / 2, ROWS = 32 * KS2;
-  constexpr int LR = ROWS + 8, NTHR = 64 * NT;
+  constexpr int LR = ROWS + 8, NTHR = 64 * NT, LTHR = LW ? kLoaderThreads<NT> : NTHR;
+  constexpr bool kAlias = LAST && NT >= 5 && D == 128;
+  static_assert(!kAlias || (LW && ROWS * LR <= ROWS * LD), "scale dS^T in the V tile");
   __shared__ __attribute__((aligned(16))) u16 Ks[ROWS * LD];              // K[n, k, i, :]
   __shared__ __attribute__((aligned(16))) u16 Vs[LAST ? ROWS * LD : 8];   // V[n, k, i, :]
   __shared__ __attribute__((aligned(16))) u16 As[ROWS * LD];              // abar[m, n, k, j, :]
   __shared__ __attribute__((aligned(16))) u16 Gs[ROWS * LD];              // d alpha_L[m, n, j, k, :]
   __shared__ __attribute__((aligned(16))) u16 Ys[LAST ? ROWS * LD : 8];   // d Y[m, n, j, k, :]
   __shared__ __attribute__((aligned(16))) u16 RT[ROWS * LR];              // R[j, i] as [i][j]
-  __shared__ __attribute__((aligned(16))) u16 ST[ROWS * LR];              // scale dS[j, i] as [i][j]
-  __shared__ float dcls[LW ? 64 : 1];                                     // d c_L of the step's columns (LW)
+  __shared__ __attribute__((aligned(16))) u16 ST_own[kAlias ? 8 : ROWS * LR];   // scale dS[j, i] as [i][j]
+  u16* ST = kAlias ? Vs : ST_own;
+  __shared__ float dcls[LW ? ROWS : 1];                                   // d c_L of the step's columns (LW)
 
   // LW: threads NTHR .. 2 NTHR - 1 are the loader waves; tid is a thread's index within its kind
   const bool loader = LW && (int)threadIdx.x >= NTHR;
@@ -1198,12 +1206,12 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
   // (the stages cover the 16 NT rows the waves own; an odd NT leaves 16 more tile rows, which the
   // 32-row steps of the second products read: zeroed once below and never written again)
   constexpr int SROWS = 16 * NT;
-  RowRegs<D, SROWS, NTHR> rk;                          // K rows
-  RowRegs<D, LAST ? SROWS : 1, NTHR> rv;               // V rows (t = T)
-  RowRegs<D, SROWS, NTHR> ra;                          // Q rows, or abar stored as bf16
-  RowRegsF32<D, kF32Ws ? SROWS : 1, NTHR> raf;         // abar stored as fp32
-  typename std::conditional<kF32Ws, RowRegsF32<D, SROWS, NTHR>, RowRegs<D, SROWS, NTHR>>::type rg;
-  typename std::conditional<kF32Ws, RowRegsF32<D, LAST ? SROWS : 1, NTHR>, RowRegs<D, LAST ? SROWS : 1, NTHR>>::type ry;
+  RowRegs<D, SROWS, LTHR> rk;                          // K rows
+  RowRegs<D, LAST ? SROWS : 1, LTHR> rv;               // V rows (t = T)
+  RowRegs<D, SROWS, LTHR> ra;                          // Q rows, or abar stored as bf16
+  RowRegsF32<D, kF32Ws ? SROWS : 1, LTHR> raf;         // abar stored as fp32
+  typename std::conditional<kF32Ws, RowRegsF32<D, SROWS, LTHR>, RowRegs<D, SROWS, LTHR>>::type rg;
+  typename std::conditional<kF32Ws, RowRegsF32<D, LAST ? SROWS : 1, LTHR>, RowRegs<D, LAST ? SROWS : 1, LTHR>>::type ry;
   auto issue_block = [&](const Item& it) {
     const int b = it.bh / p.H, hd = it.bh - b * p.H;
     const u16* Kp = (const u16*)p.K + b * p.ks.batch + hd * p.ks.head + it.krow * p.ks.token;
@@ -1244,28 +1252,27 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
   if constexpr (LW) {
     if (loader) {
       // ---- loader waves: the memory side of every step, the same sequence of steps and barriers
+      static_assert(LTHR >= ROWS, "one loader thread per column for d c_L");
       auto dcl_of = [&](const Item& it, int mlx) {
         return bp.dcL[(((size_t)it.bhl * p.ntq + mlx) * b2 + (tid < b2 ? tid : b2 - 1)) * NKtot + it.nk];
       };
       float dcl_r = 0.f;
       issue_block(cur);
       if (ml < p.ntq) {
-        if (tid < 64) dcl_r = dcl_of(cur, ml);
+        if (tid < ROWS) dcl_r = dcl_of(cur, ml);
         issue_tile(cur, ml);
       }
       while (true) {
         const bool has_tile = ml < p.ntq;
         __syncthreads();                       // the arithmetic waves are done with the tiles
-        if (newblk) {
-          rk.template store<LD>(Ks, tid);
-          if (LAST) rv.template store<LD>(Vs, tid);
-        }
+        if (newblk) rk.template store<LD>(Ks, tid);
+        if (LAST && (newblk || kAlias)) rv.template store<LD>(Vs, tid);
         if (has_tile) {
           if (first || !kF32Ws) ra.template store<LD>(As, tid);
           else raf.template store<LD>(As, tid);
           rg.template store<LD>(Gs, tid);
           if (LAST) ry.template store<LD>(Ys, tid);
-          if (tid < 64) dcls[tid] = dcl_r;
+          if (tid < ROWS) dcls[tid] = dcl_r;
         }
         const bool item_done = !has_tile || ml + 1 >= p.ntq;
         Item nxt = cur;
@@ -1285,9 +1292,10 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
         const bool nxt_tile = more && nml < p.ntq;
         if (item_done && more) issue_block(nxt);
         if (nxt_tile) {
-          if (tid < 64) dcl_r = dcl_of(nxt, nml);
+          if (tid < ROWS) dcl_r = dcl_of(nxt, nml);
           issue_tile(nxt, nml, 0);
         }
+        if (kAlias && has_tile) __syncthreads();   // (the arithmetic waves are done with the V tile)
         if (has_tile) __syncthreads();         // (the arithmetic waves' barrier between their two halves)
         if (nxt_tile) issue_tile(nxt, nml, 1);
         if (!more) break;
@@ -1301,7 +1309,10 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
     issue_block(cur);
     if (ml < p.ntq) issue_tile(cur, ml);
   }
-  for (int idx = tid; idx < ROWS * LR; idx += NTHR) { RT[idx] = 0; ST[idx] = 0; }
+  for (int idx = tid; idx < ROWS * LR; idx += NTHR) {
+    RT[idx] = 0;
+    if (!kAlias) ST[idx] = 0;
+  }
   if constexpr (ROWS > SROWS) {
     for (int idx = SROWS * LD + tid; idx < ROWS * LD; idx += NTHR) {
       Ks[idx] = 0; As[idx] = 0; Gs[idx] = 0;
@@ -1377,7 +1388,7 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
     }
     __syncthreads();
     if constexpr (LW) {
-      if (has_tile) dcl = dcls[j & 63];       // written by the loader waves before the barrier
+      if (has_tile) dcl = dcls[j];            // written by the loader waves before the barrier
     }
 
     if (has_tile) {
@@ -1396,18 +1407,28 @@ __global__ __launch_bounds__(64 * NT * (LW ? 2 : 1), LW ? 2 : (LAST ? 1 : 2)) vo
         }
         f32x4 s[NT], dr[NT];
         // (t = T: one workgroup per compute unit, one wave per SIMD: LDS reads issued ahead)
-        if constexpr (LAST) rows_dot_ahead<D, NT, LD>(Ks, qv, s, lane);
+        constexpr bool kAhead = LAST && NT <= 4;       // (beyond four waves the registers are needed elsewhere)
+        if constexpr (kAhead) rows_dot_ahead<D, NT, LD>(Ks, qv, s, lane);
         else rows_dot<D, NT, LD>(Ks, qv, s, lane);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (LAST) rows_dot_ahead<D, NT, LD>(Ks, gv, dr, lane);
+        if constexpr (kAhead) rows_dot_ahead<D, NT, LD>(Ks, gv, dr, lane);
         else rows_dot<D, NT, LD>(Ks, gv, dr, lane);
         __builtin_amdgcn_sched_barrier(0);
         if (LAST) {
           f32x4 dy[NT];
-          rows_dot_ahead<D, NT, LD>(Vs, yv, dy, lane);
+          if constexpr (kAhead) rows_dot_ahead<D, NT, LD>(Vs, yv, dy, lane);
+          else rows_dot<D, NT, LD>(Vs, yv, dy, lane);
 #pragma unroll
           for (int it = 0; it < NT; ++it) dr[it] += dy[it];
           __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (kAlias) {
+          __syncthreads();                     // every wave is done with V: its tile now takes scale dS^T
+          // columns 16 NT .. ROWS - 1 of the rows this wave writes are read as zeros below
+          if constexpr (ROWS > 16 * NT) {
+            for (int idx = lane; idx < 16 * (ROWS - 16 * NT); idx += 64)
+              ST[(16 * wave + idx / (ROWS - 16 * NT)) * LR + 16 * NT + idx % (ROWS - 16 * NT)] = 0;
+          }
         }
         float mx = -INFINITY;
 #pragma unroll
@@ -1539,7 +1560,7 @@ static hipError_t launch_cols(const BwdParams& bp, dim3 grid, int nlt, const u16
   return hipGetLastError();
 }
 
-bool bwd_bf16_r_fits(const KParams& kp) { return kp.b2 <= 64 && (kp.d == 64 || kp.d == 128); }
+bool bwd_bf16_r_fits(const KParams& kp) { return kp.b2 <= 96 && (kp.d == 64 || kp.d == 128); }
 
 // Workgroups of `kernel` the current device keeps resident at once (its compute units times the
 // workgroups of `threads` threads that fit one): the size of a persistent grid.
@@ -1557,7 +1578,22 @@ static int resident_workgroups(K kernel, int threads) {
 template <int NT, int D, typename TW>
 static hipError_t launch_r_nt(const BwdParams& bp, int nitems, bool first, bool last, hipStream_t s) {
   // persistent grid: as many workgroups as stay resident, each striding over the key blocks
-  if (last) {
+  if constexpr (NT >= 5) {
+    // 64 < b2 <= 96: loader waves at every iteration, bf16 workspace only
+    if constexpr (sizeof(TW) == 2) {
+      constexpr int threads = 64 * NT + kLoaderThreads<NT>;
+      if (last) {
+        static const int resident = resident_workgroups(k_bwdm_r<NT, D, true, TW, true>, threads);
+        k_bwdm_r<NT, D, true, TW, true><<<dim3(nitems < resident ? nitems : resident), threads, 0, s>>>(bp, first ? 1 : 0, nitems);
+      } else {
+        static const int resident = resident_workgroups(k_bwdm_r<NT, D, false, TW, true>, threads);
+        k_bwdm_r<NT, D, false, TW, true><<<dim3(nitems < resident ? nitems : resident), threads, 0, s>>>(bp, first ? 1 : 0, nitems);
+      }
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  } else if (last) {
     if constexpr (D == 128 && NT >= 3) {
       // five tiles and the two transposed arrays leave one workgroup per compute unit: loader waves
       static const int resident = resident_workgroups(k_bwdm_r<NT, D, true, TW, true>, 128 * NT);
@@ -1581,6 +1617,8 @@ static hipError_t launch_r_d(const BwdParams& bp, int nitems, bool first, bool l
     case 2: return launch_r_nt<2, D, TW>(bp, nitems, first, last, s);
     case 3: return launch_r_nt<3, D, TW>(bp, nitems, first, last, s);
     case 4: return launch_r_nt<4, D, TW>(bp, nitems, first, last, s);
+    case 5: return launch_r_nt<5, D, TW>(bp, nitems, first, last, s);
+    case 6: return launch_r_nt<6, D, TW>(bp, nitems, first, last, s);
   }
   return hipErrorInvalidValue;
 }

@@ -55,6 +55,18 @@ CASES = {
                                        iters=1, causal_chunk=2, q_frame_offset=0),
     "bf16-stream-short-visible-T2": small("bf16", head_dim=64, f_q=4, f_kv=12, h=13, w=16, b1=26, b2=8, tile=1,
                                           iters=2, causal_chunk=2, q_frame_offset=0),
+    # 64 < b2 <= 96: stage R backward with five or six arithmetic waves plus loader waves; at head_dim
+    # 128 and t = T the transposed scale dS array takes the V tile's place
+    "bf16-b2-80": small("bf16", head_dim=128, f_q=2, f_kv=4, h=8, w=80, b1=16, b2=80, tile=1, iters=2,
+                        causal_chunk=2, q_frame_offset=2),
+    "bf16-b2-72-T1": small("bf16", head_dim=64, f_q=2, f_kv=2, h=9, w=72, b1=18, b2=72, tile=0, iters=1),
+    "bf16-b2-96": small("bf16", head_dim=128, f_q=2, f_kv=2, h=6, w=96, b1=12, b2=96, tile=0, iters=2),
+    "bf16-b2-88-d64": small("bf16", head_dim=64, f_q=2, f_kv=6, h=5, w=88, b1=10, b2=88, tile=1, iters=3,
+                            causal_chunk=2, q_frame_offset=4),
+    # one head of the paper's 720p tile block (3h, w) = (135, 80) as a regular Monarch problem on a
+    # 3-frame 720p latent chunk (10800 tokens)
+    "bf16-720p-block": small("bf16", head_dim=128, heads=1, f_q=3, f_kv=3, h=45, w=80, b1=135, b2=80, tile=0,
+                             iters=1),
     # 216 key rows, three query tiles (the odd tile count leaves a zero tile), three iterations
     "bf16-stream-T3": small("bf16", head_dim=64, f_q=2, f_kv=6, h=18, w=16, b1=36, b2=8, tile=1, iters=3),
     # nine query tiles (b1 = 135, the 720p tile height): ten waves, the wider transposed arrays,
@@ -69,8 +81,8 @@ CASES = {
 
 def on_matrix_unit(wl):
     """bf16 storage: stage L backward runs on the bf16 matrix unit (bf16 operands, fp32 accumulation)
-    when b1 <= 144, stage R backward when b2 <= 64; the rest stays fp32."""
-    return wl.dtype == "bf16" and (wl.b1 <= 144 or wl.b2 <= 64)
+    when b1 <= 144, stage R backward when b2 <= 96; the rest stays fp32."""
+    return wl.dtype == "bf16" and (wl.b1 <= 144 or wl.b2 <= 96)
 
 
 def run_case(wl, heads=None, compute=None):
@@ -159,7 +171,7 @@ def test_backward_minimum_workspace_gives_same_result():
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("name", ["bf16-storage", "bf16-ragged-T3", "bf16-stream-mask"])
+@pytest.mark.parametrize("name", ["bf16-storage", "bf16-ragged-T3", "bf16-stream-mask", "bf16-b2-80"])
 def test_backward_rerun_is_bit_identical(name):
     """No kernel of the sweep uses atomics: every gradient entry has one owner, so two calls on the
     same inputs give the same bits (resident and streamed stage L kernels, regular and tiled)."""
@@ -207,7 +219,7 @@ def test_backward_head_groups_do_not_change_the_result(name):
 
 
 @pytest.mark.parametrize("name", ["bf16-stream-mask", "bf16-ragged-T3", "bf16-ragged-T1", "tiled-rect-mask",
-                                  "bf16-b1-135", "regular-T2"])
+                                  "bf16-b1-135", "regular-T2", "bf16-b2-80"])
 def test_forward_that_saves_and_backward_from_saved_intermediates(name):
     """The training-step pair: monarch_attn_fwd_save gives the forward output (bit for bit where the
     bf16 forward kernels run it, to the forward tolerance where the fp32 ones do) and leaves the
@@ -234,7 +246,7 @@ def test_forward_that_saves_and_backward_from_saved_intermediates(name):
     O_ref = pkg.monarch_attn_fwd(Qd, Kd, Vd, **kw)
     torch.cuda.synchronize()
     assert torch.isfinite(O.float()).all()
-    every_stage_bf16 = wl.dtype == "bf16" and wl.head_dim in (64, 128) and wl.b1 <= 144 and wl.b2 <= 64
+    every_stage_bf16 = wl.dtype == "bf16" and wl.head_dim in (64, 128) and wl.b1 <= 144 and wl.b2 <= 96
     if every_stage_bf16 or wl.dtype != "bf16":
         assert torch.equal(O, O_ref)                 # the same kernels ran
     else:
@@ -249,7 +261,8 @@ def test_forward_that_saves_and_backward_from_saved_intermediates(name):
 
 
 @pytest.mark.parametrize("name", ["bf16-b1-120", "bf16-b1-135", "bf16-stream-mask", "bf16-ragged-T3",
-                                  "tiled-rect-mask", "regular-T3", "bf16-stream-short-visible-T2"])
+                                  "tiled-rect-mask", "regular-T3", "bf16-stream-short-visible-T2", "bf16-b2-80",
+                                  "bf16-b2-96"])
 def test_backward_reads_nothing_it_has_not_written(name):
     """A workspace full of NaN bit patterns (what a recycled allocation may hold) gives the same bits
     as a zeroed one: every workspace entry a kernel reads was written earlier in the same call,
