@@ -726,13 +726,15 @@ mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, vo
         if (hipStreamWaitEvent(pool->side[gi - 1], pool->fork, 0) != hipSuccess) status = MRT_ERR_HIP;
       if (status != MRT_OK) { set_error("helper stream fork failed"); break; }
     }
-    // two groups: as in the forward call, the first takes the heads whose stage L workgroups fill
-    // the chip exactly once when those are at least half of the pass
+    // the heads are split evenly (the forward call's uneven split, which lets the larger group's
+    // stage L launches fill the chip exactly once, does not carry over: the streamed stage L backward
+    // kernel holds one workgroup per compute unit; 12 heads of the 480p KV-cache step: 6 + 6 1.76 ms,
+    // 9 + 3 1.82, 4 + 8 1.84, 10 + 2 1.93)
+    // The saving forward call runs the forward kernels only and takes the forward call's split.
     int first_group = 0;
-    if (ngroups == 2) {
+    if (mode == kBwdForwardOnly && ngroups == 2) {
       const long long wgs_per_head = (long long)pl.ntq_total * pl.kp.b2;
-      const long long slots = (pl.kp.b1 <= 96 ? 2LL : 1LL) * compute_units();
-      const int per_round = (int)(slots / (wgs_per_head > 0 ? wgs_per_head : 1));
+      const int per_round = (int)(2LL * compute_units() / (wgs_per_head > 0 ? wgs_per_head : 1));
       if (per_round < nbh && 2 * per_round >= nbh) first_group = per_round;
     }
     for (int gi = 0; gi < ngroups && status == MRT_OK; ++gi) {
