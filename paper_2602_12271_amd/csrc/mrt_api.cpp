@@ -679,6 +679,7 @@ mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, vo
     // (64 < b2 <= 96 runs on the matrix unit only with a bf16 workspace, i.e. when stage L does too)
     const bool r_mfma = bf16_ops && bwd_bf16_r_fits(bp.k) && (bp.k.b2 <= 64 || ws_bf16);
     bp.dq_from_r = (r_mfma && kp.ntk == 1) ? 1 : 0;
+    bp.dA1_bf16 = (r_mfma && ws_bf16) ? 1 : 0;
     for (int t = T; t >= 1; --t) {
       const bool last = t == T;
       bp.k.aL = arrD(L.off_aL(t), lo);

@@ -1483,14 +1483,15 @@ __global__ __launch_bounds__(64 * NT + (LW ? kLoaderThreads<NT> : 0), LW ? 2 : (
           pv_step<D, LD>(Ks + 32 * st * LD, pz, o, lane);
           __builtin_amdgcn_sched_barrier(0);
         }
-        // d abar of the first iteration is summed into dQ in fp32 by the last kernel of the call
-        // (with one key tile per query tile there is nothing to sum: it goes straight into dQ)
+        // d abar of the first iteration is summed over the key tiles into dQ by the last kernel of
+        // the call, from the workspace's storage type (with one key tile per query tile there is
+        // nothing to sum: it goes straight into dQ)
         if (live) {
           if (first && bp.dq_from_r) {
             const int m = p.m0 + ml, a = m / p.c2, bq = m - a * p.c2;
             const long long tok = row_offset(p, a, k) + axis_offset(p.cmap, bq * b2 + j);
             store_rows_f32<D>(bp.dQ + ((size_t)bh * p.Nq + tok) * d, o, 1.0f, g, true);
-          } else if (first) {
+          } else if (first && kF32Ws) {
             store_rows_f32<D>(bp.dA + (ablk + j) * d, o, 1.0f, g, false);
           } else {
             store_ws_row<D>((TW*)bp.dA + (ablk + j) * d, o, 1.0f, g);

@@ -111,6 +111,8 @@ struct BwdParams {
   int accumulate;       // add to dQ (stage L backward) / dK (stage R backward) instead of overwriting
   int dq_from_r;        // matrix-unit stage R backward of the first iteration adds d abar_1 to dQ itself
                         // (one key tile per query tile: nothing to sum over), no separate dQ kernel
+  int dA1_bf16;         // d abar of the first iteration is held as bf16 (matrix-unit stage R backward on a
+                        // bf16 workspace), like that of the later iterations: the dQ kernel widens it
 };
 
 struct Plan {
