@@ -517,7 +517,10 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
 namespace {
 struct BwdLayout {
   size_t rowsD, rowsS;    // bytes of one [m][j][nk][d] / [m][j][nk] array of one head
+  size_t rows;            // (m, j, nk) triples of one head
   size_t scratch;         // bytes of the matrix-unit kernels' own arrays of one head (0 if unused)
+  size_t rowsO, rowsL;    // bytes of one head's fp32 output copy [m][j][l][d] and row statistics [m][j][l]
+                          // (0 unless the streamed last-iteration stage L kernel can leave them)
   size_t per_head;
   int T;
   bool mfma;              // stage L backward runs on the bf16 matrix unit
@@ -533,16 +536,22 @@ struct BwdLayout {
   size_t off_cmx(int t) const { return base_S() + rowsS * (size_t)(T + t - 1); }        // t = 2..T
   size_t off_cinv(int t) const { return base_S() + rowsS * (size_t)(2 * T + t - 2); }   // t = 2..T
   size_t off_scratch() const { return base_S() + rowsS * (size_t)(3 * T - 1); }
+  size_t off_o32() const { return off_scratch() + scratch; }
+  size_t off_lse() const { return off_o32() + rowsO; }
 };
 BwdLayout bwd_layout(const mrt::Plan& pl, const mrt_problem* p) {
   BwdLayout L;
   const size_t rows = (size_t)pl.kp.c2 * pl.kp.b1 * pl.kp.b2 * pl.kp.ntk * pl.c1q;   // (m, j, nk) triples
+  L.rows = rows;
   L.rowsD = mrt::round256(rows * pl.kp.d * sizeof(float));
   L.rowsS = mrt::round256(rows * sizeof(float));
   L.T = pl.T;
   L.mfma = p->dtype == MRT_BF16 && p->compute == MRT_COMPUTE_DEFAULT && mrt::bwd_bf16_fits(pl.kp);
   L.scratch = L.mfma ? mrt::round256(mrt::bwd_bf16_scratch_bytes(pl.kp, pl.ntq_total)) : 0;
-  L.per_head = L.off_scratch() + L.scratch;
+  const bool stats = L.mfma && mrt::bwd_bf16_r_fits(pl.kp) && mrt::bf16_stage_l_out_streams(pl.kp);
+  L.rowsO = stats ? mrt::round256((size_t)pl.Nq * pl.kp.d * sizeof(float)) : 0;
+  L.rowsL = stats ? mrt::round256((size_t)pl.Nq * sizeof(float)) : 0;
+  L.per_head = L.off_lse() + L.rowsL;
   return L;
 }
 mrt_status bwd_plan(const mrt_problem* p, int b1, int b2, int tile, int iters, int causal_chunk,
@@ -625,10 +634,14 @@ mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, vo
   // array X of the pass starts at base + off_X * G (every array holds G heads back to back)
   auto arr = [&](size_t off) { return base + off * (size_t)G; };
 
-  // array X of heads [lo, ..) of the pass: every array keeps rowsD (or rowsS, or the scratch
-  // size) bytes per head, and a kernel launched for a group of heads packs them from its base
-  auto arrD = [&](size_t off, int lo) { return arr(off) + L.rowsD * (size_t)lo; };
-  auto arrS = [&](size_t off, int lo) { return arr(off) + L.rowsS * (size_t)lo; };
+  // array X of heads [lo, ..) of the pass: every array has room for rowsD (or rowsS) bytes per
+  // head; a kernel launched for a group of heads packs them from its base at the stride of what it
+  // stores, and so do the groups, so that a head's place does not depend on how the heads were
+  // grouped (the call that saves the intermediates and the one that reads them may group differently)
+  const size_t headD = L.rows * (size_t)pl.kp.d * (ws_bf16 ? 2 : 4), headS = L.rows * sizeof(float);
+  const size_t headO = (size_t)pl.Nq * pl.kp.d * sizeof(float), headL = (size_t)pl.Nq * sizeof(float);
+  auto arrD = [&](size_t off, int lo) { return arr(off) + headD * (size_t)lo; };
+  auto arrS = [&](size_t off, int lo) { return arr(off) + headS * (size_t)lo; };
 
   // the whole backward pass of heads [bh0 + lo, bh0 + hi) of a pass, on stream gs
   auto run_heads = [&](int bh0, int lo, int hi, hipStream_t gs) -> mrt_status {
@@ -657,7 +670,13 @@ mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, vo
         if (e != hipSuccess) return hip_fail(e, "backward: forward stage L launch");
       } else if (mode == kBwdForwardOnly) {
         kp.cmx_out = nullptr; kp.cinv_out = nullptr;
+        // the streamed kernel also leaves the rows' log-sum-exp and O in fp32 for the backward call
+        if (L.rowsL) {
+          kp.lse_out = (float*)(arr(L.off_lse()) + headL * (size_t)lo);
+          kp.o32_out = (float*)(arr(L.off_o32()) + headO * (size_t)lo);
+        }
         e = ws_bf16 ? launch_bf16_stage_l(kp, nbh, true, gs) : launch_f32_stage_l(kp, pl.dtype, nbh, true, gs);
+        kp.lse_out = nullptr; kp.o32_out = nullptr;
         if (e != hipSuccess) return hip_fail(e, "forward stage L launch");
       }
     }
@@ -680,6 +699,10 @@ mrt_status bwd_run(BwdMode mode, const void* Q, const void* K, const void* V, vo
     const bool r_mfma = bf16_ops && bwd_bf16_r_fits(bp.k) && (bp.k.b2 <= 64 || ws_bf16);
     bp.dq_from_r = (r_mfma && kp.ntk == 1) ? 1 : 0;
     bp.dA1_bf16 = (r_mfma && ws_bf16) ? 1 : 0;
+    if (mode == kBwdSweepOnly && L.rowsL) {
+      bp.lse = (const float*)(arr(L.off_lse()) + headL * (size_t)lo);
+      bp.o32 = (const float*)(arr(L.off_o32()) + headO * (size_t)lo);
+    }
     for (int t = T; t >= 1; --t) {
       const bool last = t == T;
       bp.k.aL = arrD(L.off_aL(t), lo);

@@ -609,7 +609,8 @@ struct WaveTiles {
 
 // stage L, last iteration:  O[m, l, j, :] = sum_nk softmax_nk(scale * alpha_L Q - c_L) Y
 // RMASK: regular Monarch under the chunk-causal mask (key rows of later chunks hidden per query row)
-template <int D, int QT, int NT, bool RMASK>
+// STATS: also leaves every row's base-2 log-sum-exp and the unrounded output (p.lse_out, p.o32_out)
+template <int D, int QT, int NT, bool RMASK, bool STATS = false>
 __global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KParams p) {
   constexpr int KS1 = D / 32, NVT = D / 16;
   __shared__ __attribute__((aligned(16))) unsigned char smem[FlashLds<D, true>::kBytes];
@@ -666,6 +667,25 @@ __global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KPar
     const int l = 16 * wt.lt[q] + c;
     const float lsum = xsum(st.lrun[q]);
     if (q < wt.nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / lsum, g);
+  }
+  if constexpr (STATS) {
+    // for a backward call that follows: the rows' log-sum-exp and the unrounded output
+    const size_t qr0 = (((size_t)bhl * p.ntq + ml) * b2 + j) * b1;
+#pragma unroll
+    for (int q = 0; q < QT; ++q) {
+      const int l = 16 * wt.lt[q] + c;
+      const float lsum = xsum(st.lrun[q]);
+      if (q < wt.nq && l < b1) {
+        float* row = p.o32_out + (qr0 + l) * D;
+        const float inv = 1.0f / lsum;
+#pragma unroll
+        for (int h = 0; h < D / 32; ++h) {
+          *(f32x4*)(row + 32 * h + 8 * g) = o[q][2 * h] * inv;
+          *(f32x4*)(row + 32 * h + 8 * g + 4) = o[q][2 * h + 1] * inv;
+        }
+        if (g == 0) p.lse_out[qr0 + l] = st.mrun[q] + log2_fast(lsum);
+      }
+    }
   }
   MRT_STAMP(2);
 }
@@ -1423,8 +1443,14 @@ hipError_t launch_r_d(const KParams& kp, dim3 grid, int gs, bool first, bool las
 
 template <int D, int QT, int NT>
 hipError_t launch_l_out(const KParams& kp, dim3 grid, hipStream_t s) {
-  if (kp.rl > 0) k_bf16_stage_l_out<D, QT, NT, true><<<grid, NT, 0, s>>>(kp);
-  else k_bf16_stage_l_out<D, QT, NT, false><<<grid, NT, 0, s>>>(kp);
+  const bool stats = kp.lse_out != nullptr && kp.o32_out != nullptr;
+  if (kp.rl > 0) {
+    if (stats) k_bf16_stage_l_out<D, QT, NT, true, true><<<grid, NT, 0, s>>>(kp);
+    else k_bf16_stage_l_out<D, QT, NT, true><<<grid, NT, 0, s>>>(kp);
+  } else {
+    if (stats) k_bf16_stage_l_out<D, QT, NT, false, true><<<grid, NT, 0, s>>>(kp);
+    else k_bf16_stage_l_out<D, QT, NT, false><<<grid, NT, 0, s>>>(kp);
+  }
   return hipGetLastError();
 }
 
@@ -1711,6 +1737,13 @@ hipError_t launch_l_refine_one_wide(const KParams& kp, dim3 grid, int nlt, hipSt
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+// The last iteration's stage L runs the streamed kernel (the one that can leave row statistics
+// and an fp32 output for a backward call): same conditions as in launch_bf16_stage_l below.
+bool bf16_stage_l_out_streams(const KParams& kp) {
+  const int nlt = (kp.b1 + 15) / 16, nk_max = kp.ntk * kp.b1;
+  return nlt <= kMaxLT && nk_max > kResRows && !(nk_max <= kMidRows && nlt <= 8);
 }
 
 hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_t s) {

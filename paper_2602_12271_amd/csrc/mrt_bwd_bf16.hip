@@ -832,7 +832,10 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
   // ---- sweep 1: lse2[l] and delta[l]
   float mz = -INFINITY, sz = 0.f;            // running maximum / sum of 2^(z - mz)
   float mw = -INFINITY, dw = 0.f;            // the same for the shifted logits, weighted sum of u
-  {
+  // t = T after a forward call that left its row statistics: lse2 is there, and delta[l] =
+  // sum_nk L[l, nk] (dO[l] . Y[nk]) = dO[l] . O[l], so the first sweep is not needed
+  const bool given = LAST && bp.lse != nullptr;
+  if (!given) {
     const std::integral_constant<int, 1> sw;
     issue(sw, 0);
     commit(sw, 0, 0);
@@ -893,7 +896,7 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
       __syncthreads();
     }
   }
-  if constexpr (KSPLIT > 1) {
+  if (KSPLIT > 1 && !given) {
     // the halves' statistics, merged in the same order by every wave of a tile
     if (g == 0) halves[kh][lt][c] = f32x4{mz, sz, mw, dw};
     __syncthreads();
@@ -910,8 +913,24 @@ __global__ __launch_bounds__(64 * NQT * KSPLIT, 3) void k_bwdm_l_rows_ring(BwdPa
       mw = mwn;
     }
   }
-  const float lse2 = mz + log2_fast(sz);
-  const float delta = dw * exp2_fast((LAST ? mz : mw) - lse2);
+  float lse2 = mz + log2_fast(sz);
+  float delta = dw * exp2_fast((LAST ? mz : mw) - lse2);
+  if (given) {
+    const size_t qr = (((size_t)bhl * p.ntq + ml) * b2 + j) * b1 + lc;
+    lse2 = bp.lse[qr];
+    const float* orow32 = bp.o32 + qr * D;
+    float t = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) {
+      const f32x4 o0 = *(const f32x4*)(orow32 + 32 * ks + 8 * g), o1 = *(const f32x4*)(orow32 + 32 * ks + 8 * g + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        t = fmaf((float)xv[ks][e], o0[e], t);
+        t = fmaf((float)xv[ks][e + 4], o1[e], t);
+      }
+    }
+    delta = xsum(t);
+  }
 
   // ---- sweep 2: L (or w), dZ, their transposed copies, dQ
   float* dQp = bp.dQ + (size_t)bh * p.Nq * d;

@@ -39,6 +39,8 @@ struct KParams {
   float* cL;    // c_L     [bh][m][j][nk]
   float* cmx_out;   // optional outputs of stage L (earlier iterations, any kernel): column maximum of
   float* cinv_out;  //   log L and inverse column sum behind alpha_R / c_R   [bh][m][nk][j]
+  float* lse_out;   // optional outputs of the streamed last-iteration stage L kernel: base-2
+  float* o32_out;   //   log-sum-exp of every query row's logits [bh][m][j][l] and O in fp32 [bh][m][j][l][d]
   int H;        // heads (to split the flat batch*head index)
   int bh0;      // first flat (batch,head) index of this pass
   int d;
@@ -111,6 +113,9 @@ struct BwdParams {
   int accumulate;       // add to dQ (stage L backward) / dK (stage R backward) instead of overwriting
   int dq_from_r;        // matrix-unit stage R backward of the first iteration adds d abar_1 to dQ itself
                         // (one key tile per query tile: nothing to sum over), no separate dQ kernel
+  const float* lse;     // row statistics the forward call left ([bh][m][j][l], base-2 log-sum-exp) and its
+  const float* o32;     // output in fp32 ([bh][m][j][l][d]): stage L backward at t = T then reads its key range
+                        // once (null: it forms the statistics in a sweep of its own)
   int dA1_bf16;         // d abar of the first iteration is held as bf16 (matrix-unit stage R backward on a
                         // bf16 workspace), like that of the later iterations: the dQ kernel widens it
 };
@@ -158,6 +163,7 @@ hipError_t launch_bwd_bf16_stage_r(const BwdParams& bp, int nbh, bool first, boo
 // bf16 MFMA path (mrt_bf16.hip)
 hipError_t launch_bf16_stage_r(const KParams& kp, int nbh, bool first, bool last, hipStream_t s);
 hipError_t launch_bf16_stage_l(const KParams& kp, int nbh, bool last, hipStream_t s);
+bool bf16_stage_l_out_streams(const KParams& kp);   // its last-iteration kernel fills lse_out / o32_out
 hipError_t launch_bf16_dense(const KParams& kp, int nbh, hipStream_t s);
 
 }  // namespace mrt
