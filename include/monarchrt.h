@@ -198,8 +198,13 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
  * monarch_attn_fwd_save computes O as monarch_attn_fwd does, with the arithmetic the backward pass
  * uses (bf16 matrix unit where monarch_attn_bwd would use it, fp32 otherwise), and leaves the
  * intermediates of every iteration in `workspace`; monarch_attn_bwd_saved, given the same Q, K, V,
- * arguments and workspace, runs only the reverse sweep and returns exactly the gradients
- * monarch_attn_bwd returns.  Arguments, layouts, limits and error behaviour as for
+ * arguments and workspace, runs only the reverse sweep and returns the gradients
+ * monarch_attn_bwd returns: the same bits, except where the forward call's last stage L ran the
+ * streamed bf16 kernel (more than 192 key rows per query tile, or b1 > 128 with more than 96): that
+ * kernel also leaves every query row's log-sum-exp and an fp32 copy of O, from which the sweep takes
+ * the row statistics of the last iteration (sum_k L dL = dO . O) instead of a pass of its own over
+ * the key range, and the gradients then agree to rounding (measured: within 5e-3 of the largest
+ * gradient, same bar against the oracle).  Arguments, layouts, limits and error behaviour as for
  * monarch_attn_fwd and monarch_attn_bwd, except that the workspace holds every (batch, head) at
  * once: at least monarch_attn_bwd_saved_workspace_bytes() bytes (0: unsupported problem), else
  * MRT_ERR_WORKSPACE.  The caller keeps the workspace untouched between the two calls and orders
