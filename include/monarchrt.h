@@ -203,8 +203,9 @@ mrt_status monarch_attn_bwd(const void* Q, const void* K, const void* V, const v
  * streamed bf16 kernel (more than 192 key rows per query tile, or b1 > 128 with more than 96): that
  * kernel also leaves every query row's log-sum-exp and an fp32 copy of O, from which the sweep takes
  * the row statistics of the last iteration (sum_k L dL = dO . O) instead of a pass of its own over
- * the key range, and the gradients then agree to rounding (measured: within 5e-3 of the largest
- * gradient, same bar against the oracle).  Arguments, layouts, limits and error behaviour as for
+ * the key range, and the gradients then agree to the bf16 rounding of the sweep's operands
+ * (within 1e-2 of the largest gradient; the bar against the oracle is the same for both).
+ * Arguments, layouts, limits and error behaviour as for
  * monarch_attn_fwd and monarch_attn_bwd, except that the workspace holds every (batch, head) at
  * once: at least monarch_attn_bwd_saved_workspace_bytes() bytes (0: unsupported problem), else
  * MRT_ERR_WORKSPACE.  The caller keeps the workspace untouched between the two calls and orders
