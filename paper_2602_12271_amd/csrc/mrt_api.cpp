@@ -512,8 +512,11 @@ mrt_status monarch_attn_fwd(const void* Q, const void* K, const void* V, void* O
 }
 
 // ---- backward pass -------------------------------------------------------------------------
-// fp32 workspace of one (batch, head): alpha_L and c_L of every iteration, abar of iterations
-// 2..T, Y, and the gradient buffers d alpha_L, d c_L, d Y, d abar.
+// Workspace of one (batch, head), sized for fp32 entries (the matrix-unit path stores bf16 in the
+// same places): alpha_L and c_L of every iteration, abar and its two column statistics of
+// iterations 2..T, Y, the gradient buffers d alpha_L, d c_L, d Y, d abar, the matrix-unit kernels'
+// transposed scratch, and (more than 192 key rows per problem or more than eight query tiles, bf16)
+// the fp32 output copy and row log-sum-exp that the saving forward call leaves for the sweep.
 namespace {
 struct BwdLayout {
   size_t rowsD, rowsS;    // bytes of one [m][j][nk][d] / [m][j][nk] array of one head
