@@ -267,7 +267,9 @@ struct ChunkRegs {
   static constexpr int CPR = D / 8, TOTAL = kHK * CPR, N = (TOTAL + NT - 1) / NT;
   static constexpr bool RAGGED = TOTAL % NT != 0;
   s16x8 v[N];
-  // nvalid >= 1 rows exist at src
+  // nvalid >= 1 rows exist at src.  STREAM: the rows are read once and by nobody else (non-temporal
+  // loads: they do not displace what later kernels will look for in the caches)
+  template <bool STREAM = false>
   __device__ inline void load(const u16* src, long long stride, int nvalid, int tid) {
     // thread t fetches piece t % CPR of rows t / CPR + i * (NT / CPR): a 32-bit offset from the
     // uniform chunk base, one multiply and then a uniform increment per load
@@ -276,7 +278,8 @@ struct ChunkRegs {
     unsigned off = (unsigned)(tid / CPR) * S;
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-      v[i] = *(const s16x8*)(base + (off < last ? off : last));
+      const s16x8* at = (const s16x8*)(base + (off < last ? off : last));
+      v[i] = STREAM ? __builtin_nontemporal_load(at) : *at;
       off += inc;
     }
   }
@@ -460,7 +463,7 @@ struct FlashLds {
 // the key.  Nothing here is conditional (a chunk beyond the end of the keys is fetched as copies
 // of key 0 and committed with a bias of -inf): the pipeline below then runs as straight code in
 // which the compiler's wait counts for one register set leave the other set's loads in flight.
-template <int D, bool WITH_V, int NT, int PAD = kPad>
+template <int D, bool WITH_V, int NT, int PAD = kPad, bool STREAM = false>
 struct ChunkFetch {
   ChunkRegs<D, NT, PAD> rk, rv;
   float rb;    // raw per-key value fetched by meta(); turned into the bias at commit time
@@ -471,8 +474,8 @@ struct ChunkFetch {
     const int left = nkeys - c0;                       // <= 0 beyond the end
     const int valid = left < kHK ? left : kHK;
     const int first = left > 0 ? c0 : 0, rows = valid > 0 ? valid : 1;
-    rk.load(kbase + (long long)first * kstride, kstride, rows, tid);
-    if (WITH_V) rv.load(vbase + (long long)first * vstride, vstride, rows, tid);
+    rk.template load<STREAM>(kbase + (long long)first * kstride, kstride, rows, tid);
+    if (WITH_V) rv.template load<STREAM>(vbase + (long long)first * vstride, vstride, rows, tid);
     rvalid = valid;
     const int k = tid & (kHK - 1);
     meta(first + (k < rows ? k : rows - 1), rb, rc);
@@ -500,7 +503,7 @@ struct ChunkFetch {
 // NSET = 4 keeps four register sets in flight (two pairs ahead), for workgroups that have a compute
 // unit to themselves and few registers per set (512 threads): with one workgroup per compute unit
 // two chunks in flight do not cover the memory latency at the streaming rate.
-template <int D, int QT, int NQ, bool WITH_V, bool MASKED, int NT, int NSET, int PAD, typename Meta>
+template <int D, int QT, int NQ, bool WITH_V, bool MASKED, int NT, int NSET, int PAD, bool STREAM, typename Meta>
 __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u16* vbase,
                                     long long vstride, int nkeys, Meta& meta, FlashLds<D, WITH_V, PAD>& lds,
                                     const bf16x8 (&qv)[QT][D / 32], float scale,
@@ -508,7 +511,7 @@ __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u
                                     f32x4 (&o)[QT][D / 16], int tid, int lane) {
   const int npairs = (nkeys + 2 * kHK - 1) / (2 * kHK);
   static_assert(NSET == 2 || NSET == 4, "two or four register sets");
-  using Fetch = ChunkFetch<D, WITH_V, NT, PAD>;
+  using Fetch = ChunkFetch<D, WITH_V, NT, PAD, STREAM>;
   Fetch fa, fb;
   auto fetch = [&](Fetch& f, int chunk) {
     f.fetch(kbase, kstride, vbase, vstride, nkeys, chunk * kHK, meta, tid);
@@ -567,20 +570,21 @@ __device__ inline void flash_loop_n(const u16* kbase, long long kstride, const u
 
 // nq = query tiles the wave owns (uniform over the wave): QT, QT - 1 or none; every path runs
 // the same fetches, commits and barriers.
-template <int D, int QT, bool WITH_V, bool MASKED, int NT, int PAD = kPad, int NSET = 2, typename Meta>
+template <int D, int QT, bool WITH_V, bool MASKED, int NT, int PAD = kPad, int NSET = 2, bool STREAM = false,
+          typename Meta>
 __device__ inline void flash_loop(const u16* kbase, long long kstride, const u16* vbase,
                                   long long vstride, int nkeys, Meta meta, FlashLds<D, WITH_V, PAD>& lds,
                                   const bf16x8 (&qv)[QT][D / 32], int nq, float scale,
                                   const int (&qchunk)[QT], FlashState<QT>& st,
                                   f32x4 (&o)[QT][D / 16], int tid, int lane) {
   if (nq == QT)
-    flash_loop_n<D, QT, QT, WITH_V, MASKED, NT, NSET, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
+    flash_loop_n<D, QT, QT, WITH_V, MASKED, NT, NSET, PAD, STREAM>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
                                                      qchunk, st, o, tid, lane);
   else if (QT > 1 && nq == QT - 1)
-    flash_loop_n<D, QT, (QT > 1 ? QT - 1 : 0), WITH_V, MASKED, NT, NSET, PAD>(kbase, kstride, vbase, vstride, nkeys, meta,
+    flash_loop_n<D, QT, (QT > 1 ? QT - 1 : 0), WITH_V, MASKED, NT, NSET, PAD, STREAM>(kbase, kstride, vbase, vstride, nkeys, meta,
                                                                        lds, qv, scale, qchunk, st, o, tid, lane);
   else
-    flash_loop_n<D, QT, 0, WITH_V, MASKED, NT, NSET, PAD>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
+    flash_loop_n<D, QT, 0, WITH_V, MASKED, NT, NSET, PAD, STREAM>(kbase, kstride, vbase, vstride, nkeys, meta, lds, qv, scale,
                                                     qchunk, st, o, tid, lane);
 }
 
@@ -657,7 +661,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KPar
   }
   MRT_STAMP(0);
   auto meta = [&](int key, float& raw, int& chunk) { raw = cLp[key]; chunk = RMASK ? key / p.rl : 0; };
-  flash_loop<D, QT, true, RMASK, NT, kPad, (NT == 512 ? 4 : 2)>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq,
+  flash_loop<D, QT, true, RMASK, NT, kPad, (NT == 512 ? 4 : 2), true>(aLp, D, Yp, D, NK, meta, lds, qv, wt.nq,
                                                                  p.scale * kLog2e, qchunk, st, o,
                                      tid, lane);
   MRT_STAMP(1);
