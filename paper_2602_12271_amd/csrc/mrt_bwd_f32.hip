@@ -418,11 +418,14 @@ __global__ __launch_bounds__(kThreads) void k_bwd_q_first(BwdParams bp) {
   float* dQp = bp.dQ + (size_t)bh * p.Nq * d;
   const long long qrow = row_offset(p, a, k);
   if (bp.dA1_bf16) {
-    // bf16 terms (d is 64 or 128 there): eight features per lane, four key tiles in flight
+    // bf16 terms (d is 64 or 128 there): eight features per lane, four key tiles in flight; the
+    // terms are read once and by nobody else (non-temporal loads)
     const unsigned short* dA16 = (const unsigned short*)bp.dA + ((size_t)bhl * p.ntq + ml) * NKtot * b2 * d;
-    const uint4* src = (const uint4*)(dA16 + (size_t)k * b2 * d);
+    typedef __attribute__((ext_vector_type(4))) unsigned ux4;
+    const ux4* src = (const ux4*)(dA16 + (size_t)k * b2 * d);
+    auto ld = [&](size_t at) { return __builtin_nontemporal_load(src + at); };
     const size_t per_n = (size_t)b1 * b2 * d / 8;
-    auto add8 = [](f32x4& lo, f32x4& hi, const uint4 x) {
+    auto add8 = [](f32x4& lo, f32x4& hi, const ux4 x) {
       lo += f32x4{__uint_as_float(x.x << 16), __uint_as_float(x.x & 0xffff0000u),
                   __uint_as_float(x.y << 16), __uint_as_float(x.y & 0xffff0000u)};
       hi += f32x4{__uint_as_float(x.z << 16), __uint_as_float(x.z & 0xffff0000u),
@@ -433,11 +436,11 @@ __global__ __launch_bounds__(kThreads) void k_bwd_q_first(BwdParams bp) {
       f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
       int n = 0;
       for (; n + 4 <= nvis; n += 4) {
-        const uint4 x0 = src[(size_t)n * per_n + idx], x1 = src[(size_t)(n + 1) * per_n + idx];
-        const uint4 x2 = src[(size_t)(n + 2) * per_n + idx], x3 = src[(size_t)(n + 3) * per_n + idx];
+        const ux4 x0 = ld((size_t)n * per_n + idx), x1 = ld((size_t)(n + 1) * per_n + idx);
+        const ux4 x2 = ld((size_t)(n + 2) * per_n + idx), x3 = ld((size_t)(n + 3) * per_n + idx);
         add8(s0, s1, x0); add8(s0, s1, x1); add8(s0, s1, x2); add8(s0, s1, x3);
       }
-      for (; n < nvis; ++n) add8(s0, s1, src[(size_t)n * per_n + idx]);
+      for (; n < nvis; ++n) add8(s0, s1, ld((size_t)n * per_n + idx));
       f32x4* dst = (f32x4*)(dQp + (qrow + axis_offset(p.cmap, bq * b2 + jj)) * d + v);
       dst[0] += s0;
       dst[1] += s1;
