@@ -670,7 +670,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 1 : 2) void k_bf16_stage_l_out(KPar
   for (int q = 0; q < QT; ++q) {
     const int l = 16 * wt.lt[q] + c;
     const float lsum = xsum(st.lrun[q]);
-    if (q < wt.nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / lsum, g);
+    if (q < wt.nq && l < b1) store_rows_nt<D>(Op + orow(l), o[q], 1.0f / lsum, g);
   }
   if constexpr (STATS) {
     // for a backward call that follows: the rows' log-sum-exp and the unrounded output
@@ -1097,7 +1097,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_res(KParams p) {
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
       const int l = 16 * (QT * pair + q) + c;
-      if (q < nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
+      if (q < nq && l < b1) store_rows_nt<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
     }
   }
   MRT_STAMP(3);
@@ -1602,7 +1602,7 @@ __global__ __launch_bounds__(256, 3) void k_bf16_stage_l_out_mid(KParams p) {
 #pragma unroll
     for (int q = 0; q < QT; ++q) {
       const int l = 16 * wt.lt[q] + c;
-      if (q < wt.nq && l < b1) store_rows<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
+      if (q < wt.nq && l < b1) store_rows_nt<D>(Op + orow(l), o[q], 1.0f / sum[q], g);
     }
   }
   MRT_STAMP(4);

@@ -204,6 +204,18 @@ __device__ inline void store_rows(u16* row, const f32x4* acc, float mul, int g) 
   }
 }
 
+// The same row with non-temporal stores: the operator's output, which no later kernel of the call
+// reads (it would only displace the workspace arrays from the caches).
+template <int D>
+__device__ inline void store_rows_nt(u16* row, const f32x4* acc, float mul, int g) {
+  typedef __attribute__((ext_vector_type(4))) unsigned ux4;
+#pragma unroll
+  for (int q = 0; q < D / 32; ++q) {
+    bf16x8 o = pack8(acc[2 * q] * mul, acc[2 * q + 1] * mul);
+    __builtin_nontemporal_store(__builtin_bit_cast(ux4, o), (ux4*)(row + 32 * q + 8 * g));
+  }
+}
+
 // Half h of such a row from the D/32 tiles pv_step_half accumulates.
 template <int D>
 __device__ inline void store_rows_half(u16* row, const f32x4* acc, float mul, int g, int h) {

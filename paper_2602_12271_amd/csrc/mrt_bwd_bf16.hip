@@ -201,6 +201,17 @@ __device__ inline void pv_step_nat(const u16* vals, const bf16x8 (&pb)[NB], int 
 }
 
 // A lane's D/16 accumulator tiles as fp32: 8 consecutive features at 32q + 8g per pair of tiles.
+// The same rows with non-temporal stores: gradients that no later kernel of the call reads or adds
+// to (they would only displace the workspace arrays from the caches).
+template <int D>
+__device__ inline void store_rows_f32_nt(float* row, const f32x4* acc, float mul, int g) {
+#pragma unroll
+  for (int q = 0; q < D / 32; ++q) {
+    f32x4* p = (f32x4*)(row + 32 * q + 8 * g);
+    __builtin_nontemporal_store(acc[2 * q] * mul, p);
+    __builtin_nontemporal_store(acc[2 * q + 1] * mul, p + 1);
+  }
+}
 template <int D>
 __device__ inline void store_rows_f32(float* row, const f32x4* acc, float mul, int g, bool add) {
 #pragma unroll
@@ -1355,8 +1366,9 @@ __global__ __launch_bounds__(64 * NT + (LW ? kLoaderThreads<NT> : 0), LW ? 2 : (
   auto store_kv = [&]() {
     if (j < b2) {
       const long long tok = pkrow + axis_offset(p.cmap, pbn * b2 + j);
-      store_rows_f32<D>(bp.dK + ((size_t)pbh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
-      if (LAST) store_rows_f32<D>(bp.dV + ((size_t)pbh * p.Nkv + tok) * d, oV[0], 1.0f, g, false);
+      if (first && !bp.accumulate) store_rows_f32_nt<D>(bp.dK + ((size_t)pbh * p.Nkv + tok) * d, oK[0], 1.0f, g);
+      else store_rows_f32<D>(bp.dK + ((size_t)pbh * p.Nkv + tok) * d, oK[0], 1.0f, g, bp.accumulate != 0);
+      if (LAST) store_rows_f32_nt<D>(bp.dV + ((size_t)pbh * p.Nkv + tok) * d, oV[0], 1.0f, g);
     }
 #pragma unroll
     for (int vt = 0; vt < NVT; ++vt) {
